@@ -1,0 +1,175 @@
+/*
+ * spp.h -- C interface of the per-partition data path of VIP-cached, partitioned GNN
+ * minibatch preparation on one AMD MI355X (gfx950):
+ *
+ *   spp_vip_propagate     vertex-inclusion probabilities, Proposition 1 (Sec. 3.1)
+ *   spp_build_vip_cache   VIP-ranked replica cache of remote feature rows (Secs. 3.2, 4.2)
+ *   spp_sample_mfg        node-wise fanout sampling into per-layer message-flow graphs
+ *                         (Sec. 2.3; steps (i)-(iii) of the random process of Sec. 3.1)
+ *   spp_gather_features   cache-aware feature gather: local shard / replica cache / remote
+ *                         rows on a miss (Secs. 4.1-4.3; stages 5-10 of Appendix D)
+ *
+ * Conventions
+ *   G        directed graph in CSR on the device: rowptr int64[N+1], col int32[M].  Row v,
+ *            adj(v) = col[rowptr[v] .. rowptr[v+1]), is the list v samples its neighbours
+ *            from; d(v) = |adj(v)|.  Rows ascending, duplicate-free, no self loops.
+ *   T        training vertices of the owned partition (device int32, distinct).
+ *   fanouts  host int32[L]; fanouts[h-1] = f_h, hop h = 1 being the hop next to the minibatch.
+ *   [lo,hi)  the owned partition's contiguous vertex-id range (Sec. 4.1).
+ *   K, alpha number of partitions and replication factor: the cache holds at most
+ *            floor(alpha * N / K) rows (Sec. 3.2).
+ *   remote store: the feature matrix with the owned range cut out, row-major;
+ *            row of vertex g = g if g < lo, else g - (hi - lo).
+ *
+ * Pointers named d_* are device memory, host_* pinned (device-mapped) host memory unless
+ * said otherwise; the rest is ordinary host memory.  The caller owns every buffer it passes;
+ * the library owns only what lives behind its opaque handles.  All device work is enqueued
+ * on the context's stream (the miss path of the gather also uses a side stream owned by the
+ * context and joins it back before returning).  Calls on one context must not overlap.
+ *
+ * Every function returns SPP_OK (0) or a negative code; spp_last_error() then describes it.
+ * Nothing here throws, aborts or falls back to the CPU.
+ */
+#ifndef SPP_H
+#define SPP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPP_MAX_L       8      /* most hops / GNN layers */
+#define SPP_MAX_FANOUT  64     /* largest fanout (one wavefront lane per slot) */
+
+enum {
+    SPP_OK          =  0,
+    SPP_E_ARG       = -1,      /* null pointer, size out of range, misaligned rows, L or fanout too large */
+    SPP_E_CAPACITY  = -2,      /* an output buffer is smaller than the bound the call needs */
+    SPP_E_OOM       = -3,      /* device or host allocation failed */
+    SPP_E_HIP       = -4       /* a HIP runtime call failed (text in spp_last_error) */
+};
+
+/* flags */
+#define SPP_SYNC              0x1u   /* wait for the stream before returning and fill host outputs */
+#define SPP_VIP_INCLUDE_HOP0  0x2u   /* also multiply (1 - p^[0]) into eq. (1); default: as printed, h = 1..L */
+#define SPP_GRAPH_IN_LISTS    0x4u   /* spp_graph_create: also build the in-lists vip_propagate needs */
+
+typedef struct spp_ctx   spp_ctx;    /* workspaces, side stream, events */
+typedef struct spp_graph spp_graph;  /* refers to the caller's CSR; owns the library-built in-lists */
+typedef struct spp_cache spp_cache;  /* owns the id->slot table and the cached rows in HBM */
+
+/* Thread-local description of the last error on this thread; valid until the next call. */
+const char* spp_last_error(void);
+
+/* Creates a context on `device`; `hip_stream` is the caller's hipStream_t (NULL = the null
+ * stream).  The caller keeps the stream alive until spp_ctx_destroy. */
+int  spp_ctx_create(spp_ctx** out, int device, void* hip_stream);
+void spp_ctx_destroy(spp_ctx* ctx);
+/* Blocks until everything the context enqueued has finished. */
+int  spp_ctx_sync(spp_ctx* ctx);
+
+/* Wraps a device CSR (not copied; must outlive the handle).  With SPP_GRAPH_IN_LISTS it also
+ * builds, once, the transposed structure (for every u the ascending list of v with u in
+ * adj(v)), which costs about 4*M + 8*N bytes of device memory plus 16*M bytes of temporary
+ * space while it is built.  Synchronous. */
+int  spp_graph_create(spp_ctx* ctx, int64_t N, int64_t M, const int64_t* d_rowptr,
+                      const int32_t* d_col, uint32_t flags, spp_graph** out);
+void spp_graph_destroy(spp_graph* g);
+
+/* (1) Vertex-inclusion probabilities, Proposition 1 with the uniform instantiation of Sec. 3.1:
+ *       p^[0](u) = min(1, B/nT) for u in T, else 0
+ *       p^[h](u) = 1 - prod over {v : u in adj(v)} of (1 - min(1, f_h/d(v)) * p^[h-1](v))    eq. (2)
+ *       p(u)     = 1 - prod_{h=1..L} (1 - p^[h](u))                                         eq. (1)
+ *     Products are carried as sums of log1p in fp64; results are stored as fp32.
+ *     d_p_total: fp32[N], required.  d_p_hop: fp32[L*N] (hop h at offset (h-1)*N) or NULL.
+ *     flags: SPP_VIP_INCLUDE_HOP0, SPP_SYNC.  The graph must have been created with
+ *     SPP_GRAPH_IN_LISTS (else SPP_E_ARG).  Vertices with d(v) = 0 contribute nothing. */
+int  spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t* d_T, int64_t nT,
+                       int32_t B, const int32_t* fanouts, int32_t L,
+                       float* d_p_total, float* d_p_hop, uint32_t flags);
+
+/* (2) Replica cache (Sec. 3.2): among the vertices outside [lo,hi) with d_score > 0, the first
+ *     C = floor(alpha*N/K) in the order (score descending as fp32, id ascending); slot = rank.
+ *     d_score fp32[N] is the VIP vector (or any other ranking score, e.g. degree).
+ *     Writes the ids in rank order to d_cache_ids (device, capacity >= C) and their number to
+ *     *n_cached (host), builds the id->slot hash table (Sec. 4.2) and copies the chosen rows once
+ *     from the remote store (pinned host memory, or device memory) into HBM.  remote may be
+ *     NULL: then no rows are copied and the cache only answers membership (spp_cache_lookup).
+ *     Row size D*elem_bytes must be a multiple of 2.  Synchronous. */
+int  spp_build_vip_cache(spp_ctx* ctx, const float* d_score, int64_t N, int64_t lo, int64_t hi,
+                         int32_t K, double alpha, const void* remote, int32_t D,
+                         int32_t elem_bytes, int32_t* d_cache_ids, int64_t* n_cached,
+                         spp_cache** out);
+void spp_cache_destroy(spp_cache* c);
+/* Limits the cache to its first `n_slots` ranks (the cache of a smaller alpha is a prefix of a
+ * larger one); n_slots < 0 restores all built rows. */
+int  spp_cache_set_limit(spp_cache* c, int64_t n_slots);
+/* d_slot_out[i] = slot of d_ids[i] in the cache, or -1.  Enqueued on the context's stream. */
+int  spp_cache_lookup(spp_ctx* ctx, const spp_cache* c, const int32_t* d_ids, int64_t n,
+                      int32_t* d_slot_out);
+
+/* (3) Sampling.  S_0 = seeds (device int32[nseeds], distinct).  At hop h every vertex v of
+ *     S_{h-1}, in order, takes c = min(f_h, d(v)) positions of adj(v): all of them in row order
+ *     if d(v) <= f_h, otherwise Floyd's subset algorithm with one draw per slot j: m = d-f+j,
+ *     t = (rand32 * (m+1)) >> 32, position t unless already taken, else m.  rand32 is word j%4 of
+ *     Philox-4x32-10 with key (seed low, seed high) and counter (v, j/4, h, batch_index low).
+ *     S_h = S_{h-1} followed by the ids not seen before in order of first appearance (target-
+ *     major, slot-minor).  MFG h has targets S_{h-1} and sources S_h: d_indptr[h-1] holds
+ *     n_{h-1}+1 offsets, d_src[h-1] the index in S_h of each sampled neighbour; the message of
+ *     edge e flows from source d_src[h-1][e] to its target.
+ *
+ *     The caller sizes the buffers with spp_mfg_bound and fills the capacities and pointers;
+ *     the library fills the buffers and d_counts (device int64[2*(SPP_MAX_L+1)]: n_0..n_L at
+ *     [0..L], e_0..e_L at [SPP_MAX_L+1 ..]; e_0 = 0).  With SPP_SYNC it also waits and fills the
+ *     host fields n[] and e[].  Capacities below the bounds give SPP_E_CAPACITY before any work. */
+typedef struct {
+    int64_t  n_nodes_cap;               /* in: entries in d_node_ids (>= n_bound[L]) */
+    int64_t  n_edges_cap[SPP_MAX_L];    /* in: entries in d_src[h-1] (>= e_bound[h]) */
+    int32_t* d_node_ids;                /* out: S_L; its first n[h] entries are S_h */
+    int32_t* d_indptr[SPP_MAX_L];       /* out: hop h at [h-1], int32[n_bound[h-1] + 1] */
+    int32_t* d_src[SPP_MAX_L];          /* out: hop h at [h-1] */
+    int64_t* d_counts;                  /* out: device int64[2*(SPP_MAX_L+1)] */
+    int64_t  n[SPP_MAX_L + 1];          /* out (host, with SPP_SYNC): |S_h| */
+    int64_t  e[SPP_MAX_L + 1];          /* out (host, with SPP_SYNC): edges of hop h */
+} spp_mfg;
+
+/* n_bound[h] = min(N, n_bound[h-1] * (1 + f_h)), e_bound[h] = n_bound[h-1] * f_h; arrays of L+1. */
+int  spp_mfg_bound(int32_t nseeds, const int32_t* fanouts, int32_t L, int64_t N,
+                   int64_t* n_bound, int64_t* e_bound);
+int  spp_sample_mfg(spp_ctx* ctx, const spp_graph* g, const int32_t* d_seeds, int32_t nseeds,
+                    const int32_t* fanouts, int32_t L, uint64_t seed, uint64_t batch_index,
+                    spp_mfg* io, uint32_t flags);
+
+/* (4) Gather: d_out[i,:] = row of vertex d_node_ids[i] (in [0, N)), i < n, taken from
+ *       d_local  [hi-lo, D]  if lo <= g < hi            (row g - lo)
+ *       the cache             if g is cached             (row = slot)
+ *       remote                otherwise, a miss          (row g, or g - (hi-lo) above the range)
+ *     Hits are copied by one kernel on the context's stream; the compacted miss list is served
+ *     by a second kernel on the context's side stream reading the pinned host rows directly,
+ *     and joined back before the call returns to the stream.  cache may be NULL (alpha = 0).
+ *     n is the number of ids, or an upper bound when d_n (device int64, e.g. &d_counts[L]) is
+ *     given, in which case the count is read on the device.  Row size D*elem_bytes must be a
+ *     multiple of 2; 16-byte multiples take the widest path.  Duplicate ids are allowed.
+ *     `remote` is pinned host memory (or device memory); it may be NULL only if no id misses.
+ *     stats (host, may be NULL) is filled when SPP_SYNC is set; otherwise read it later with
+ *     spp_gather_last_stats after synchronising. */
+typedef struct { int64_t n_local, n_cache_hit, n_miss, miss_bytes; } spp_gather_stats;
+int  spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
+                         int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D, int32_t elem_bytes,
+                         const int32_t* d_node_ids, int64_t n, const int64_t* d_n, void* d_out,
+                         spp_gather_stats* stats, uint32_t flags);
+int  spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats);
+
+/* Durations, in milliseconds, of the device work of the most recent call of each kind on this
+ * context, measured with events on the streams the kernels ran on.  Valid after the work
+ * finished (SPP_SYNC or spp_ctx_sync).  Index with the SPP_T_* constants. */
+enum { SPP_T_VIP_TOTAL = 0, SPP_T_VIP_HOP_FIRST = 1 /* .. +L-1 */, SPP_T_SAMPLE = 9,
+       SPP_T_GATHER_HIT = 10, SPP_T_GATHER_MISS = 11, SPP_T_GATHER_CLASSIFY = 12, SPP_T_COUNT = 16 };
+int  spp_ctx_timing(spp_ctx* ctx, int enable);             /* record events from now on (0/1) */
+int  spp_ctx_last_times(spp_ctx* ctx, float* ms_out /* [SPP_T_COUNT] */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPP_H */

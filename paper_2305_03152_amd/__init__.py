@@ -1,0 +1,8 @@
+"""MI355X-native per-partition data path of VIP-cached, partitioned GNN minibatch preparation.
+
+Four calls, each a thin binding over the C interface in include/spp.h whose work runs in
+hand-written HIP kernels for gfx950: vip_propagate, build_vip_cache, sample_mfg,
+gather_features.
+"""
+from .api import (Cache, Context, Graph, MFGBuffers, SppError, build_vip_cache, gather_features,  # noqa: F401
+                  gather_last_stats, load_library, mfg_bound, sample_mfg, vip_propagate, EXPORTS, LIB_PATH)

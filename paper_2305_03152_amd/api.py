@@ -1,0 +1,340 @@
+"""Python binding of libspp.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C interface (include/spp.h);
+torch is used here for device memory and streams.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspp.so")
+
+SPP_MAX_L = 8
+SPP_MAX_FANOUT = 64
+SPP_SYNC = 0x1
+SPP_VIP_INCLUDE_HOP0 = 0x2
+SPP_GRAPH_IN_LISTS = 0x4
+SPP_T_VIP_TOTAL, SPP_T_VIP_HOP_FIRST, SPP_T_SAMPLE = 0, 1, 9
+SPP_T_GATHER_HIT, SPP_T_GATHER_MISS, SPP_T_GATHER_CLASSIFY, SPP_T_COUNT = 10, 11, 12, 16
+
+EXPORTS = [
+    "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
+    "spp_graph_destroy", "spp_vip_propagate", "spp_build_vip_cache", "spp_cache_destroy",
+    "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg",
+    "spp_gather_features", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_last_times",
+]
+
+
+class SppError(RuntimeError):
+    pass
+
+
+class _MfgStruct(C.Structure):
+    _fields_ = [
+        ("n_nodes_cap", C.c_int64),
+        ("n_edges_cap", C.c_int64 * SPP_MAX_L),
+        ("d_node_ids", C.c_void_p),
+        ("d_indptr", C.c_void_p * SPP_MAX_L),
+        ("d_src", C.c_void_p * SPP_MAX_L),
+        ("d_counts", C.c_void_p),
+        ("n", C.c_int64 * (SPP_MAX_L + 1)),
+        ("e", C.c_int64 * (SPP_MAX_L + 1)),
+    ]
+
+
+class _GatherStats(C.Structure):
+    _fields_ = [("n_local", C.c_int64), ("n_cache_hit", C.c_int64), ("n_miss", C.c_int64),
+                ("miss_bytes", C.c_int64)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libspp.so (built in-tree by build.py); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise SppError(f"{LIB_PATH} is missing: build it with `python -m paper_2305_03152_amd.build` "
+                       "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    lib.spp_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        getattr(lib, name)          # AttributeError if a declared symbol is not exported
+    lib.spp_ctx_destroy.restype = None
+    lib.spp_graph_destroy.restype = None
+    lib.spp_cache_destroy.restype = None
+    lib.spp_ctx_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_void_p]
+    lib.spp_ctx_destroy.argtypes = [C.c_void_p]
+    lib.spp_ctx_sync.argtypes = [C.c_void_p]
+    lib.spp_graph_create.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_uint32,
+                                     C.POINTER(C.c_void_p)]
+    lib.spp_graph_destroy.argtypes = [C.c_void_p]
+    lib.spp_vip_propagate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                      C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
+    lib.spp_build_vip_cache.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
+                                        C.c_double, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                        C.POINTER(C.c_int64), C.POINTER(C.c_void_p)]
+    lib.spp_cache_destroy.argtypes = [C.c_void_p]
+    lib.spp_cache_set_limit.argtypes = [C.c_void_p, C.c_int64]
+    lib.spp_cache_lookup.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.spp_mfg_bound.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_int64,
+                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.spp_sample_mfg.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
+                                   C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(_MfgStruct), C.c_uint32]
+    lib.spp_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                        C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
+                                        C.c_void_p, C.POINTER(_GatherStats), C.c_uint32]
+    lib.spp_gather_last_stats.argtypes = [C.c_void_p, C.POINTER(_GatherStats)]
+    lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
+    lib.spp_ctx_last_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SppError(f"libspp error {rc}: {load_library().spp_last_error().decode()}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise SppError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+    return t
+
+
+def _fan(fanouts: Sequence[int]):
+    L = len(fanouts)
+    return (C.c_int32 * L)(*[int(f) for f in fanouts]), L
+
+
+class Context:
+    """Owns the library context bound to a torch stream (default: the current stream)."""
+
+    def __init__(self, device: int = 0, stream: Optional[torch.cuda.Stream] = None):
+        lib = load_library()
+        if not torch.cuda.is_available():
+            raise SppError("no GPU visible: the path has no CPU fallback")
+        torch.cuda.set_device(device)
+        self.device = device
+        self.stream = stream if stream is not None else torch.cuda.current_stream(device)
+        self._h = C.c_void_p()
+        _check(lib.spp_ctx_create(C.byref(self._h), device, C.c_void_p(self.stream.cuda_stream)))
+
+    def sync(self):
+        _check(load_library().spp_ctx_sync(self._h))
+
+    def timing(self, enable: bool = True):
+        _check(load_library().spp_ctx_timing(self._h, int(enable)))
+
+    def last_times(self) -> List[float]:
+        buf = (C.c_float * SPP_T_COUNT)()
+        _check(load_library().spp_ctx_last_times(self._h, buf))
+        return list(buf)
+
+    def close(self):
+        if self._h:
+            load_library().spp_ctx_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Graph:
+    """G in CSR on the device: rowptr int64[N+1], col int32[M]; keeps the tensors alive."""
+
+    def __init__(self, ctx: Context, rowptr: torch.Tensor, col: torch.Tensor, in_lists: bool = False):
+        self.ctx = ctx
+        self.rowptr = _dev(rowptr, torch.int64, "rowptr")
+        self.col = _dev(col, torch.int32, "col")
+        self.N = rowptr.numel() - 1
+        self.M = col.numel()
+        self._h = C.c_void_p()
+        flags = SPP_GRAPH_IN_LISTS if in_lists else 0
+        _check(load_library().spp_graph_create(ctx._h, self.N, self.M, _ptr(rowptr), _ptr(col), flags,
+                                               C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            load_library().spp_graph_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def vip_propagate(ctx: Context, graph: Graph, T: torch.Tensor, B: int, fanouts: Sequence[int],
+                  per_hop: bool = False, include_hop0: bool = False, sync: bool = True):
+    """Proposition 1.  Returns p_total fp32[N] (and p_hop fp32[L, N] when per_hop)."""
+    T = _dev(T, torch.int32, "T")
+    f, L = _fan(fanouts)
+    p_total = torch.empty(graph.N, dtype=torch.float32, device=T.device)
+    p_hop = torch.empty((L, graph.N), dtype=torch.float32, device=T.device) if per_hop else None
+    flags = (SPP_SYNC if sync else 0) | (SPP_VIP_INCLUDE_HOP0 if include_hop0 else 0)
+    _check(load_library().spp_vip_propagate(ctx._h, graph._h, _ptr(T), T.numel(), int(B), f, L, _ptr(p_total),
+                                            _ptr(p_hop), flags))
+    return (p_total, p_hop) if per_hop else p_total
+
+
+class Cache:
+    """Replica cache handle: ids in rank order (slot = rank) plus the library-owned table and rows."""
+
+    def __init__(self, ctx, handle, ids, N, lo, hi, remote_keepalive):
+        self.ctx, self._h, self.ids, self.N, self.lo, self.hi = ctx, handle, ids, N, lo, hi
+        self._keep = remote_keepalive
+
+    @property
+    def n_cached(self) -> int:
+        return int(self.ids.numel())
+
+    def set_limit(self, n_slots: int):
+        _check(load_library().spp_cache_set_limit(self._h, int(n_slots)))
+
+    def lookup(self, ids: torch.Tensor) -> torch.Tensor:
+        ids = _dev(ids, torch.int32, "ids")
+        out = torch.empty_like(ids)
+        _check(load_library().spp_cache_lookup(self.ctx._h, self._h, _ptr(ids), ids.numel(), _ptr(out)))
+        return out
+
+    def close(self):
+        if self._h:
+            load_library().spp_cache_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _row_store(t: Optional[torch.Tensor], name: str):
+    if t is None:
+        return None
+    if not t.is_contiguous() or t.dim() != 2:
+        raise SppError(f"{name} must be a contiguous 2-D tensor")
+    if not (t.is_cuda or t.is_pinned()):
+        raise SppError(f"{name} must live in pinned host memory or on the GPU")
+    return t
+
+
+def build_vip_cache(ctx: Context, score: torch.Tensor, lo: int, hi: int, K: int, alpha: float,
+                    remote: Optional[torch.Tensor], D: int, elem_bytes: int) -> Cache:
+    """Top floor(alpha*N/K) remote vertices by (score desc, id asc); table built, rows copied once."""
+    score = _dev(score, torch.float32, "score")
+    N = score.numel()
+    remote = _row_store(remote, "remote")
+    cap = int(alpha * float(N) / K)          # floor for non-negative values; the library recomputes it
+    ids = torch.empty(cap + 1, dtype=torch.int32, device=score.device)
+    n_cached = C.c_int64(0)
+    h = C.c_void_p()
+    _check(load_library().spp_build_vip_cache(ctx._h, _ptr(score), N, int(lo), int(hi), int(K), float(alpha),
+                                              _ptr(remote), int(D), int(elem_bytes), _ptr(ids),
+                                              C.byref(n_cached), C.byref(h)))
+    return Cache(ctx, h, ids[:n_cached.value], N, lo, hi, remote)
+
+
+def mfg_bound(nseeds: int, fanouts: Sequence[int], N: int):
+    f, L = _fan(fanouts)
+    nb = (C.c_int64 * (L + 1))()
+    eb = (C.c_int64 * (L + 1))()
+    _check(load_library().spp_mfg_bound(int(nseeds), f, L, int(N), nb, eb))
+    return list(nb), list(eb)
+
+
+class MFGBuffers:
+    """Caller-owned output buffers of sample_mfg, sized once from the bounds and reused."""
+
+    def __init__(self, device, max_seeds: int, fanouts: Sequence[int], N: int):
+        self.fanouts = tuple(int(f) for f in fanouts)
+        self.L = len(self.fanouts)
+        self.nb, self.eb = mfg_bound(max_seeds, self.fanouts, N)
+        self.node_ids = torch.empty(max(self.nb[self.L], 1), dtype=torch.int32, device=device)
+        self.indptr = [torch.empty(self.nb[h] + 1, dtype=torch.int32, device=device) for h in range(self.L)]
+        self.src = [torch.empty(max(self.eb[h + 1], 1), dtype=torch.int32, device=device) for h in range(self.L)]
+        self.counts = torch.zeros(2 * (SPP_MAX_L + 1), dtype=torch.int64, device=device)
+        self.n: List[int] = [0] * (self.L + 1)
+        self.e: List[int] = [0] * (self.L + 1)
+        s = _MfgStruct()
+        s.n_nodes_cap = self.node_ids.numel()
+        s.d_node_ids = self.node_ids.data_ptr()
+        s.d_counts = self.counts.data_ptr()
+        for h in range(self.L):
+            s.n_edges_cap[h] = self.src[h].numel()
+            s.d_indptr[h] = self.indptr[h].data_ptr()
+            s.d_src[h] = self.src[h].data_ptr()
+        self._s = s
+
+    @property
+    def n_final_device(self) -> torch.Tensor:
+        """Device view of |S_L| (for a gather that must not wait for the host)."""
+        return self.counts[self.L:self.L + 1]
+
+
+def sample_mfg(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: Sequence[int], seed: int,
+               batch_index: int, out: Optional[MFGBuffers] = None, sync: bool = True) -> MFGBuffers:
+    """Multi-hop fanout sampling into per-layer MFGs.  With sync the host counts out.n / out.e are filled."""
+    seeds = _dev(seeds, torch.int32, "seeds")
+    if out is None:
+        out = MFGBuffers(seeds.device, seeds.numel(), fanouts, graph.N)
+    f, L = _fan(fanouts)
+    _check(load_library().spp_sample_mfg(ctx._h, graph._h, _ptr(seeds), seeds.numel(), f, L,
+                                         C.c_uint64(int(seed) & (2**64 - 1)), C.c_uint64(int(batch_index) & (2**64 - 1)),
+                                         C.byref(out._s), SPP_SYNC if sync else 0))
+    if sync:
+        out.n = [int(out._s.n[h]) for h in range(L + 1)]
+        out.e = [int(out._s.e[h]) for h in range(L + 1)]
+    return out
+
+
+def gather_features(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,
+                    remote: Optional[torch.Tensor], node_ids: torch.Tensor, n: Optional[int] = None,
+                    n_device: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                    sync: bool = True):
+    """out[i,:] = row of node_ids[i] from the local shard, the cache, or the remote store on a miss.
+
+    Returns (out, stats) where stats = dict(n_local, n_cache_hit, n_miss, miss_bytes) when sync, else None.
+    """
+    local = _row_store(local, "local")
+    if not local.is_cuda:
+        raise SppError("local must be on the GPU")
+    remote = _row_store(remote, "remote")
+    node_ids = _dev(node_ids, torch.int32, "node_ids")
+    n = int(node_ids.numel() if n is None else n)
+    D, eb = local.shape[1], local.element_size()
+    if out is None:
+        out = torch.empty((n, D), dtype=local.dtype, device=local.device)
+    if out.shape[0] < n or out.shape[1] != D or not out.is_contiguous():
+        raise SppError("out is too small or not contiguous")
+    st = _GatherStats()
+    _check(load_library().spp_gather_features(ctx._h, cache._h if cache is not None else None, _ptr(local),
+                                              int(N), int(lo), int(hi), _ptr(remote), D, eb, _ptr(node_ids), n,
+                                              _ptr(n_device), _ptr(out), C.byref(st), SPP_SYNC if sync else 0))
+    stats = None
+    if sync:
+        stats = dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)
+    return out, stats
+
+
+def gather_last_stats(ctx: Context):
+    st = _GatherStats()
+    _check(load_library().spp_gather_last_stats(ctx._h, C.byref(st)))
+    return dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)

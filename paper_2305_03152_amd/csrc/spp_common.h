@@ -1,0 +1,146 @@
+// Shared host-side plumbing of the library: error reporting, handle layouts, workspace helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include "../../include/spp.h"
+
+namespace spp {
+
+void set_error(const char* fmt, ...);
+
+#define SPP_HIP(call)                                                                       \
+    do {                                                                                    \
+        hipError_t e__ = (call);                                                            \
+        if (e__ != hipSuccess) {                                                            \
+            spp::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, \
+                           __LINE__);                                                       \
+            return (e__ == hipErrorOutOfMemory) ? SPP_E_OOM : SPP_E_HIP;                    \
+        }                                                                                   \
+    } while (0)
+
+#define SPP_CHECK(cond, code, ...)                                                          \
+    do {                                                                                    \
+        if (!(cond)) {                                                                      \
+            spp::set_error(__VA_ARGS__);                                                    \
+            return (code);                                                                  \
+        }                                                                                   \
+    } while (0)
+
+#define SPP_TRY(expr)                                                                       \
+    do {                                                                                    \
+        int rc__ = (expr);                                                                  \
+        if (rc__ != SPP_OK) return rc__;                                                    \
+    } while (0)
+
+// A grow-only device buffer owned by a context.
+struct DevBuf {
+    void*  ptr = nullptr;
+    size_t bytes = 0;
+    int reserve(size_t need) {
+        if (need <= bytes) return SPP_OK;
+        if (ptr) { (void)hipFree(ptr); ptr = nullptr; bytes = 0; }
+        size_t want = need + need / 8 + 256;
+        hipError_t e = hipMalloc(&ptr, want);
+        if (e != hipSuccess) {
+            ptr = nullptr;
+            set_error("hipMalloc of %zu bytes failed: %s", want, hipGetErrorString(e));
+            return SPP_E_OOM;
+        }
+        bytes = want;
+        return SPP_OK;
+    }
+    void release() { if (ptr) (void)hipFree(ptr); ptr = nullptr; bytes = 0; }
+    template <class T> T* as() const { return reinterpret_cast<T*>(ptr); }
+};
+
+constexpr int kNumTimers = SPP_T_COUNT;
+
+}  // namespace spp
+
+struct spp_ctx {
+    int         device = 0;
+    hipStream_t stream = nullptr;       // caller's stream
+    hipStream_t side = nullptr;         // miss path
+    hipEvent_t  ev_fork = nullptr, ev_join = nullptr;
+    int         num_cu = 256;
+    // sampling workspaces
+    spp::DevBuf table;                  // uint64 hash table: global id -> local id / first position
+    spp::DevBuf flat;                   // int32 sampled global ids of the current hop
+    spp::DevBuf partials;               // scan partial sums
+    // gather workspaces
+    spp::DevBuf srcdesc;                // int64 per row: where the row comes from
+    spp::DevBuf misslist;               // int32 positions of the rows that miss
+    spp::DevBuf gcount;                 // device counters of the gather (int64[8])
+    int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
+    // vip workspaces
+    spp::DevBuf y0, y1, tot, hubacc;
+    // timing
+    int         timing = 0;
+    hipEvent_t  t0[spp::kNumTimers] = {}, t1[spp::kNumTimers] = {};
+    bool        t_valid[spp::kNumTimers] = {};
+};
+
+struct spp_graph {
+    int            device = 0;          // handles outlive contexts: they keep the device, not the context
+    int64_t        N = 0, M = 0;
+    const int64_t* rowptr = nullptr;    // caller's
+    const int32_t* col = nullptr;       // caller's
+    // in-lists (transpose), library-owned
+    bool     has_in = false;
+    int64_t* in_rowptr = nullptr;       // int64[N+1]
+    int32_t* in_col = nullptr;          // int32[M], ascending within a row
+    int32_t* blk_row = nullptr;         // int32[nblk+1]: first in-row starting at or after edge b*kVipChunk
+    int64_t  nblk = 0;
+    int32_t* hub_rows = nullptr;        // in-rows longer than kVipChunk
+    int64_t* hub_slice_ptr = nullptr;   // int64[nhub+1]: prefix of slices per hub
+    int64_t  nhub = 0, nslices = 0;
+};
+
+struct spp_cache {
+    int       device = 0;
+    int64_t   N = 0, lo = 0, hi = 0;
+    int64_t   n_rows = 0;               // rows built
+    int64_t   limit = 0;                // rows in use (<= n_rows)
+    int64_t   row_bytes = 0;
+    uint64_t* table = nullptr;          // (id << 32 | slot), empty = ~0
+    uint32_t  table_mask = 0;
+    int       table_shift = 0;
+    void*     rows = nullptr;           // [n_rows, row_bytes] or null (membership only)
+};
+
+namespace spp {
+
+constexpr int kVipChunk = 4096;         // in-list edges per workgroup of the pull kernel
+constexpr int kHubSlice = 16384;        // edges per workgroup slice of a hub row
+
+struct ScopedTimer {
+    spp_ctx* c; int idx; hipStream_t s;
+    ScopedTimer(spp_ctx* ctx, int i, hipStream_t st) : c(ctx), idx(i), s(st) {
+        if (c->timing) { (void)hipEventRecord(c->t0[idx], s); }
+    }
+    ~ScopedTimer() {
+        if (c->timing) { (void)hipEventRecord(c->t1[idx], s); c->t_valid[idx] = true; }
+    }
+};
+
+// 64-bit LSD radix sort of `n` keys on bits [bit_lo, bit_hi); stable.  keys_a holds the input and,
+// on return, *result points at whichever of keys_a / keys_b holds the sorted output.
+int radix_sort_u64(spp_ctx* ctx, uint64_t* keys_a, uint64_t* keys_b, int64_t n, int bit_lo,
+                   int bit_hi, uint64_t** result);
+
+// Rows copied from a row store that may be pinned host memory: out[i,:] = src[rows[i],:].
+int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, int64_t n,
+                      int64_t row_bytes, void* d_out, int num_cu);
+
+static inline uint32_t next_pow2(uint64_t x) {
+    uint64_t p = 1;
+    while (p < x) p <<= 1;
+    return (uint32_t)p;
+}
+
+}  // namespace spp

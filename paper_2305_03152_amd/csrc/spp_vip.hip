@@ -1,0 +1,192 @@
+// Vertex-inclusion probabilities, Proposition 1 (Sec. 3.1), in pull form over the in-lists.
+//
+// Per hop h every vertex v carries y_h(v) = log1p(-x_h(v)), x_h(v) = min(1, f_h/d(v)) * p^[h-1](v)
+// (0 for d(v) = 0), stored as fp32.  Then eq. (2) is
+//     S_h(u) = sum over {v : u in adj(v)} of y_h(v)     (all terms <= 0: no cancellation; fp64 sums)
+//     p^[h](u) = -expm1(S_h(u))
+// and because log(1 - p^[h](u)) = S_h(u), eq. (1) is p(u) = -expm1(sum_h S_h(u)).
+//
+// One workgroup owns the in-rows whose lists start inside one 4096-edge chunk of the transposed
+// CSR: it streams the chunk's source ids (coalesced), gathers their y into LDS, and each thread
+// then sums one row from LDS in fp64 and finishes the vertex (p^[h], running total, next hop's y)
+// in the same kernel.  Rows longer than a chunk (hubs) are split into slices over many workgroups
+// and combined with fp64 atomic adds.
+#include "spp_common.h"
+#include "spp_device.h"
+
+namespace spp {
+
+struct VipHop {
+    const int64_t* rowptr;     // forward CSR, for d(u)
+    const int64_t* in_rowptr;
+    const int32_t* in_col;
+    const float*   y;          // this hop's y
+    float*         y_next;     // next hop's y (unused at the last hop)
+    double*        tot;        // running sum of S over hops
+    float*         p_hop;      // p^[h] or null
+    float*         p_total;    // written at the last hop
+    double         f_next;     // f_{h+1}
+    int            first;      // first hop and hop 0 not included: tot is not read
+    int            last;
+};
+
+__device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, double S) {
+    const double ph = -expm1(S);
+    if (a.p_hop) a.p_hop[u] = (float)ph;
+    const double T = a.first ? S : a.tot[u] + S;
+    if (a.last) {
+        a.p_total[u] = (float)(-expm1(T));
+    } else {
+        a.tot[u] = T;
+        const int64_t d = a.rowptr[u + 1] - a.rowptr[u];
+        float yn = 0.f;
+        if (d > 0 && ph > 0.0) {
+            double t = a.f_next / (double)d;
+            if (t > 1.0) t = 1.0;
+            yn = (float)log1p(-(t * ph));
+        }
+        a.y_next[u] = yn;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) vip_pull_kernel(VipHop a, const int32_t* __restrict__ blk_row) {
+    __shared__ float ys[2 * kVipChunk];
+    const int64_t r0 = blk_row[blockIdx.x], r1 = blk_row[blockIdx.x + 1];
+    if (r0 >= r1) return;
+    const int64_t e0 = a.in_rowptr[r0];
+    int64_t e1 = a.in_rowptr[r1];
+    const int64_t last_start = a.in_rowptr[r1 - 1];
+    if (e1 - last_start > kVipChunk) e1 = last_start;      // a hub can only be the last row here
+    const int n = (int)(e1 - e0);                          // < 2 * kVipChunk
+    for (int k = threadIdx.x; k < n; k += kBlock) ys[k] = a.y[a.in_col[e0 + k]];
+    __syncthreads();
+    for (int64_t r = r0 + threadIdx.x; r < r1; r += kBlock) {
+        const int64_t s = a.in_rowptr[r], t = a.in_rowptr[r + 1];
+        if (t - s > kVipChunk) continue;                   // hub: finished by the hub kernels
+        double S = 0.0;
+        for (int k = (int)(s - e0); k < (int)(t - e0); ++k) S += (double)ys[k];
+        vip_finish_vertex(a, r, S);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) vip_hub_slice_kernel(VipHop a, const int32_t* __restrict__ hub_rows,
+                                                               const int64_t* __restrict__ hub_slice_ptr,
+                                                               int64_t nhub, double* __restrict__ hubacc) {
+    __shared__ double red[4];
+    const int64_t slice = blockIdx.x;
+    int64_t lo = 0, hi = nhub;                             // last k with hub_slice_ptr[k] <= slice
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (hub_slice_ptr[mid] <= slice) lo = mid; else hi = mid;
+    }
+    const int64_t k = lo;
+    const int64_t row = hub_rows[k];
+    const int64_t b = a.in_rowptr[row] + (slice - hub_slice_ptr[k]) * kHubSlice;
+    const int64_t rend = a.in_rowptr[row + 1];
+    const int64_t e = b + kHubSlice < rend ? b + kHubSlice : rend;
+    double s = 0.0;
+    for (int64_t i = b + threadIdx.x; i < e; i += kBlock) s += (double)a.y[a.in_col[i]];
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_down(s, off, kWave);
+    if (lane_id() == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(&hubacc[k], red[0] + red[1] + red[2] + red[3]);
+}
+
+__global__ void vip_hub_finish_kernel(VipHop a, const int32_t* __restrict__ hub_rows, int64_t nhub,
+                                      const double* __restrict__ hubacc) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < nhub) vip_finish_vertex(a, hub_rows[k], hubacc[k]);
+}
+
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+__global__ void fill_f64_kernel(double* p, int64_t n, double v) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
+// y_1(v) for the training vertices (p^[0] = min(1, B/|T|), Sec. 3.1); optionally hop 0 into the total.
+__global__ void vip_init_kernel(const int32_t* __restrict__ T, int64_t nT, int64_t N, double p0, double f1,
+                                const int64_t* __restrict__ rowptr, float* __restrict__ y,
+                                double* __restrict__ tot, int include_hop0, int* __restrict__ bad) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nT) return;
+    const int64_t v = T[i];
+    if (v < 0 || v >= N) { *bad = 1; return; }
+    const int64_t d = rowptr[v + 1] - rowptr[v];
+    if (d > 0) {
+        double t = f1 / (double)d;
+        if (t > 1.0) t = 1.0;
+        y[v] = (float)log1p(-(t * p0));
+    }
+    if (include_hop0) tot[v] = log1p(-p0);
+}
+
+}  // namespace spp
+
+extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t* d_T, int64_t nT,
+                                 int32_t B, const int32_t* fanouts, int32_t L,
+                                 float* d_p_total, float* d_p_hop, uint32_t flags) {
+    using namespace spp;
+    SPP_CHECK(ctx && g && d_T && fanouts && d_p_total, SPP_E_ARG, "spp_vip_propagate: null argument");
+    SPP_CHECK(g->has_in, SPP_E_ARG, "spp_vip_propagate: the graph was created without SPP_GRAPH_IN_LISTS");
+    SPP_CHECK(L >= 1 && L <= SPP_MAX_L, SPP_E_ARG, "spp_vip_propagate: L = %d not in [1, %d]", L, SPP_MAX_L);
+    SPP_CHECK(nT > 0 && B > 0, SPP_E_ARG, "spp_vip_propagate: nT = %lld, B = %d must be positive", (long long)nT, B);
+    for (int h = 0; h < L; ++h)
+        SPP_CHECK(fanouts[h] >= 1, SPP_E_ARG, "spp_vip_propagate: fanout %d of hop %d", fanouts[h], h + 1);
+    SPP_HIP(hipSetDevice(ctx->device));
+    hipStream_t st = ctx->stream;
+    const int64_t N = g->N;
+    SPP_TRY(ctx->y0.reserve((size_t)N * sizeof(float)));
+    SPP_TRY(ctx->y1.reserve((size_t)N * sizeof(float)));
+    SPP_TRY(ctx->tot.reserve((size_t)N * sizeof(double) + sizeof(int)));
+    SPP_TRY(ctx->hubacc.reserve((size_t)(g->nhub > 0 ? g->nhub : 1) * sizeof(double)));
+    float* ycur = ctx->y0.as<float>();
+    float* ynext = ctx->y1.as<float>();
+    double* tot = ctx->tot.as<double>();
+    int* d_bad = reinterpret_cast<int*>(tot + N);
+    const int include0 = (flags & SPP_VIP_INCLUDE_HOP0) ? 1 : 0;
+    const int fill_grid = ctx->num_cu * 8;
+    double p0 = (double)B / (double)nT;
+    if (p0 > 1.0) p0 = 1.0;
+
+    {
+        ScopedTimer tt(ctx, SPP_T_VIP_TOTAL, st);
+        fill_f32_kernel<<<fill_grid, kBlock, 0, st>>>(ycur, N, 0.f);
+        if (include0) fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(tot, N, 0.0);
+        fill_f32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<float*>(d_bad), 1, 0.f);
+        vip_init_kernel<<<(unsigned)((nT + kBlock - 1) / kBlock), kBlock, 0, st>>>(
+            d_T, nT, N, p0, (double)fanouts[0], g->rowptr, ycur, tot, include0, d_bad);
+        for (int h = 1; h <= L; ++h) {
+            ScopedTimer th(ctx, SPP_T_VIP_HOP_FIRST + h - 1, st);
+            VipHop a;
+            a.rowptr = g->rowptr; a.in_rowptr = g->in_rowptr; a.in_col = g->in_col;
+            a.y = ycur; a.y_next = ynext; a.tot = tot;
+            a.p_hop = d_p_hop ? d_p_hop + (int64_t)(h - 1) * N : nullptr;
+            a.p_total = d_p_total;
+            a.f_next = h < L ? (double)fanouts[h] : 0.0;
+            a.first = (h == 1 && !include0) ? 1 : 0;
+            a.last = (h == L) ? 1 : 0;
+            if (g->nhub > 0) {
+                fill_f64_kernel<<<(unsigned)((g->nhub + kBlock - 1) / kBlock), kBlock, 0, st>>>(ctx->hubacc.as<double>(), g->nhub, 0.0);
+                vip_hub_slice_kernel<<<(unsigned)g->nslices, kBlock, 0, st>>>(a, g->hub_rows, g->hub_slice_ptr, g->nhub, ctx->hubacc.as<double>());
+            }
+            vip_pull_kernel<<<(unsigned)g->nblk, kBlock, 0, st>>>(a, g->blk_row);
+            if (g->nhub > 0)
+                vip_hub_finish_kernel<<<(unsigned)((g->nhub + kBlock - 1) / kBlock), kBlock, 0, st>>>(a, g->hub_rows, g->nhub, ctx->hubacc.as<double>());
+            float* t = ycur; ycur = ynext; ynext = t;
+        }
+    }
+    SPP_HIP(hipGetLastError());
+    // training ids are checked on the device; the flag is read when the caller asks to wait
+    if (flags & SPP_SYNC) {
+        int bad = 0;
+        SPP_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(int), hipMemcpyDeviceToHost, st));
+        SPP_HIP(hipStreamSynchronize(st));
+        SPP_CHECK(bad == 0, SPP_E_ARG, "spp_vip_propagate: a training vertex id lies outside [0, N)");
+    }
+    return SPP_OK;
+}

@@ -1,0 +1,62 @@
+"""The C interface without a GPU: the library loads, exports every declared symbol, and its
+host-side argument checks answer with error codes (no compute is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2305_03152_amd as spp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "spp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spp_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(spp.LIB_PATH):
+        from paper_2305_03152_amd import build
+        build.build()
+    return spp.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert len(names) >= 15
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(spp.EXPORTS) == names
+
+
+def test_mfg_bound_host_logic(lib):
+    nb, eb = spp.mfg_bound(1024, (15, 10, 5), 2_400_000)
+    assert nb == [1024, 16384, 180224, 1081344] and eb == [0, 15360, 163840, 901120]
+    nb, eb = spp.mfg_bound(256, (15, 10, 5), 10_000)
+    assert nb == [256, 4096, 10000, 10000] and eb == [0, 3840, 40960, 50000]
+    with pytest.raises(spp.SppError):
+        spp.mfg_bound(4, (65,), 100)          # fanout above SPP_MAX_FANOUT
+    with pytest.raises(spp.SppError):
+        spp.mfg_bound(4, (1,) * 9, 100)       # more hops than SPP_MAX_L
+
+
+def test_null_arguments_are_errors_not_crashes(lib):
+    assert lib.spp_ctx_sync(None) == -1
+    assert b"null" in lib.spp_last_error()
+    assert lib.spp_gather_last_stats(None, None) == -1
+    assert lib.spp_cache_set_limit(None, 0) == -1
+    lib.spp_ctx_destroy(None)
+    lib.spp_graph_destroy(None)
+    lib.spp_cache_destroy(None)
+
+
+def test_product_path_fails_loudly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    with pytest.raises(spp.SppError):
+        spp.Context(0)

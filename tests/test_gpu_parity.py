@@ -1,0 +1,312 @@
+"""GPU parity: the HIP path, called through the C interface, against the CPU oracle on the same
+seeded inputs.  Integer outputs (MFGs, relabel maps, cache membership, gathered rows, counts) must
+match bit for bit; fp32 vertex-inclusion probabilities within 1e-5 relative (floor 1e-37)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import synth as S
+
+pytestmark = pytest.mark.gpu
+
+VIP_RTOL, VIP_FLOOR = 1e-5, 1e-37
+
+
+def _say(*a):
+    print("[case]", *a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def spp():
+    import paper_2305_03152_amd as m
+    m.load_library()
+    return m
+
+
+@pytest.fixture(scope="module")
+def ctx(spp):
+    c = spp.Context(0)
+    yield c
+    c.close()
+
+
+class Case:
+    """A workload on the GPU plus the same arrays on the host for the oracle."""
+
+    def __init__(self, spp, ctx, cfg, gen_device="cpu", in_lists=True):
+        self.cfg = cfg
+        dev = torch.device("cuda:0")
+        g = S.make_graph(cfg, gen_device)
+        self.N, self.M = g.N, g.M
+        self.rowptr_d, self.col_d = g.rowptr.to(dev), g.col.to(dev)
+        self.rp, self.col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
+        T = S.make_training_set(cfg, gen_device)
+        self.Tk_d = S.local_training_set(cfg, T).to(dev)
+        self.Tk = self.Tk_d.cpu().numpy()
+        self.T_all = T.cpu().numpy()
+        self.lo, self.hi = cfg.bounds()
+        self.G = spp.Graph(ctx, self.rowptr_d, self.col_d, in_lists=in_lists)
+
+    def features(self):
+        cfg = self.cfg
+        dev = torch.device("cuda:0")
+        self.local_d = S.feature_block(cfg, self.lo, self.hi, dev)
+        nrem = cfg.N - (self.hi - self.lo)
+        self.remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
+        for a in range(0, nrem, 1 << 20):
+            b = min(nrem, a + (1 << 20))
+            self.remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
+        torch.cuda.synchronize()
+
+
+def _bits(a):
+    a = np.ascontiguousarray(a)
+    return a.view({2: np.uint16, 4: np.uint32}[a.dtype.itemsize])
+
+
+def _np(t):
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy()
+    return t.cpu().numpy()
+
+
+def _check_vip(p_gpu, p_ref):
+    p = p_gpu.cpu().numpy().astype(np.float64)
+    err = np.abs(p - p_ref)
+    tol = VIP_RTOL * p_ref + VIP_FLOOR
+    bad = np.flatnonzero(err > tol)
+    assert bad.size == 0, (bad[:5], p[bad[:5]], p_ref[bad[:5]])
+    assert np.all(p[p_ref == 0] == 0) and np.all(p_ref[p == 0] < 1e-37)
+
+
+def _check_mfg(m, ref, L):
+    assert m.n == ref.n and m.e == ref.e, (m.n, ref.n, m.e, ref.e)
+    assert np.array_equal(m.node_ids[:m.n[L]].cpu().numpy(), ref.node_ids)
+    for h in range(L):
+        assert np.array_equal(m.indptr[h][:m.n[h] + 1].cpu().numpy(), ref.indptr[h]), f"indptr hop {h + 1}"
+        assert np.array_equal(m.src[h][:m.e[h + 1]].cpu().numpy(), ref.src[h]), f"src hop {h + 1}"
+
+
+# ----------------------------------------------------------------------------------------------
+# tiny graphs with known answers first: a fault here names the kernel at once
+# ----------------------------------------------------------------------------------------------
+
+def _mini_graph(spp, ctx, adj, N):
+    rp = np.zeros(N + 1, dtype=np.int64)
+    col = []
+    for v in range(N):
+        col.extend(sorted(adj.get(v, [])))
+        rp[v + 1] = len(col)
+    col = np.asarray(col, dtype=np.int32)
+    dev = torch.device("cuda:0")
+    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev) if col.size else torch.zeros(0, dtype=torch.int32, device=dev),
+                  in_lists=True)
+    return G, rp, col
+
+
+def test_vip_hand_worked(spp, ctx):
+    _say("vip hand-worked graphs")
+    dev = torch.device("cuda:0")
+    G, rp, col = _mini_graph(spp, ctx, {0: [2, 3], 1: [3, 4, 5], 3: [5, 6]}, 7)
+    T = torch.tensor([0, 1], dtype=torch.int32, device=dev)
+    p, ph = spp.vip_propagate(ctx, G, T, 1, (1, 1), per_hop=True)
+    want = [0, 0, 0.25, 0.375, 1 / 6, 31 / 96, 3 / 16]
+    np.testing.assert_allclose(p.cpu().numpy(), want, rtol=1e-6)
+    ref_t, ref_h = oracle.vip(rp, col, [0, 1], 1, (1, 1))
+    np.testing.assert_allclose(ph.cpu().numpy(), ref_h, rtol=1e-6)
+    # x = 1 exactly gives p = 1 exactly; clamp of p^[0]; hop 0 included on request
+    G2, rp2, col2 = _mini_graph(spp, ctx, {0: [1, 2]}, 3)
+    T2 = torch.tensor([0], dtype=torch.int32, device=dev)
+    assert spp.vip_propagate(ctx, G2, T2, 5, (2,)).cpu().tolist() == [0.0, 1.0, 1.0]
+    p0 = spp.vip_propagate(ctx, G, T, 1, (1, 1), include_hop0=True)
+    ref0, _ = oracle.vip(rp, col, [0, 1], 1, (1, 1), include_hop0=True)
+    np.testing.assert_allclose(p0.cpu().numpy(), ref0, rtol=1e-6)
+    # a graph without edges
+    G3, _, _ = _mini_graph(spp, ctx, {}, 5)
+    assert spp.vip_propagate(ctx, G3, T2, 1, (3, 3)).cpu().tolist() == [0.0] * 5
+
+
+def test_sampler_mini(spp, ctx):
+    _say("sampler on a 3-vertex graph, zero-degree vertex, empty batch")
+    dev = torch.device("cuda:0")
+    G, rp, col = _mini_graph(spp, ctx, {0: [1, 2], 2: [0]}, 3)
+    for seeds, fan in (([1], (2, 2)), ([0, 1], (2,)), ([], (2,)), ([2, 0], (1, 1, 1))):
+        s = torch.tensor(seeds, dtype=torch.int32, device=dev)
+        m = spp.sample_mfg(ctx, G, s, fan, 1, 0)
+        ref = oracle.sample_mfg(rp, col, seeds, fan, 1, 0)
+        _check_mfg(m, ref, len(fan))
+
+
+# ----------------------------------------------------------------------------------------------
+# Tiny config, all four calls
+# ----------------------------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def tiny_case(spp, ctx):
+    _say("building Tiny")
+    c = Case(spp, ctx, S.TINY)
+    c.features()
+    return c
+
+
+def test_vip_tiny(spp, ctx, tiny_case):
+    c = tiny_case
+    cfg = c.cfg
+    for name, T_d, T_h, B, fan in (("clamped p0", c.Tk_d, c.Tk, cfg.B, cfg.fanouts),
+                                   ("global T", torch.from_numpy(c.T_all).cuda(), c.T_all, cfg.B, cfg.fanouts),
+                                   ("tiny p0", torch.from_numpy(c.T_all).cuda(), c.T_all, 1, (2, 2, 2)),
+                                   ("one hop", c.Tk_d, c.Tk, 16, (3,))):
+        _say("vip tiny", name)
+        p, ph = spp.vip_propagate(ctx, c.G, T_d, B, fan, per_hop=True)
+        ref_t, ref_h = oracle.vip(c.rp, c.col, T_h, B, fan)
+        _check_vip(p, ref_t)
+        for h in range(len(fan)):
+            _check_vip(ph[h], ref_h[h])
+
+
+def test_cache_tiny(spp, ctx, tiny_case):
+    c = tiny_case
+    cfg = c.cfg
+    p = spp.vip_propagate(ctx, c.G, c.Tk_d, cfg.B, cfg.fanouts)
+    score = p.cpu().numpy()
+    for alpha in (0.0, 0.05, cfg.alpha, 0.5, 3.0):
+        _say("cache tiny alpha", alpha)
+        cache = spp.build_vip_cache(ctx, p, c.lo, c.hi, cfg.K, alpha, c.remote, cfg.D, cfg.elem_bytes)
+        ref = oracle.cache_select(score, c.lo, c.hi, cfg.K, alpha)
+        assert np.array_equal(cache.ids.cpu().numpy(), ref)
+        probe = torch.arange(cfg.N, dtype=torch.int32, device="cuda")
+        slots = cache.lookup(probe).cpu().numpy()
+        want = np.full(cfg.N, -1, dtype=np.int32)
+        want[ref] = np.arange(ref.size)
+        assert np.array_equal(slots, want)
+        cache.close()
+    # heavy ties and a degree-like score
+    _say("cache tiny ties")
+    deg = torch.from_numpy(np.bincount(c.col, minlength=cfg.N).astype(np.float32)).cuda()
+    cache = spp.build_vip_cache(ctx, deg, c.lo, c.hi, cfg.K, 0.2, None, cfg.D, cfg.elem_bytes)
+    assert np.array_equal(cache.ids.cpu().numpy(), oracle.cache_select(deg.cpu().numpy(), c.lo, c.hi, cfg.K, 0.2))
+    cache.close()
+
+
+def test_sample_and_gather_tiny(spp, ctx, tiny_case):
+    c = tiny_case
+    cfg = c.cfg
+    p = spp.vip_propagate(ctx, c.G, c.Tk_d, cfg.B, cfg.fanouts)
+    cache = spp.build_vip_cache(ctx, p, c.lo, c.hi, cfg.K, cfg.alpha, c.remote, cfg.D, cfg.elem_bytes)
+    ids_ref = oracle.cache_select(p.cpu().numpy(), c.lo, c.hi, cfg.K, cfg.alpha)
+    local = c.local_d.cpu().numpy()
+    remote = c.remote.numpy()
+    cache_rows = S.feature_rows(cfg, torch.from_numpy(ids_ref)).numpy()
+    bufs = spp.MFGBuffers("cuda", cfg.B, cfg.fanouts, cfg.N)
+    for epoch in range(2):
+        for bi, seeds in enumerate(S.epoch_batches(cfg, torch.from_numpy(c.Tk), epoch)):
+            _say("tiny batch", epoch, bi, "seeds", seeds.numel())
+            m = spp.sample_mfg(ctx, c.G, seeds.cuda(), cfg.fanouts, cfg.seed_sampler, epoch * 100 + bi, out=bufs)
+            ref = oracle.sample_mfg(c.rp, c.col, seeds.numpy(), cfg.fanouts, cfg.seed_sampler, epoch * 100 + bi)
+            _check_mfg(m, ref, cfg.L)
+            out, stats = spp.gather_features(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, m.node_ids, n=m.n[-1])
+            want, _, counts = oracle.gather(cfg.N, c.lo, c.hi, local, cache_rows, ids_ref, remote, ref.node_ids)
+            assert np.array_equal(_bits(out.cpu().numpy()), _bits(want))
+            assert (stats["n_local"], stats["n_cache_hit"], stats["n_miss"]) == counts
+            assert stats["miss_bytes"] == counts[2] * cfg.D * cfg.elem_bytes
+    # the same gather without a host round trip for the count, and with no cache at all
+    m = spp.sample_mfg(ctx, c.G, torch.from_numpy(c.Tk[:100]).cuda(), (4, 3), 7, 3)
+    out = torch.zeros((m.nb[-1], cfg.D), dtype=torch.float32, device="cuda")
+    spp.gather_features(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, m.node_ids, n=m.nb[-1],
+                        n_device=m.n_final_device, out=out, sync=False)
+    ctx.sync()
+    st = spp.gather_last_stats(ctx)
+    ids = m.node_ids[:m.n[-1]].cpu()
+    assert torch.equal(out[:m.n[-1]].cpu(), S.feature_rows(cfg, ids))
+    assert torch.all(out[m.n[-1]:] == 0)
+    assert st["n_cache_hit"] == 0 and st["n_local"] + st["n_miss"] == m.n[-1]
+    cache.close()
+
+
+def test_gather_edge_cases(spp, ctx, tiny_case):
+    c = tiny_case
+    cfg = c.cfg
+    _say("gather: empty, duplicates, alpha sweep by limit")
+    out, st = spp.gather_features(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote,
+                                  torch.zeros(0, dtype=torch.int32, device="cuda"))
+    assert out.shape[0] == 0 and st["n_local"] == st["n_miss"] == 0
+    ids = torch.tensor([5, c.hi + 5, 5, cfg.N - 1, 0, c.hi], dtype=torch.int32, device="cuda")
+    out, st = spp.gather_features(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, ids)
+    assert torch.equal(out.cpu(), S.feature_rows(cfg, ids.cpu()))
+    assert (st["n_local"], st["n_cache_hit"], st["n_miss"]) == (3, 0, 3)
+    p = spp.vip_propagate(ctx, c.G, c.Tk_d, cfg.B, cfg.fanouts)
+    cache = spp.build_vip_cache(ctx, p, c.lo, c.hi, cfg.K, 0.5, c.remote, cfg.D, cfg.elem_bytes)
+    allids = torch.arange(cfg.N, dtype=torch.int32, device="cuda")
+    prev = -1
+    for a in (0.0, 0.05, 0.1, 0.2, 0.5):
+        cache.set_limit(min(cfg.cache_capacity(a), cache.n_cached))
+        out, st = spp.gather_features(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, allids)
+        ref_ids = oracle.cache_select(p.cpu().numpy(), c.lo, c.hi, cfg.K, a)
+        assert st["n_cache_hit"] == ref_ids.size and st["n_cache_hit"] >= prev
+        prev = st["n_cache_hit"]
+        assert torch.equal(out.cpu(), S.feature_rows(cfg, allids.cpu()))
+    cache.close()
+    # bad ids are reported, not dereferenced
+    with pytest.raises(spp.SppError):
+        spp.gather_features(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote,
+                            torch.tensor([1, cfg.N, -3], dtype=torch.int32, device="cuda"))
+    # odd row width: 6-byte rows go through the 2-byte path
+    loc = torch.arange(30, dtype=torch.int16, device="cuda").reshape(10, 3)
+    rem = (1000 + torch.arange(90, dtype=torch.int16)).reshape(30, 3).pin_memory()
+    ids = torch.tensor([0, 9, 10, 39, 3], dtype=torch.int32, device="cuda")
+    out, st = spp.gather_features(ctx, None, loc, 40, 0, 10, rem, ids)
+    full = torch.cat([loc.cpu(), rem])
+    assert torch.equal(out.cpu(), full[ids.cpu().long()])
+
+
+# ----------------------------------------------------------------------------------------------
+# scaled copies of the other configs: several tiles, ragged tails, hubs, 16-bit rows
+# ----------------------------------------------------------------------------------------------
+
+SCALED = [
+    ("mid", S.scaled(S.MID, 150_000)),
+    ("large", S.scaled(S.LARGE, 200_000)),
+    ("wide", S.scaled(S.WIDE, 200_000, pop_cap=20_000)),
+    ("skew", S.scaled(S.SKEW, 1 << 17)),
+]
+
+
+@pytest.mark.parametrize("name,cfg", SCALED, ids=[n for n, _ in SCALED])
+def test_scaled_config_end_to_end(spp, ctx, name, cfg):
+    _say("scaled", name, "N", cfg.N)
+    c = Case(spp, ctx, cfg, gen_device="cuda")
+    _say("graph M", c.M, "max in-degree", int(np.bincount(c.col, minlength=cfg.N).max()), "|T_k|", c.Tk.size)
+    c.features()
+    p, ph = spp.vip_propagate(ctx, c.G, c.Tk_d, cfg.B, cfg.fanouts, per_hop=True)
+    ref_t, ref_h = oracle.vip(c.rp, c.col, c.Tk, cfg.B, cfg.fanouts)
+    _check_vip(p, ref_t)
+    for h in range(cfg.L):
+        _check_vip(ph[h], ref_h[h])
+    _say("vip ok")
+    cache = spp.build_vip_cache(ctx, p, c.lo, c.hi, cfg.K, cfg.alpha, c.remote, cfg.D, cfg.elem_bytes)
+    ids_ref = oracle.cache_select(p.cpu().numpy(), c.lo, c.hi, cfg.K, cfg.alpha)
+    assert np.array_equal(cache.ids.cpu().numpy(), ids_ref)
+    _say("cache ok", ids_ref.size)
+    # end to end: oracle p -> oracle cache differs from the GPU's only at scores within tolerance of the cut
+    ids_o = oracle.cache_select(ref_t.astype(np.float32), c.lo, c.hi, cfg.K, cfg.alpha)
+    diff = np.setxor1d(ids_o, ids_ref)
+    if diff.size:
+        cut = ref_t[ids_o[-1]]
+        assert np.all(np.abs(ref_t[diff] - cut) <= 1e-5 * cut)
+    local = _np(c.local_d)
+    remote = _np(c.remote)
+    cache_rows = _np(S.feature_rows(cfg, torch.from_numpy(ids_ref)))
+    bufs = spp.MFGBuffers("cuda", cfg.B, cfg.fanouts, cfg.N)
+    batches = S.epoch_batches(cfg, torch.from_numpy(c.Tk), 0)
+    for bi, seeds in enumerate(batches[:2] + batches[-1:]):
+        _say("batch", bi, "seeds", seeds.numel())
+        m = spp.sample_mfg(ctx, c.G, seeds.cuda(), cfg.fanouts, cfg.seed_sampler, bi, out=bufs)
+        ref = oracle.sample_mfg(c.rp, c.col, seeds.numpy(), cfg.fanouts, cfg.seed_sampler, bi)
+        _check_mfg(m, ref, cfg.L)
+        out, stats = spp.gather_features(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, m.node_ids, n=m.n[-1])
+        want, _, counts = oracle.gather(cfg.N, c.lo, c.hi, local, cache_rows, ids_ref, remote, ref.node_ids)
+        assert np.array_equal(_bits(_np(out)), _bits(want))
+        assert (stats["n_local"], stats["n_cache_hit"], stats["n_miss"]) == counts
+    cache.close()
+    c.G.close()

@@ -119,8 +119,9 @@ def scaled(cfg: WorkloadConfig, N: int, **kw) -> WorkloadConfig:
         rs = int(math.log2(N))
         N = 1 << rs
     pop = min(cfg.pop_cap, max(16, N // (64 * cfg.K)))
-    return dataclasses.replace(cfg, name=f"{cfg.name}@{N}", N=N, degree_cap=cap, rmat_scale=rs,
-                               pop_cap=pop, **kw)
+    args = dict(name=f"{cfg.name}@{N}", N=N, degree_cap=cap, rmat_scale=rs, pop_cap=pop)
+    args.update(kw)
+    return dataclasses.replace(cfg, **args)
 
 
 # ----------------------------------------------------------------------------------------------
