@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-partition data path on one MI355X.
+
+A step is one minibatch through the per-batch rows of the path: multi-hop fanout sampling into
+MFGs, then the cache-aware feature gather of |S_L| rows (local shard / VIP cache in HBM, misses
+from pinned host memory on a side stream).  The one-time rows (VIP propagation, cache ranking and
+fill) run before the timed region and are reported in the same line with their own figures.
+Inputs are resident (graph, shard and cache in HBM, remote rows pinned) before timing starts.
+
+Prints ONE JSON line; see the design doc for the byte accounting behind `roofline`.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
+PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="mid", help="workload: tiny | mid (default, the metric's configuration)")
+    ap.add_argument("--vip-reps", type=int, default=5)
+    ap.add_argument("--pipeline", type=int, default=2,
+                    help="minibatches in flight: contexts (each with its own stream and buffers) used round-robin")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one partition's share of the method); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2305_03152_amd as spp
+    from workloads import synth as S
+
+    cfg = S.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    K, W = args.steps, args.warmup
+    lo, hi = cfg.bounds()
+    row_bytes = cfg.D * cfg.elem_bytes
+
+    # ---- inputs, resident before anything is timed ------------------------------------------
+    t = time.time()
+    g = S.make_graph(cfg, dev)
+    T_all = S.make_training_set(cfg, dev)
+    Tk = S.local_training_set(cfg, T_all)
+    log(f"graph N={g.N} M={g.M} |T_k|={Tk.numel()} ({time.time() - t:.1f}s)")
+    ctx = spp.Context(0)
+    t = time.time()
+    G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True)
+    t_inlists = time.time() - t
+    local = S.feature_block(cfg, lo, hi, dev)
+    nrem = cfg.N - (hi - lo)
+    remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
+    for a in range(0, nrem, 1 << 19):
+        b = min(nrem, a + (1 << 19))
+        remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
+    torch.cuda.synchronize()
+    log(f"features local {tuple(local.shape)} remote {tuple(remote.shape)} pinned; in-lists built in {t_inlists:.2f}s")
+
+    # ---- one-time rows: VIP propagation, cache ranking + fill -------------------------------
+    p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts)            # warm-up, allocates workspaces
+    ctx.timing(True)
+    for _ in range(args.vip_reps):
+        p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts, sync=False)
+    ms, cnt = ctx.times()
+    ctx.timing(False)
+    vip_total_ms = ms[0] / max(cnt[0], 1)
+    vip_hop_ms = [ms[1 + h] / max(cnt[1 + h], 1) for h in range(cfg.L)]
+    # algorithmic bytes of one hop: one int32 source id per edge, the in-list offsets, y read once,
+    # and the per-vertex result written once
+    vip_hop_bytes = 4 * g.M + 8 * (g.N + 1) + 4 * g.N + 4 * g.N
+    worst = max(vip_hop_ms)
+    vip_roof = {"bound": "hbm", "achieved": vip_hop_bytes / (worst * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "kernel": "vip_pull_kernel (slowest hop)", "traffic": None}
+    vip_roof["frac"] = vip_roof["achieved"] / HBM_PEAK_GBS
+    t = time.time()
+    cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)
+    torch.cuda.synchronize()
+    cache_s = time.time() - t
+    log(f"vip {vip_total_ms:.3f} ms (hops {['%.3f' % x for x in vip_hop_ms]}), cache {cache.n_cached} rows in {cache_s:.3f}s")
+
+    # ---- minibatches -------------------------------------------------------------------------
+    batches = []
+    ep = 0
+    while len(batches) < W + K:
+        batches.extend(b for b in S.epoch_batches(cfg, Tk, ep) if b.numel() == min(cfg.B, Tk.numel()))
+        ep += 1
+    batches = batches[:W + K]
+    # Each minibatch in flight has its own context (stream, workspaces), MFG buffers and output
+    # rows, so the sampling of one batch overlaps the PCIe misses of the one before it.
+    P = max(1, args.pipeline)
+    lanes = []
+    for k in range(P):
+        c = ctx if k == 0 else spp.Context(0, stream=torch.cuda.Stream(dev))
+        b = spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N)
+        o = torch.empty((b.nb[-1], cfg.D), dtype=cfg.torch_dtype, device=dev)
+        lanes.append((c, b, o))
+    bufs, out = lanes[0][1], lanes[0][2]
+
+    def step(i):
+        c, b, o = lanes[i % P]
+        spp.sample_mfg(c, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=b, sync=False)
+        spp.gather_features(c, cache, local, cfg.N, lo, hi, remote, b.node_ids, n=b.nb[-1],
+                            n_device=b.n_final_device, out=o, sync=False)
+
+    torch.cuda.synchronize()
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    for c, _, _ in lanes:
+        c.timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        step(i)
+    for c, _, _ in lanes:
+        c.sync()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms, cnt = [0.0] * 16, [0] * 16
+    for c, _, _ in lanes:
+        m_, c_ = c.times()
+        ms = [a + b for a, b in zip(ms, m_)]
+        cnt = [a + b for a, b in zip(cnt, c_)]
+        c.timing(False)
+    elapsed = t1 - t0
+    ms_per_step = elapsed / K * 1e3
+
+    # per-batch counts of the same K batches (untimed; same keys, so the same batches)
+    tot = dict(n_nodes=0, n_edges=0, n_local=0, n_cache_hit=0, n_miss=0)
+    for i in range(W, W + K):
+        m = spp.sample_mfg(ctx, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=bufs)
+        _, st = spp.gather_features(ctx, cache, local, cfg.N, lo, hi, remote, bufs.node_ids, n=m.n[-1], out=out)
+        tot["n_nodes"] += m.n[-1]
+        tot["n_edges"] += sum(m.e)
+        for k in ("n_local", "n_cache_hit", "n_miss"):
+            tot[k] += st[k]
+    avg = {k: v / K for k, v in tot.items()}
+
+    T_HIT, T_MISS, T_CLS, T_SAMPLE = 10, 11, 12, 9
+    hit_ms = ms[T_HIT] / max(cnt[T_HIT], 1)
+    miss_ms = ms[T_MISS] / max(cnt[T_MISS], 1)
+    cls_ms = ms[T_CLS] / max(cnt[T_CLS], 1)
+    sample_ms = ms[T_SAMPLE] / max(cnt[T_SAMPLE], 1)
+    hit_rows = avg["n_local"] + avg["n_cache_hit"]
+    hit_bytes = hit_rows * 2 * row_bytes                 # read the source row + write the output row
+    roof = {"bound": "hbm", "achieved": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms > 0 else 0.0,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>", "traffic": None,
+            "bytes_per_launch": hit_bytes, "avg_launch_ms": hit_ms}
+    roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
+    miss_bytes = avg["n_miss"] * row_bytes
+    pcie = {"bound": "pcie", "achieved": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms > 0 else 0.0,
+            "peak": PCIE_PEAK_GBS, "unit": "GB/s", "kernel": "rows_indexed_kernel<16> (miss path)",
+            "bytes_per_launch": miss_bytes, "avg_launch_ms": miss_ms}
+    pcie["frac"] = pcie["achieved"] / PCIE_PEAK_GBS
+
+    # ---- CPU baseline: the oracle as it stands, single thread, bounded sample ---------------
+    cpu = None
+    if args.cpu_seconds > 0:
+        import oracle
+        rp, col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
+        local_h = local.cpu()
+        local_np = local_h.view(torch.int16).numpy() if cfg.dtype == "bf16" else local_h.numpy()
+        remote_np = remote.view(torch.int16).numpy() if cfg.dtype == "bf16" else remote.numpy()
+        ids_np = cache.ids.cpu().numpy()
+        crow = S.feature_rows(cfg, cache.ids.long())
+        crow_np = (crow.view(torch.int16) if cfg.dtype == "bf16" else crow).cpu().numpy()
+        nb, spent, checked = 0, 0.0, 0
+        while nb < K and spent < args.cpu_seconds:
+            i = W + nb
+            seeds = batches[i].cpu().numpy()
+            c0 = time.perf_counter()
+            ref = oracle.sample_mfg(rp, col, seeds, cfg.fanouts, cfg.seed_sampler, i)
+            want, _, counts = oracle.gather(cfg.N, lo, hi, local_np, crow_np, ids_np, remote_np, ref.node_ids)
+            spent += time.perf_counter() - c0
+            if nb < 2:      # the timed batches are also parity-checked against the HIP path
+                m = spp.sample_mfg(ctx, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=bufs)
+                o, st = spp.gather_features(ctx, cache, local, cfg.N, lo, hi, remote, bufs.node_ids, n=m.n[-1], out=out)
+                got = o[:m.n[-1]]
+                got = (got.view(torch.int16) if cfg.dtype == "bf16" else got).cpu().numpy()
+                ok = (m.n == ref.n and np.array_equal(bufs.node_ids[:m.n[-1]].cpu().numpy(), ref.node_ids)
+                      and all(np.array_equal(bufs.src[h][:m.e[h + 1]].cpu().numpy(), ref.src[h]) for h in range(cfg.L))
+                      and np.array_equal(got.view(np.uint8), want.view(np.uint8))
+                      and (st["n_local"], st["n_cache_hit"], st["n_miss"]) == counts)
+                if not ok:
+                    log("PARITY FAILURE against the oracle on batch", i)
+                    sys.exit(1)
+                checked += 1
+            nb += 1
+        cpu = {"value": nb / spent, "unit": "minibatches/s", "cores": 1, "kind": "oracle",
+               "sample": f"{nb} of the timed minibatches (sample_mfg + gather), {spent:.1f}s; {checked} checked against the HIP path"}
+
+    line = {
+        "metric": "sampled+gathered minibatches/s per partition on 1 GPU",
+        "value": K / elapsed, "unit": "minibatches/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"fp32": "f32", "fp16": "f16", "bf16": "bf16"}[cfg.dtype] + " rows (byte copy), int32 ids",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: N={g.N} M={g.M} D={cfg.D} {cfg.dtype} fanouts={list(cfg.fanouts)} "
+                               f"B={cfg.B} K={cfg.K} alpha={cfg.alpha} owned partition {cfg.owned_partition}",
+                   "minibatches_in_flight": P,
+                   "avg_per_batch": {k: round(v, 1) for k, v in avg.items()},
+                   "hit_rate_of_remote": avg["n_cache_hit"] / max(avg["n_cache_hit"] + avg["n_miss"], 1e-9)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "pcie": pcie,
+        "kernels_ms": {"sample_mfg": sample_ms, "gather_classify": cls_ms, "gather_hit": hit_ms, "gather_miss": miss_ms},
+        "vip": {"ms_total": vip_total_ms, "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
+                "in_lists_build_s": t_inlists, "cache_build_s": cache_s, "n_cached": cache.n_cached},
+    }
+    print(json.dumps(line), flush=True)
+    cache.close()
+    G.close()
+    for c, _, _ in lanes:
+        c.close()
+
+
+if __name__ == "__main__":
+    main()

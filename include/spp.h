@@ -161,13 +161,15 @@ int  spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_loc
                          spp_gather_stats* stats, uint32_t flags);
 int  spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats);
 
-/* Durations, in milliseconds, of the device work of the most recent call of each kind on this
- * context, measured with events on the streams the kernels ran on.  Valid after the work
- * finished (SPP_SYNC or spp_ctx_sync).  Index with the SPP_T_* constants. */
+/* Device-time accounting.  After spp_ctx_timing(ctx, 1) every call brackets its pieces of device
+ * work with events on the stream they run on (vip total and per hop, the whole sampling of a
+ * batch, gather classify / hit copy / miss copy).  spp_ctx_times waits for the context's streams,
+ * returns for each SPP_T_* index the summed duration in milliseconds and the number of pieces
+ * since the last call, and starts a new accumulation.  spp_ctx_timing(ctx, 0) stops recording. */
 enum { SPP_T_VIP_TOTAL = 0, SPP_T_VIP_HOP_FIRST = 1 /* .. +L-1 */, SPP_T_SAMPLE = 9,
        SPP_T_GATHER_HIT = 10, SPP_T_GATHER_MISS = 11, SPP_T_GATHER_CLASSIFY = 12, SPP_T_COUNT = 16 };
-int  spp_ctx_timing(spp_ctx* ctx, int enable);             /* record events from now on (0/1) */
-int  spp_ctx_last_times(spp_ctx* ctx, float* ms_out /* [SPP_T_COUNT] */);
+int  spp_ctx_timing(spp_ctx* ctx, int enable);
+int  spp_ctx_times(spp_ctx* ctx, float* sum_ms /* [SPP_T_COUNT] */, int64_t* count /* [SPP_T_COUNT] */);
 
 #ifdef __cplusplus
 }

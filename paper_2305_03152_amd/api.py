@@ -27,7 +27,7 @@ EXPORTS = [
     "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
     "spp_graph_destroy", "spp_vip_propagate", "spp_build_vip_cache", "spp_cache_destroy",
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg",
-    "spp_gather_features", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_last_times",
+    "spp_gather_features", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_times",
 ]
 
 
@@ -94,7 +94,7 @@ def load_library():
                                         C.c_void_p, C.POINTER(_GatherStats), C.c_uint32]
     lib.spp_gather_last_stats.argtypes = [C.c_void_p, C.POINTER(_GatherStats)]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
-    lib.spp_ctx_last_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+    lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -138,10 +138,12 @@ class Context:
     def timing(self, enable: bool = True):
         _check(load_library().spp_ctx_timing(self._h, int(enable)))
 
-    def last_times(self) -> List[float]:
-        buf = (C.c_float * SPP_T_COUNT)()
-        _check(load_library().spp_ctx_last_times(self._h, buf))
-        return list(buf)
+    def times(self):
+        """(sum_ms, count) per SPP_T_* index since timing was enabled or last read; waits for the streams."""
+        ms = (C.c_float * SPP_T_COUNT)()
+        cnt = (C.c_int64 * SPP_T_COUNT)()
+        _check(load_library().spp_ctx_times(self._h, ms, cnt))
+        return list(ms), list(cnt)
 
     def close(self):
         if self._h:

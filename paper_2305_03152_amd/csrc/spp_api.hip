@@ -37,10 +37,6 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 64 * sizeof(int64_t), hipHostMallocDefault);
-    for (int i = 0; i < spp::kNumTimers && e == hipSuccess; ++i) {
-        e = hipEventCreate(&c->t0[i]);
-        if (e == hipSuccess) e = hipEventCreate(&c->t1[i]);
-    }
     if (e != hipSuccess) {
         spp::set_error("spp_ctx_create: %s", hipGetErrorString(e));
         spp_ctx_destroy(c);
@@ -58,10 +54,8 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
-    for (int i = 0; i < spp::kNumTimers; ++i) {
-        if (c->t0[i]) (void)hipEventDestroy(c->t0[i]);
-        if (c->t1[i]) (void)hipEventDestroy(c->t1[i]);
-    }
+    for (auto& sp : c->spans) { (void)hipEventDestroy(sp.t0); (void)hipEventDestroy(sp.t1); }
+    for (hipEvent_t e : c->ev_free) (void)hipEventDestroy(e);
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
     c->table.release(); c->flat.release(); c->partials.release();
     c->srcdesc.release(); c->misslist.release(); c->gcount.release();
@@ -76,21 +70,30 @@ extern "C" int spp_ctx_sync(spp_ctx* c) {
     return SPP_OK;
 }
 
+static void recycle_spans(spp_ctx* c) {
+    for (auto& sp : c->spans) { c->ev_free.push_back(sp.t0); c->ev_free.push_back(sp.t1); }
+    c->spans.clear();
+}
+
 extern "C" int spp_ctx_timing(spp_ctx* c, int enable) {
     SPP_CHECK(c != nullptr, SPP_E_ARG, "spp_ctx_timing: ctx is null");
+    SPP_TRY(spp_ctx_sync(c));
+    recycle_spans(c);
     c->timing = enable ? 1 : 0;
-    if (!enable) for (int i = 0; i < spp::kNumTimers; ++i) c->t_valid[i] = false;
     return SPP_OK;
 }
 
-extern "C" int spp_ctx_last_times(spp_ctx* c, float* ms_out) {
-    SPP_CHECK(c != nullptr && ms_out != nullptr, SPP_E_ARG, "spp_ctx_last_times: null argument");
-    for (int i = 0; i < spp::kNumTimers; ++i) {
-        ms_out[i] = -1.0f;
-        if (!c->t_valid[i]) continue;
+extern "C" int spp_ctx_times(spp_ctx* c, float* sum_ms, int64_t* count) {
+    SPP_CHECK(c != nullptr && sum_ms != nullptr && count != nullptr, SPP_E_ARG, "spp_ctx_times: null argument");
+    SPP_TRY(spp_ctx_sync(c));
+    for (int i = 0; i < spp::kNumTimers; ++i) { sum_ms[i] = 0.f; count[i] = 0; }
+    for (auto& sp : c->spans) {
         float ms = 0.f;
-        hipError_t e = hipEventElapsedTime(&ms, c->t0[i], c->t1[i]);
-        if (e == hipSuccess) ms_out[i] = ms;
+        if (hipEventElapsedTime(&ms, sp.t0, sp.t1) == hipSuccess && sp.idx >= 0 && sp.idx < spp::kNumTimers) {
+            sum_ms[sp.idx] += ms;
+            count[sp.idx] += 1;
+        }
     }
+    recycle_spans(c);
     return SPP_OK;
 }

@@ -7,6 +7,8 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/spp.h"
 
 namespace spp {
@@ -79,10 +81,17 @@ struct spp_ctx {
     int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
     // vip workspaces
     spp::DevBuf y0, y1, tot, hubacc;
-    // timing
+    // timing: while enabled every timed piece of device work gets its own pair of events
     int         timing = 0;
-    hipEvent_t  t0[spp::kNumTimers] = {}, t1[spp::kNumTimers] = {};
-    bool        t_valid[spp::kNumTimers] = {};
+    struct Span { int idx; hipEvent_t t0, t1; };
+    std::vector<hipEvent_t> ev_free;
+    std::vector<Span>       spans;
+    hipEvent_t take_event() {
+        if (!ev_free.empty()) { hipEvent_t e = ev_free.back(); ev_free.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
 };
 
 struct spp_graph {
@@ -119,12 +128,16 @@ constexpr int kVipChunk = 4096;         // in-list edges per workgroup of the pu
 constexpr int kHubSlice = 16384;        // edges per workgroup slice of a hub row
 
 struct ScopedTimer {
-    spp_ctx* c; int idx; hipStream_t s;
+    spp_ctx* c; int idx; hipStream_t s; hipEvent_t a = nullptr, b = nullptr;
     ScopedTimer(spp_ctx* ctx, int i, hipStream_t st) : c(ctx), idx(i), s(st) {
-        if (c->timing) { (void)hipEventRecord(c->t0[idx], s); }
+        if (!c->timing) return;
+        a = c->take_event(); b = c->take_event();
+        if (a && b) (void)hipEventRecord(a, s);
     }
     ~ScopedTimer() {
-        if (c->timing) { (void)hipEventRecord(c->t1[idx], s); c->t_valid[idx] = true; }
+        if (!c->timing || !a || !b) return;
+        (void)hipEventRecord(b, s);
+        c->spans.push_back({idx, a, b});
     }
 };
 

@@ -11,6 +11,8 @@
 #include "spp_device.h"
 #include "spp_rowcopy.h"
 
+#include <stdlib.h>
+
 namespace spp {
 
 struct ClassifyArgs {
@@ -31,19 +33,25 @@ __global__ void gather_zero_kernel(unsigned long long* counters) {
     if (threadIdx.x < 8) counters[threadIdx.x] = 0ull;
 }
 
+constexpr int kClsPer = 8;             // ids per thread: a workgroup classifies 2048 consecutive ids per round
+
+// One workgroup classifies a run of consecutive ids, then reserves room for all of its misses in
+// the miss list with a single atomic (ranks inside the workgroup come from a scan), so the list
+// counter sees one atomic per 2048 ids instead of one per wavefront.
 __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
+    __shared__ int scan_lds[4];
+    __shared__ unsigned long long base_lds;
     const int64_t n = a.n_ptr ? *a.n_ptr : a.n;
-    const int lane = lane_id();
-    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    unsigned long long n_local = 0, n_hit = 0;
-    // the loop bound is rounded up to whole wavefronts so that every lane reaches the ballots
-    const int64_t n_round = (n + kWave - 1) / kWave * kWave;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n_round; i += stride) {
-        bool miss = false;
-        int64_t d = make_desc(kTagSkip, 0);
-        if (i < n) {
+    constexpr int64_t kChunk = (int64_t)kBlock * kClsPer;
+    int n_local = 0, n_hit = 0;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n; base += (int64_t)gridDim.x * kChunk) {
+        uint32_t missbits = 0;
+#pragma unroll
+        for (int k = 0; k < kClsPer; ++k) {
+            const int64_t i = base + (int64_t)k * kBlock + threadIdx.x;
+            if (i >= n) continue;
             const int64_t g = a.ids[i];
+            int64_t d = make_desc(kTagSkip, 0);
             if (g < 0 || g >= a.N) {
                 atomicOr(&a.counters[3], 1ull);
             } else if (g >= a.lo && g < a.hi) {
@@ -54,28 +62,27 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
                 const bool found = a.tab && table_find(a.tab, a.mask, a.shift, (uint32_t)g, slot) >= 0 &&
                                    (int64_t)slot < a.limit;
                 if (found) { d = make_desc(kTagCache, slot); ++n_hit; }
-                else       { d = make_desc(kTagMiss, g < a.lo ? g : g - (a.hi - a.lo)); miss = true; }
+                else       { d = make_desc(kTagMiss, g < a.lo ? g : g - (a.hi - a.lo)); missbits |= 1u << k; }
             }
             a.desc[i] = d;
         }
-        // compact the misses: one atomic per wavefront, ranks from the ballot
-        const uint64_t mm = __ballot(miss);
-        if (mm) {
-            unsigned long long base = 0;
-            const int leader = __ffsll((unsigned long long)mm) - 1;
-            if (lane == leader) base = atomicAdd(&a.counters[2], (unsigned long long)__popcll(mm));
-            base = __shfl((long long)base, leader, kWave);
-            if (miss) a.misslist[base + __popcll(mm & lt_mask)] = (int32_t)i;
+        int total;
+        const int ex = block_exclusive_scan(__popc(missbits), scan_lds, total);
+        if (total > 0) {
+            if (threadIdx.x == 0) base_lds = atomicAdd(&a.counters[2], (unsigned long long)total);
+            __syncthreads();
+            unsigned long long pos = base_lds + (unsigned long long)ex;
+#pragma unroll
+            for (int k = 0; k < kClsPer; ++k)
+                if (missbits & (1u << k)) a.misslist[pos++] = (int32_t)(base + (int64_t)k * kBlock + threadIdx.x);
+            __syncthreads();                      // base_lds is reused by the next round
         }
     }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        n_local += __shfl_down((long long)n_local, off, kWave);
-        n_hit += __shfl_down((long long)n_hit, off, kWave);
-    }
-    if (lane == 0) {
-        if (n_local) atomicAdd(&a.counters[0], n_local);
-        if (n_hit) atomicAdd(&a.counters[1], n_hit);
+    const int tl = block_reduce_sum(n_local, scan_lds);
+    const int th = block_reduce_sum(n_hit, scan_lds);
+    if (threadIdx.x == 0) {
+        if (tl) atomicAdd(&a.counters[0], (unsigned long long)tl);
+        if (th) atomicAdd(&a.counters[1], (unsigned long long)th);
     }
 }
 
@@ -176,7 +183,7 @@ extern "C" int spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const v
         a.mask = cache ? cache->table_mask : 0; a.shift = cache ? cache->table_shift : 0;
         a.limit = cache ? cache->limit : 0;
         a.desc = ctx->srcdesc.as<int64_t>(); a.misslist = ctx->misslist.as<int32_t>(); a.counters = counters;
-        const int64_t cneed = (n + kBlock - 1) / kBlock;
+        const int64_t cneed = (n + kBlock * kClsPer - 1) / (kBlock * kClsPer);
         const int cgrid = (int)(cneed < (int64_t)ctx->num_cu * 8 ? cneed : (int64_t)ctx->num_cu * 8);
         {
             ScopedTimer tc(ctx, SPP_T_GATHER_CLASSIFY, st);
@@ -187,7 +194,11 @@ extern "C" int spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const v
         const int64_t vecs = n * (row_bytes / V);
         const int64_t need = (vecs + kBlock * kCopyUnroll - 1) / (kBlock * kCopyUnroll);
         const int grid = (int)(need < (int64_t)ctx->num_cu * 16 ? need : (int64_t)ctx->num_cu * 16);
-        const int mgrid = (int)(need < (int64_t)ctx->num_cu * 4 ? need : (int64_t)ctx->num_cu * 4);
+        // The miss kernel is kept to a few workgroups on purpose: 64 of them already saturate
+        // the PCIe link, and every CU that hosts host-memory loads serves other kernels slowly.
+        int64_t mcap = 64;
+        if (const char* env = getenv("SPP_MISS_BLOCKS")) { const long v = atol(env); if (v > 0) mcap = v; }
+        const int mgrid = (int)(need < mcap ? need : mcap);
         // miss path on the side stream, after the classification
         if (dremote) {
             SPP_HIP(hipEventRecord(ctx->ev_fork, st));
