@@ -171,6 +171,14 @@ enum { SPP_T_VIP_TOTAL = 0, SPP_T_VIP_HOP_FIRST = 1 /* .. +L-1 */, SPP_T_SAMPLE 
 int  spp_ctx_timing(spp_ctx* ctx, int enable);
 int  spp_ctx_times(spp_ctx* ctx, float* sum_ms /* [SPP_T_COUNT] */, int64_t* count /* [SPP_T_COUNT] */);
 
+/* Running sums over the calls made on this context since the last reset, kept on the device so
+ * that a loop of asynchronous calls can be accounted for without a host round trip per batch:
+ *   out[0] minibatches sampled, out[1] sum of |S_L|, out[2] sum of sampled edges over all hops,
+ *   out[3] gather calls, out[4] rows from the local shard, out[5] rows from the cache,
+ *   out[6] rows missed (served from the remote store), out[7] unused.
+ * Waits for the context's streams. */
+int  spp_ctx_totals(spp_ctx* ctx, int64_t* out /* [8] */, int reset);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = [
     "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
     "spp_graph_destroy", "spp_vip_propagate", "spp_build_vip_cache", "spp_cache_destroy",
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg",
-    "spp_gather_features", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_times",
+    "spp_gather_features", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
 ]
 
 
@@ -95,6 +95,7 @@ def load_library():
     lib.spp_gather_last_stats.argtypes = [C.c_void_p, C.POINTER(_GatherStats)]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
     lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
+    lib.spp_ctx_totals.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_int]
     _lib = lib
     return lib
 
@@ -144,6 +145,13 @@ class Context:
         cnt = (C.c_int64 * SPP_T_COUNT)()
         _check(load_library().spp_ctx_times(self._h, ms, cnt))
         return list(ms), list(cnt)
+
+    def totals(self, reset: bool = False):
+        """Running sums since the last reset: batches, |S_L|, edges, gather calls, local / cache / missed rows."""
+        buf = (C.c_int64 * 8)()
+        _check(load_library().spp_ctx_totals(self._h, buf, int(reset)))
+        keys = ("batches", "n_nodes", "n_edges", "gather_calls", "n_local", "n_cache_hit", "n_miss")
+        return dict(zip(keys, list(buf)))
 
     def close(self):
         if self._h:

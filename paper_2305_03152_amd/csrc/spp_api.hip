@@ -37,6 +37,8 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 64 * sizeof(int64_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->totals), 8 * sizeof(int64_t));
+    if (e == hipSuccess) e = hipMemset(c->totals, 0, 8 * sizeof(int64_t));
     if (e != hipSuccess) {
         spp::set_error("spp_ctx_create: %s", hipGetErrorString(e));
         spp_ctx_destroy(c);
@@ -57,6 +59,7 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     for (auto& sp : c->spans) { (void)hipEventDestroy(sp.t0); (void)hipEventDestroy(sp.t1); }
     for (hipEvent_t e : c->ev_free) (void)hipEventDestroy(e);
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
+    if (c->totals) (void)hipFree(c->totals);
     c->table.release(); c->flat.release(); c->partials.release();
     c->srcdesc.release(); c->misslist.release(); c->gcount.release();
     c->y0.release(); c->y1.release(); c->tot.release(); c->hubacc.release();
@@ -95,5 +98,13 @@ extern "C" int spp_ctx_times(spp_ctx* c, float* sum_ms, int64_t* count) {
         }
     }
     recycle_spans(c);
+    return SPP_OK;
+}
+
+extern "C" int spp_ctx_totals(spp_ctx* c, int64_t* out, int reset) {
+    SPP_CHECK(c != nullptr && out != nullptr, SPP_E_ARG, "spp_ctx_totals: null argument");
+    SPP_TRY(spp_ctx_sync(c));
+    SPP_HIP(hipMemcpy(out, c->totals, 8 * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (reset) SPP_HIP(hipMemset(c->totals, 0, 8 * sizeof(int64_t)));
     return SPP_OK;
 }

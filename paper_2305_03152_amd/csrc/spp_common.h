@@ -79,6 +79,7 @@ struct spp_ctx {
     spp::DevBuf misslist;               // int32 positions of the rows that miss
     spp::DevBuf gcount;                 // device counters of the gather (int64[8])
     int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
+    int64_t*    totals = nullptr;       // device int64[8], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces
     spp::DevBuf y0, y1, tot, hubacc;
     // timing: while enabled every timed piece of device work gets its own pair of events

@@ -27,6 +27,7 @@ struct ClassifyArgs {
     int64_t*       desc;
     int32_t*       misslist;
     unsigned long long* counters;      // [0] local, [1] cache hit, [2] miss, [3] bad id
+    unsigned long long* totals;        // context-wide running sums: [3] calls, [4] local, [5] cache hit, [6] miss
 };
 
 __global__ void gather_zero_kernel(unsigned long long* counters) {
@@ -69,7 +70,10 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
         int total;
         const int ex = block_exclusive_scan(__popc(missbits), scan_lds, total);
         if (total > 0) {
-            if (threadIdx.x == 0) base_lds = atomicAdd(&a.counters[2], (unsigned long long)total);
+            if (threadIdx.x == 0) {
+                base_lds = atomicAdd(&a.counters[2], (unsigned long long)total);
+                atomicAdd(&a.totals[6], (unsigned long long)total);
+            }
             __syncthreads();
             unsigned long long pos = base_lds + (unsigned long long)ex;
 #pragma unroll
@@ -81,8 +85,9 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
     const int tl = block_reduce_sum(n_local, scan_lds);
     const int th = block_reduce_sum(n_hit, scan_lds);
     if (threadIdx.x == 0) {
-        if (tl) atomicAdd(&a.counters[0], (unsigned long long)tl);
-        if (th) atomicAdd(&a.counters[1], (unsigned long long)th);
+        if (tl) { atomicAdd(&a.counters[0], (unsigned long long)tl); atomicAdd(&a.totals[4], (unsigned long long)tl); }
+        if (th) { atomicAdd(&a.counters[1], (unsigned long long)th); atomicAdd(&a.totals[5], (unsigned long long)th); }
+        if (blockIdx.x == 0) atomicAdd(&a.totals[3], 1ull);
     }
 }
 
@@ -183,6 +188,7 @@ extern "C" int spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const v
         a.mask = cache ? cache->table_mask : 0; a.shift = cache ? cache->table_shift : 0;
         a.limit = cache ? cache->limit : 0;
         a.desc = ctx->srcdesc.as<int64_t>(); a.misslist = ctx->misslist.as<int32_t>(); a.counters = counters;
+        a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
         const int64_t cneed = (n + kBlock * kClsPer - 1) / (kBlock * kClsPer);
         const int cgrid = (int)(cneed < (int64_t)ctx->num_cu * 8 ? cneed : (int64_t)ctx->num_cu * 8);
         {

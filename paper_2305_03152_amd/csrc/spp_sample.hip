@@ -28,6 +28,8 @@ struct SampleArgs {
     int32_t*       src;        // this hop
     int32_t*       flat;       // sampled global ids of this hop
     int64_t*       counts;     // n[0..MAX_L], e[0..MAX_L]
+    unsigned long long* totals; // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
+    int            L;
     int            h;          // hop, 1-based
     int            f;          // fanout of this hop
     uint64_t       seed;
@@ -77,6 +79,7 @@ struct CountFin {
     __device__ void operator()(int total) const {
         a.indptr[a.counts[a.h - 1]] = total;
         a.counts[SPP_MAX_L + 1 + a.h] = total;
+        atomicAdd(&a.totals[2], (unsigned long long)(uint32_t)total);
     }
 };
 
@@ -159,7 +162,11 @@ struct NewOut {
 };
 struct NewFin {
     SampleArgs a;
-    __device__ void operator()(int total) const { a.counts[a.h] = a.counts[a.h - 1] + total; }
+    __device__ void operator()(int total) const {
+        const int64_t n = a.counts[a.h - 1] + total;
+        a.counts[a.h] = n;
+        if (a.h == a.L) { atomicAdd(&a.totals[1], (unsigned long long)n); atomicAdd(&a.totals[0], 1ull); }
+    }
 };
 
 // ---- step 4 ----
@@ -235,6 +242,7 @@ extern "C" int spp_sample_mfg(spp_ctx* ctx, const spp_graph* g, const int32_t* d
     a.tab = ctx->table.as<unsigned long long>(); a.mask = cap - 1; a.shift = shift;
     a.S = io->d_node_ids; a.flat = ctx->flat.as<int32_t>(); a.counts = io->d_counts;
     a.seed = seed; a.batch_lo = (uint32_t)batch_index;
+    a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.L = L;
     a.indptr = nullptr; a.src = nullptr; a.h = 0; a.f = 0;
 
     {

@@ -199,6 +199,8 @@ def test_sample_and_gather_tiny(spp, ctx, tiny_case):
     remote = c.remote.numpy()
     cache_rows = S.feature_rows(cfg, torch.from_numpy(ids_ref)).numpy()
     bufs = spp.MFGBuffers("cuda", cfg.B, cfg.fanouts, cfg.N)
+    ctx.totals(reset=True)
+    sums = dict(batches=0, n_nodes=0, n_edges=0, gather_calls=0, n_local=0, n_cache_hit=0, n_miss=0)
     for epoch in range(2):
         for bi, seeds in enumerate(S.epoch_batches(cfg, torch.from_numpy(c.Tk), epoch)):
             _say("tiny batch", epoch, bi, "seeds", seeds.numel())
@@ -210,6 +212,10 @@ def test_sample_and_gather_tiny(spp, ctx, tiny_case):
             assert np.array_equal(_bits(out.cpu().numpy()), _bits(want))
             assert (stats["n_local"], stats["n_cache_hit"], stats["n_miss"]) == counts
             assert stats["miss_bytes"] == counts[2] * cfg.D * cfg.elem_bytes
+            for k, v in (("batches", 1), ("n_nodes", ref.n[-1]), ("n_edges", sum(ref.e)), ("gather_calls", 1),
+                         ("n_local", counts[0]), ("n_cache_hit", counts[1]), ("n_miss", counts[2])):
+                sums[k] += v
+    assert ctx.totals() == sums
     # the same gather without a host round trip for the count, and with no cache at all
     m = spp.sample_mfg(ctx, c.G, torch.from_numpy(c.Tk[:100]).cuda(), (4, 3), 7, 3)
     out = torch.zeros((m.nb[-1], cfg.D), dtype=torch.float32, device="cuda")
