@@ -58,7 +58,21 @@ __global__ void __launch_bounds__(kBlock) vip_pull_kernel(VipHop a, const int32_
     const int64_t last_start = a.in_rowptr[r1 - 1];
     if (e1 - last_start > kVipChunk) e1 = last_start;      // a hub can only be the last row here
     const int n = (int)(e1 - e0);                          // < 2 * kVipChunk
-    for (int k = threadIdx.x; k < n; k += kBlock) ys[k] = a.y[a.in_col[e0 + k]];
+    // eight independent gathers per thread are issued before any is consumed: the kernel lives on
+    // the number of y reads in flight, not on arithmetic
+    const int32_t* __restrict__ cols = a.in_col + e0;
+    int k = threadIdx.x;
+    for (; k + 7 * kBlock < n; k += 8 * kBlock) {
+        int32_t c[8];
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u] = __builtin_nontemporal_load(cols + k + u * kBlock);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = a.y[c[u]];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ys[k + u * kBlock] = v[u];
+    }
+    for (; k < n; k += kBlock) ys[k] = a.y[cols[k]];
     __syncthreads();
     for (int64_t r = r0 + threadIdx.x; r < r1; r += kBlock) {
         const int64_t s = a.in_rowptr[r], t = a.in_rowptr[r + 1];
@@ -85,7 +99,18 @@ __global__ void __launch_bounds__(kBlock) vip_hub_slice_kernel(VipHop a, const i
     const int64_t rend = a.in_rowptr[row + 1];
     const int64_t e = b + kHubSlice < rend ? b + kHubSlice : rend;
     double s = 0.0;
-    for (int64_t i = b + threadIdx.x; i < e; i += kBlock) s += (double)a.y[a.in_col[i]];
+    int64_t i = b + threadIdx.x;
+    for (; i + 7 * kBlock < e; i += 8 * kBlock) {
+        int32_t c[8];
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u] = __builtin_nontemporal_load(a.in_col + i + u * kBlock);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = a.y[c[u]];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)v[u];
+    }
+    for (; i < e; i += kBlock) s += (double)a.y[a.in_col[i]];
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_down(s, off, kWave);
     if (lane_id() == 0) red[threadIdx.x >> 6] = s;
