@@ -49,7 +49,7 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
-def vip(rowptr, col, T, B, fanouts, include_hop0=False, literal_product=False):
+def vip(rowptr, col, T, B, fanouts, include_hop0=False, literal_product=False, verbose=False):
     """Proposition 1 in fp64.  Returns (p_total[N], p_hop[L, N]) as float64 arrays."""
     lib = _load()
     rowptr, col, T = _i64(rowptr), _i32(col), _i32(T)
@@ -60,7 +60,7 @@ def vip(rowptr, col, T, B, fanouts, include_hop0=False, literal_product=False):
     p_tot = np.empty(N, dtype=np.float64)
     rc = lib.orc_vip(C.c_int64(N), _p(rowptr), _p(col), _p(T), C.c_int64(T.size), C.c_int32(int(B)),
                      _p(f), C.c_int32(L), C.c_int(int(include_hop0)), C.c_int(int(literal_product)),
-                     _p(p_hop), _p(p_tot))
+                     _p(p_hop), _p(p_tot), C.c_int(int(verbose)))
     if rc != 0:
         raise ValueError(f"orc_vip failed ({rc})")
     return p_tot, p_hop

@@ -20,6 +20,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -39,11 +40,12 @@
  * p_total: double[N],   eq. (1): 1 - prod_{h=1..L}(1 - p^[h](u)); hop 0 multiplied in as well
  *          when include_hop0 != 0.
  * B > |T| clamps p^[0] to 1.  Vertices with d(v) = 0 contribute nothing.
+ * verbose != 0 prints one line per finished hop (long runs on 10^9-edge graphs).
  * Returns 0, or -1 on bad arguments / allocation failure.
  * ---------------------------------------------------------------------------------------- */
 int orc_vip(int64_t N, const int64_t *rowptr, const int32_t *col, const int32_t *T, int64_t nT,
             int32_t B, const int32_t *fanouts, int32_t L, int include_hop0, int form,
-            double *p_hop, double *p_total)
+            double *p_hop, double *p_total, int verbose)
 {
     if (N <= 0 || L <= 0 || nT <= 0 || B <= 0) return -1;
     double *prev = (double *)calloc((size_t)N, sizeof(double));
@@ -71,9 +73,10 @@ int orc_vip(int64_t N, const int64_t *rowptr, const int32_t *col, const int32_t 
             double t = f / (double)d;
             if (t > 1.0) t = 1.0;
             double x = t * prev[v];
+            double lw = log1p(-x);                 /* the same factor for every member of v's row */
             for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
                 int32_t u = col[e];
-                if (form == 0) acc[u] += log1p(-x);
+                if (form == 0) acc[u] += lw;
                 else           acc[u] *= (1.0 - x);
             }
         }
@@ -84,6 +87,7 @@ int orc_vip(int64_t N, const int64_t *rowptr, const int32_t *col, const int32_t 
             else           tot[u] *= (1.0 - ph);
             prev[u] = ph;
         }
+        if (verbose) { fprintf(stderr, "[oracle] vip hop %d of %d done\n", h, L); fflush(stderr); }
     }
     for (int64_t u = 0; u < N; ++u)
         p_total[u] = (form == 0) ? -expm1(tot[u]) : 1.0 - tot[u];
