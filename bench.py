@@ -35,7 +35,10 @@ def main():
     ap.add_argument("--config", default="mid", help="workload: tiny | mid (default, the metric's configuration)")
     ap.add_argument("--vip-reps", type=int, default=5)
     ap.add_argument("--pipeline", type=int, default=2,
-                    help="minibatches in flight: contexts (each with its own stream and buffers) used round-robin")
+                    help="lanes: contexts (each with its own stream and buffers) used round-robin")
+    ap.add_argument("--group", type=int, default=8,
+                    help="minibatches a lane samples back to back and then gathers with ONE set of launches "
+                         "(pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -103,34 +106,42 @@ def main():
         batches.extend(b for b in S.epoch_batches(cfg, Tk, ep) if b.numel() == min(cfg.B, Tk.numel()))
         ep += 1
     batches = batches[:W + K]
-    # Each minibatch in flight has its own context (stream, workspaces), MFG buffers and output
-    # rows, so the sampling of one batch overlaps the PCIe misses of the one before it.
+    # A lane = one context (stream, workspaces) with `group` sets of MFG buffers and output rows.
+    # A lane samples `group` minibatches back to back, then gathers all of them with one
+    # classification, one hit copy and one miss copy; lanes alternate, so the sampling of one
+    # lane overlaps the PCIe misses of the other.
     P = max(1, args.pipeline)
+    Gsz = max(1, min(args.group, 16))
     lanes = []
     for k in range(P):
         c = ctx if k == 0 else spp.Context(0, stream=torch.cuda.Stream(dev))
-        b = spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N)
-        o = torch.empty((b.nb[-1], cfg.D), dtype=cfg.torch_dtype, device=dev)
+        b = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N) for _ in range(Gsz)]
+        o = [torch.empty((b[0].nb[-1], cfg.D), dtype=cfg.torch_dtype, device=dev) for _ in range(Gsz)]
         lanes.append((c, b, o))
-    bufs, out = lanes[0][1], lanes[0][2]
+    bufs, out = lanes[0][1][0], lanes[0][2][0]
 
-    def step(i):
-        c, b, o = lanes[i % P]
-        spp.sample_mfg(c, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=b, sync=False)
-        spp.gather_features(c, cache, local, cfg.N, lo, hi, remote, b.node_ids, n=b.nb[-1],
-                            n_device=b.n_final_device, out=o, sync=False)
+    def run(first, count):
+        """Enqueue minibatches first .. first+count-1 (no host synchronisation inside)."""
+        gi = 0
+        for g0 in range(first, first + count, Gsz):
+            c, b, o = lanes[gi % P]
+            gi += 1
+            idx = range(g0, min(g0 + Gsz, first + count))
+            for k, i in enumerate(idx):
+                spp.sample_mfg(c, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=b[k], sync=False)
+            spp.gather_features_multi(c, cache, local, cfg.N, lo, hi, remote,
+                                      [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(len(idx))],
+                                      sync=False)
 
     torch.cuda.synchronize()
-    for i in range(W):
-        step(i)
+    run(0, W)
     torch.cuda.synchronize()
     for c, _, _ in lanes:
         c.timing(True)
         c.totals(reset=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(W, W + K):
-        step(i)
+    run(W, K)
     for c, _, _ in lanes:
         c.sync()
     torch.cuda.synchronize()
@@ -157,13 +168,15 @@ def main():
     miss_ms = ms[T_MISS] / max(cnt[T_MISS], 1)
     cls_ms = ms[T_CLS] / max(cnt[T_CLS], 1)
     sample_ms = ms[T_SAMPLE] / max(cnt[T_SAMPLE], 1)
-    hit_rows = avg["n_local"] + avg["n_cache_hit"]
+    # per LAUNCH: a launch of the hit / miss kernel covers one group of minibatches
+    n_launch = max(cnt[T_HIT], 1)
+    hit_rows = (tot["n_local"] + tot["n_cache_hit"]) / n_launch
     hit_bytes = hit_rows * 2 * row_bytes                 # read the source row + write the output row
     roof = {"bound": "hbm", "achieved": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms > 0 else 0.0,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>", "traffic": None,
             "bytes_per_launch": hit_bytes, "avg_launch_ms": hit_ms}
     roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
-    miss_bytes = avg["n_miss"] * row_bytes
+    miss_bytes = tot["n_miss"] / max(cnt[T_MISS], 1) * row_bytes
     pcie = {"bound": "pcie", "achieved": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms > 0 else 0.0,
             "peak": PCIE_PEAK_GBS, "unit": "GB/s", "kernel": "rows_indexed_kernel<16> (miss path)",
             "bytes_per_launch": miss_bytes, "avg_launch_ms": miss_ms}
@@ -213,13 +226,14 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={g.N} M={g.M} D={cfg.D} {cfg.dtype} fanouts={list(cfg.fanouts)} "
                                f"B={cfg.B} K={cfg.K} alpha={cfg.alpha} owned partition {cfg.owned_partition}",
-                   "minibatches_in_flight": P,
+                   "lanes": P, "minibatches_per_gather_launch": Gsz, "minibatches_in_flight": P * Gsz,
                    "avg_per_batch": {k: round(v, 1) for k, v in avg.items()},
                    "hit_rate_of_remote": avg["n_cache_hit"] / max(avg["n_cache_hit"] + avg["n_miss"], 1e-9)},
         "roofline": roof,
         "cpu_baseline": cpu,
         "pcie": pcie,
-        "kernels_ms": {"sample_mfg": sample_ms, "gather_classify": cls_ms, "gather_hit": hit_ms, "gather_miss": miss_ms},
+        "kernels_ms": {"sample_mfg_per_batch": sample_ms, "gather_classify_per_launch": cls_ms,
+                       "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms},
         "vip": {"ms_total": vip_total_ms, "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
                 "in_lists_build_s": t_inlists, "cache_build_s": cache_s, "n_cached": cache.n_cached},
     }

@@ -41,6 +41,7 @@ extern "C" {
 
 #define SPP_MAX_L       8      /* most hops / GNN layers */
 #define SPP_MAX_FANOUT  64     /* largest fanout (one wavefront lane per slot) */
+#define SPP_MAX_GATHER_LISTS 16 /* most id lists in one spp_gather_features_multi call */
 
 enum {
     SPP_OK          =  0,
@@ -160,6 +161,22 @@ int  spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_loc
                          const int32_t* d_node_ids, int64_t n, const int64_t* d_n, void* d_out,
                          spp_gather_stats* stats, uint32_t flags);
 int  spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats);
+
+/* The same gather for up to SPP_MAX_GATHER_LISTS id lists in one set of launches (one
+ * classification, one hit copy, one miss copy), e.g. the minibatches a pipeline keeps in flight
+ * (Sec. 4.3 keeps ten): each kernel then moves several minibatches' worth of rows per launch.
+ * List j: d_out[i,:] = row of vertex d_node_ids[i], i < n (n an upper bound when d_n is given).
+ * The statistics are summed over the lists. */
+typedef struct {
+    const int32_t* d_node_ids;
+    int64_t        n;
+    const int64_t* d_n;      /* device int64 count, or NULL */
+    void*          d_out;    /* [n, D] */
+} spp_gather_list;
+int  spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
+                               int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                               int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
+                               spp_gather_stats* stats, uint32_t flags);
 
 /* Device-time accounting.  After spp_ctx_timing(ctx, 1) every call brackets its pieces of device
  * work with events on the stream they run on (vip total and per hop, the whole sampling of a

@@ -27,7 +27,7 @@ EXPORTS = [
     "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
     "spp_graph_destroy", "spp_vip_propagate", "spp_build_vip_cache", "spp_cache_destroy",
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg",
-    "spp_gather_features", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
+    "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
 ]
 
 
@@ -46,6 +46,10 @@ class _MfgStruct(C.Structure):
         ("n", C.c_int64 * (SPP_MAX_L + 1)),
         ("e", C.c_int64 * (SPP_MAX_L + 1)),
     ]
+
+
+class _GatherList(C.Structure):
+    _fields_ = [("d_node_ids", C.c_void_p), ("n", C.c_int64), ("d_n", C.c_void_p), ("d_out", C.c_void_p)]
 
 
 class _GatherStats(C.Structure):
@@ -92,6 +96,9 @@ def load_library():
     lib.spp_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                         C.c_void_p, C.POINTER(_GatherStats), C.c_uint32]
+    lib.spp_gather_features_multi.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                              C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_GatherList), C.c_int32,
+                                              C.POINTER(_GatherStats), C.c_uint32]
     lib.spp_gather_last_stats.argtypes = [C.c_void_p, C.POINTER(_GatherStats)]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
     lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
@@ -342,6 +349,35 @@ def gather_features(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N
     if sync:
         stats = dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)
     return out, stats
+
+
+def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,
+                          remote: Optional[torch.Tensor], lists, sync: bool = True):
+    """One classification / hit copy / miss copy over several id lists.
+
+    `lists` is a sequence of (node_ids, n, n_device or None, out); returns the summed stats when sync.
+    """
+    local = _row_store(local, "local")
+    if not local.is_cuda:
+        raise SppError("local must be on the GPU")
+    remote = _row_store(remote, "remote")
+    D, eb = local.shape[1], local.element_size()
+    arr = (_GatherList * max(len(lists), 1))()
+    for j, (ids, n, n_dev, out) in enumerate(lists):
+        ids = _dev(ids, torch.int32, "node_ids")
+        if out.shape[0] < n or out.shape[1] != D or not out.is_contiguous() or out.dtype != local.dtype:
+            raise SppError(f"out of list {j} is too small, not contiguous or of another type")
+        arr[j].d_node_ids = ids.data_ptr()
+        arr[j].n = int(n)
+        arr[j].d_n = n_dev.data_ptr() if n_dev is not None else None
+        arr[j].d_out = out.data_ptr()
+    st = _GatherStats()
+    _check(load_library().spp_gather_features_multi(ctx._h, cache._h if cache is not None else None, _ptr(local),
+                                                    int(N), int(lo), int(hi), _ptr(remote), D, eb, arr, len(lists),
+                                                    C.byref(st), SPP_SYNC if sync else 0))
+    if sync:
+        return dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)
+    return None
 
 
 def gather_last_stats(ctx: Context):

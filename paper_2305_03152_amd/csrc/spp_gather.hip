@@ -11,47 +11,66 @@
 #include "spp_device.h"
 #include "spp_rowcopy.h"
 
-#include <stdlib.h>
-
 namespace spp {
 
+constexpr int kMissBlocks = 64;        // workgroups of the miss kernel (see gather_lists)
+constexpr int kClsPer = 8;             // ids per thread: a workgroup classifies 2048 consecutive ids per round
+static_assert(kBlock * kClsPer == kListAlign, "a classification chunk must not straddle two lists");
+
 struct ClassifyArgs {
-    const int32_t* ids;
-    int64_t        n;
-    const int64_t* n_ptr;
+    ListTable      t;
     int64_t        N, lo, hi;
     const unsigned long long* tab;     // null: no cache
     uint32_t       mask;
     int            shift;
     int64_t        limit;              // slots in use
-    int64_t*       desc;
-    int32_t*       misslist;
+    int64_t*       desc;               // per virtual row
+    int32_t*       misslist;           // virtual rows that miss
     unsigned long long* counters;      // [0] local, [1] cache hit, [2] miss, [3] bad id
     unsigned long long* totals;        // context-wide running sums: [3] calls, [4] local, [5] cache hit, [6] miss
 };
 
-__global__ void gather_zero_kernel(unsigned long long* counters) {
+struct PrologueArgs {
+    int64_t        n[kMaxLists];       // host counts (upper bounds when n_ptr is given)
+    const int64_t* n_ptr[kMaxLists];   // device counts or null
+    int            n_lists;
+};
+
+// Zeroes the per-call counters and lays the lists out in the virtual row space.
+__global__ void gather_prologue_kernel(PrologueArgs p, unsigned long long* counters, int64_t* off, int64_t* cnt) {
     if (threadIdx.x < 8) counters[threadIdx.x] = 0ull;
+    if (threadIdx.x == 0) {
+        int64_t o = 0;
+        for (int j = 0; j < p.n_lists; ++j) {
+            int64_t c = p.n_ptr[j] ? *p.n_ptr[j] : p.n[j];
+            if (c < 0) c = 0;
+            if (c > p.n[j]) c = p.n[j];             // never beyond what the caller's buffers hold
+            off[j] = o;
+            cnt[j] = c;
+            o = (o + c + kListAlign - 1) / kListAlign * kListAlign;
+        }
+        off[p.n_lists] = o;
+    }
 }
 
-constexpr int kClsPer = 8;             // ids per thread: a workgroup classifies 2048 consecutive ids per round
-
-// One workgroup classifies a run of consecutive ids, then reserves room for all of its misses in
-// the miss list with a single atomic (ranks inside the workgroup come from a scan), so the list
-// counter sees one atomic per 2048 ids instead of one per wavefront.
+// One workgroup classifies a run of 2048 consecutive ids of one list, then reserves room for all of
+// its misses in the miss list with a single atomic (ranks inside the workgroup come from a scan),
+// so the list counter sees one atomic per 2048 ids instead of one per wavefront.
 __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
     __shared__ int scan_lds[4];
     __shared__ unsigned long long base_lds;
-    const int64_t n = a.n_ptr ? *a.n_ptr : a.n;
-    constexpr int64_t kChunk = (int64_t)kBlock * kClsPer;
+    const int64_t total = a.t.off[a.t.n_lists];
     int n_local = 0, n_hit = 0;
-    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n; base += (int64_t)gridDim.x * kChunk) {
+    for (int64_t base = (int64_t)blockIdx.x * kListAlign; base < total; base += (int64_t)gridDim.x * kListAlign) {
+        const int j = list_of(a.t, base);
+        const int64_t lbeg = a.t.off[j], n = a.t.cnt[j];
+        const int32_t* __restrict__ ids = a.t.ids[j];
         uint32_t missbits = 0;
 #pragma unroll
         for (int k = 0; k < kClsPer; ++k) {
-            const int64_t i = base + (int64_t)k * kBlock + threadIdx.x;
+            const int64_t i = base - lbeg + (int64_t)k * kBlock + threadIdx.x;
             if (i >= n) continue;
-            const int64_t g = a.ids[i];
+            const int64_t g = ids[i];
             int64_t d = make_desc(kTagSkip, 0);
             if (g < 0 || g >= a.N) {
                 atomicOr(&a.counters[3], 1ull);
@@ -65,14 +84,14 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
                 if (found) { d = make_desc(kTagCache, slot); ++n_hit; }
                 else       { d = make_desc(kTagMiss, g < a.lo ? g : g - (a.hi - a.lo)); missbits |= 1u << k; }
             }
-            a.desc[i] = d;
+            a.desc[lbeg + i] = d;
         }
-        int total;
-        const int ex = block_exclusive_scan(__popc(missbits), scan_lds, total);
-        if (total > 0) {
+        int total_miss;
+        const int ex = block_exclusive_scan(__popc(missbits), scan_lds, total_miss);
+        if (total_miss > 0) {
             if (threadIdx.x == 0) {
-                base_lds = atomicAdd(&a.counters[2], (unsigned long long)total);
-                atomicAdd(&a.totals[6], (unsigned long long)total);
+                base_lds = atomicAdd(&a.counters[2], (unsigned long long)total_miss);
+                atomicAdd(&a.totals[6], (unsigned long long)total_miss);
             }
             __syncthreads();
             unsigned long long pos = base_lds + (unsigned long long)ex;
@@ -89,21 +108,6 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
         if (th) { atomicAdd(&a.counters[1], (unsigned long long)th); atomicAdd(&a.totals[5], (unsigned long long)th); }
         if (blockIdx.x == 0) atomicAdd(&a.totals[3], 1ull);
     }
-}
-
-template <int V>
-static void launch_hit(int grid, hipStream_t st, const int64_t* desc, int64_t n, const int64_t* n_ptr,
-                       const void* local, const void* cache, int64_t row_bytes, void* out) {
-    gather_hit_kernel<V><<<grid, kBlock, 0, st>>>(desc, n, n_ptr, (const char*)local, (const char*)cache,
-                                                  (uint32_t)(row_bytes / V), (char*)out);
-}
-
-template <int V>
-static void launch_indexed(int grid, hipStream_t st, const void* src, const int64_t* rowidx_or_desc,
-                           const int32_t* list, int64_t count, const int64_t* count_ptr, int64_t row_bytes,
-                           void* out) {
-    rows_indexed_kernel<V><<<grid, kBlock, 0, st>>>((const char*)src, rowidx_or_desc, list, count, count_ptr,
-                                                    (uint32_t)(row_bytes / V), (char*)out);
 }
 
 // Device-visible address of a row store that is either device memory or pinned host memory.
@@ -134,15 +138,16 @@ int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, 
     if (n <= 0) return SPP_OK;
     const void* dsrc = nullptr;
     SPP_TRY(device_view(src, &dsrc));
-    const int V = pick_vec(row_bytes, dsrc, d_out, nullptr, nullptr);
-    const int64_t vecs = n * (row_bytes / V);
+    const int V = pick_vec(row_bytes, (uintptr_t)dsrc | (uintptr_t)d_out);
+    const uint32_t vpr = (uint32_t)(row_bytes / V);
+    const int64_t vecs = n * vpr;
     int64_t need = (vecs + kBlock * kCopyUnroll - 1) / (kBlock * kCopyUnroll);
     const int grid = (int)(need < (int64_t)num_cu * 8 ? need : (int64_t)num_cu * 8);
     switch (V) {
-        case 16: launch_indexed<16>(grid, st, dsrc, d_rowidx, nullptr, n, nullptr, row_bytes, d_out); break;
-        case 8:  launch_indexed<8>(grid, st, dsrc, d_rowidx, nullptr, n, nullptr, row_bytes, d_out); break;
-        case 4:  launch_indexed<4>(grid, st, dsrc, d_rowidx, nullptr, n, nullptr, row_bytes, d_out); break;
-        default: launch_indexed<2>(grid, st, dsrc, d_rowidx, nullptr, n, nullptr, row_bytes, d_out); break;
+        case 16: rows_indexed_kernel<16><<<grid, kBlock, 0, st>>>((const char*)dsrc, d_rowidx, n, vpr, (char*)d_out); break;
+        case 8:  rows_indexed_kernel<8><<<grid, kBlock, 0, st>>>((const char*)dsrc, d_rowidx, n, vpr, (char*)d_out); break;
+        case 4:  rows_indexed_kernel<4><<<grid, kBlock, 0, st>>>((const char*)dsrc, d_rowidx, n, vpr, (char*)d_out); break;
+        default: rows_indexed_kernel<2><<<grid, kBlock, 0, st>>>((const char*)dsrc, d_rowidx, n, vpr, (char*)d_out); break;
     }
     SPP_HIP(hipGetLastError());
     return SPP_OK;
@@ -150,19 +155,19 @@ int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, 
 
 }  // namespace spp
 
-extern "C" int spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
-                                   int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
-                                   int32_t elem_bytes, const int32_t* d_node_ids, int64_t n,
-                                   const int64_t* d_n, void* d_out, spp_gather_stats* stats, uint32_t flags) {
+extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
+                                         int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                                         int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
+                                         spp_gather_stats* stats, uint32_t flags) {
     using namespace spp;
     SPP_CHECK(ctx, SPP_E_ARG, "spp_gather_features: ctx is null");
-    SPP_CHECK(n >= 0 && N > 0 && lo >= 0 && lo <= hi && hi <= N, SPP_E_ARG,
-              "spp_gather_features: n = %lld, range [%lld, %lld) of N = %lld", (long long)n, (long long)lo, (long long)hi, (long long)N);
+    SPP_CHECK(n_lists >= 0 && n_lists <= SPP_MAX_GATHER_LISTS && (lists || n_lists == 0), SPP_E_ARG,
+              "spp_gather_features: %d lists (at most %d)", n_lists, SPP_MAX_GATHER_LISTS);
+    SPP_CHECK(N > 0 && lo >= 0 && lo <= hi && hi <= N, SPP_E_ARG,
+              "spp_gather_features: range [%lld, %lld) of N = %lld", (long long)lo, (long long)hi, (long long)N);
     SPP_CHECK(D >= 1 && elem_bytes >= 1, SPP_E_ARG, "spp_gather_features: D = %d, elem_bytes = %d", D, elem_bytes);
     const int64_t row_bytes = (int64_t)D * elem_bytes;
     SPP_CHECK(row_bytes % 2 == 0, SPP_E_ARG, "spp_gather_features: row size %lld is odd", (long long)row_bytes);
-    SPP_CHECK(n == 0 || (d_node_ids && d_out), SPP_E_ARG, "spp_gather_features: null ids or output");
-    SPP_CHECK(hi == lo || d_local || n == 0, SPP_E_ARG, "spp_gather_features: local shard is null");
     if (cache) {
         SPP_CHECK(cache->lo == lo && cache->hi == hi && cache->N == N, SPP_E_ARG,
                   "spp_gather_features: the cache was built for another partition range");
@@ -170,65 +175,99 @@ extern "C" int spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const v
         SPP_CHECK(cache->row_bytes == row_bytes || cache->limit == 0, SPP_E_ARG,
                   "spp_gather_features: cache rows are %lld bytes, requested %lld", (long long)cache->row_bytes, (long long)row_bytes);
     }
-    SPP_HIP(hipSetDevice(ctx->device));
-    hipStream_t st = ctx->stream;
+    const void* crow = cache ? cache->rows : nullptr;
     const void* dremote = nullptr;
+    SPP_HIP(hipSetDevice(ctx->device));
     SPP_TRY(device_view(remote, &dremote));
-    SPP_TRY(ctx->gcount.reserve(8 * sizeof(unsigned long long)));
-    unsigned long long* counters = ctx->gcount.as<unsigned long long>();
-    if (n > 0) {
-        SPP_TRY(ctx->srcdesc.reserve((size_t)n * sizeof(int64_t)));
-        SPP_TRY(ctx->misslist.reserve((size_t)n * sizeof(int32_t)));
+
+    ClassifyArgs a;
+    PrologueArgs pro;
+    memset(&a, 0, sizeof(a));
+    memset(&pro, 0, sizeof(pro));
+    int64_t vbound = 0;                 // virtual rows, with padding
+    uintptr_t addr_bits = (uintptr_t)d_local | (uintptr_t)crow | (uintptr_t)dremote;
+    for (int j = 0; j < n_lists; ++j) {
+        SPP_CHECK(lists[j].n >= 0, SPP_E_ARG, "spp_gather_features: list %d has n = %lld", j, (long long)lists[j].n);
+        SPP_CHECK(lists[j].n == 0 || (lists[j].d_node_ids && lists[j].d_out), SPP_E_ARG,
+                  "spp_gather_features: list %d has null ids or output", j);
+        a.t.ids[j] = lists[j].d_node_ids;
+        a.t.out[j] = static_cast<char*>(lists[j].d_out);
+        pro.n[j] = lists[j].n;
+        pro.n_ptr[j] = lists[j].d_n;
+        vbound = (vbound + lists[j].n + kListAlign - 1) / kListAlign * kListAlign;
+        addr_bits |= (uintptr_t)lists[j].d_out;
     }
-    gather_zero_kernel<<<1, 64, 0, st>>>(counters);
-    if (n > 0) {
-        ClassifyArgs a;
-        a.ids = d_node_ids; a.n = n; a.n_ptr = d_n; a.N = N; a.lo = lo; a.hi = hi;
+    SPP_CHECK(vbound < 0x7FFFFFFFll, SPP_E_ARG, "spp_gather_features: %lld rows in one call exceed the 32-bit miss list", (long long)vbound);
+    SPP_CHECK(hi == lo || d_local || vbound == 0, SPP_E_ARG, "spp_gather_features: local shard is null");
+    a.t.n_lists = pro.n_lists = n_lists;
+
+    hipStream_t st = ctx->stream;
+    SPP_TRY(ctx->gcount.reserve((8 + 2 * (kMaxLists + 1)) * sizeof(int64_t)));
+    unsigned long long* counters = ctx->gcount.as<unsigned long long>();
+    int64_t* off = ctx->gcount.as<int64_t>() + 8;
+    int64_t* cnt = off + kMaxLists + 1;
+    a.t.off = off; a.t.cnt = cnt;
+    if (vbound > 0) {
+        SPP_TRY(ctx->srcdesc.reserve((size_t)vbound * sizeof(int64_t)));
+        SPP_TRY(ctx->misslist.reserve((size_t)vbound * sizeof(int32_t)));
+    }
+    gather_prologue_kernel<<<1, 64, 0, st>>>(pro, counters, off, cnt);
+    if (vbound > 0) {
+        a.N = N; a.lo = lo; a.hi = hi;
         a.tab = cache && cache->limit > 0 ? reinterpret_cast<const unsigned long long*>(cache->table) : nullptr;
         a.mask = cache ? cache->table_mask : 0; a.shift = cache ? cache->table_shift : 0;
         a.limit = cache ? cache->limit : 0;
         a.desc = ctx->srcdesc.as<int64_t>(); a.misslist = ctx->misslist.as<int32_t>(); a.counters = counters;
         a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
-        const int64_t cneed = (n + kBlock * kClsPer - 1) / (kBlock * kClsPer);
+        const int64_t cneed = vbound / kListAlign;
         const int cgrid = (int)(cneed < (int64_t)ctx->num_cu * 8 ? cneed : (int64_t)ctx->num_cu * 8);
         {
             ScopedTimer tc(ctx, SPP_T_GATHER_CLASSIFY, st);
             classify_kernel<<<cgrid, kBlock, 0, st>>>(a);
         }
-        const void* crow = cache ? cache->rows : nullptr;
-        const int V = pick_vec(row_bytes, d_local, crow, dremote, d_out);
-        const int64_t vecs = n * (row_bytes / V);
-        const int64_t need = (vecs + kBlock * kCopyUnroll - 1) / (kBlock * kCopyUnroll);
-        const int grid = (int)(need < (int64_t)ctx->num_cu * 16 ? need : (int64_t)ctx->num_cu * 16);
+        const int V = pick_vec(row_bytes, addr_bits);
+        const uint32_t vpr = (uint32_t)(row_bytes / V);
+        const int64_t vecs = vbound * vpr;
+        // hit copy: many small workgroups (512 vectors each, at most 64 per CU in the grid) let the
+        // dispatcher balance the copy around CUs that are busy with slow host-memory loads
+        const int64_t hneed = (vecs + kBlock * kHitUnroll - 1) / (kBlock * kHitUnroll);
+        const int grid = (int)(hneed < (int64_t)ctx->num_cu * 64 ? hneed : (int64_t)ctx->num_cu * 64);
         // The miss kernel is kept to a few workgroups on purpose: 64 of them already saturate
         // the PCIe link, and every CU that hosts host-memory loads serves other kernels slowly.
-        int64_t mcap = 64;
-        if (const char* env = getenv("SPP_MISS_BLOCKS")) { const long v = atol(env); if (v > 0) mcap = v; }
-        const int mgrid = (int)(need < mcap ? need : mcap);
-        // miss path on the side stream, after the classification
+        const int64_t mneed = (vecs + kBlock * kCopyUnroll - 1) / (kBlock * kCopyUnroll);
+        const int mgrid = (int)(mneed < kMissBlocks ? mneed : kMissBlocks);
+        // Order on purpose: the hit copy runs first and alone, the miss copy starts on the side
+        // stream when it is done.  Run together, the host-memory loads of the miss kernel held up
+        // the hit copy on every CU they shared (it then ran at a third of its rate), and the hit
+        // copy is short next to the PCIe transfer, so nothing is gained by overlapping the two.
+        // The side stream still lets the caller's stream go on with independent work (the next
+        // minibatch's sampling) while the misses arrive.
+        {
+            ScopedTimer th(ctx, SPP_T_GATHER_HIT, st);
+            const char* loc = static_cast<const char*>(d_local);
+            const char* cr = static_cast<const char*>(crow);
+            switch (V) {
+                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
+                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
+                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
+                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
+            }
+        }
         if (dremote) {
             SPP_HIP(hipEventRecord(ctx->ev_fork, st));
             SPP_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
             {
                 ScopedTimer tm(ctx, SPP_T_GATHER_MISS, ctx->side);
                 const int64_t* miss_count = reinterpret_cast<const int64_t*>(counters + 2);
+                const char* src = static_cast<const char*>(dremote);
                 switch (V) {
-                    case 16: launch_indexed<16>(mgrid, ctx->side, dremote, a.desc, a.misslist, 0, miss_count, row_bytes, d_out); break;
-                    case 8:  launch_indexed<8>(mgrid, ctx->side, dremote, a.desc, a.misslist, 0, miss_count, row_bytes, d_out); break;
-                    case 4:  launch_indexed<4>(mgrid, ctx->side, dremote, a.desc, a.misslist, 0, miss_count, row_bytes, d_out); break;
-                    default: launch_indexed<2>(mgrid, ctx->side, dremote, a.desc, a.misslist, 0, miss_count, row_bytes, d_out); break;
+                    case 16: gather_miss_kernel<16><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
+                    case 8:  gather_miss_kernel<8><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
+                    case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
+                    default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
                 }
             }
             SPP_HIP(hipEventRecord(ctx->ev_join, ctx->side));
-        }
-        {
-            ScopedTimer th(ctx, SPP_T_GATHER_HIT, st);
-            switch (V) {
-                case 16: launch_hit<16>(grid, st, a.desc, n, d_n, d_local, crow, row_bytes, d_out); break;
-                case 8:  launch_hit<8>(grid, st, a.desc, n, d_n, d_local, crow, row_bytes, d_out); break;
-                case 4:  launch_hit<4>(grid, st, a.desc, n, d_n, d_local, crow, row_bytes, d_out); break;
-                default: launch_hit<2>(grid, st, a.desc, n, d_n, d_local, crow, row_bytes, d_out); break;
-            }
         }
         if (dremote) SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
     }
@@ -242,6 +281,15 @@ extern "C" int spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const v
         return spp_gather_last_stats(ctx, stats);
     }
     return SPP_OK;
+}
+
+extern "C" int spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
+                                   int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                                   int32_t elem_bytes, const int32_t* d_node_ids, int64_t n,
+                                   const int64_t* d_n, void* d_out, spp_gather_stats* stats, uint32_t flags) {
+    spp_gather_list one;
+    one.d_node_ids = d_node_ids; one.n = n; one.d_n = d_n; one.d_out = d_out;
+    return spp_gather_features_multi(ctx, cache, d_local, N, lo, hi, remote, D, elem_bytes, &one, 1, stats, flags);
 }
 
 extern "C" int spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats) {

@@ -266,6 +266,37 @@ def test_gather_edge_cases(spp, ctx, tiny_case):
     assert torch.equal(out.cpu(), full[ids.cpu().long()])
 
 
+def test_gather_multi_lists(spp, ctx, tiny_case):
+    """Several id lists in one call: same rows as one call per list, summed statistics."""
+    c = tiny_case
+    cfg = c.cfg
+    _say("gather multi: lists of 0, 1, 2047, 2048, 2049 and 7000 ids, one with a device count")
+    p = spp.vip_propagate(ctx, c.G, c.Tk_d, cfg.B, cfg.fanouts)
+    cache = spp.build_vip_cache(ctx, p, c.lo, c.hi, cfg.K, cfg.alpha, c.remote, cfg.D, cfg.elem_bytes)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    sizes = [0, 1, 2047, 2048, 2049, 7000]
+    lists, singles, tot = [], [], dict(n_local=0, n_cache_hit=0, n_miss=0)
+    for k, n in enumerate(sizes):
+        ids = torch.randint(0, cfg.N, (n + 5,), device="cuda", generator=g, dtype=torch.int32)
+        out = torch.zeros((n + 5, cfg.D), dtype=torch.float32, device="cuda")
+        n_dev = torch.tensor([n], dtype=torch.int64, device="cuda") if k == 4 else None
+        lists.append((ids, n + 5 if n_dev is not None else n, n_dev, out))
+        ref, st = spp.gather_features(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, ids, n=n)
+        singles.append(ref)
+        for key in tot:
+            tot[key] += st[key]
+    st = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists)
+    assert {k: st[k] for k in tot} == tot
+    for (ids, n, n_dev, out), ref, n0 in zip(lists, singles, sizes):
+        assert torch.equal(out[:n0], ref[:n0])
+        assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
+        assert torch.all(out[n0:] == 0)
+    with pytest.raises(spp.SppError):
+        spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists * 3)   # 18 lists
+    cache.close()
+
+
 # ----------------------------------------------------------------------------------------------
 # scaled copies of the other configs: several tiles, ragged tails, hubs, 16-bit rows
 # ----------------------------------------------------------------------------------------------
