@@ -27,6 +27,45 @@ def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
+def alpha_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi):
+    """Cache quality over the replication factor: VIP-ranked against degree-ranked (Sec. 3.2, Fig. 2)."""
+    alphas = [0.0, 0.05, 0.1, 0.2, 0.5]
+    row_bytes = cfg.D * cfg.elem_bytes
+    # "deg.": in-list count (how many vertices can sample u), only for vertices reachable from the
+    # partition's training set (p > 0)
+    indeg = torch.bincount(g.col.long(), minlength=g.N).to(torch.float32)
+    deg_score = torch.where(p > 0, indeg, torch.zeros_like(indeg))
+    del indeg
+    batches = [b for b in S.epoch_batches(cfg, Tk, 0) if b.numel() == min(cfg.B, Tk.numel())][:args.sweep_batches]
+    bufs = spp.MFGBuffers(local.device, cfg.B, cfg.fanouts, cfg.N)
+    out = torch.empty((bufs.nb[-1], cfg.D), dtype=cfg.torch_dtype, device=local.device)
+    rows = []
+    for policy, score in (("vip", p), ("degree", deg_score)):
+        cache = spp.build_vip_cache(ctx, score, lo, hi, cfg.K, max(alphas), remote, cfg.D, cfg.elem_bytes)
+        for a in alphas:
+            cache.set_limit(min(cfg.cache_capacity(a), cache.n_cached))
+            tot = dict(n_local=0, n_cache_hit=0, n_miss=0)
+            ctx.timing(True)
+            for i, seeds in enumerate(batches):
+                m = spp.sample_mfg(ctx, G, seeds, cfg.fanouts, cfg.seed_sampler, i, out=bufs)
+                _, st = spp.gather_features(ctx, cache, local, cfg.N, lo, hi, remote, bufs.node_ids, n=m.n[-1], out=out)
+                for k in tot:
+                    tot[k] += st[k]
+            ms, cnt = ctx.times()
+            ctx.timing(False)
+            nb = len(batches)
+            remote_rows = tot["n_cache_hit"] + tot["n_miss"]
+            rows.append({"policy": policy, "alpha": a, "cached_rows": min(cfg.cache_capacity(a), cache.n_cached),
+                         "hit_rate_of_remote": tot["n_cache_hit"] / max(remote_rows, 1),
+                         "miss_rows_per_batch": tot["n_miss"] / nb,
+                         "host_miss_bytes_per_batch": tot["n_miss"] * row_bytes / nb,
+                         "gather_hit_ms": ms[10] / max(cnt[10], 1), "gather_miss_ms": ms[11] / max(cnt[11], 1)})
+            log(rows[-1])
+        cache.close()
+    print(json.dumps({"phase": "alpha-sweep", "workload": cfg.name, "N": g.N, "M": g.M, "batches": len(batches),
+                      "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,6 +79,11 @@ def main():
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
                          "(pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
+    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep"],
+                    help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
+                         "alpha-sweep: hit rate and host-miss bytes per batch over alpha in {0,.05,.1,.2,.5}, VIP-ranked "
+                         "against degree-ranked cache (the experiment shape of Fig. 2 / Fig. 7), e.g. with --config skew")
+    ap.add_argument("--sweep-batches", type=int, default=8)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition's share of the method); "
@@ -91,8 +135,18 @@ def main():
     vip_hop_bytes = 4 * g.M + 8 * (g.N + 1) + 4 * g.N + 4 * g.N
     worst = max(vip_hop_ms)
     vip_roof = {"bound": "hbm", "achieved": vip_hop_bytes / (worst * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "kernel": "vip_pull_kernel (slowest hop)", "traffic": None}
+                "unit": "GB/s", "kernel": "vip_pull_kernel (slowest hop, a dense one: all M edges)", "traffic": None}
     vip_roof["frac"] = vip_roof["achieved"] / HBM_PEAK_GBS
+    vip_pushed, vip_frontier_edges = spp.vip_last_hops(ctx, cfg.L)
+    if args.phase == "vip":
+        print(json.dumps({"phase": "vip", "workload": cfg.name, "N": g.N, "M": g.M, "ms_total": vip_total_ms,
+                          "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
+                          "hop_pushed_over_sparse_frontier": vip_pushed,
+                          "frontier_out_edges_per_hop": vip_frontier_edges}), flush=True)
+        return
+    if args.phase == "alpha-sweep":
+        alpha_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
+        return
     t = time.time()
     cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)
     torch.cuda.synchronize()
@@ -235,6 +289,7 @@ def main():
         "kernels_ms": {"sample_mfg_per_batch": sample_ms, "gather_classify_per_launch": cls_ms,
                        "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms},
         "vip": {"ms_total": vip_total_ms, "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
+                "hop_pushed_over_sparse_frontier": vip_pushed, "frontier_out_edges_per_hop": vip_frontier_edges,
                 "in_lists_build_s": t_inlists, "cache_build_s": cache_s, "n_cached": cache.n_cached},
     }
     print(json.dumps(line), flush=True)

@@ -82,13 +82,21 @@ void spp_graph_destroy(spp_graph* g);
  *       p^[0](u) = min(1, B/nT) for u in T, else 0
  *       p^[h](u) = 1 - prod over {v : u in adj(v)} of (1 - min(1, f_h/d(v)) * p^[h-1](v))    eq. (2)
  *       p(u)     = 1 - prod_{h=1..L} (1 - p^[h](u))                                         eq. (1)
- *     Products are carried as sums of log1p in fp64; results are stored as fp32.
+ *     Products are carried as sums of log1p in fp64; results are stored as fp32.  The call waits
+ *     for the device once per hop (it reads the size of the hop's frontier to choose between the
+ *     push and the pull form).
  *     d_p_total: fp32[N], required.  d_p_hop: fp32[L*N] (hop h at offset (h-1)*N) or NULL.
  *     flags: SPP_VIP_INCLUDE_HOP0, SPP_SYNC.  The graph must have been created with
  *     SPP_GRAPH_IN_LISTS (else SPP_E_ARG).  Vertices with d(v) = 0 contribute nothing. */
 int  spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t* d_T, int64_t nT,
                        int32_t B, const int32_t* fanouts, int32_t L,
                        float* d_p_total, float* d_p_hop, uint32_t flags);
+
+/* How the last spp_vip_propagate on this context walked each hop: pushed[h-1] = 1 if hop h was done
+ * in push form over a sparse frontier (its out-edges were at most M/16), 0 if it was pulled over
+ * the in-lists; frontier_edges[h-1] = out-edges of the vertices with a non-zero weight at hop h
+ * (the edges a hop has to touch at all).  Either array may be NULL. */
+int  spp_vip_last_hops(spp_ctx* ctx, int32_t* pushed, int64_t* frontier_edges, int32_t L);
 
 /* (2) Replica cache (Sec. 3.2): among the vertices outside [lo,hi) with d_score > 0, the first
  *     C = floor(alpha*N/K) in the order (score descending as fp32, id ascending); slot = rank.

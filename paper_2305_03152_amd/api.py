@@ -25,7 +25,7 @@ SPP_T_GATHER_HIT, SPP_T_GATHER_MISS, SPP_T_GATHER_CLASSIFY, SPP_T_COUNT = 10, 11
 
 EXPORTS = [
     "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
-    "spp_graph_destroy", "spp_vip_propagate", "spp_build_vip_cache", "spp_cache_destroy",
+    "spp_graph_destroy", "spp_vip_propagate", "spp_vip_last_hops", "spp_build_vip_cache", "spp_cache_destroy",
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg",
     "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
 ]
@@ -83,6 +83,7 @@ def load_library():
     lib.spp_graph_destroy.argtypes = [C.c_void_p]
     lib.spp_vip_propagate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                       C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
+    lib.spp_vip_last_hops.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.c_int32]
     lib.spp_build_vip_cache.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
                                         C.c_double, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                         C.POINTER(C.c_int64), C.POINTER(C.c_void_p)]
@@ -209,6 +210,14 @@ def vip_propagate(ctx: Context, graph: Graph, T: torch.Tensor, B: int, fanouts: 
     _check(load_library().spp_vip_propagate(ctx._h, graph._h, _ptr(T), T.numel(), int(B), f, L, _ptr(p_total),
                                             _ptr(p_hop), flags))
     return (p_total, p_hop) if per_hop else p_total
+
+
+def vip_last_hops(ctx: Context, L: int):
+    """Per hop of the last vip_propagate: (pushed over a sparse frontier?, out-edges of the frontier)."""
+    pushed = (C.c_int32 * L)()
+    edges = (C.c_int64 * L)()
+    _check(load_library().spp_vip_last_hops(ctx._h, pushed, edges, L))
+    return [bool(x) for x in pushed], [int(x) for x in edges]
 
 
 class Cache:

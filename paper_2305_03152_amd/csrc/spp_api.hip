@@ -62,7 +62,7 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     if (c->totals) (void)hipFree(c->totals);
     c->table.release(); c->flat.release(); c->partials.release();
     c->srcdesc.release(); c->misslist.release(); c->gcount.release();
-    c->y0.release(); c->y1.release(); c->tot.release(); c->hubacc.release();
+    c->y0.release(); c->y1.release(); c->tot.release(); c->hubacc.release(); c->acc.release(); c->frontier.release();
     delete c;
 }
 
@@ -106,5 +106,14 @@ extern "C" int spp_ctx_totals(spp_ctx* c, int64_t* out, int reset) {
     SPP_TRY(spp_ctx_sync(c));
     SPP_HIP(hipMemcpy(out, c->totals, 8 * sizeof(int64_t), hipMemcpyDeviceToHost));
     if (reset) SPP_HIP(hipMemset(c->totals, 0, 8 * sizeof(int64_t)));
+    return SPP_OK;
+}
+
+extern "C" int spp_vip_last_hops(spp_ctx* c, int32_t* pushed, int64_t* frontier_edges, int32_t L) {
+    SPP_CHECK(c != nullptr && L >= 0 && L <= SPP_MAX_L, SPP_E_ARG, "spp_vip_last_hops: bad argument");
+    for (int h = 0; h < L; ++h) {
+        if (pushed) pushed[h] = c->vip_pushed[h];
+        if (frontier_edges) frontier_edges[h] = c->vip_frontier_edges[h];
+    }
     return SPP_OK;
 }

@@ -81,7 +81,9 @@ struct spp_ctx {
     int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
     int64_t*    totals = nullptr;       // device int64[8], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces
-    spp::DevBuf y0, y1, tot, hubacc;
+    spp::DevBuf y0, y1, tot, hubacc, acc, frontier;
+    int         vip_pushed[SPP_MAX_L] = {};          // last vip_propagate: hop done in push form?
+    int64_t     vip_frontier_edges[SPP_MAX_L] = {};  // last vip_propagate: out-edges of each hop's frontier
     // timing: while enabled every timed piece of device work gets its own pair of events
     int         timing = 0;
     struct Span { int idx; hipEvent_t t0, t1; };

@@ -11,10 +11,17 @@
 // then sums one row from LDS in fp64 and finishes the vertex (p^[h], running total, next hop's y)
 // in the same kernel.  Rows longer than a chunk (hubs) are split into slices over many workgroups
 // and combined with fp64 atomic adds.
+//
+// Early hops touch few edges (hop 1 only the rows of T), so before each hop the vertices with
+// y != 0 are compacted into a frontier and their out-edges counted; when that is a small share of
+// the graph the hop is done in push form instead: each frontier vertex adds its y to the fp64
+// accumulator of every member of its row (atomic adds), and one pass finishes all vertices.
 #include "spp_common.h"
 #include "spp_device.h"
 
 namespace spp {
+
+constexpr int64_t kPushShare = 16;       // push when the frontier's out-edges are at most M/16
 
 struct VipHop {
     const int64_t* rowptr;     // forward CSR, for d(u)
@@ -115,7 +122,7 @@ __global__ void __launch_bounds__(kBlock) vip_hub_slice_kernel(VipHop a, const i
     for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_down(s, off, kWave);
     if (lane_id() == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(&hubacc[k], red[0] + red[1] + red[2] + red[3]);
+    if (threadIdx.x == 0) unsafeAtomicAdd(&hubacc[k], red[0] + red[1] + red[2] + red[3]);
 }
 
 __global__ void vip_hub_finish_kernel(VipHop a, const int32_t* __restrict__ hub_rows, int64_t nhub,
@@ -131,6 +138,75 @@ __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
 __global__ void fill_f64_kernel(double* p, int64_t n, double v) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
+// Size of a hop's frontier: counters[0] = vertices whose y is not zero, counters[1] = their out-edges.
+__global__ void __launch_bounds__(kBlock) vip_frontier_stats_kernel(const float* __restrict__ y,
+                                                                    const int64_t* __restrict__ rowptr, int64_t N,
+                                                                    unsigned long long* __restrict__ counters) {
+    unsigned long long verts = 0, edges = 0;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < N; v += stride) {
+        if (y[v] != 0.0f) { ++verts; edges += (unsigned long long)(rowptr[v + 1] - rowptr[v]); }
+    }
+    // one pair of atomics per workgroup: atomics on one address cost ~15 ns each, back to back
+    __shared__ unsigned long long red[2][4];
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        verts += __shfl_down((long long)verts, off, kWave);
+        edges += __shfl_down((long long)edges, off, kWave);
+    }
+    if (lane_id() == 0) { red[0][threadIdx.x >> 6] = verts; red[1][threadIdx.x >> 6] = edges; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long tv = red[0][0] + red[0][1] + red[0][2] + red[0][3];
+        const unsigned long long te = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+        if (tv) { atomicAdd(&counters[0], tv); atomicAdd(&counters[1], te); }
+    }
+}
+
+// The frontier itself (any order): list[0 .. *cursor) = vertices whose y is not zero.
+__global__ void __launch_bounds__(kBlock) vip_frontier_list_kernel(const float* __restrict__ y, int64_t N,
+                                                                   int32_t* __restrict__ list,
+                                                                   unsigned long long* __restrict__ cursor) {
+    const int lane = lane_id();
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const int64_t n_round = (N + kWave - 1) / kWave * kWave;      // whole wavefronts reach the ballot
+    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n_round; v += stride) {
+        const bool in = v < N && y[v] != 0.0f;
+        const uint64_t m = __ballot(in);
+        if (m) {
+            const int leader = __ffsll((unsigned long long)m) - 1;
+            unsigned long long base = 0;
+            if (lane == leader) base = atomicAdd(cursor, (unsigned long long)__popcll(m));
+            base = __shfl((long long)base, leader, kWave);
+            if (in) list[base + __popcll(m & lt_mask)] = (int32_t)v;
+        }
+    }
+}
+
+// Push form of eq. (2): one wavefront per frontier vertex adds y(v) into the accumulator of every
+// member of adj(v).
+__global__ void __launch_bounds__(kBlock) vip_push_kernel(const int32_t* __restrict__ list, int64_t nf,
+                                                          const float* __restrict__ y,
+                                                          const int64_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ col,
+                                                          double* __restrict__ acc) {
+    const int lane = lane_id();
+    const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+    for (int64_t i = wave; i < nf; i += nwaves) {
+        const int64_t v = list[i];
+        const double yv = (double)y[v];
+        const int64_t b = rowptr[v], e = rowptr[v + 1];
+        for (int64_t k = b + lane; k < e; k += kWave) unsafeAtomicAdd(&acc[col[k]], yv);   // hardware fp64 add
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) vip_push_finish_kernel(VipHop a, const double* __restrict__ acc, int64_t N) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) vip_finish_vertex(a, u, acc[u]);
 }
 
 // y_1(v) for the training vertices (p^[0] = min(1, B/|T|), Sec. 3.1); optionally hop 0 into the total.
@@ -169,6 +245,10 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
     SPP_TRY(ctx->y1.reserve((size_t)N * sizeof(float)));
     SPP_TRY(ctx->tot.reserve((size_t)N * sizeof(double) + sizeof(int)));
     SPP_TRY(ctx->hubacc.reserve((size_t)(g->nhub > 0 ? g->nhub : 1) * sizeof(double)));
+    SPP_TRY(ctx->acc.reserve((size_t)N * sizeof(double)));
+    SPP_TRY(ctx->frontier.reserve((size_t)(N + 2) * sizeof(int32_t) + 4 * sizeof(unsigned long long)));
+    int32_t* flist = ctx->frontier.as<int32_t>();
+    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (N + (N & 1)));
     float* ycur = ctx->y0.as<float>();
     float* ynext = ctx->y1.as<float>();
     double* tot = ctx->tot.as<double>();
@@ -195,13 +275,34 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
             a.f_next = h < L ? (double)fanouts[h] : 0.0;
             a.first = (h == 1 && !include0) ? 1 : 0;
             a.last = (h == L) ? 1 : 0;
-            if (g->nhub > 0) {
-                fill_f64_kernel<<<(unsigned)((g->nhub + kBlock - 1) / kBlock), kBlock, 0, st>>>(ctx->hubacc.as<double>(), g->nhub, 0.0);
-                vip_hub_slice_kernel<<<(unsigned)g->nslices, kBlock, 0, st>>>(a, g->hub_rows, g->hub_slice_ptr, g->nhub, ctx->hubacc.as<double>());
+            // frontier of this hop and its out-edges; a small frontier is pushed, a large one pulled
+            fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount), 3, 0.0);
+            vip_frontier_stats_kernel<<<ctx->num_cu * 2, kBlock, 0, st>>>(ycur, g->rowptr, N, fcount);
+            volatile unsigned long long* fc = reinterpret_cast<volatile unsigned long long*>(ctx->h_pinned + 56);
+            SPP_HIP(hipMemcpyAsync(ctx->h_pinned + 56, fcount, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+            SPP_HIP(hipStreamSynchronize(st));
+            const bool push = (int64_t)fc[1] * kPushShare <= g->M;
+            if (push) {
+                double* acc = ctx->acc.as<double>();
+                fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
+                if (fc[0] > 0) {
+                    vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(ycur, N, flist, fcount + 2);
+                    const int64_t need = ((int64_t)fc[0] * kWave + kBlock - 1) / kBlock;
+                    const int pgrid = (int)(need < (int64_t)ctx->num_cu * 32 ? need : (int64_t)ctx->num_cu * 32);
+                    vip_push_kernel<<<pgrid, kBlock, 0, st>>>(flist, (int64_t)fc[0], ycur, g->rowptr, g->col, acc);
+                }
+                vip_push_finish_kernel<<<fill_grid, kBlock, 0, st>>>(a, acc, N);
+            } else {
+                if (g->nhub > 0) {
+                    fill_f64_kernel<<<(unsigned)((g->nhub + kBlock - 1) / kBlock), kBlock, 0, st>>>(ctx->hubacc.as<double>(), g->nhub, 0.0);
+                    vip_hub_slice_kernel<<<(unsigned)g->nslices, kBlock, 0, st>>>(a, g->hub_rows, g->hub_slice_ptr, g->nhub, ctx->hubacc.as<double>());
+                }
+                vip_pull_kernel<<<(unsigned)g->nblk, kBlock, 0, st>>>(a, g->blk_row);
+                if (g->nhub > 0)
+                    vip_hub_finish_kernel<<<(unsigned)((g->nhub + kBlock - 1) / kBlock), kBlock, 0, st>>>(a, g->hub_rows, g->nhub, ctx->hubacc.as<double>());
             }
-            vip_pull_kernel<<<(unsigned)g->nblk, kBlock, 0, st>>>(a, g->blk_row);
-            if (g->nhub > 0)
-                vip_hub_finish_kernel<<<(unsigned)((g->nhub + kBlock - 1) / kBlock), kBlock, 0, st>>>(a, g->hub_rows, g->nhub, ctx->hubacc.as<double>());
+            ctx->vip_pushed[h - 1] = push ? 1 : 0;
+            ctx->vip_frontier_edges[h - 1] = (int64_t)fc[1];
             float* t = ycur; ycur = ynext; ynext = t;
         }
     }
