@@ -73,7 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="mid", help="workload: tiny | mid (default, the metric's configuration)")
     ap.add_argument("--vip-reps", type=int, default=5)
-    ap.add_argument("--pipeline", type=int, default=2,
+    ap.add_argument("--pipeline", type=int, default=1,
                     help="lanes: contexts (each with its own stream and buffers) used round-robin")
     ap.add_argument("--group", type=int, default=8,
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
@@ -160,32 +160,41 @@ def main():
         batches.extend(b for b in S.epoch_batches(cfg, Tk, ep) if b.numel() == min(cfg.B, Tk.numel()))
         ep += 1
     batches = batches[:W + K]
-    # A lane = one context (stream, workspaces) with `group` sets of MFG buffers and output rows.
-    # A lane samples `group` minibatches back to back, then gathers all of them with one
-    # classification, one hit copy and one miss copy; lanes alternate, so the sampling of one
-    # lane overlaps the PCIe misses of the other.
+    # A lane = one context (stream, side stream, workspaces) with two sets of `group` MFG buffers and
+    # output rows, used alternately.  Per group the lane samples `group` minibatches back to back,
+    # then gathers all of them with one classification, one hit copy and one miss copy.  The miss
+    # copy is left running on the side stream (SPP_NO_JOIN) while the lane samples the next group
+    # into its other buffer set; the stream joins it (where a consumer of the rows would sit) just
+    # before the next gather.  One lane already keeps the PCIe link busy; more lanes only contend.
     P = max(1, args.pipeline)
     Gsz = max(1, min(args.group, 16))
     lanes = []
     for k in range(P):
         c = ctx if k == 0 else spp.Context(0, stream=torch.cuda.Stream(dev))
-        b = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N) for _ in range(Gsz)]
-        o = [torch.empty((b[0].nb[-1], cfg.D), dtype=cfg.torch_dtype, device=dev) for _ in range(Gsz)]
-        lanes.append((c, b, o))
-    bufs, out = lanes[0][1][0], lanes[0][2][0]
+        sets = []
+        for _ in range(2):
+            b = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N) for _ in range(Gsz)]
+            o = [torch.empty((b[0].nb[-1], cfg.D), dtype=cfg.torch_dtype, device=dev) for _ in range(Gsz)]
+            sets.append((b, o))
+        lanes.append((c, sets, None))
+    bufs, out = lanes[0][1][0][0][0], lanes[0][1][0][1][0]
 
     def run(first, count):
         """Enqueue minibatches first .. first+count-1 (no host synchronisation inside)."""
         gi = 0
         for g0 in range(first, first + count, Gsz):
-            c, b, o = lanes[gi % P]
+            c, sets, _ = lanes[gi % P]
+            b, o = sets[(gi // P) % 2]
             gi += 1
             idx = range(g0, min(g0 + Gsz, first + count))
             for k, i in enumerate(idx):
                 spp.sample_mfg(c, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=b[k], sync=False)
+            spp.gather_join(c)          # rows of the lane's previous group are complete from here on
             spp.gather_features_multi(c, cache, local, cfg.N, lo, hi, remote,
                                       [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(len(idx))],
-                                      sync=False)
+                                      sync=False, join=False)
+        for c, _, _ in lanes:
+            spp.gather_join(c)
 
     torch.cuda.synchronize()
     run(0, W)
@@ -280,7 +289,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={g.N} M={g.M} D={cfg.D} {cfg.dtype} fanouts={list(cfg.fanouts)} "
                                f"B={cfg.B} K={cfg.K} alpha={cfg.alpha} owned partition {cfg.owned_partition}",
-                   "lanes": P, "minibatches_per_gather_launch": Gsz, "minibatches_in_flight": P * Gsz,
+                   "lanes": P, "minibatches_per_gather_launch": Gsz, "minibatches_in_flight": 2 * P * Gsz,
                    "avg_per_batch": {k: round(v, 1) for k, v in avg.items()},
                    "hit_rate_of_remote": avg["n_cache_hit"] / max(avg["n_cache_hit"] + avg["n_miss"], 1e-9)},
         "roofline": roof,

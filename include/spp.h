@@ -55,6 +55,7 @@ enum {
 #define SPP_SYNC              0x1u   /* wait for the stream before returning and fill host outputs */
 #define SPP_VIP_INCLUDE_HOP0  0x2u   /* also multiply (1 - p^[0]) into eq. (1); default: as printed, h = 1..L */
 #define SPP_GRAPH_IN_LISTS    0x4u   /* spp_graph_create: also build the in-lists vip_propagate needs */
+#define SPP_NO_JOIN           0x8u   /* gather: leave the miss copy running on the side stream; see spp_gather_join */
 
 typedef struct spp_ctx   spp_ctx;    /* workspaces, side stream, events */
 typedef struct spp_graph spp_graph;  /* refers to the caller's CSR; owns the library-built in-lists */
@@ -169,6 +170,12 @@ int  spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_loc
                          const int32_t* d_node_ids, int64_t n, const int64_t* d_n, void* d_out,
                          spp_gather_stats* stats, uint32_t flags);
 int  spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats);
+/* With SPP_NO_JOIN a gather returns to the context's stream as soon as the hit copy is enqueued,
+ * while the missed rows are still arriving on the side stream; work enqueued next on the stream
+ * (the sampling of the following minibatches) overlaps the PCIe transfer.  spp_gather_join makes
+ * the stream wait for that miss copy: call it before anything that reads the gathered rows.  The
+ * next gather on the same context, spp_ctx_sync and SPP_SYNC join by themselves. */
+int  spp_gather_join(spp_ctx* ctx);
 
 /* The same gather for up to SPP_MAX_GATHER_LISTS id lists in one set of launches (one
  * classification, one hit copy, one miss copy), e.g. the minibatches a pipeline keeps in flight

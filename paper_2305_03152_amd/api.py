@@ -20,6 +20,7 @@ SPP_MAX_FANOUT = 64
 SPP_SYNC = 0x1
 SPP_VIP_INCLUDE_HOP0 = 0x2
 SPP_GRAPH_IN_LISTS = 0x4
+SPP_NO_JOIN = 0x8
 SPP_T_VIP_TOTAL, SPP_T_VIP_HOP_FIRST, SPP_T_SAMPLE = 0, 1, 9
 SPP_T_GATHER_HIT, SPP_T_GATHER_MISS, SPP_T_GATHER_CLASSIFY, SPP_T_COUNT = 10, 11, 12, 16
 
@@ -27,7 +28,7 @@ EXPORTS = [
     "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
     "spp_graph_destroy", "spp_vip_propagate", "spp_vip_last_hops", "spp_build_vip_cache", "spp_cache_destroy",
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg",
-    "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
+    "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
 ]
 
 
@@ -101,6 +102,7 @@ def load_library():
                                               C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_GatherList), C.c_int32,
                                               C.POINTER(_GatherStats), C.c_uint32]
     lib.spp_gather_last_stats.argtypes = [C.c_void_p, C.POINTER(_GatherStats)]
+    lib.spp_gather_join.argtypes = [C.c_void_p]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
     lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
     lib.spp_ctx_totals.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_int]
@@ -361,7 +363,7 @@ def gather_features(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N
 
 
 def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,
-                          remote: Optional[torch.Tensor], lists, sync: bool = True):
+                          remote: Optional[torch.Tensor], lists, sync: bool = True, join: bool = True):
     """One classification / hit copy / miss copy over several id lists.
 
     `lists` is a sequence of (node_ids, n, n_device or None, out); returns the summed stats when sync.
@@ -383,10 +385,15 @@ def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Ten
     st = _GatherStats()
     _check(load_library().spp_gather_features_multi(ctx._h, cache._h if cache is not None else None, _ptr(local),
                                                     int(N), int(lo), int(hi), _ptr(remote), D, eb, arr, len(lists),
-                                                    C.byref(st), SPP_SYNC if sync else 0))
+                                                    C.byref(st), (SPP_SYNC if sync else 0) | (0 if join else SPP_NO_JOIN)))
     if sync:
         return dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)
     return None
+
+
+def gather_join(ctx: Context):
+    """Make the context's stream wait for a miss copy left running by a gather called with join=False."""
+    _check(load_library().spp_gather_join(ctx._h))
 
 
 def gather_last_stats(ctx: Context):

@@ -70,6 +70,7 @@ extern "C" int spp_ctx_sync(spp_ctx* c) {
     SPP_CHECK(c != nullptr, SPP_E_ARG, "spp_ctx_sync: ctx is null");
     SPP_HIP(hipStreamSynchronize(c->stream));
     SPP_HIP(hipStreamSynchronize(c->side));
+    c->join_pending = false;
     return SPP_OK;
 }
 

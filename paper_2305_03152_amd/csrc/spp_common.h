@@ -69,6 +69,7 @@ struct spp_ctx {
     hipStream_t stream = nullptr;       // caller's stream
     hipStream_t side = nullptr;         // miss path
     hipEvent_t  ev_fork = nullptr, ev_join = nullptr;
+    bool        join_pending = false;   // a miss copy was left running on the side stream (SPP_NO_JOIN)
     int         num_cu = 256;
     // sampling workspaces
     spp::DevBuf table;                  // uint64 hash table: global id -> local id / first position

@@ -202,6 +202,12 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
     a.t.n_lists = pro.n_lists = n_lists;
 
     hipStream_t st = ctx->stream;
+    // a miss copy left running by an earlier SPP_NO_JOIN call still reads this context's
+    // descriptors and miss list: the stream waits for it before they are overwritten
+    if (ctx->join_pending) {
+        SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
+        ctx->join_pending = false;
+    }
     SPP_TRY(ctx->gcount.reserve((8 + 2 * (kMaxLists + 1)) * sizeof(int64_t)));
     unsigned long long* counters = ctx->gcount.as<unsigned long long>();
     int64_t* off = ctx->gcount.as<int64_t>() + 8;
@@ -269,16 +275,30 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
             }
             SPP_HIP(hipEventRecord(ctx->ev_join, ctx->side));
         }
-        if (dremote) SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
+        if (dremote) {
+            if (flags & SPP_NO_JOIN) ctx->join_pending = true;
+            else SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
+        }
     }
     SPP_HIP(hipGetLastError());
     int64_t* hp = ctx->h_pinned + 40;
+    // the counters are final once the classification has run, whether or not the misses have landed
     SPP_HIP(hipMemcpyAsync(hp, counters, 4 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
     ctx->h_pinned[48] = row_bytes;
     ctx->h_pinned[49] = dremote ? 1 : 0;
     if (flags & SPP_SYNC) {
+        SPP_TRY(spp_gather_join(ctx));
         SPP_HIP(hipStreamSynchronize(st));
         return spp_gather_last_stats(ctx, stats);
+    }
+    return SPP_OK;
+}
+
+extern "C" int spp_gather_join(spp_ctx* ctx) {
+    SPP_CHECK(ctx, SPP_E_ARG, "spp_gather_join: ctx is null");
+    if (ctx->join_pending) {
+        SPP_HIP(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+        ctx->join_pending = false;
     }
     return SPP_OK;
 }

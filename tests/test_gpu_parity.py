@@ -294,6 +294,20 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
         assert torch.all(out[n0:] == 0)
     with pytest.raises(spp.SppError):
         spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists * 3)   # 18 lists
+    # miss copy left running on the side stream while the stream samples the next minibatch, joined later
+    _say("gather multi: deferred join")
+    for (_, _, _, out) in lists:
+        out.zero_()
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists, sync=False, join=False)
+    m = spp.sample_mfg(ctx, c.G, torch.from_numpy(c.Tk[:64]).cuda(), (3, 2), 5, 1, sync=False)
+    spp.gather_join(ctx)
+    ctx.sync()
+    for (ids, n, n_dev, out), n0 in zip(lists, sizes):
+        assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
+    # and a second gather right after a deferred one joins by itself
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists[3:], sync=False, join=False)
+    st2 = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists[:3])
+    assert st2["n_local"] + st2["n_cache_hit"] + st2["n_miss"] == sum(sizes[:3])
     cache.close()
 
 
