@@ -59,11 +59,13 @@ __global__ void gather_prologue_kernel(PrologueArgs p, unsigned long long* count
 __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
     __shared__ int scan_lds[4];
     __shared__ unsigned long long base_lds;
-    const int64_t total = a.t.off[a.t.n_lists];
+    __shared__ ListLds ls;
+    load_lists(a.t, ls);
+    const int64_t total = ls.off[a.t.n_lists];
     int n_local = 0, n_hit = 0;
     for (int64_t base = (int64_t)blockIdx.x * kListAlign; base < total; base += (int64_t)gridDim.x * kListAlign) {
-        const int j = list_of(a.t, base);
-        const int64_t lbeg = a.t.off[j], n = a.t.cnt[j];
+        const int j = list_of(ls, a.t.n_lists, base);
+        const int64_t lbeg = ls.off[j], n = ls.cnt[j];
         const int32_t* __restrict__ ids = a.t.ids[j];
         uint32_t missbits = 0;
 #pragma unroll

@@ -51,10 +51,21 @@ struct ListTable {
     int            n_lists;
 };
 
+// The offsets and counts are read many times by every workgroup: a copy in LDS keeps the search for
+// a row's list off the global-memory latency path.
+struct ListLds {
+    int64_t off[kMaxLists + 1];
+    int64_t cnt[kMaxLists];
+};
+__device__ __forceinline__ void load_lists(const ListTable& t, ListLds& s) {
+    if (threadIdx.x <= (unsigned)t.n_lists) s.off[threadIdx.x] = t.off[threadIdx.x];
+    if (threadIdx.x < (unsigned)t.n_lists) s.cnt[threadIdx.x] = t.cnt[threadIdx.x];
+    __syncthreads();
+}
 // Index of the list that owns virtual row r (r < off[n_lists]).
-__device__ __forceinline__ int list_of(const ListTable& t, int64_t r) {
+__device__ __forceinline__ int list_of(const ListLds& s, int n_lists, int64_t r) {
     int j = 0;
-    while (j + 1 < t.n_lists && r >= t.off[j + 1]) ++j;
+    while (j + 1 < n_lists && r >= s.off[j + 1]) ++j;
     return j;
 }
 
@@ -69,17 +80,19 @@ __global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __res
                                                             const char* __restrict__ local,
                                                             const char* __restrict__ cache, uint32_t vpr) {
     typedef typename VecOf<V>::type vec_t;
-    const uint64_t total = (uint64_t)t.off[t.n_lists] * vpr;
+    __shared__ ListLds ls;
+    load_lists(t, ls);
+    const uint64_t total = (uint64_t)ls.off[t.n_lists] * vpr;
     const uint64_t span = (uint64_t)kBlock * U;
     for (uint64_t base = (uint64_t)blockIdx.x * span; base < total; base += (uint64_t)gridDim.x * span) {
         const uint64_t row0 = base / vpr;                        // uniform: picks the list of this span
-        const int j = list_of(t, (int64_t)row0);
-        const uint64_t vbeg = (uint64_t)t.off[j] * vpr;
-        const uint64_t vcnt = (uint64_t)t.cnt[j] * vpr;
+        const int j = list_of(ls, t.n_lists, (int64_t)row0);
+        const uint64_t vbeg = (uint64_t)ls.off[j] * vpr;
+        const uint64_t vcnt = (uint64_t)ls.cnt[j] * vpr;
         if (base - vbeg >= vcnt) continue;                       // padding after the list's last row
         const bool small = vcnt <= 0xFFFFFFFFull;                // 32-bit division is far cheaper
         char* __restrict__ out = t.out[j];
-        const int64_t* __restrict__ dl = desc + t.off[j];
+        const int64_t* __restrict__ dl = desc + ls.off[j];
         vec_t v[U];
         bool ok[U];
 #pragma unroll
@@ -115,6 +128,8 @@ __global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restr
                                                              const int64_t* __restrict__ count_ptr, ListTable t,
                                                              uint32_t vpr) {
     typedef typename VecOf<V>::type vec_t;
+    __shared__ ListLds ls;
+    load_lists(t, ls);
     const uint64_t total = (uint64_t)(*count_ptr) * vpr;
     const bool small = total <= 0xFFFFFFFFull;
     const uint64_t span = (uint64_t)kBlock * kCopyUnroll;
@@ -130,10 +145,10 @@ __global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restr
                 const uint64_t m = small ? (uint64_t)((uint32_t)c / vpr) : c / vpr;
                 const uint32_t k = (uint32_t)(c - m * vpr);
                 const int64_t r = misslist[m];
-                const int j = list_of(t, r);
+                const int j = list_of(ls, t.n_lists, r);
                 const int64_t row = desc_row(desc[r]);
                 v[u] = load_stream<V>(src + ((uint64_t)row * vpr + k) * (uint64_t)V);
-                dst[u] = t.out[j] + ((uint64_t)(r - t.off[j]) * vpr + k) * (uint64_t)V;
+                dst[u] = t.out[j] + ((uint64_t)(r - ls.off[j]) * vpr + k) * (uint64_t)V;
             }
         }
 #pragma unroll
