@@ -22,6 +22,14 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
 PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
+# same counters on a plain 1 GiB elementwise kernel (factors 2.0 and 1.0): profiles/gather_hit_mid_traffic.txt
+# and profiles/vip_pull_mid_counters.txt.  Keyed by (workload, minibatches per gather launch); other
+# shapes report null.
+MEASURED_TRAFFIC = {
+    ("mid", 8): {"gather_hit": 163.0e6 + 124.3e6, "vip_pull": 1.80e9 + 20.5e6},
+}
+
 
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
@@ -79,10 +87,12 @@ def main():
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
                          "(pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
-    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep"],
+    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
                          "alpha-sweep: hit rate and host-miss bytes per batch over alpha in {0,.05,.1,.2,.5}, VIP-ranked "
-                         "against degree-ranked cache (the experiment shape of Fig. 2 / Fig. 7), e.g. with --config skew")
+                         "against degree-ranked cache (the experiment shape of Fig. 2 / Fig. 7), e.g. with --config skew; "
+                         "calibrate: a plain elementwise pass over 1 GiB (read 1 GiB, write 1 GiB), the known-size kernel "
+                         "that scales the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
     ap.add_argument("--sweep-batches", type=int, default=8)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,6 +108,15 @@ def main():
     cfg = S.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
+    if args.phase == "calibrate":
+        x = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        y = torch.empty_like(x)
+        for _ in range(5):
+            torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
+        print(json.dumps({"phase": "calibrate", "kernel": "elementwise add", "bytes_read": x.numel() * 4,
+                          "bytes_written": y.numel() * 4, "launches": 5}), flush=True)
+        return
     K, W = args.steps, args.warmup
     lo, hi = cfg.bounds()
     row_bytes = cfg.D * cfg.elem_bytes
@@ -134,8 +153,10 @@ def main():
     # and the per-vertex result written once
     vip_hop_bytes = 4 * g.M + 8 * (g.N + 1) + 4 * g.N + 4 * g.N
     worst = max(vip_hop_ms)
+    measured = MEASURED_TRAFFIC.get((cfg.name, max(1, min(args.group, 16))), {})
     vip_roof = {"bound": "hbm", "achieved": vip_hop_bytes / (worst * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "kernel": "vip_pull_kernel (slowest hop, a dense one: all M edges)", "traffic": None}
+                "unit": "GB/s", "kernel": "vip_pull_kernel (slowest hop, a dense one: all M edges)",
+                "traffic": measured.get("vip_pull")}
     vip_roof["frac"] = vip_roof["achieved"] / HBM_PEAK_GBS
     vip_pushed, vip_frontier_edges = spp.vip_last_hops(ctx, cfg.L)
     if args.phase == "vip":
@@ -236,12 +257,13 @@ def main():
     hit_rows = (tot["n_local"] + tot["n_cache_hit"]) / n_launch
     hit_bytes = hit_rows * 2 * row_bytes                 # read the source row + write the output row
     roof = {"bound": "hbm", "achieved": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms > 0 else 0.0,
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>", "traffic": None,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>",
+            "traffic": measured.get("gather_hit") if P == 1 else None,
             "bytes_per_launch": hit_bytes, "avg_launch_ms": hit_ms}
     roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
     miss_bytes = tot["n_miss"] / max(cnt[T_MISS], 1) * row_bytes
     pcie = {"bound": "pcie", "achieved": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms > 0 else 0.0,
-            "peak": PCIE_PEAK_GBS, "unit": "GB/s", "kernel": "rows_indexed_kernel<16> (miss path)",
+            "peak": PCIE_PEAK_GBS, "unit": "GB/s", "kernel": "gather_miss_kernel<16> (miss path, side stream)",
             "bytes_per_launch": miss_bytes, "avg_launch_ms": miss_ms}
     pcie["frac"] = pcie["achieved"] / PCIE_PEAK_GBS
 
@@ -257,8 +279,8 @@ def main():
         crow = S.feature_rows(cfg, cache.ids.long())
         crow_np = (crow.view(torch.int16) if cfg.dtype == "bf16" else crow).cpu().numpy()
         nb, spent, checked = 0, 0.0, 0
-        while nb < K and spent < args.cpu_seconds:
-            i = W + nb
+        while nb < 20 * K and spent < args.cpu_seconds:
+            i = W + nb % K
             seeds = batches[i].cpu().numpy()
             c0 = time.perf_counter()
             ref = oracle.sample_mfg(rp, col, seeds, cfg.fanouts, cfg.seed_sampler, i)
@@ -279,7 +301,8 @@ def main():
                 checked += 1
             nb += 1
         cpu = {"value": nb / spent, "unit": "minibatches/s", "cores": 1, "kind": "oracle",
-               "sample": f"{nb} of the timed minibatches (sample_mfg + gather), {spent:.1f}s; {checked} checked against the HIP path"}
+               "sample": f"{nb} minibatches drawn from the {K} timed ones (sample_mfg + gather), {spent:.1f}s of one core; "
+                         f"{checked} checked against the HIP path"}
 
     line = {
         "metric": "sampled+gathered minibatches/s per partition on 1 GPU",
