@@ -208,8 +208,8 @@ def main():
             b, o = sets[(gi // P) % 2]
             gi += 1
             idx = range(g0, min(g0 + Gsz, first + count))
-            for k, i in enumerate(idx):
-                spp.sample_mfg(c, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=b[k], sync=False)
+            spp.sample_mfg_multi(c, G, [(batches[i], i, b[k]) for k, i in enumerate(idx)], cfg.fanouts,
+                                 cfg.seed_sampler, sync=False)
             spp.gather_join(c)          # rows of the lane's previous group are complete from here on
             spp.gather_features_multi(c, cache, local, cfg.N, lo, hi, remote,
                                       [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(len(idx))],
@@ -318,7 +318,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "pcie": pcie,
-        "kernels_ms": {"sample_mfg_per_batch": sample_ms, "gather_classify_per_launch": cls_ms,
+        "kernels_ms": {"sample_mfg_per_launch": sample_ms, "gather_classify_per_launch": cls_ms,
                        "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms},
         "vip": {"ms_total": vip_total_ms, "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
                 "hop_pushed_over_sparse_frontier": vip_pushed, "frontier_out_edges_per_hop": vip_frontier_edges,

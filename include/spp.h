@@ -42,6 +42,7 @@ extern "C" {
 #define SPP_MAX_L       8      /* most hops / GNN layers */
 #define SPP_MAX_FANOUT  64     /* largest fanout (one wavefront lane per slot) */
 #define SPP_MAX_GATHER_LISTS 16 /* most id lists in one spp_gather_features_multi call */
+#define SPP_MAX_SAMPLE_BATCHES 16 /* most minibatches in one spp_sample_mfg_multi call */
 
 enum {
     SPP_OK          =  0,
@@ -150,6 +151,20 @@ int  spp_mfg_bound(int32_t nseeds, const int32_t* fanouts, int32_t L, int64_t N,
 int  spp_sample_mfg(spp_ctx* ctx, const spp_graph* g, const int32_t* d_seeds, int32_t nseeds,
                     const int32_t* fanouts, int32_t L, uint64_t seed, uint64_t batch_index,
                     spp_mfg* io, uint32_t flags);
+
+/* The same sampling for up to SPP_MAX_SAMPLE_BATCHES minibatches in one set of launches (every kernel
+ * gets a second grid dimension that names the minibatch; each minibatch has its own id table and
+ * counts and its own caller-provided spp_mfg, so results are those of one call per minibatch).
+ * A single minibatch of B = 1024 seeds cannot fill 256 CUs, and its ~26 launches are latency-bound;
+ * sampling the minibatches a pipeline keeps in flight together spreads that latency over all of them. */
+typedef struct {
+    const int32_t* d_seeds;
+    int32_t        nseeds;
+    uint64_t       batch_index;
+    spp_mfg*       io;
+} spp_sample_item;
+int  spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_item* items, int32_t n_items,
+                          const int32_t* fanouts, int32_t L, uint64_t seed, uint32_t flags);
 
 /* (4) Gather: d_out[i,:] = row of vertex d_node_ids[i] (in [0, N)), i < n, taken from
  *       d_local  [hi-lo, D]  if lo <= g < hi            (row g - lo)

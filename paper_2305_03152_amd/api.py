@@ -27,7 +27,7 @@ SPP_T_GATHER_HIT, SPP_T_GATHER_MISS, SPP_T_GATHER_CLASSIFY, SPP_T_COUNT = 10, 11
 EXPORTS = [
     "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
     "spp_graph_destroy", "spp_vip_propagate", "spp_vip_last_hops", "spp_build_vip_cache", "spp_cache_destroy",
-    "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg",
+    "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg", "spp_sample_mfg_multi",
     "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
 ]
 
@@ -47,6 +47,11 @@ class _MfgStruct(C.Structure):
         ("n", C.c_int64 * (SPP_MAX_L + 1)),
         ("e", C.c_int64 * (SPP_MAX_L + 1)),
     ]
+
+
+class _SampleItem(C.Structure):
+    _fields_ = [("d_seeds", C.c_void_p), ("nseeds", C.c_int32), ("batch_index", C.c_uint64),
+                ("io", C.POINTER(_MfgStruct))]
 
 
 class _GatherList(C.Structure):
@@ -95,6 +100,8 @@ def load_library():
                                   C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.spp_sample_mfg.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32),
                                    C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(_MfgStruct), C.c_uint32]
+    lib.spp_sample_mfg_multi.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_SampleItem), C.c_int32,
+                                         C.POINTER(C.c_int32), C.c_int32, C.c_uint64, C.c_uint32]
     lib.spp_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                         C.c_void_p, C.POINTER(_GatherStats), C.c_uint32]
@@ -331,6 +338,29 @@ def sample_mfg(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: Sequenc
         out.n = [int(out._s.n[h]) for h in range(L + 1)]
         out.e = [int(out._s.e[h]) for h in range(L + 1)]
     return out
+
+
+def sample_mfg_multi(ctx: Context, graph: Graph, items, fanouts: Sequence[int], seed: int, sync: bool = True):
+    """Several minibatches sampled by one set of launches.
+
+    `items` is a sequence of (seeds, batch_index, MFGBuffers); each MFGBuffers receives the result of
+    its minibatch exactly as a single sample_mfg call would produce it.
+    """
+    f, L = _fan(fanouts)
+    arr = (_SampleItem * max(len(items), 1))()
+    for j, (seeds, batch_index, out) in enumerate(items):
+        seeds = _dev(seeds, torch.int32, "seeds")
+        arr[j].d_seeds = seeds.data_ptr()
+        arr[j].nseeds = seeds.numel()
+        arr[j].batch_index = int(batch_index) & (2**64 - 1)
+        arr[j].io = C.pointer(out._s)
+    _check(load_library().spp_sample_mfg_multi(ctx._h, graph._h, arr, len(items), f, L,
+                                               C.c_uint64(int(seed) & (2**64 - 1)), SPP_SYNC if sync else 0))
+    if sync:
+        for _, _, out in items:
+            out.n = [int(out._s.n[h]) for h in range(L + 1)]
+            out.e = [int(out._s.e[h]) for h in range(L + 1)]
+    return [out for _, _, out in items]
 
 
 def gather_features(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,

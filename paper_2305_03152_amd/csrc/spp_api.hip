@@ -36,7 +36,7 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
     hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 64 * sizeof(int64_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 512 * sizeof(int64_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->totals), 8 * sizeof(int64_t));
     if (e == hipSuccess) e = hipMemset(c->totals, 0, 8 * sizeof(int64_t));
     if (e != hipSuccess) {
@@ -44,7 +44,7 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
         spp_ctx_destroy(c);
         return SPP_E_HIP;
     }
-    memset(c->h_pinned, 0, 64 * sizeof(int64_t));
+    memset(c->h_pinned, 0, 512 * sizeof(int64_t));
     *out = c;
     return SPP_OK;
 }
@@ -60,7 +60,7 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     for (hipEvent_t e : c->ev_free) (void)hipEventDestroy(e);
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
     if (c->totals) (void)hipFree(c->totals);
-    c->table.release(); c->flat.release(); c->partials.release();
+    c->table.release(); c->flat.release(); c->slots.release(); c->partials.release();
     c->srcdesc.release(); c->misslist.release(); c->gcount.release();
     c->y0.release(); c->y1.release(); c->tot.release(); c->hubacc.release(); c->acc.release(); c->frontier.release();
     delete c;

@@ -74,6 +74,10 @@ struct spp_ctx {
     // sampling workspaces
     spp::DevBuf table;                  // uint64 hash table: global id -> local id / first position
     spp::DevBuf flat;                   // int32 sampled global ids of the current hop
+    spp::DevBuf slots;                  // int32 table slot of every sampled vertex
+    void*       table_clean_ptr = nullptr;   // the id tables in this buffer are empty ...
+    int64_t     table_clean_cap = 0;         // ... for this capacity per minibatch ...
+    int         table_clean_regions = 0;     // ... in this many regions
     spp::DevBuf partials;               // scan partial sums
     // gather workspaces
     spp::DevBuf srcdesc;                // int64 per row: where the row comes from

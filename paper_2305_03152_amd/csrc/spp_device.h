@@ -115,6 +115,64 @@ inline void grid_scan(hipStream_t st, int grid, const int64_t* n_ptr, In in, Out
     scan_write_kernel<In, Out><<<grid, kBlock, 0, st>>>(n_ptr, in, out, partial);
 }
 
+// The same scan for several independent sequences at once: blockIdx.y names the sequence ("batch") j.
+//   In:  int64_t n(int j) const (length, read on the device); int operator()(int j, int64_t i) const
+//   Out: void operator()(int j, int64_t i, int ex, int v) const
+//   Fin: void operator()(int j, int total) const
+// `partial` holds gridDim.x ints per sequence.
+template <class In>
+__global__ void __launch_bounds__(kBlock) bscan_reduce_kernel(In in, int* partial) {
+    __shared__ int lds[4];
+    const int j = blockIdx.y;
+    int64_t b, e;
+    scan_range(in.n(j), b, e);
+    int acc = 0;
+    for (int64_t i = b + threadIdx.x; i < e; i += kBlock) acc = uadd(acc, in(j, i));
+    int t = block_reduce_sum(acc, lds);
+    if (threadIdx.x == 0) partial[(int64_t)j * gridDim.x + blockIdx.x] = t;
+}
+
+template <class Fin>
+__global__ void __launch_bounds__(kBlock) bscan_partials_kernel(int* partial, int nparts, Fin fin) {
+    __shared__ int lds[4];
+    const int j = blockIdx.x;                       // one workgroup per sequence
+    int* p = partial + (int64_t)j * nparts;
+    int carry = 0;
+    for (int base = 0; base < nparts; base += kBlock) {
+        int i = base + threadIdx.x;
+        int v = i < nparts ? p[i] : 0;
+        int total;
+        int ex = block_exclusive_scan(v, lds, total);
+        if (i < nparts) p[i] = uadd(carry, ex);
+        carry = uadd(carry, total);
+    }
+    if (threadIdx.x == 0) fin(j, carry);
+}
+
+template <class In, class Out>
+__global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, const int* partial) {
+    __shared__ int lds[4];
+    const int j = blockIdx.y;
+    int64_t b, e;
+    scan_range(in.n(j), b, e);
+    int carry = partial[(int64_t)j * gridDim.x + blockIdx.x];
+    for (int64_t base = b; base < e; base += kBlock) {
+        int64_t i = base + threadIdx.x;
+        int v = i < e ? in(j, i) : 0;
+        int total;
+        int ex = block_exclusive_scan(v, lds, total);
+        if (i < e) out(j, i, uadd(carry, ex), v);
+        carry = uadd(carry, total);
+    }
+}
+
+template <class In, class Out, class Fin>
+inline void grid_scan_batched(hipStream_t st, int grid, int nbatch, In in, Out out, Fin fin, int* partial) {
+    bscan_reduce_kernel<In><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, partial);
+    bscan_partials_kernel<Fin><<<nbatch, kBlock, 0, st>>>(partial, grid, fin);
+    bscan_write_kernel<In, Out><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, out, partial);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Open-addressing table of 64-bit entries (key << 32 | value), empty = all ones, linear probing.
 // The capacity is a power of two at least twice the number of keys, so probes end.
@@ -125,21 +183,21 @@ __device__ __forceinline__ uint32_t table_hash(uint32_t key, int shift) {
     return (key * 0x9E3779B1u) >> shift;         // top log2(capacity) bits of a Fibonacci product
 }
 
-// Keeps, per key, the smallest value ever offered.
-__device__ __forceinline__ void table_insert_min(unsigned long long* tab, uint32_t mask, int shift,
-                                                 uint32_t key, uint32_t value) {
+// Keeps, per key, the smallest value ever offered; returns the slot that holds the key.
+__device__ __forceinline__ uint32_t table_insert_min(unsigned long long* tab, uint32_t mask, int shift,
+                                                     uint32_t key, uint32_t value) {
     const unsigned long long want = ((unsigned long long)key << 32) | value;
     uint32_t h = table_hash(key, shift);
     for (;;) {
         unsigned long long cur = __hip_atomic_load(&tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (cur == kEmpty) {
             unsigned long long old = atomicCAS(&tab[h], (unsigned long long)kEmpty, want);
-            if (old == kEmpty) return;
+            if (old == kEmpty) return h;
             cur = old;
         }
         if ((uint32_t)(cur >> 32) == key) {
             if (want < cur) atomicMin(&tab[h], want);
-            return;
+            return h;
         }
         h = (h + 1) & mask;
     }

@@ -26,7 +26,8 @@ struct ClassifyArgs {
     int64_t        limit;              // slots in use
     int64_t*       desc;               // per virtual row
     int32_t*       misslist;           // virtual rows that miss
-    unsigned long long* counters;      // [0] local, [1] cache hit, [2] miss, [3] bad id
+    int32_t*       hitlist;            // virtual rows served from the shard or the cache
+    unsigned long long* counters;      // [0] local, [1] cache hit, [2] miss, [3] bad id, [4] rows in hitlist
     unsigned long long* totals;        // context-wide running sums: [3] calls, [4] local, [5] cache hit, [6] miss
 };
 
@@ -58,7 +59,7 @@ __global__ void gather_prologue_kernel(PrologueArgs p, unsigned long long* count
 // so the list counter sees one atomic per 2048 ids instead of one per wavefront.
 __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
     __shared__ int scan_lds[4];
-    __shared__ unsigned long long base_lds;
+    __shared__ unsigned long long base_lds[2];
     __shared__ ListLds ls;
     load_lists(a.t, ls);
     const int64_t total = ls.off[a.t.n_lists];
@@ -67,7 +68,7 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
         const int j = list_of(ls, a.t.n_lists, base);
         const int64_t lbeg = ls.off[j], n = ls.cnt[j];
         const int32_t* __restrict__ ids = a.t.ids[j];
-        uint32_t missbits = 0;
+        uint32_t missbits = 0, hitbits = 0;
 #pragma unroll
         for (int k = 0; k < kClsPer; ++k) {
             const int64_t i = base - lbeg + (int64_t)k * kBlock + threadIdx.x;
@@ -79,29 +80,38 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
             } else if (g >= a.lo && g < a.hi) {
                 d = make_desc(kTagLocal, g - a.lo);
                 ++n_local;
+                hitbits |= 1u << k;
             } else {
                 uint32_t slot = 0;
                 const bool found = a.tab && table_find(a.tab, a.mask, a.shift, (uint32_t)g, slot) >= 0 &&
                                    (int64_t)slot < a.limit;
-                if (found) { d = make_desc(kTagCache, slot); ++n_hit; }
+                if (found) { d = make_desc(kTagCache, slot); ++n_hit; hitbits |= 1u << k; }
                 else       { d = make_desc(kTagMiss, g < a.lo ? g : g - (a.hi - a.lo)); missbits |= 1u << k; }
             }
             a.desc[lbeg + i] = d;
         }
-        int total_miss;
-        const int ex = block_exclusive_scan(__popc(missbits), scan_lds, total_miss);
-        if (total_miss > 0) {
-            if (threadIdx.x == 0) {
-                base_lds = atomicAdd(&a.counters[2], (unsigned long long)total_miss);
+        // both lists are compacted with one scan: misses in the low half-word, hits in the high one
+        // (a workgroup's totals are at most 2048 each)
+        int total_packed;
+        const int ex = block_exclusive_scan(__popc(missbits) | (__popc(hitbits) << 16), scan_lds, total_packed);
+        const int total_miss = total_packed & 0xFFFF, total_hit = total_packed >> 16;
+        if (threadIdx.x == 0) {
+            if (total_miss) {
+                base_lds[0] = atomicAdd(&a.counters[2], (unsigned long long)total_miss);
                 atomicAdd(&a.totals[6], (unsigned long long)total_miss);
             }
-            __syncthreads();
-            unsigned long long pos = base_lds + (unsigned long long)ex;
-#pragma unroll
-            for (int k = 0; k < kClsPer; ++k)
-                if (missbits & (1u << k)) a.misslist[pos++] = (int32_t)(base + (int64_t)k * kBlock + threadIdx.x);
-            __syncthreads();                      // base_lds is reused by the next round
+            if (total_hit) base_lds[1] = atomicAdd(&a.counters[4], (unsigned long long)total_hit);
         }
+        __syncthreads();
+        unsigned long long mpos = base_lds[0] + (unsigned long long)(ex & 0xFFFF);
+        unsigned long long hpos = base_lds[1] + (unsigned long long)(ex >> 16);
+#pragma unroll
+        for (int k = 0; k < kClsPer; ++k) {
+            const int32_t r = (int32_t)(base + (int64_t)k * kBlock + threadIdx.x);
+            if (missbits & (1u << k)) a.misslist[mpos++] = r;
+            if (hitbits & (1u << k)) a.hitlist[hpos++] = r;
+        }
+        __syncthreads();                          // base_lds is reused by the next round
     }
     const int tl = block_reduce_sum(n_local, scan_lds);
     const int th = block_reduce_sum(n_hit, scan_lds);
@@ -217,7 +227,7 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
     a.t.off = off; a.t.cnt = cnt;
     if (vbound > 0) {
         SPP_TRY(ctx->srcdesc.reserve((size_t)vbound * sizeof(int64_t)));
-        SPP_TRY(ctx->misslist.reserve((size_t)vbound * sizeof(int32_t)));
+        SPP_TRY(ctx->misslist.reserve((size_t)vbound * sizeof(int32_t) * 2));     // miss list, then hit list
     }
     gather_prologue_kernel<<<1, 64, 0, st>>>(pro, counters, off, cnt);
     if (vbound > 0) {
@@ -226,6 +236,7 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
         a.mask = cache ? cache->table_mask : 0; a.shift = cache ? cache->table_shift : 0;
         a.limit = cache ? cache->limit : 0;
         a.desc = ctx->srcdesc.as<int64_t>(); a.misslist = ctx->misslist.as<int32_t>(); a.counters = counters;
+        a.hitlist = a.misslist + vbound;
         a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
         const int64_t cneed = vbound / kListAlign;
         const int cgrid = (int)(cneed < (int64_t)ctx->num_cu * 8 ? cneed : (int64_t)ctx->num_cu * 8);
@@ -254,11 +265,12 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
             ScopedTimer th(ctx, SPP_T_GATHER_HIT, st);
             const char* loc = static_cast<const char*>(d_local);
             const char* cr = static_cast<const char*>(crow);
+            const int64_t* hit_count = reinterpret_cast<const int64_t*>(counters + 4);
             switch (V) {
-                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
-                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
-                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
-                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.t, loc, cr, vpr); break;
+                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
             }
         }
         if (dremote) {

@@ -1,6 +1,9 @@
 // Node-wise fanout sampling into per-layer message-flow graphs (Sec. 2.3; the process of Sec. 3.1).
 //
-// Per hop h, all on the context's stream with every count kept on the device:
+// Up to 16 minibatches are sampled by one set of launches: every kernel has a second grid dimension
+// that names the minibatch, and each minibatch has its own id table, flat-id buffer and counts, so
+// the minibatches never interact.  Per hop h, all on the context's stream with every count kept on
+// the device:
 //   1. grid scan of c_i = min(f_h, d(S_{h-1}[i]))            -> indptr of MFG h, e_h
 //   2. sample: a group of G lanes (G = 8/16/32/64 >= f_h) per target draws its slots in parallel
 //      (one Philox block per lane), resolves Floyd's "already taken" rule with ballots, reads the
@@ -9,92 +12,123 @@
 //                                                            -> S_h appended in order, n_h, table value := local id
 //   4. relabel: src[e] = table value of the e-th sampled id
 // The table (open addressing, global memory, sized for the bound on |S_L|) lives for the whole
-// batch: after hop h every key's value is its index in S_h, which is below any position offered
-// at hop h+1, so earlier vertices keep their ids.
+// minibatch: after hop h every key's value is its index in S_h, which is below any position offered
+// at hop h+1, so earlier vertices keep their ids.  The bound is loose (a Mid minibatch uses 66k of
+// 1.08M possible vertices), so the tables are not wiped per call: every vertex remembers the slot it
+// occupies and a last kernel empties exactly those slots, which leaves the tables clean for the next
+// call without streaming 32 MB per minibatch through the caches.
 #include "spp_common.h"
 #include "spp_device.h"
 
 namespace spp {
 
+constexpr int kMaxBatches = SPP_MAX_SAMPLE_BATCHES;
+
+// What differs between the minibatches of one call (stored in device memory once per call).
+struct BatchDesc {
+    const int32_t* seeds;
+    int32_t*       S;                   // node ids
+    int32_t*       indptr[SPP_MAX_L];
+    int32_t*       src[SPP_MAX_L];
+    int64_t*       counts;              // n[0..MAX_L], e[0..MAX_L]
+    int32_t*       slots;               // table slot of S[i] (workspace)
+    int32_t        nseeds;
+    uint32_t       batch_lo;
+};
+struct BatchTable {
+    BatchDesc b[kMaxBatches];
+};
+
+// What the minibatches of one call share.
 struct SampleArgs {
     const int64_t* rowptr;
     const int32_t* col;
     int64_t        N;
-    unsigned long long* tab;
+    unsigned long long* tab;            // one region of `cap` entries per minibatch
+    int64_t        cap;
     uint32_t       mask;
     int            shift;
-    int32_t*       S;          // node ids
-    int32_t*       indptr;     // this hop
-    int32_t*       src;        // this hop
-    int32_t*       flat;       // sampled global ids of this hop
-    int64_t*       counts;     // n[0..MAX_L], e[0..MAX_L]
-    unsigned long long* totals; // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
+    int32_t*       flat;                // one region of `flat_stride` sampled global ids per minibatch (current hop)
+    int64_t        flat_stride;
+    unsigned long long* totals;         // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
+    int*           bad;
     int            L;
-    int            h;          // hop, 1-based
-    int            f;          // fanout of this hop
+    int            h;                   // hop, 1-based
+    int            f;                   // fanout of this hop
     uint64_t       seed;
-    uint32_t       batch_lo;
 };
 
-__device__ __forceinline__ const int64_t* n_ptr(const SampleArgs& a, int h) { return a.counts + h; }
-__device__ __forceinline__ const int64_t* e_ptr(const SampleArgs& a, int h) { return a.counts + (SPP_MAX_L + 1) + h; }
+__device__ __forceinline__ unsigned long long* tab_of(const SampleArgs& a, int j) { return a.tab + (int64_t)j * a.cap; }
+__device__ __forceinline__ int32_t* flat_of(const SampleArgs& a, int j) { return a.flat + (int64_t)j * a.flat_stride; }
+constexpr int kE = SPP_MAX_L + 1;      // offset of e[] inside counts
 
-// Empties the id table and zeroes the counts and the error flag of a new batch.
-__global__ void __launch_bounds__(kBlock) sample_init_kernel(SampleArgs a, int64_t cap, int nseeds, int* __restrict__ bad) {
+// Zeroes the counts of the new minibatches; wipes their id tables when they are not known to be clean
+// (first use, a different capacity, or a call that did not finish).
+__global__ void __launch_bounds__(kBlock) sample_init_kernel(SampleArgs a, const BatchTable* __restrict__ t, int wipe) {
+    const int j = blockIdx.y;
+    unsigned long long* tab = tab_of(a, j);
     const int64_t stride = (int64_t)gridDim.x * kBlock;
-    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    for (int64_t i = t; i < cap; i += stride) a.tab[i] = ~0ull;
-    if (t == 0) {
-        for (int k = 0; k <= SPP_MAX_L; ++k) { a.counts[k] = 0; a.counts[SPP_MAX_L + 1 + k] = 0; }
-        a.counts[0] = nseeds;
-        *bad = 0;
+    const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (wipe) for (int64_t i = tid; i < a.cap; i += stride) tab[i] = ~0ull;
+    if (tid == 0) {
+        int64_t* c = t->b[j].counts;
+        for (int k = 0; k <= SPP_MAX_L; ++k) { c[k] = 0; c[kE + k] = 0; }
+        c[0] = t->b[j].nseeds;
     }
 }
 
-__global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const int32_t* __restrict__ seeds, int nseeds,
-                                                       int* __restrict__ bad) {
+__global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const int j = blockIdx.y;
     const int i = blockIdx.x * kBlock + threadIdx.x;
-    if (i >= nseeds) return;
-    int32_t v = seeds[i];
-    if (v < 0 || v >= a.N) { v = 0; atomicOr(bad, 1); }       // reported; keeps later row reads in range
-    a.S[i] = v;
-    table_insert_min(a.tab, a.mask, a.shift, (uint32_t)v, (uint32_t)i);
+    if (i >= t->b[j].nseeds) return;
+    int32_t v = t->b[j].seeds[i];
+    if (v < 0 || v >= a.N) { v = 0; atomicOr(a.bad, 1); }       // reported; keeps later row reads in range
+    t->b[j].S[i] = v;
+    t->b[j].slots[i] = (int32_t)table_insert_min(tab_of(a, j), a.mask, a.shift, (uint32_t)v, (uint32_t)i);
 }
 
 // ---- step 1 ----
 struct CountIn {
-    SampleArgs a;
-    __device__ int operator()(int64_t i) const {
-        const int64_t v = a.S[i];
+    SampleArgs a; const BatchTable* t;
+    __device__ int64_t n(int j) const { return t->b[j].counts[a.h - 1]; }
+    __device__ int operator()(int j, int64_t i) const {
+        const int64_t v = t->b[j].S[i];
         const int64_t d = a.rowptr[v + 1] - a.rowptr[v];
         return (int)(d < a.f ? d : a.f);
     }
 };
 struct CountOut {
-    SampleArgs a;
-    __device__ void operator()(int64_t i, int ex, int) const { a.indptr[i] = ex; }
+    SampleArgs a; const BatchTable* t;
+    __device__ void operator()(int j, int64_t i, int ex, int) const { t->b[j].indptr[a.h - 1][i] = ex; }
 };
 struct CountFin {
-    SampleArgs a;
-    __device__ void operator()(int total) const {
-        a.indptr[a.counts[a.h - 1]] = total;
-        a.counts[SPP_MAX_L + 1 + a.h] = total;
+    SampleArgs a; const BatchTable* t;
+    __device__ void operator()(int j, int total) const {
+        int64_t* c = t->b[j].counts;
+        t->b[j].indptr[a.h - 1][c[a.h - 1]] = total;
+        c[kE + a.h] = total;
         atomicAdd(&a.totals[2], (unsigned long long)(uint32_t)total);
     }
 };
 
 // ---- step 2 ----
 template <int G>
-__global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a) {
+__global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const int jb = blockIdx.y;
     const int lane = lane_id();
     const int j = lane & (G - 1);                  // slot handled by this lane
     const int gbase = lane - j;                    // first lane of the group inside the wavefront
     const uint64_t gmask = (G == 64) ? ~0ull : (((1ull << (G & 63)) - 1ull) << gbase);
     constexpr int kGroupsPerWave = kWave / G;
-    const int64_t n_prev = *n_ptr(a, a.h - 1);
+    const int64_t n_prev = t->b[jb].counts[a.h - 1];
+    const uint32_t batch_lo = t->b[jb].batch_lo;
     const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
     const int f = a.f;
+    const int32_t* __restrict__ S = t->b[jb].S;
+    const int32_t* __restrict__ indptr = t->b[jb].indptr[a.h - 1];
+    int32_t* __restrict__ flat = flat_of(a, jb);
+    unsigned long long* tab = tab_of(a, jb);
 
     for (int64_t first = wave * kGroupsPerWave; first < n_prev; first += nwaves * kGroupsPerWave) {
         const int64_t i = first + (lane / G);
@@ -102,10 +136,10 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a) {
         int64_t r0 = 0, d = 0;
         int32_t off = 0, v = 0;
         if (valid) {
-            v = a.S[i];
+            v = S[i];
             r0 = a.rowptr[v];
             d = a.rowptr[v + 1] - r0;
-            off = a.indptr[i];
+            off = indptr[i];
         }
         const bool floyd = d > f;
         const int c = floyd ? f : (int)d;
@@ -113,15 +147,15 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a) {
         if (floyd) {
             // Floyd's subset algorithm, one draw per slot: m = d - f + j, t uniform on [0, m]
             const uint64_t m = (uint64_t)(d - f + j);
-            uint64_t t = 0;
+            uint64_t tt = 0;
             if (j < f) {
-                const uint32_t r = rand32(a.seed, a.batch_lo, (uint32_t)a.h, (uint32_t)v, (uint32_t)j);
-                t = ((uint64_t)r * (m + 1ull)) >> 32;
+                const uint32_t r = rand32(a.seed, batch_lo, (uint32_t)a.h, (uint32_t)v, (uint32_t)j);
+                tt = ((uint64_t)r * (m + 1ull)) >> 32;
             }
-            pos = (int64_t)t;
+            pos = (int64_t)tt;
             // slot jj takes t_jj unless an earlier slot already holds it, else m_jj (never held before)
             for (int jj = 1; jj < f; ++jj) {
-                const int64_t tj = __shfl((long long)t, gbase + jj, kWave);
+                const int64_t tj = __shfl((long long)tt, gbase + jj, kWave);
                 const bool hit = (j < jj) && (pos == tj);
                 const uint64_t b = __ballot(hit) & gmask;
                 if (j == jj && b != 0ull) pos = (int64_t)m;
@@ -130,60 +164,82 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a) {
         if (valid && j < c) {
             const int32_t gid = a.col[r0 + pos];
             const int64_t e = (int64_t)off + j;
-            a.flat[e] = gid;
-            table_insert_min(a.tab, a.mask, a.shift, (uint32_t)gid, (uint32_t)(n_prev + e));
+            flat[e] = gid;
+            table_insert_min(tab, a.mask, a.shift, (uint32_t)gid, (uint32_t)(n_prev + e));
         }
     }
 }
 
 // ---- step 3 ----
 struct NewIn {
-    SampleArgs a;
-    __device__ int operator()(int64_t e) const {
+    SampleArgs a; const BatchTable* t;
+    __device__ int64_t n(int j) const { return t->b[j].counts[kE + a.h]; }
+    __device__ int operator()(int j, int64_t e) const {
         uint32_t val = 0;
-        table_find(a.tab, a.mask, a.shift, (uint32_t)a.flat[e], val);
-        return (int64_t)val == a.counts[a.h - 1] + e ? 1 : 0;
+        table_find(tab_of(a, j), a.mask, a.shift, (uint32_t)flat_of(a, j)[e], val);
+        return (int64_t)val == t->b[j].counts[a.h - 1] + e ? 1 : 0;
     }
 };
 struct NewOut {
-    SampleArgs a;
-    __device__ void operator()(int64_t e, int ex, int v) const {
+    SampleArgs a; const BatchTable* t;
+    __device__ void operator()(int j, int64_t e, int ex, int v) const {
         if (!v) return;
-        const uint32_t gid = (uint32_t)a.flat[e];
+        unsigned long long* tab = tab_of(a, j);
+        const uint32_t gid = (uint32_t)flat_of(a, j)[e];
         uint32_t val = 0;
-        const int64_t slot = table_find(a.tab, a.mask, a.shift, gid, val);
-        const int64_t id = a.counts[a.h - 1] + ex;
-        a.S[id] = (int32_t)gid;
+        const int64_t slot = table_find(tab, a.mask, a.shift, gid, val);
+        const int64_t id = t->b[j].counts[a.h - 1] + ex;
+        t->b[j].S[id] = (int32_t)gid;
+        t->b[j].slots[id] = (int32_t)slot;
         // the new value is <= the old one and is never equal to another entry's own position, so
         // threads still testing "first appearance" read either value with the same outcome
-        __hip_atomic_store(&a.tab[slot], ((unsigned long long)gid << 32) | (uint32_t)id, __ATOMIC_RELAXED,
+        __hip_atomic_store(&tab[slot], ((unsigned long long)gid << 32) | (uint32_t)id, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     }
 };
 struct NewFin {
-    SampleArgs a;
-    __device__ void operator()(int total) const {
-        const int64_t n = a.counts[a.h - 1] + total;
-        a.counts[a.h] = n;
+    SampleArgs a; const BatchTable* t;
+    __device__ void operator()(int j, int total) const {
+        int64_t* c = t->b[j].counts;
+        const int64_t n = c[a.h - 1] + total;
+        c[a.h] = n;
         if (a.h == a.L) { atomicAdd(&a.totals[1], (unsigned long long)n); atomicAdd(&a.totals[0], 1ull); }
     }
 };
 
 // ---- step 4 ----
-__global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a) {
-    const int64_t e_h = *e_ptr(a, a.h);
+__global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const int j = blockIdx.y;
+    const int64_t e_h = t->b[j].counts[kE + a.h];
+    const unsigned long long* tab = tab_of(a, j);
+    const int32_t* __restrict__ flat = flat_of(a, j);
+    int32_t* __restrict__ src = t->b[j].src[a.h - 1];
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < e_h; e += stride) {
         uint32_t val = 0;
-        table_find(a.tab, a.mask, a.shift, (uint32_t)a.flat[e], val);
-        a.src[e] = (int32_t)val;
+        table_find(tab, a.mask, a.shift, (uint32_t)flat[e], val);
+        src[e] = (int32_t)val;
     }
 }
 
-template <int G>
-static void launch_sample(int grid, hipStream_t st, const SampleArgs& a) {
-    sample_kernel<G><<<grid, kBlock, 0, st>>>(a);
+// Leaves the id tables empty again: every vertex of S_L clears the slot it occupies.
+__global__ void __launch_bounds__(kBlock) table_release_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const int j = blockIdx.y;
+    const int64_t n = t->b[j].counts[a.L];
+    unsigned long long* tab = tab_of(a, j);
+    const int32_t* __restrict__ slots = t->b[j].slots;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) tab[(uint32_t)slots[i]] = ~0ull;
 }
+
+// Stores the call's table of per-minibatch pointers in device memory and clears the error flag.
+__global__ void __launch_bounds__(kBlock) batch_table_store_kernel(BatchTable src, BatchTable* dst, int* bad) {
+    const uint64_t* s = reinterpret_cast<const uint64_t*>(&src);
+    uint64_t* d = reinterpret_cast<uint64_t*>(dst);
+    for (unsigned i = threadIdx.x; i < sizeof(BatchTable) / sizeof(uint64_t); i += kBlock) d[i] = s[i];
+    if (threadIdx.x == 0) *bad = 0;
+}
+static_assert(sizeof(BatchTable) % sizeof(uint64_t) == 0, "copied as 64-bit words");
 
 }  // namespace spp
 
@@ -204,80 +260,127 @@ extern "C" int spp_mfg_bound(int32_t nseeds, const int32_t* fanouts, int32_t L, 
     return SPP_OK;
 }
 
-extern "C" int spp_sample_mfg(spp_ctx* ctx, const spp_graph* g, const int32_t* d_seeds, int32_t nseeds,
-                              const int32_t* fanouts, int32_t L, uint64_t seed, uint64_t batch_index,
-                              spp_mfg* io, uint32_t flags) {
+extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_item* items, int32_t n_items,
+                                    const int32_t* fanouts, int32_t L, uint64_t seed, uint32_t flags) {
     using namespace spp;
-    SPP_CHECK(ctx && g && fanouts && io, SPP_E_ARG, "spp_sample_mfg: null argument");
-    SPP_CHECK(nseeds >= 0 && (d_seeds || nseeds == 0), SPP_E_ARG, "spp_sample_mfg: seeds");
-    int64_t nb[SPP_MAX_L + 1], eb[SPP_MAX_L + 1];
-    SPP_TRY(spp_mfg_bound(nseeds, fanouts, L, g->N, nb, eb));
-    SPP_CHECK(nseeds <= g->N, SPP_E_ARG, "spp_sample_mfg: more seeds than vertices");
-    SPP_CHECK(io->d_node_ids && io->d_counts, SPP_E_ARG, "spp_sample_mfg: null output buffer");
-    SPP_CHECK(io->n_nodes_cap >= nb[L] && io->n_nodes_cap >= 1, SPP_E_CAPACITY,
-              "spp_sample_mfg: d_node_ids holds %lld entries, the bound is %lld", (long long)io->n_nodes_cap, (long long)nb[L]);
-    int64_t emax = 1;
-    for (int h = 1; h <= L; ++h) {
-        SPP_CHECK(io->d_indptr[h - 1] && io->d_src[h - 1], SPP_E_ARG, "spp_sample_mfg: null buffer of hop %d", h);
-        SPP_CHECK(io->n_edges_cap[h - 1] >= eb[h], SPP_E_CAPACITY, "spp_sample_mfg: d_src of hop %d holds %lld entries, the bound is %lld",
-                  h, (long long)io->n_edges_cap[h - 1], (long long)eb[h]);
-        SPP_CHECK(eb[h] < 0x7FFFFFFFll && nb[h] + eb[h] < 0xFFFFFFFFll, SPP_E_ARG, "spp_sample_mfg: hop %d exceeds 32-bit offsets", h);
-        if (eb[h] > emax) emax = eb[h];
+    SPP_CHECK(ctx && g && fanouts && (items || n_items == 0), SPP_E_ARG, "spp_sample_mfg: null argument");
+    SPP_CHECK(n_items >= 0 && n_items <= SPP_MAX_SAMPLE_BATCHES, SPP_E_ARG, "spp_sample_mfg: %d minibatches (at most %d)",
+              n_items, SPP_MAX_SAMPLE_BATCHES);
+    if (n_items == 0) return SPP_OK;
+    BatchTable ht;
+    memset(&ht, 0, sizeof(ht));
+    int64_t nb[SPP_MAX_L + 1] = {0}, eb[SPP_MAX_L + 1] = {0};       // bounds of the largest minibatch
+    int max_seeds = 0;
+    for (int j = 0; j < n_items; ++j) {
+        const spp_sample_item& it = items[j];
+        spp_mfg* io = it.io;
+        SPP_CHECK(io, SPP_E_ARG, "spp_sample_mfg: minibatch %d has no output struct", j);
+        SPP_CHECK(it.nseeds >= 0 && (it.d_seeds || it.nseeds == 0), SPP_E_ARG, "spp_sample_mfg: seeds of minibatch %d", j);
+        SPP_CHECK(it.nseeds <= g->N, SPP_E_ARG, "spp_sample_mfg: more seeds than vertices");
+        int64_t nbj[SPP_MAX_L + 1], ebj[SPP_MAX_L + 1];
+        SPP_TRY(spp_mfg_bound(it.nseeds, fanouts, L, g->N, nbj, ebj));
+        SPP_CHECK(io->d_node_ids && io->d_counts, SPP_E_ARG, "spp_sample_mfg: null output buffer");
+        SPP_CHECK(io->n_nodes_cap >= nbj[L] && io->n_nodes_cap >= 1, SPP_E_CAPACITY,
+                  "spp_sample_mfg: d_node_ids holds %lld entries, the bound is %lld", (long long)io->n_nodes_cap, (long long)nbj[L]);
+        for (int h = 1; h <= L; ++h) {
+            SPP_CHECK(io->d_indptr[h - 1] && io->d_src[h - 1], SPP_E_ARG, "spp_sample_mfg: null buffer of hop %d", h);
+            SPP_CHECK(io->n_edges_cap[h - 1] >= ebj[h], SPP_E_CAPACITY,
+                      "spp_sample_mfg: d_src of hop %d holds %lld entries, the bound is %lld", h,
+                      (long long)io->n_edges_cap[h - 1], (long long)ebj[h]);
+            SPP_CHECK(ebj[h] < 0x7FFFFFFFll && nbj[h] + ebj[h] < 0xFFFFFFFFll, SPP_E_ARG, "spp_sample_mfg: hop %d exceeds 32-bit offsets", h);
+            ht.b[j].indptr[h - 1] = io->d_indptr[h - 1];
+            ht.b[j].src[h - 1] = io->d_src[h - 1];
+        }
+        for (int h = 0; h <= L; ++h) { if (nbj[h] > nb[h]) nb[h] = nbj[h]; if (ebj[h] > eb[h]) eb[h] = ebj[h]; }
+        ht.b[j].seeds = it.d_seeds; ht.b[j].nseeds = it.nseeds; ht.b[j].batch_lo = (uint32_t)it.batch_index;
+        ht.b[j].S = io->d_node_ids; ht.b[j].counts = io->d_counts;
+        if (it.nseeds > max_seeds) max_seeds = it.nseeds;
     }
+    int64_t emax = 1;
+    for (int h = 1; h <= L; ++h) if (eb[h] > emax) emax = eb[h];
     SPP_HIP(hipSetDevice(ctx->device));
     hipStream_t st = ctx->stream;
 
     const uint32_t cap = next_pow2((uint64_t)(2 * nb[L] > 1024 ? 2 * nb[L] : 1024));
     int shift = 32;
     for (uint32_t c = cap; c > 1; c >>= 1) --shift;
-    const int scan_grid = ctx->num_cu * 4;
-    SPP_TRY(ctx->table.reserve((size_t)cap * sizeof(uint64_t)));
-    SPP_TRY(ctx->flat.reserve((size_t)emax * sizeof(int32_t)));
-    SPP_TRY(ctx->partials.reserve((size_t)scan_grid * sizeof(int) + 64));
+    // workgroups per minibatch in the scans and the table clear: the whole call gets about 4 per CU
+    const int per_batch = (ctx->num_cu * 4 + n_items - 1) / n_items;
+    const int scan_grid = per_batch < 32 ? 32 : per_batch;
+    SPP_TRY(ctx->table.reserve((size_t)cap * sizeof(uint64_t) * n_items));
+    SPP_TRY(ctx->flat.reserve((size_t)emax * sizeof(int32_t) * n_items));
+    SPP_TRY(ctx->slots.reserve((size_t)(nb[L] > 1 ? nb[L] : 1) * sizeof(int32_t) * n_items));
+    for (int j = 0; j < n_items; ++j) ht.b[j].slots = ctx->slots.as<int32_t>() + (int64_t)j * (nb[L] > 1 ? nb[L] : 1);
+    // the tables are clean if the last call used this buffer with this capacity, covered at least
+    // these regions and was enqueued completely
+    const bool wipe = !(ctx->table_clean_ptr == ctx->table.ptr && ctx->table_clean_cap == (int64_t)cap &&
+                        ctx->table_clean_regions >= n_items);
+    ctx->table_clean_ptr = nullptr;
+    SPP_TRY(ctx->partials.reserve((size_t)scan_grid * n_items * sizeof(int) + 64 + sizeof(BatchTable) + 256));
     int* partial = ctx->partials.as<int>();
-    int* d_bad = partial + scan_grid;
+    int* d_bad = partial + (size_t)scan_grid * n_items;
+    // the per-minibatch pointers live in device memory: the table is too large to ride in the
+    // argument block of every kernel, so one small kernel stores it once per call
+    BatchTable* dt = reinterpret_cast<BatchTable*>(
+        (reinterpret_cast<uintptr_t>(d_bad) + 64 + 255) & ~static_cast<uintptr_t>(255));
 
     SampleArgs a;
     a.rowptr = g->rowptr; a.col = g->col; a.N = g->N;
-    a.tab = ctx->table.as<unsigned long long>(); a.mask = cap - 1; a.shift = shift;
-    a.S = io->d_node_ids; a.flat = ctx->flat.as<int32_t>(); a.counts = io->d_counts;
-    a.seed = seed; a.batch_lo = (uint32_t)batch_index;
-    a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.L = L;
-    a.indptr = nullptr; a.src = nullptr; a.h = 0; a.f = 0;
+    a.tab = ctx->table.as<unsigned long long>(); a.cap = cap; a.mask = cap - 1; a.shift = shift;
+    a.flat = ctx->flat.as<int32_t>(); a.flat_stride = emax;
+    a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.bad = d_bad;
+    a.L = L; a.h = 0; a.f = 0; a.seed = seed;
 
+    auto capped = [&](int64_t need, int64_t lim) {
+        return (unsigned)(need < 1 ? 1 : (need < lim ? need : lim));
+    };
+    const int64_t share = (int64_t)ctx->num_cu * 16 / n_items + 1;    // workgroups per minibatch in the wide kernels
     {
         ScopedTimer tt(ctx, SPP_T_SAMPLE, st);
-        const int fill_grid = (int)((cap / kBlock) < (uint32_t)(ctx->num_cu * 8) ? (cap / kBlock) : (uint32_t)(ctx->num_cu * 8));
-        sample_init_kernel<<<fill_grid > 0 ? fill_grid : 1, kBlock, 0, st>>>(a, (int64_t)cap, nseeds, d_bad);
-        if (nseeds > 0) seeds_kernel<<<(nseeds + kBlock - 1) / kBlock, kBlock, 0, st>>>(a, d_seeds, nseeds, d_bad);
+        batch_table_store_kernel<<<1, kBlock, 0, st>>>(ht, dt, d_bad);
+        sample_init_kernel<<<dim3(wipe ? capped(cap / kBlock, scan_grid) : 1, n_items), kBlock, 0, st>>>(a, dt, wipe ? 1 : 0);
+        if (max_seeds > 0) seeds_kernel<<<dim3((max_seeds + kBlock - 1) / kBlock, n_items), kBlock, 0, st>>>(a, dt);
         for (int h = 1; h <= L; ++h) {
             a.h = h; a.f = fanouts[h - 1];
-            a.indptr = io->d_indptr[h - 1];
-            a.src = io->d_src[h - 1];
-            grid_scan(st, scan_grid, a.counts + (h - 1), CountIn{a}, CountOut{a}, CountFin{a}, partial);
+            grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial);
             const int G = a.f <= 8 ? 8 : a.f <= 16 ? 16 : a.f <= 32 ? 32 : 64;
-            int64_t need = (nb[h - 1] * G + kBlock - 1) / kBlock;
-            const int grid = (int)(need < (int64_t)ctx->num_cu * 16 ? (need > 0 ? need : 1) : (int64_t)ctx->num_cu * 16);
+            const dim3 sgrid(capped((nb[h - 1] * G + kBlock - 1) / kBlock, share), n_items);
             switch (G) {
-                case 8:  launch_sample<8>(grid, st, a); break;
-                case 16: launch_sample<16>(grid, st, a); break;
-                case 32: launch_sample<32>(grid, st, a); break;
-                default: launch_sample<64>(grid, st, a); break;
+                case 8:  sample_kernel<8><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+                case 16: sample_kernel<16><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+                case 32: sample_kernel<32><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+                default: sample_kernel<64><<<sgrid, kBlock, 0, st>>>(a, dt); break;
             }
-            grid_scan(st, scan_grid, a.counts + (SPP_MAX_L + 1) + h, NewIn{a}, NewOut{a}, NewFin{a}, partial);
-            int64_t rneed = (eb[h] + kBlock - 1) / kBlock;
-            const int rgrid = (int)(rneed < (int64_t)ctx->num_cu * 8 ? (rneed > 0 ? rneed : 1) : (int64_t)ctx->num_cu * 8);
-            relabel_kernel<<<rgrid, kBlock, 0, st>>>(a);
+            grid_scan_batched(st, scan_grid, n_items, NewIn{a, dt}, NewOut{a, dt}, NewFin{a, dt}, partial);
+            relabel_kernel<<<dim3(capped((eb[h] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
         }
+        table_release_kernel<<<dim3(capped((nb[L] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
     }
     SPP_HIP(hipGetLastError());
+    ctx->table_clean_ptr = ctx->table.ptr;
+    ctx->table_clean_cap = cap;
+    if (wipe || n_items > ctx->table_clean_regions) ctx->table_clean_regions = n_items;
     if (flags & SPP_SYNC) {
-        int64_t* hp = ctx->h_pinned;
-        SPP_HIP(hipMemcpyAsync(hp, io->d_counts, 2 * (SPP_MAX_L + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-        SPP_HIP(hipMemcpyAsync(hp + 32, d_bad, sizeof(int), hipMemcpyDeviceToHost, st));
+        int64_t* hp = ctx->h_pinned + 64;            // 16 x 18 counts, then the flag
+        for (int j = 0; j < n_items; ++j)
+            SPP_HIP(hipMemcpyAsync(hp + j * 2 * kE, items[j].io->d_counts, 2 * kE * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        SPP_HIP(hipMemcpyAsync(hp + kMaxBatches * 2 * kE, d_bad, sizeof(int), hipMemcpyDeviceToHost, st));
         SPP_HIP(hipStreamSynchronize(st));
-        for (int k = 0; k <= SPP_MAX_L; ++k) { io->n[k] = hp[k]; io->e[k] = hp[SPP_MAX_L + 1 + k]; }
-        SPP_CHECK(*reinterpret_cast<int*>(hp + 32) == 0, SPP_E_ARG, "spp_sample_mfg: a seed lies outside [0, N)");
+        for (int j = 0; j < n_items; ++j)
+            for (int k = 0; k <= SPP_MAX_L; ++k) {
+                items[j].io->n[k] = hp[j * 2 * kE + k];
+                items[j].io->e[k] = hp[j * 2 * kE + kE + k];
+            }
+        SPP_CHECK(*reinterpret_cast<int*>(hp + kMaxBatches * 2 * kE) == 0, SPP_E_ARG, "spp_sample_mfg: a seed lies outside [0, N)");
     }
     return SPP_OK;
+}
+
+extern "C" int spp_sample_mfg(spp_ctx* ctx, const spp_graph* g, const int32_t* d_seeds, int32_t nseeds,
+                              const int32_t* fanouts, int32_t L, uint64_t seed, uint64_t batch_index,
+                              spp_mfg* io, uint32_t flags) {
+    SPP_CHECK(io, SPP_E_ARG, "spp_sample_mfg: null argument");
+    spp_sample_item one;
+    one.d_seeds = d_seeds; one.nseeds = nseeds; one.batch_index = batch_index; one.io = io;
+    return spp_sample_mfg_multi(ctx, g, &one, 1, fanouts, L, seed, flags);
 }

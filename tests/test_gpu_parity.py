@@ -266,6 +266,23 @@ def test_gather_edge_cases(spp, ctx, tiny_case):
     assert torch.equal(out.cpu(), full[ids.cpu().long()])
 
 
+def test_sample_multi_batches(spp, ctx, tiny_case):
+    """Several minibatches in one set of launches: each equals the oracle's single-batch result."""
+    c = tiny_case
+    cfg = c.cfg
+    _say("sample multi: 5 minibatches of 228, 1, 0, 100 and 37 seeds in one call")
+    rng = np.random.default_rng(9)
+    seeds = [c.Tk, c.Tk[:1], c.Tk[:0], rng.permutation(c.Tk)[:100], rng.permutation(c.Tk)[:37]]
+    items = [(torch.from_numpy(np.ascontiguousarray(s_)).cuda(), 40 + k, spp.MFGBuffers("cuda", cfg.B, cfg.fanouts, cfg.N))
+             for k, s_ in enumerate(seeds)]
+    spp.sample_mfg_multi(ctx, c.G, items, cfg.fanouts, cfg.seed_sampler)
+    for (sd, bi, m), s_ in zip(items, seeds):
+        ref = oracle.sample_mfg(c.rp, c.col, s_, cfg.fanouts, cfg.seed_sampler, bi)
+        _check_mfg(m, ref, cfg.L)
+    with pytest.raises(spp.SppError):
+        spp.sample_mfg_multi(ctx, c.G, items * 4, cfg.fanouts, cfg.seed_sampler)       # 20 minibatches
+
+
 def test_gather_multi_lists(spp, ctx, tiny_case):
     """Several id lists in one call: same rows as one call per list, summed statistics."""
     c = tiny_case
