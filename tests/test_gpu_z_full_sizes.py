@@ -35,6 +35,16 @@ def _say(*a):
     print("[case]", time.strftime("%H:%M:%S"), *a, flush=True)
 
 
+def _release_memory():
+    """Give pinned host blocks and device blocks cached by torch back before the next large case."""
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+
+
 def _as_np(t):
     return (t.view(torch.int16) if t.dtype == torch.bfloat16 else t).cpu().numpy()
 
@@ -43,6 +53,14 @@ def _as_np(t):
 def test_full_size(name):
     if name not in _WANT:
         pytest.skip(f"SPP_FULL_SIZE excludes the full-size {name} case")
+    _release_memory()
+    try:
+        _full_size(name)
+    finally:
+        _release_memory()
+
+
+def _full_size(name):
     import paper_2305_03152_amd as spp
     cfg = S.CONFIGS[name]
     dev = torch.device("cuda:0")
