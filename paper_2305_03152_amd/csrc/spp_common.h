@@ -74,10 +74,7 @@ struct spp_ctx {
     // sampling workspaces
     spp::DevBuf table;                  // uint64 hash table: global id -> local id / first position
     spp::DevBuf flat;                   // int32 sampled global ids of the current hop
-    spp::DevBuf slots;                  // int32 table slot of every sampled vertex
-    void*       table_clean_ptr = nullptr;   // the id tables in this buffer are empty ...
-    int64_t     table_clean_cap = 0;         // ... for this capacity per minibatch ...
-    int         table_clean_regions = 0;     // ... in this many regions
+    spp::DevBuf slots;                  // per minibatch: mask and shift of the id table of the current hop
     spp::DevBuf partials;               // scan partial sums
     // gather workspaces
     spp::DevBuf srcdesc;                // int64 per row: where the row comes from

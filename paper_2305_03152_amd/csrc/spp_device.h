@@ -57,12 +57,41 @@ __device__ __forceinline__ int block_reduce_sum(int v, int* lds) {
 //   Out: void operator()(int64_t i, int ex, int v)  receives the exclusive prefix
 //   Fin: void operator()(int total) const           called once by one thread
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void scan_range(int64_t n, int64_t& begin, int64_t& end) {
+__device__ __forceinline__ void scan_range(int64_t n, unsigned block, int64_t& begin, int64_t& end) {
     int64_t per = (n + gridDim.x - 1) / gridDim.x;
     per = (per + kBlock - 1) / kBlock * kBlock;
-    begin = (int64_t)blockIdx.x * per;
+    begin = (int64_t)block * per;
     end = begin + per < n ? begin + per : n;
     if (begin > n) begin = n;
+}
+__device__ __forceinline__ void scan_range(int64_t n, int64_t& begin, int64_t& end) { scan_range(n, blockIdx.x, begin, end); }
+
+// Which sequence ("batch") and which of its gridDim.x workgroups this workgroup is, in a launch of
+// gridDim.x x gridDim.y workgroups over gridDim.y independent sequences.  Workgroups are handed to
+// the eight XCDs in turn by their linear index, and each XCD has an L2 of its own, so the mapping
+// keeps all workgroups of a sequence on one XCD when the counts allow it (a multiple of 8 sequences,
+// or 1/2/4 sequences with gridDim.x a multiple of 8): data that only this sequence touches (its id
+// table) then stays in one L2 instead of moving between eight.  Any other shape uses (x, y) as
+// given.  Only speed depends on where workgroups land; every shape is a bijection.
+struct BatchBlock { int j; unsigned x; };
+__device__ __forceinline__ BatchBlock batch_block() {
+    const unsigned nb = gridDim.y, gx = gridDim.x;
+    const unsigned w = blockIdx.y * gx + blockIdx.x;
+    const unsigned xcd = w & 7u, r = w >> 3;
+    BatchBlock bb;
+    if ((nb & 7u) == 0) {
+        const unsigned k = nb >> 3;
+        bb.j = (int)(xcd + 8u * (r % k));
+        bb.x = r / k;
+    } else if (nb < 8 && (8u % nb) == 0 && (gx & 7u) == 0) {
+        const unsigned k = 8u / nb;
+        bb.j = (int)(xcd % nb);
+        bb.x = r * k + xcd / nb;
+    } else {
+        bb.j = (int)blockIdx.y;
+        bb.x = blockIdx.x;
+    }
+    return bb;
 }
 
 template <class In>
@@ -115,7 +144,7 @@ inline void grid_scan(hipStream_t st, int grid, const int64_t* n_ptr, In in, Out
     scan_write_kernel<In, Out><<<grid, kBlock, 0, st>>>(n_ptr, in, out, partial);
 }
 
-// The same scan for several independent sequences at once: blockIdx.y names the sequence ("batch") j.
+// The same scan for several independent sequences at once; batch_block() names the sequence ("batch") j.
 //   In:  int64_t n(int j) const (length, read on the device); int operator()(int j, int64_t i) const
 //   Out: void operator()(int j, int64_t i, int ex, int v) const
 //   Fin: void operator()(int j, int total) const
@@ -123,13 +152,14 @@ inline void grid_scan(hipStream_t st, int grid, const int64_t* n_ptr, In in, Out
 template <class In>
 __global__ void __launch_bounds__(kBlock) bscan_reduce_kernel(In in, int* partial) {
     __shared__ int lds[4];
-    const int j = blockIdx.y;
+    const BatchBlock bb = batch_block();
+    const int j = bb.j;
     int64_t b, e;
-    scan_range(in.n(j), b, e);
+    scan_range(in.n(j), bb.x, b, e);
     int acc = 0;
     for (int64_t i = b + threadIdx.x; i < e; i += kBlock) acc = uadd(acc, in(j, i));
     int t = block_reduce_sum(acc, lds);
-    if (threadIdx.x == 0) partial[(int64_t)j * gridDim.x + blockIdx.x] = t;
+    if (threadIdx.x == 0) partial[(int64_t)j * gridDim.x + bb.x] = t;
 }
 
 template <class Fin>
@@ -152,10 +182,11 @@ __global__ void __launch_bounds__(kBlock) bscan_partials_kernel(int* partial, in
 template <class In, class Out>
 __global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, const int* partial) {
     __shared__ int lds[4];
-    const int j = blockIdx.y;
+    const BatchBlock bb = batch_block();
+    const int j = bb.j;
     int64_t b, e;
-    scan_range(in.n(j), b, e);
-    int carry = partial[(int64_t)j * gridDim.x + blockIdx.x];
+    scan_range(in.n(j), bb.x, b, e);
+    int carry = partial[(int64_t)j * gridDim.x + bb.x];
     for (int64_t base = b; base < e; base += kBlock) {
         int64_t i = base + threadIdx.x;
         int v = i < e ? in(j, i) : 0;
@@ -174,44 +205,97 @@ inline void grid_scan_batched(hipStream_t st, int grid, int nbatch, In in, Out o
 }
 
 // ---------------------------------------------------------------------------------------------
-// Open-addressing table of 64-bit entries (key << 32 | value), empty = all ones, linear probing.
-// The capacity is a power of two at least twice the number of keys, so probes end.
+// Open-addressing table of 64-bit entries (key << 32 | value), empty = all ones.  Keys are vertex
+// ids (below 2^31).  The capacity is a power of two >= 1024 and at least twice the number of keys.
+// A key hashes to a slot; a probe reads the slot's whole bucket of 8 (one 64-byte line) with four
+// 128-bit loads and walks it from the hashed slot round to the slot before it, then does the same
+// in the next bucket with the same starting offset: at half load nearly every lookup ends in the
+// first bucket, so a lookup costs one memory round trip (the kernels that use the table are bound
+// by that latency, not by bandwidth), and keys of one bucket start at different slots, so
+// concurrent insertions seldom compete for the same empty slot.
+// The bucket is read with plain loads, which may return an older state of a slot.  That is safe:
+// a slot's key is written once (by the compare-and-swap that claims it) and its value only ever
+// decreases, so an old view can only show a claimed slot as still empty, where the
+// compare-and-swap then fails and returns the current entry, or show a larger value, where the
+// atomic minimum still applies.  Lookups run in later launches than the insertions they read.
 // ---------------------------------------------------------------------------------------------
 constexpr uint64_t kEmpty = ~0ull;
+constexpr int kBucketSlots = 8;
 
 __device__ __forceinline__ uint32_t table_hash(uint32_t key, int shift) {
     return (key * 0x9E3779B1u) >> shift;         // top log2(capacity) bits of a Fibonacci product
 }
 
+// s[idx] for a run-time idx without indexing registers through memory
+__device__ __forceinline__ unsigned long long table_pick(const unsigned long long (&s)[8], uint32_t idx) {
+    const unsigned long long a = (idx & 1u) ? s[1] : s[0];
+    const unsigned long long b = (idx & 1u) ? s[3] : s[2];
+    const unsigned long long c = (idx & 1u) ? s[5] : s[4];
+    const unsigned long long d = (idx & 1u) ? s[7] : s[6];
+    const unsigned long long ab = (idx & 2u) ? b : a;
+    const unsigned long long cd = (idx & 2u) ? d : c;
+    return (idx & 4u) ? cd : ab;
+}
+
+__device__ __forceinline__ void table_load_bucket(const unsigned long long* tab, uint32_t b,
+                                                  unsigned long long (&s)[kBucketSlots]) {
+    typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+    const u64x2* p = reinterpret_cast<const u64x2*>(tab + (size_t)b * kBucketSlots);
+#pragma unroll
+    for (int k = 0; k < kBucketSlots / 2; ++k) {
+        const u64x2 v = p[k];
+        s[2 * k] = v.x;
+        s[2 * k + 1] = v.y;
+    }
+}
+
 // Keeps, per key, the smallest value ever offered; returns the slot that holds the key.
+// `mask` = capacity - 1, `shift` = 32 - log2(capacity).
 __device__ __forceinline__ uint32_t table_insert_min(unsigned long long* tab, uint32_t mask, int shift,
                                                      uint32_t key, uint32_t value) {
     const unsigned long long want = ((unsigned long long)key << 32) | value;
-    uint32_t h = table_hash(key, shift);
+    const uint32_t bmask = mask >> 3;
+    const uint32_t h0 = table_hash(key, shift);
+    uint32_t b = h0 >> 3;
     for (;;) {
-        unsigned long long cur = __hip_atomic_load(&tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (cur == kEmpty) {
-            unsigned long long old = atomicCAS(&tab[h], (unsigned long long)kEmpty, want);
-            if (old == kEmpty) return h;
-            cur = old;
+        unsigned long long s[kBucketSlots];
+        table_load_bucket(tab, b, s);
+#pragma unroll
+        for (int k = 0; k < kBucketSlots; ++k) {
+            const uint32_t idx = (h0 + k) & 7u;
+            unsigned long long cur = table_pick(s, idx);
+            const uint32_t h = b * kBucketSlots + idx;
+            if ((uint32_t)(cur >> 32) == 0xFFFFFFFFu) {          // seen empty: claim it
+                const unsigned long long old = atomicCAS(&tab[h], (unsigned long long)kEmpty, want);
+                if (old == kEmpty) return h;
+                cur = old;                                       // someone else's entry, current
+            }
+            if ((uint32_t)(cur >> 32) == key) {
+                if (want < cur) atomicMin(&tab[h], want);
+                return h;
+            }
         }
-        if ((uint32_t)(cur >> 32) == key) {
-            if (want < cur) atomicMin(&tab[h], want);
-            return h;
-        }
-        h = (h + 1) & mask;
+        b = (b + 1) & bmask;
     }
 }
 
 // Returns the slot index of `key`, or -1; `value` receives the stored value.
 __device__ __forceinline__ int64_t table_find(const unsigned long long* tab, uint32_t mask, int shift,
                                               uint32_t key, uint32_t& value) {
-    uint32_t h = table_hash(key, shift);
+    const uint32_t bmask = mask >> 3;
+    const uint32_t h0 = table_hash(key, shift);
+    uint32_t b = h0 >> 3;
     for (;;) {
-        unsigned long long cur = __hip_atomic_load(&tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (cur == kEmpty) return -1;
-        if ((uint32_t)(cur >> 32) == key) { value = (uint32_t)cur; return (int64_t)h; }
-        h = (h + 1) & mask;
+        unsigned long long s[kBucketSlots];
+        table_load_bucket(tab, b, s);
+#pragma unroll
+        for (int k = 0; k < kBucketSlots; ++k) {
+            const uint32_t idx = (h0 + k) & 7u;
+            const unsigned long long cur = table_pick(s, idx);
+            if (cur == kEmpty) return -1;
+            if ((uint32_t)(cur >> 32) == key) { value = (uint32_t)cur; return (int64_t)b * kBucketSlots + idx; }
+        }
+        b = (b + 1) & bmask;
     }
 }
 

@@ -11,12 +11,13 @@
 //   3. grid scan of "this flat entry is the first appearance of a new id"
 //                                                            -> S_h appended in order, n_h, table value := local id
 //   4. relabel: src[e] = table value of the e-th sampled id
-// The table (open addressing, global memory, sized for the bound on |S_L|) lives for the whole
-// minibatch: after hop h every key's value is its index in S_h, which is below any position offered
-// at hop h+1, so earlier vertices keep their ids.  The bound is loose (a Mid minibatch uses 66k of
-// 1.08M possible vertices), so the tables are not wiped per call: every vertex remembers the slot it
-// occupies and a last kernel empties exactly those slots, which leaves the tables clean for the next
-// call without streaming 32 MB per minibatch through the caches.
+// The id table (open addressing, global memory) is right-sized per hop on the device: once e_h is
+// known, the hop uses the first 2^k >= 2 (n_{h-1} + e_h) slots of the minibatch's region, clears
+// exactly those, and the sample kernel re-offers S_{h-1} (value = index, which is below any
+// position offered at this hop, so earlier vertices keep their ids) next to the new ids.  The
+// worst-case bound on |S_L| only sizes the allocation: a Mid minibatch reaches 66k of 1.08M
+// possible vertices, and a table laid out for the bound (32 MB per minibatch, touched at random)
+// pushed the feature rows out of the caches (the hit copy ran 20 % slower) besides missing L2 itself.
 #include "spp_common.h"
 #include "spp_device.h"
 
@@ -31,7 +32,7 @@ struct BatchDesc {
     int32_t*       indptr[SPP_MAX_L];
     int32_t*       src[SPP_MAX_L];
     int64_t*       counts;              // n[0..MAX_L], e[0..MAX_L]
-    int32_t*       slots;               // table slot of S[i] (workspace)
+    uint32_t*      tinfo;               // [0] mask, [1] shift of the table for the current hop (workspace)
     int32_t        nseeds;
     uint32_t       batch_lo;
 };
@@ -45,9 +46,7 @@ struct SampleArgs {
     const int32_t* col;
     int64_t        N;
     unsigned long long* tab;            // one region of `cap` entries per minibatch
-    int64_t        cap;
-    uint32_t       mask;
-    int            shift;
+    int64_t        cap;                 // slots per region (a power of two, sized for the bound on |S_L|)
     int32_t*       flat;                // one region of `flat_stride` sampled global ids per minibatch (current hop)
     int64_t        flat_stride;
     unsigned long long* totals;         // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
@@ -62,29 +61,21 @@ __device__ __forceinline__ unsigned long long* tab_of(const SampleArgs& a, int j
 __device__ __forceinline__ int32_t* flat_of(const SampleArgs& a, int j) { return a.flat + (int64_t)j * a.flat_stride; }
 constexpr int kE = SPP_MAX_L + 1;      // offset of e[] inside counts
 
-// Zeroes the counts of the new minibatches; wipes their id tables when they are not known to be clean
-// (first use, a different capacity, or a call that did not finish).
-__global__ void __launch_bounds__(kBlock) sample_init_kernel(SampleArgs a, const BatchTable* __restrict__ t, int wipe) {
-    const int j = blockIdx.y;
-    unsigned long long* tab = tab_of(a, j);
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    const int64_t tid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (wipe) for (int64_t i = tid; i < a.cap; i += stride) tab[i] = ~0ull;
-    if (tid == 0) {
+// Zeroes the counts of the new minibatches and copies the seeds into S_0.
+__global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const BatchBlock bb = batch_block();
+    const int j = bb.j;
+    const int i = bb.x * kBlock + threadIdx.x;
+    if (i == 0) {
         int64_t* c = t->b[j].counts;
-        for (int k = 0; k <= SPP_MAX_L; ++k) { c[k] = 0; c[kE + k] = 0; }
+        for (int k = 1; k <= SPP_MAX_L; ++k) c[k] = 0;
+        for (int k = 0; k <= SPP_MAX_L; ++k) c[kE + k] = 0;
         c[0] = t->b[j].nseeds;
     }
-}
-
-__global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    const int j = blockIdx.y;
-    const int i = blockIdx.x * kBlock + threadIdx.x;
     if (i >= t->b[j].nseeds) return;
     int32_t v = t->b[j].seeds[i];
     if (v < 0 || v >= a.N) { v = 0; atomicOr(a.bad, 1); }       // reported; keeps later row reads in range
     t->b[j].S[i] = v;
-    t->b[j].slots[i] = (int32_t)table_insert_min(tab_of(a, j), a.mask, a.shift, (uint32_t)v, (uint32_t)i);
 }
 
 // ---- step 1 ----
@@ -108,13 +99,32 @@ struct CountFin {
         t->b[j].indptr[a.h - 1][c[a.h - 1]] = total;
         c[kE + a.h] = total;
         atomicAdd(&a.totals[2], (unsigned long long)(uint32_t)total);
+        // this hop's table: the smallest power of two >= 2 (n_{h-1} + e_h), at least 1024 slots,
+        // never more than the region (the host sized it for the bound, which dominates)
+        const uint64_t want = 2ull * (uint64_t)(c[a.h - 1] + total);
+        uint32_t capj = 1024;
+        int shift = 22;
+        while (capj < want && (int64_t)capj < a.cap) { capj <<= 1; --shift; }
+        t->b[j].tinfo[0] = capj - 1;
+        t->b[j].tinfo[1] = (uint32_t)shift;
     }
 };
 
 // ---- step 2 ----
+// Empties the part of the region that this hop's table occupies.
+__global__ void __launch_bounds__(kBlock) table_clear_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const BatchBlock bb = batch_block();
+    const int j = bb.j;
+    unsigned long long* tab = tab_of(a, j);
+    const int64_t capj = (int64_t)t->b[j].tinfo[0] + 1;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)bb.x * kBlock + threadIdx.x; i < capj; i += stride) tab[i] = ~0ull;
+}
+
 template <int G>
 __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    const int jb = blockIdx.y;
+    const BatchBlock bb = batch_block();
+    const int jb = bb.j;
     const int lane = lane_id();
     const int j = lane & (G - 1);                  // slot handled by this lane
     const int gbase = lane - j;                    // first lane of the group inside the wavefront
@@ -122,13 +132,15 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
     constexpr int kGroupsPerWave = kWave / G;
     const int64_t n_prev = t->b[jb].counts[a.h - 1];
     const uint32_t batch_lo = t->b[jb].batch_lo;
-    const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const int64_t wave = ((int64_t)bb.x * kBlock + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
     const int f = a.f;
     const int32_t* __restrict__ S = t->b[jb].S;
     const int32_t* __restrict__ indptr = t->b[jb].indptr[a.h - 1];
     int32_t* __restrict__ flat = flat_of(a, jb);
     unsigned long long* tab = tab_of(a, jb);
+    const uint32_t mask = t->b[jb].tinfo[0];
+    const int shift = (int)t->b[jb].tinfo[1];
 
     for (int64_t first = wave * kGroupsPerWave; first < n_prev; first += nwaves * kGroupsPerWave) {
         const int64_t i = first + (lane / G);
@@ -161,12 +173,22 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
                 if (j == jj && b != 0ull) pos = (int64_t)m;
             }
         }
+        // the table was emptied for this hop, so the target is offered again with its index; the
+        // group's last lane does it when it has no neighbour of its own (c < G), else lane 0 after
+        // its neighbour
+        const bool spare = c < G;
+        uint32_t key = 0, val = 0;
+        bool ins = false;
         if (valid && j < c) {
             const int32_t gid = a.col[r0 + pos];
             const int64_t e = (int64_t)off + j;
             flat[e] = gid;
-            table_insert_min(tab, a.mask, a.shift, (uint32_t)gid, (uint32_t)(n_prev + e));
+            key = (uint32_t)gid; val = (uint32_t)(n_prev + e); ins = true;
+        } else if (valid && spare && j == G - 1) {
+            key = (uint32_t)v; val = (uint32_t)i; ins = true;
         }
+        if (ins) table_insert_min(tab, mask, shift, key, val);
+        if (valid && !spare && j == 0) table_insert_min(tab, mask, shift, (uint32_t)v, (uint32_t)i);
     }
 }
 
@@ -176,7 +198,7 @@ struct NewIn {
     __device__ int64_t n(int j) const { return t->b[j].counts[kE + a.h]; }
     __device__ int operator()(int j, int64_t e) const {
         uint32_t val = 0;
-        table_find(tab_of(a, j), a.mask, a.shift, (uint32_t)flat_of(a, j)[e], val);
+        table_find(tab_of(a, j), t->b[j].tinfo[0], (int)t->b[j].tinfo[1], (uint32_t)flat_of(a, j)[e], val);
         return (int64_t)val == t->b[j].counts[a.h - 1] + e ? 1 : 0;
     }
 };
@@ -187,10 +209,9 @@ struct NewOut {
         unsigned long long* tab = tab_of(a, j);
         const uint32_t gid = (uint32_t)flat_of(a, j)[e];
         uint32_t val = 0;
-        const int64_t slot = table_find(tab, a.mask, a.shift, gid, val);
+        const int64_t slot = table_find(tab, t->b[j].tinfo[0], (int)t->b[j].tinfo[1], gid, val);
         const int64_t id = t->b[j].counts[a.h - 1] + ex;
         t->b[j].S[id] = (int32_t)gid;
-        t->b[j].slots[id] = (int32_t)slot;
         // the new value is <= the old one and is never equal to another entry's own position, so
         // threads still testing "first appearance" read either value with the same outcome
         __hip_atomic_store(&tab[slot], ((unsigned long long)gid << 32) | (uint32_t)id, __ATOMIC_RELAXED,
@@ -209,27 +230,20 @@ struct NewFin {
 
 // ---- step 4 ----
 __global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    const int j = blockIdx.y;
+    const BatchBlock bb = batch_block();
+    const int j = bb.j;
     const int64_t e_h = t->b[j].counts[kE + a.h];
     const unsigned long long* tab = tab_of(a, j);
     const int32_t* __restrict__ flat = flat_of(a, j);
     int32_t* __restrict__ src = t->b[j].src[a.h - 1];
+    const uint32_t mask = t->b[j].tinfo[0];
+    const int shift = (int)t->b[j].tinfo[1];
     const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < e_h; e += stride) {
+    for (int64_t e = (int64_t)bb.x * kBlock + threadIdx.x; e < e_h; e += stride) {
         uint32_t val = 0;
-        table_find(tab, a.mask, a.shift, (uint32_t)flat[e], val);
+        table_find(tab, mask, shift, (uint32_t)flat[e], val);
         src[e] = (int32_t)val;
     }
-}
-
-// Leaves the id tables empty again: every vertex of S_L clears the slot it occupies.
-__global__ void __launch_bounds__(kBlock) table_release_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    const int j = blockIdx.y;
-    const int64_t n = t->b[j].counts[a.L];
-    unsigned long long* tab = tab_of(a, j);
-    const int32_t* __restrict__ slots = t->b[j].slots;
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) tab[(uint32_t)slots[i]] = ~0ull;
 }
 
 // Stores the call's table of per-minibatch pointers in device memory and clears the error flag.
@@ -302,20 +316,13 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
     hipStream_t st = ctx->stream;
 
     const uint32_t cap = next_pow2((uint64_t)(2 * nb[L] > 1024 ? 2 * nb[L] : 1024));
-    int shift = 32;
-    for (uint32_t c = cap; c > 1; c >>= 1) --shift;
     // workgroups per minibatch in the scans and the table clear: the whole call gets about 4 per CU
     const int per_batch = (ctx->num_cu * 4 + n_items - 1) / n_items;
-    const int scan_grid = per_batch < 32 ? 32 : per_batch;
+    const int scan_grid = ((per_batch < 32 ? 32 : per_batch) + 7) & ~7;     // multiples of 8: see batch_block()
     SPP_TRY(ctx->table.reserve((size_t)cap * sizeof(uint64_t) * n_items));
     SPP_TRY(ctx->flat.reserve((size_t)emax * sizeof(int32_t) * n_items));
-    SPP_TRY(ctx->slots.reserve((size_t)(nb[L] > 1 ? nb[L] : 1) * sizeof(int32_t) * n_items));
-    for (int j = 0; j < n_items; ++j) ht.b[j].slots = ctx->slots.as<int32_t>() + (int64_t)j * (nb[L] > 1 ? nb[L] : 1);
-    // the tables are clean if the last call used this buffer with this capacity, covered at least
-    // these regions and was enqueued completely
-    const bool wipe = !(ctx->table_clean_ptr == ctx->table.ptr && ctx->table_clean_cap == (int64_t)cap &&
-                        ctx->table_clean_regions >= n_items);
-    ctx->table_clean_ptr = nullptr;
+    SPP_TRY(ctx->slots.reserve((size_t)2 * sizeof(uint32_t) * n_items));
+    for (int j = 0; j < n_items; ++j) ht.b[j].tinfo = ctx->slots.as<uint32_t>() + 2 * j;
     SPP_TRY(ctx->partials.reserve((size_t)scan_grid * n_items * sizeof(int) + 64 + sizeof(BatchTable) + 256));
     int* partial = ctx->partials.as<int>();
     int* d_bad = partial + (size_t)scan_grid * n_items;
@@ -326,23 +333,27 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
 
     SampleArgs a;
     a.rowptr = g->rowptr; a.col = g->col; a.N = g->N;
-    a.tab = ctx->table.as<unsigned long long>(); a.cap = cap; a.mask = cap - 1; a.shift = shift;
+    a.tab = ctx->table.as<unsigned long long>(); a.cap = cap;
     a.flat = ctx->flat.as<int32_t>(); a.flat_stride = emax;
     a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.bad = d_bad;
     a.L = L; a.h = 0; a.f = 0; a.seed = seed;
 
     auto capped = [&](int64_t need, int64_t lim) {
-        return (unsigned)(need < 1 ? 1 : (need < lim ? need : lim));
+        const int64_t g = need < 1 ? 1 : (need < lim ? need : lim);
+        return (unsigned)((g + 7) & ~(int64_t)7);
     };
     const int64_t share = (int64_t)ctx->num_cu * 16 / n_items + 1;    // workgroups per minibatch in the wide kernels
     {
         ScopedTimer tt(ctx, SPP_T_SAMPLE, st);
         batch_table_store_kernel<<<1, kBlock, 0, st>>>(ht, dt, d_bad);
-        sample_init_kernel<<<dim3(wipe ? capped(cap / kBlock, scan_grid) : 1, n_items), kBlock, 0, st>>>(a, dt, wipe ? 1 : 0);
-        if (max_seeds > 0) seeds_kernel<<<dim3((max_seeds + kBlock - 1) / kBlock, n_items), kBlock, 0, st>>>(a, dt);
+        seeds_kernel<<<dim3(capped((max_seeds + kBlock - 1) / kBlock, 1 << 20), n_items), kBlock, 0, st>>>(a, dt);
         for (int h = 1; h <= L; ++h) {
             a.h = h; a.f = fanouts[h - 1];
             grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial);
+            {   // the hop's table holds at most 2 (n_bound[h-1] + e_bound[h]) keys' worth of slots
+                const int64_t slots_bound = 4 * (nb[h - 1] + eb[h]) < (int64_t)cap ? 4 * (nb[h - 1] + eb[h]) : (int64_t)cap;
+                table_clear_kernel<<<dim3(capped((slots_bound + kBlock * 8 - 1) / (kBlock * 8), share), n_items), kBlock, 0, st>>>(a, dt);
+            }
             const int G = a.f <= 8 ? 8 : a.f <= 16 ? 16 : a.f <= 32 ? 32 : 64;
             const dim3 sgrid(capped((nb[h - 1] * G + kBlock - 1) / kBlock, share), n_items);
             switch (G) {
@@ -354,12 +365,8 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
             grid_scan_batched(st, scan_grid, n_items, NewIn{a, dt}, NewOut{a, dt}, NewFin{a, dt}, partial);
             relabel_kernel<<<dim3(capped((eb[h] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
         }
-        table_release_kernel<<<dim3(capped((nb[L] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
     }
     SPP_HIP(hipGetLastError());
-    ctx->table_clean_ptr = ctx->table.ptr;
-    ctx->table_clean_cap = cap;
-    if (wipe || n_items > ctx->table_clean_regions) ctx->table_clean_regions = n_items;
     if (flags & SPP_SYNC) {
         int64_t* hp = ctx->h_pinned + 64;            // 16 x 18 counts, then the flag
         for (int j = 0; j < n_items; ++j)
