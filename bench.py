@@ -27,7 +27,7 @@ PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 # and profiles/vip_pull_mid_counters.txt.  Keyed by (workload, minibatches per gather launch); other
 # shapes report null.
 MEASURED_TRAFFIC = {
-    ("mid", 8): {"gather_hit": 163.0e6 + 124.3e6, "vip_pull": 1.80e9 + 20.5e6},
+    ("mid", 8): {"gather_hit": 174.0e6 + 134.9e6, "vip_pull": 1.803e9 + 20.5e6},
 }
 
 
