@@ -34,6 +34,7 @@ def _load():
         _lib.orc_cache_select.restype = C.c_int64
         _lib.orc_cache_capacity.restype = C.c_int64
         _lib.orc_rand32.restype = C.c_uint32
+        _lib.orc_local_capacity.restype = C.c_int64
     return _lib
 
 
@@ -178,4 +179,59 @@ def gather(N, lo, hi, local, cache_rows, cache_ids, remote, node_ids):
                         _p(node_ids), C.c_int64(node_ids.size), _p(out), _p(tag), _p(counts))
     if rc != 0:
         raise ValueError(f"orc_gather failed ({rc})")
+    return out, tag[:node_ids.size], tuple(int(c) for c in counts)
+
+
+def local_capacity(beta, n_local) -> int:
+    """floor(beta * n_local): local rows kept in device memory."""
+    return int(_load().orc_local_capacity(C.c_double(float(beta)), C.c_int64(int(n_local))))
+
+
+def local_rank(score, lo, hi):
+    """Order of the partition's own vertices [lo, hi) by (score descending, id ascending).
+
+    Returns (rank[int32, hi-lo], order[int32, hi-lo]): rank[i] is the position of vertex lo+i,
+    order[r] the local index at position r.
+    """
+    lib = _load()
+    score = np.ascontiguousarray(score, dtype=np.float32)
+    n = int(hi) - int(lo)
+    rank = np.empty(max(n, 1), dtype=np.int32)
+    order = np.empty(max(n, 1), dtype=np.int32)
+    rc = lib.orc_local_rank(_p(score), C.c_int64(int(lo)), C.c_int64(int(hi)), _p(rank), _p(order))
+    if rc != 0:
+        raise MemoryError("orc_local_rank")
+    return rank[:n], order[:n]
+
+
+def gather_split(N, lo, hi, local_dev, local_host, rank, n_dev, cache_rows, cache_ids, remote, node_ids):
+    """The gather with the local store split into a device prefix (rows in rank order) and the
+    host array (all local rows in id order).
+
+    Returns (out, src_tag[int8: 0 local device / 1 cache / 2 miss / 3 local host],
+             (n_local_dev, n_cache_hit, n_miss, n_local_host)).
+    """
+    lib = _load()
+    local_host = np.ascontiguousarray(local_host)
+    remote = np.ascontiguousarray(remote)
+    D = local_host.shape[1]
+    row_bytes = D * local_host.dtype.itemsize
+    if local_dev is None or int(n_dev) == 0:
+        local_dev = np.empty((1, D), dtype=local_host.dtype)
+    local_dev = np.ascontiguousarray(local_dev)
+    cache_ids = _i32(cache_ids if cache_ids is not None else [])
+    if cache_rows is None or cache_ids.size == 0:
+        cache_rows = np.empty((1, D), dtype=local_host.dtype)
+    cache_rows = np.ascontiguousarray(cache_rows)
+    rank = _i32(rank)
+    node_ids = _i32(node_ids)
+    out = np.empty((node_ids.size, D), dtype=local_host.dtype)
+    tag = np.empty(max(node_ids.size, 1), dtype=np.int8)
+    counts = np.zeros(4, dtype=np.int64)
+    rc = lib.orc_gather_split(C.c_int64(int(N)), C.c_int64(int(lo)), C.c_int64(int(hi)), _p(local_dev),
+                              _p(local_host), _p(rank), C.c_int64(int(n_dev)), _p(cache_rows), _p(cache_ids),
+                              C.c_int64(cache_ids.size), _p(remote), C.c_int64(row_bytes), _p(node_ids),
+                              C.c_int64(node_ids.size), _p(out), _p(tag), _p(counts))
+    if rc != 0:
+        raise ValueError(f"orc_gather_split failed ({rc})")
     return out, tag[:node_ids.size], tuple(int(c) for c in counts)

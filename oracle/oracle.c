@@ -292,3 +292,88 @@ int orc_gather(int64_t N, int64_t lo, int64_t hi, const void *local, const void 
     free(slot);
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * VIP-ordered local storage (Sec. 3.2, paragraph on host-to-device transfer reduction; Sec. 4.1;
+ * the experiment of Sec. 5 on local partition storage on CPU versus GPU): the partition's own
+ * vertices are ranked by decreasing score, and the features of the first floor(beta * (hi-lo))
+ * of that order are kept in device memory; the others stay in host memory.
+ * Order: score descending, vertex id ascending among equal scores; a score that is not
+ * positive (or not a number) counts as 0.  A constant score therefore gives the id order
+ * (the "no reorder" baseline of that experiment).
+ *   rank[i]  = position of local vertex lo + i in the order
+ *   order[r] = local index of the vertex at position r
+ * ---------------------------------------------------------------------------------------- */
+int64_t orc_local_capacity(double beta, int64_t n_local)
+{
+    if (!(beta > 0.0)) return 0;
+    double c = floor(beta * (double)n_local);
+    if (c > (double)n_local) c = (double)n_local;
+    return (int64_t)c;
+}
+
+typedef struct { float s; int32_t i; } orc_local_item;
+
+static int orc_local_cmp(const void *a, const void *b)
+{
+    const orc_local_item *x = (const orc_local_item *)a, *y = (const orc_local_item *)b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return (x->i > y->i) - (x->i < y->i);
+}
+
+int orc_local_rank(const float *score, int64_t lo, int64_t hi, int32_t *rank, int32_t *order)
+{
+    const int64_t n = hi - lo;
+    if (n <= 0) return 0;
+    orc_local_item *it = (orc_local_item *)malloc((size_t)n * sizeof(orc_local_item));
+    if (!it) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        const float s = score[lo + i];
+        it[i].s = (s > 0.0f) ? s : 0.0f;          /* false for NaN too */
+        it[i].i = (int32_t)i;
+    }
+    qsort(it, (size_t)n, sizeof(orc_local_item), orc_local_cmp);
+    for (int64_t r = 0; r < n; ++r) {
+        order[r] = it[r].i;
+        rank[it[r].i] = (int32_t)r;
+    }
+    free(it);
+    return 0;
+}
+
+/* The gather of orc_gather with the local store split in two:
+ *   local_dev  [n_dev rows]   rows of the first n_dev vertices of the order (row = rank)
+ *   local_host [hi-lo rows]   all local rows in id order (row g - lo); read for rank >= n_dev
+ * src_tag: 0 local from device, 1 cache, 2 remote miss, 3 local from host.
+ * counts: the same four, in that order.  The split never changes a byte of the result. */
+int orc_gather_split(int64_t N, int64_t lo, int64_t hi, const void *local_dev, const void *local_host,
+                     const int32_t *rank, int64_t n_dev, const void *cache, const int32_t *cache_ids,
+                     int64_t n_cached, const void *remote, int64_t row_bytes, const int32_t *node_ids,
+                     int64_t n, void *out, int8_t *src_tag, int64_t counts[4])
+{
+    int32_t *slot = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    if (!slot) return -1;
+    for (int64_t g = 0; g < N; ++g) slot[g] = -1;
+    for (int64_t s = 0; s < n_cached; ++s) slot[cache_ids[s]] = (int32_t)s;
+    counts[0] = counts[1] = counts[2] = counts[3] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t g = node_ids[i];
+        if (g < 0 || g >= N) { free(slot); return -1; }
+        const char *from;
+        int tag;
+        if (g >= lo && g < hi) {
+            const int64_t r = rank[g - lo];
+            if (r < n_dev) { from = (const char *)local_dev + r * row_bytes; tag = 0; }
+            else           { from = (const char *)local_host + (g - lo) * row_bytes; tag = 3; }
+        }
+        else if (slot[g] >= 0)   { from = (const char *)cache + (int64_t)slot[g] * row_bytes; tag = 1; }
+        else { int64_t r = g < lo ? g : g - (hi - lo);
+               from = (const char *)remote + r * row_bytes; tag = 2; }
+        memcpy((char *)out + i * row_bytes, from, (size_t)row_bytes);
+        if (src_tag) src_tag[i] = (int8_t)tag;
+        counts[tag]++;
+    }
+    free(slot);
+    return 0;
+}
