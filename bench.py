@@ -74,6 +74,48 @@ def alpha_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, h
                       "rows": rows}), flush=True)
 
 
+def beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi):
+    """Host reads for local vertices over the device-resident share beta of the partition's rows:
+    VIP order against the id order (Sec. 3.2 on host-to-device transfers; the experiment shape of the
+    figure on local partition storage on CPU versus GPU)."""
+    betas = [0.0, 0.02, 0.05, 0.1, 0.2, 0.5, 1.0]
+    row_bytes = cfg.D * cfg.elem_bytes
+    local_host = torch.empty(tuple(local.shape), dtype=local.dtype).pin_memory()
+    local_host.copy_(local)
+    cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)
+    batches = [b for b in S.epoch_batches(cfg, Tk, 0) if b.numel() == min(cfg.B, Tk.numel())][:args.sweep_batches]
+    bufs = [spp.MFGBuffers(local.device, cfg.B, cfg.fanouts, cfg.N) for _ in batches]
+    outs = [torch.empty((bufs[0].nb[-1], cfg.D), dtype=cfg.torch_dtype, device=local.device) for _ in batches]
+    spp.sample_mfg_multi(ctx, G, [(b, i, bufs[i]) for i, b in enumerate(batches)], cfg.fanouts, cfg.seed_sampler)
+    lists = [(bufs[i].node_ids, bufs[i].nb[-1], bufs[i].n_final_device, outs[i]) for i in range(len(batches))]
+    rows = []
+    for order, score in (("vip", p), ("id (no reorder)", torch.zeros_like(p))):
+        t = time.time()
+        store = spp.build_local_store(ctx, score, lo, hi, 1.0, local_host)
+        build_s = time.time() - t
+        for beta in betas:
+            n_dev = int(beta * (hi - lo))
+            store.set_limit(n_dev)
+            spp.gather_features_multi(ctx, cache, store, cfg.N, lo, hi, remote, lists)          # warm-up
+            ctx.timing(True)
+            st = spp.gather_features_multi(ctx, cache, store, cfg.N, lo, hi, remote, lists)
+            ms, cnt = ctx.times()
+            ctx.timing(False)
+            nb = len(batches)
+            rows.append({"order": order, "beta": beta, "device_rows": n_dev, "build_s": build_s,
+                         "local_rows_per_batch": st["n_local"] / nb,
+                         "local_host_rows_per_batch": st["n_local_host"] / nb,
+                         "local_served_from_device": 1.0 - st["n_local_host"] / max(st["n_local"], 1),
+                         "local_host_bytes_per_batch": st["n_local_host"] * row_bytes / nb,
+                         "remote_miss_rows_per_batch": st["n_miss"] / nb,
+                         "gather_hit_ms": ms[10] / max(cnt[10], 1), "gather_miss_ms": ms[11] / max(cnt[11], 1)})
+            log(rows[-1])
+        store.close()
+    cache.close()
+    print(json.dumps({"phase": "beta-sweep", "workload": cfg.name, "N": g.N, "M": g.M, "batches": len(batches),
+                      "alpha": cfg.alpha, "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,10 +129,13 @@ def main():
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
                          "(pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
-    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "calibrate"],
+    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
                          "alpha-sweep: hit rate and host-miss bytes per batch over alpha in {0,.05,.1,.2,.5}, VIP-ranked "
                          "against degree-ranked cache (the experiment shape of Fig. 2 / Fig. 7), e.g. with --config skew; "
+                         "beta-sweep: local rows read from host memory over the device-resident share beta of the "
+                         "partition's rows, VIP order against id order (the experiment shape of the figure on local "
+                         "storage on CPU versus GPU); "
                          "calibrate: a plain elementwise pass over 1 GiB (read 1 GiB, write 1 GiB), the known-size kernel "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
     ap.add_argument("--sweep-batches", type=int, default=8)
@@ -133,12 +178,18 @@ def main():
     t_inlists = time.time() - t
     local = S.feature_block(cfg, lo, hi, dev)
     nrem = cfg.N - (hi - lo)
-    remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
+    if args.phase == "beta-sweep":
+        # this sweep measures host reads of LOCAL rows: the remote store sits in device memory so that
+        # the host's pinning limit is left to the partition's own rows
+        remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype, device=dev)
+    else:
+        remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
     for a in range(0, nrem, 1 << 19):
         b = min(nrem, a + (1 << 19))
         remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
     torch.cuda.synchronize()
-    log(f"features local {tuple(local.shape)} remote {tuple(remote.shape)} pinned; in-lists built in {t_inlists:.2f}s")
+    log(f"features local {tuple(local.shape)} remote {tuple(remote.shape)} "
+        f"{'pinned' if remote.is_pinned() else 'in device memory'}; in-lists built in {t_inlists:.2f}s")
 
     # ---- one-time rows: VIP propagation, cache ranking + fill -------------------------------
     p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts)            # warm-up, allocates workspaces
@@ -167,6 +218,9 @@ def main():
         return
     if args.phase == "alpha-sweep":
         alpha_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
+        return
+    if args.phase == "beta-sweep":
+        beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
         return
     t = time.time()
     cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)

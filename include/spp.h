@@ -179,7 +179,10 @@ int  spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
  *     `remote` is pinned host memory (or device memory); it may be NULL only if no id misses.
  *     stats (host, may be NULL) is filled when SPP_SYNC is set; otherwise read it later with
  *     spp_gather_last_stats after synchronising. */
-typedef struct { int64_t n_local, n_cache_hit, n_miss, miss_bytes; } spp_gather_stats;
+/* n_local counts every id of the owned range; n_local_host of them were read from host memory
+ * (only with a split local store, see spp_build_local_store).  miss_bytes = bytes read from host
+ * memory = (n_miss + n_local_host) * row size. */
+typedef struct { int64_t n_local, n_cache_hit, n_miss, miss_bytes, n_local_host; } spp_gather_stats;
 int  spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
                          int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D, int32_t elem_bytes,
                          const int32_t* d_node_ids, int64_t n, const int64_t* d_n, void* d_out,
@@ -208,6 +211,36 @@ int  spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, const void*
                                int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
                                spp_gather_stats* stats, uint32_t flags);
 
+/* (f) VIP-ordered local storage (Sec. 3.2, paragraph on host-to-device transfer reduction; Sec. 4.1;
+ *     Sec. 5, local partition storage on CPU versus GPU).  The partition's own vertices [lo, hi) are
+ *     ranked by (d_score descending, id ascending; a score that is not positive counts as 0, so a
+ *     constant score gives the id order) and the rows of the first floor(beta * (hi-lo)) of that
+ *     order are copied into device memory, in rank order; the other local rows are read from
+ *     local_rows when a gather needs them, on the miss path (side stream), like remote misses.
+ *     local_rows [hi-lo, D] (row g - lo) is pinned host memory (or device memory) owned by the
+ *     caller; it must stay valid while the store is used.  The store keeps a device array
+ *     int32[hi-lo] with every local vertex's rank (the paper renumbers the vertices instead).
+ *     n_device_rows (host, out) = rows kept in device memory.
+ *     spp_local_store_set_limit: use only the first n_rows of the device rows (a smaller beta is a
+ *     prefix of a larger one); negative = all.
+ *     spp_local_store_rank: d_rank_out[i] = rank of d_ids[i], or -1 if it is not in [lo, hi). */
+typedef struct spp_local_store spp_local_store;
+int  spp_build_local_store(spp_ctx* ctx, const float* d_score, int64_t N, int64_t lo, int64_t hi, double beta,
+                           const void* local_rows, int32_t D, int32_t elem_bytes,
+                           int64_t* n_device_rows, spp_local_store** out);
+void spp_local_store_destroy(spp_local_store* store);
+int  spp_local_store_set_limit(spp_local_store* store, int64_t n_rows);
+int  spp_local_store_rank(spp_ctx* ctx, const spp_local_store* store, const int32_t* d_ids, int64_t n,
+                          int32_t* d_rank_out);
+/*     The gather of spp_gather_features_multi with the local shard held by such a store: a local
+ *     id whose rank is below the limit is copied from the device rows by the hit kernel, any other
+ *     local id joins the miss list and is read from local_rows.  Results are byte-identical to
+ *     the gather with the whole shard in device memory. */
+int  spp_gather_features_split(spp_ctx* ctx, const spp_cache* cache, const spp_local_store* store,
+                               int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                               int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
+                               spp_gather_stats* stats, uint32_t flags);
+
 /* Device-time accounting.  After spp_ctx_timing(ctx, 1) every call brackets its pieces of device
  * work with events on the stream they run on (vip total and per hop, the whole sampling of a
  * batch, gather classify / hit copy / miss copy).  spp_ctx_times waits for the context's streams,
@@ -222,7 +255,7 @@ int  spp_ctx_times(spp_ctx* ctx, float* sum_ms /* [SPP_T_COUNT] */, int64_t* cou
  * that a loop of asynchronous calls can be accounted for without a host round trip per batch:
  *   out[0] minibatches sampled, out[1] sum of |S_L|, out[2] sum of sampled edges over all hops,
  *   out[3] gather calls, out[4] rows from the local shard, out[5] rows from the cache,
- *   out[6] rows missed (served from the remote store), out[7] unused.
+ *   out[6] rows missed (served from the remote store), out[7] local rows read from host memory.
  * Waits for the context's streams. */
 int  spp_ctx_totals(spp_ctx* ctx, int64_t* out /* [8] */, int reset);
 

@@ -29,6 +29,8 @@ EXPORTS = [
     "spp_graph_destroy", "spp_vip_propagate", "spp_vip_last_hops", "spp_build_vip_cache", "spp_cache_destroy",
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg", "spp_sample_mfg_multi",
     "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
+    "spp_build_local_store", "spp_local_store_destroy", "spp_local_store_set_limit", "spp_local_store_rank",
+    "spp_gather_features_split",
 ]
 
 
@@ -60,7 +62,7 @@ class _GatherList(C.Structure):
 
 class _GatherStats(C.Structure):
     _fields_ = [("n_local", C.c_int64), ("n_cache_hit", C.c_int64), ("n_miss", C.c_int64),
-                ("miss_bytes", C.c_int64)]
+                ("miss_bytes", C.c_int64), ("n_local_host", C.c_int64)]
 
 
 _lib = None
@@ -109,6 +111,16 @@ def load_library():
                                               C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_GatherList), C.c_int32,
                                               C.POINTER(_GatherStats), C.c_uint32]
     lib.spp_gather_last_stats.argtypes = [C.c_void_p, C.POINTER(_GatherStats)]
+    lib.spp_local_store_destroy.restype = None
+    lib.spp_build_local_store.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                          C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64),
+                                          C.POINTER(C.c_void_p)]
+    lib.spp_local_store_destroy.argtypes = [C.c_void_p]
+    lib.spp_local_store_set_limit.argtypes = [C.c_void_p, C.c_int64]
+    lib.spp_local_store_rank.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.spp_gather_features_split.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                              C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_GatherList), C.c_int32,
+                                              C.POINTER(_GatherStats), C.c_uint32]
     lib.spp_gather_join.argtypes = [C.c_void_p]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
     lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
@@ -164,10 +176,11 @@ class Context:
         return list(ms), list(cnt)
 
     def totals(self, reset: bool = False):
-        """Running sums since the last reset: batches, |S_L|, edges, gather calls, local / cache / missed rows."""
+        """Running sums since the last reset: batches, |S_L|, edges, gather calls, local / cache / missed rows,
+        local rows read from host memory (split local store)."""
         buf = (C.c_int64 * 8)()
         _check(load_library().spp_ctx_totals(self._h, buf, int(reset)))
-        keys = ("batches", "n_nodes", "n_edges", "gather_calls", "n_local", "n_cache_hit", "n_miss")
+        keys = ("batches", "n_nodes", "n_edges", "gather_calls", "n_local", "n_cache_hit", "n_miss", "n_local_host")
         return dict(zip(keys, list(buf)))
 
     def close(self):
@@ -287,6 +300,54 @@ def build_vip_cache(ctx: Context, score: torch.Tensor, lo: int, hi: int, K: int,
     return Cache(ctx, h, ids[:n_cached.value], N, lo, hi, remote)
 
 
+class LocalStore:
+    """The partition's own rows split by a score order: a device-resident prefix plus the caller's host array."""
+
+    def __init__(self, ctx, handle, n_device_rows, N, lo, hi, local_rows):
+        self.ctx, self._h, self.n_device_rows, self.N, self.lo, self.hi = ctx, handle, n_device_rows, N, lo, hi
+        self.local_rows = local_rows            # kept alive: the library reads it on the miss path
+
+    def set_limit(self, n_rows: int):
+        _check(load_library().spp_local_store_set_limit(self._h, int(n_rows)))
+
+    def rank(self, ids: torch.Tensor) -> torch.Tensor:
+        ids = _dev(ids, torch.int32, "ids")
+        out = torch.empty_like(ids)
+        _check(load_library().spp_local_store_rank(self.ctx._h, self._h, _ptr(ids), ids.numel(), _ptr(out)))
+        return out
+
+    def close(self):
+        if self._h:
+            load_library().spp_local_store_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def build_local_store(ctx: Context, score: torch.Tensor, lo: int, hi: int, beta: float,
+                      local_rows: torch.Tensor) -> LocalStore:
+    """Rank the vertices of [lo, hi) by (score desc, id asc); rows of the first floor(beta*(hi-lo)) go to the GPU."""
+    score = _dev(score, torch.float32, "score")
+    local_rows = _row_store(local_rows, "local_rows")
+    if local_rows.shape[0] != hi - lo:
+        raise SppError("local_rows must hold hi - lo rows")
+    n_rows = C.c_int64(0)
+    h = C.c_void_p()
+    _check(load_library().spp_build_local_store(ctx._h, _ptr(score), score.numel(), int(lo), int(hi), float(beta),
+                                                _ptr(local_rows), int(local_rows.shape[1]),
+                                                int(local_rows.element_size()), C.byref(n_rows), C.byref(h)))
+    return LocalStore(ctx, h, n_rows.value, score.numel(), lo, hi, local_rows)
+
+
+def _stats_dict(st):
+    return dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes,
+                n_local_host=st.n_local_host)
+
+
 def mfg_bound(nseeds: int, fanouts: Sequence[int], N: int):
     f, L = _fan(fanouts)
     nb = (C.c_int64 * (L + 1))()
@@ -369,8 +430,18 @@ def gather_features(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N
                     sync: bool = True):
     """out[i,:] = row of node_ids[i] from the local shard, the cache, or the remote store on a miss.
 
-    Returns (out, stats) where stats = dict(n_local, n_cache_hit, n_miss, miss_bytes) when sync, else None.
+    `local` is the partition's rows on the GPU, or a LocalStore (rows split between GPU and host).
+    Returns (out, stats) where stats = dict(n_local, n_cache_hit, n_miss, miss_bytes, n_local_host) when sync,
+    else None.
     """
+    if isinstance(local, LocalStore):
+        node_ids = _dev(node_ids, torch.int32, "node_ids")
+        n = int(node_ids.numel() if n is None else n)
+        rows = local.local_rows
+        if out is None:
+            out = torch.empty((n, rows.shape[1]), dtype=rows.dtype, device=node_ids.device)
+        stats = gather_features_multi(ctx, cache, local, N, lo, hi, remote, [(node_ids, n, n_device, out)], sync=sync)
+        return out, stats
     local = _row_store(local, "local")
     if not local.is_cuda:
         raise SppError("local must be on the GPU")
@@ -386,10 +457,7 @@ def gather_features(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N
     _check(load_library().spp_gather_features(ctx._h, cache._h if cache is not None else None, _ptr(local),
                                               int(N), int(lo), int(hi), _ptr(remote), D, eb, _ptr(node_ids), n,
                                               _ptr(n_device), _ptr(out), C.byref(st), SPP_SYNC if sync else 0))
-    stats = None
-    if sync:
-        stats = dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)
-    return out, stats
+    return out, (_stats_dict(st) if sync else None)
 
 
 def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,
@@ -397,10 +465,12 @@ def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Ten
     """One classification / hit copy / miss copy over several id lists.
 
     `lists` is a sequence of (node_ids, n, n_device or None, out); returns the summed stats when sync.
+    `local` is the partition's rows on the GPU, or a LocalStore (rows split between GPU and host).
     """
-    local = _row_store(local, "local")
-    if not local.is_cuda:
-        raise SppError("local must be on the GPU")
+    store = local if isinstance(local, LocalStore) else None
+    local = _row_store(store.local_rows if store is not None else local, "local")
+    if store is None and not local.is_cuda:
+        raise SppError("local must be on the GPU (or pass a LocalStore)")
     remote = _row_store(remote, "remote")
     D, eb = local.shape[1], local.element_size()
     arr = (_GatherList * max(len(lists), 1))()
@@ -413,12 +483,17 @@ def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Ten
         arr[j].d_n = n_dev.data_ptr() if n_dev is not None else None
         arr[j].d_out = out.data_ptr()
     st = _GatherStats()
-    _check(load_library().spp_gather_features_multi(ctx._h, cache._h if cache is not None else None, _ptr(local),
-                                                    int(N), int(lo), int(hi), _ptr(remote), D, eb, arr, len(lists),
-                                                    C.byref(st), (SPP_SYNC if sync else 0) | (0 if join else SPP_NO_JOIN)))
-    if sync:
-        return dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)
-    return None
+    flags = (SPP_SYNC if sync else 0) | (0 if join else SPP_NO_JOIN)
+    lib = load_library()
+    if store is not None:
+        _check(lib.spp_gather_features_split(ctx._h, cache._h if cache is not None else None, store._h,
+                                             int(N), int(lo), int(hi), _ptr(remote), D, eb, arr, len(lists),
+                                             C.byref(st), flags))
+    else:
+        _check(lib.spp_gather_features_multi(ctx._h, cache._h if cache is not None else None, _ptr(local),
+                                             int(N), int(lo), int(hi), _ptr(remote), D, eb, arr, len(lists),
+                                             C.byref(st), flags))
+    return _stats_dict(st) if sync else None
 
 
 def gather_join(ctx: Context):
@@ -429,4 +504,4 @@ def gather_join(ctx: Context):
 def gather_last_stats(ctx: Context):
     st = _GatherStats()
     _check(load_library().spp_gather_last_stats(ctx._h, C.byref(st)))
-    return dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes)
+    return _stats_dict(st)

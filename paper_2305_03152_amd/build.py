@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspp.so")
 SOURCES = ["spp_api.hip", "spp_radix.hip", "spp_graph.hip", "spp_vip.hip", "spp_sample.hip",
-           "spp_gather.hip", "spp_cache.hip"]
+           "spp_gather.hip", "spp_cache.hip", "spp_local.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation

@@ -127,6 +127,17 @@ struct spp_cache {
     void*     rows = nullptr;           // [n_rows, row_bytes] or null (membership only)
 };
 
+struct spp_local_store {
+    int       device = 0;
+    int64_t   N = 0, lo = 0, hi = 0;
+    int64_t   n_rows = 0;               // rows held in device memory
+    int64_t   limit = 0;                // rows in use (<= n_rows)
+    int64_t   row_bytes = 0;
+    int32_t*  rank = nullptr;           // [hi-lo] position of every local vertex in the order
+    void*     rows = nullptr;           // [n_rows, row_bytes], in rank order
+    const void* host_rows = nullptr;    // the caller's [hi-lo, row_bytes] (device-visible address)
+};
+
 namespace spp {
 
 constexpr int kVipChunk = 4096;         // in-list edges per workgroup of the pull kernel
@@ -151,6 +162,8 @@ struct ScopedTimer {
 int radix_sort_u64(spp_ctx* ctx, uint64_t* keys_a, uint64_t* keys_b, int64_t n, int bit_lo,
                    int bit_hi, uint64_t** result);
 
+// Device-visible address of a row store that is either device memory or pinned host memory.
+int device_view(const void* p, const void** out);
 // Rows copied from a row store that may be pinned host memory: out[i,:] = src[rows[i],:].
 int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, int64_t n,
                       int64_t row_bytes, void* d_out, int num_cu);

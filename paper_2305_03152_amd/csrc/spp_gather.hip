@@ -7,6 +7,9 @@
 //                            output walked flat so that stores are dense
 //   miss copy (side stream)  rows read straight from pinned host memory over PCIe, started as
 //                            soon as the classification is done and joined before the call ends
+// With a split local store (Sec. 3.2 on host-to-device transfers, Sec. 4.1) a local id is looked up
+// in the store's rank array: below the limit it is a hit on the device rows (stored in rank order),
+// else it joins the miss list and is read from the host-resident local rows.
 #include "spp_common.h"
 #include "spp_device.h"
 #include "spp_rowcopy.h"
@@ -24,11 +27,15 @@ struct ClassifyArgs {
     uint32_t       mask;
     int            shift;
     int64_t        limit;              // slots in use
+    const int32_t* local_rank;         // null: the whole local shard is in device memory, row = g - lo
+    int64_t        local_limit;        // ranks below this are in device memory (row = rank)
     int64_t*       desc;               // per virtual row
     int32_t*       misslist;           // virtual rows that miss
     int32_t*       hitlist;            // virtual rows served from the shard or the cache
-    unsigned long long* counters;      // [0] local, [1] cache hit, [2] miss, [3] bad id, [4] rows in hitlist
-    unsigned long long* totals;        // context-wide running sums: [3] calls, [4] local, [5] cache hit, [6] miss
+    unsigned long long* counters;      // [0] local, [1] cache hit, [2] rows in misslist, [3] bad id, [4] rows in hitlist,
+                                       // [5] local rows read from the host (part of [0] and of [2])
+    unsigned long long* totals;        // context-wide running sums: [3] calls, [4] local, [5] cache hit,
+                                       // [6] remote miss, [7] local rows read from the host
 };
 
 struct PrologueArgs {
@@ -63,7 +70,7 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
     __shared__ ListLds ls;
     load_lists(a.t, ls);
     const int64_t total = ls.off[a.t.n_lists];
-    int n_local = 0, n_hit = 0;
+    int n_local = 0, n_hit = 0, n_rmiss = 0, n_lhost = 0;
     for (int64_t base = (int64_t)blockIdx.x * kListAlign; base < total; base += (int64_t)gridDim.x * kListAlign) {
         const int j = list_of(ls, a.t.n_lists, base);
         const int64_t lbeg = ls.off[j], n = ls.cnt[j];
@@ -78,15 +85,22 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
             if (g < 0 || g >= a.N) {
                 atomicOr(&a.counters[3], 1ull);
             } else if (g >= a.lo && g < a.hi) {
-                d = make_desc(kTagLocal, g - a.lo);
                 ++n_local;
-                hitbits |= 1u << k;
+                const int64_t r = a.local_rank ? (int64_t)a.local_rank[g - a.lo] : g - a.lo;
+                if (!a.local_rank || r < a.local_limit) {
+                    d = make_desc(kTagLocal, r);
+                    hitbits |= 1u << k;
+                } else {
+                    d = make_desc(kTagLocalHost, g - a.lo);
+                    ++n_lhost;
+                    missbits |= 1u << k;
+                }
             } else {
                 uint32_t slot = 0;
                 const bool found = a.tab && table_find(a.tab, a.mask, a.shift, (uint32_t)g, slot) >= 0 &&
                                    (int64_t)slot < a.limit;
                 if (found) { d = make_desc(kTagCache, slot); ++n_hit; hitbits |= 1u << k; }
-                else       { d = make_desc(kTagMiss, g < a.lo ? g : g - (a.hi - a.lo)); missbits |= 1u << k; }
+                else       { d = make_desc(kTagMiss, g < a.lo ? g : g - (a.hi - a.lo)); ++n_rmiss; missbits |= 1u << k; }
             }
             a.desc[lbeg + i] = d;
         }
@@ -96,10 +110,7 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
         const int ex = block_exclusive_scan(__popc(missbits) | (__popc(hitbits) << 16), scan_lds, total_packed);
         const int total_miss = total_packed & 0xFFFF, total_hit = total_packed >> 16;
         if (threadIdx.x == 0) {
-            if (total_miss) {
-                base_lds[0] = atomicAdd(&a.counters[2], (unsigned long long)total_miss);
-                atomicAdd(&a.totals[6], (unsigned long long)total_miss);
-            }
+            if (total_miss) base_lds[0] = atomicAdd(&a.counters[2], (unsigned long long)total_miss);
             if (total_hit) base_lds[1] = atomicAdd(&a.counters[4], (unsigned long long)total_hit);
         }
         __syncthreads();
@@ -115,7 +126,11 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
     }
     const int tl = block_reduce_sum(n_local, scan_lds);
     const int th = block_reduce_sum(n_hit, scan_lds);
+    const int tm = block_reduce_sum(n_rmiss, scan_lds);
+    const int tlh = block_reduce_sum(n_lhost, scan_lds);
     if (threadIdx.x == 0) {
+        if (tm) atomicAdd(&a.totals[6], (unsigned long long)tm);
+        if (tlh) { atomicAdd(&a.counters[5], (unsigned long long)tlh); atomicAdd(&a.totals[7], (unsigned long long)tlh); }
         if (tl) { atomicAdd(&a.counters[0], (unsigned long long)tl); atomicAdd(&a.totals[4], (unsigned long long)tl); }
         if (th) { atomicAdd(&a.counters[1], (unsigned long long)th); atomicAdd(&a.totals[5], (unsigned long long)th); }
         if (blockIdx.x == 0) atomicAdd(&a.totals[3], 1ull);
@@ -123,14 +138,14 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
 }
 
 // Device-visible address of a row store that is either device memory or pinned host memory.
-static int device_view(const void* p, const void** out) {
+int device_view(const void* p, const void** out) {
     *out = p;
     if (!p) return SPP_OK;
     hipPointerAttribute_t attr;
     hipError_t e = hipPointerGetAttributes(&attr, p);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        set_error("the remote row store is neither device memory nor pinned host memory (%s)", hipGetErrorString(e));
+        set_error("a row store is neither device memory nor pinned host memory (%s)", hipGetErrorString(e));
         return SPP_E_ARG;
     }
     if (attr.type == hipMemoryTypeHost) {
@@ -139,7 +154,7 @@ static int device_view(const void* p, const void** out) {
         if (e != hipSuccess) { set_error("hipHostGetDevicePointer: %s", hipGetErrorString(e)); return SPP_E_HIP; }
         *out = dp;
     } else if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged) {
-        set_error("the remote row store is ordinary pageable host memory; pin it (hipHostMalloc)");
+        set_error("a row store is ordinary pageable host memory; pin it (hipHostMalloc)");
         return SPP_E_ARG;
     }
     return SPP_OK;
@@ -167,10 +182,12 @@ int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, 
 
 }  // namespace spp
 
-extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
-                                         int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
-                                         int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
-                                         spp_gather_stats* stats, uint32_t flags) {
+// The gather behind both entry points: the local shard is either d_local (all rows in device
+// memory) or a split store.
+static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_local, const spp_local_store* store,
+                        int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                        int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
+                        spp_gather_stats* stats, uint32_t flags) {
     using namespace spp;
     SPP_CHECK(ctx, SPP_E_ARG, "spp_gather_features: ctx is null");
     SPP_CHECK(n_lists >= 0 && n_lists <= SPP_MAX_GATHER_LISTS && (lists || n_lists == 0), SPP_E_ARG,
@@ -189,6 +206,15 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
     }
     const void* crow = cache ? cache->rows : nullptr;
     const void* dremote = nullptr;
+    const void* lhost = nullptr;        // host-resident local rows (split store only)
+    if (store) {
+        SPP_CHECK(store->lo == lo && store->hi == hi && store->N == N, SPP_E_ARG,
+                  "spp_gather_features: the local store was built for another partition range");
+        SPP_CHECK(store->row_bytes == row_bytes, SPP_E_ARG, "spp_gather_features: local store rows are %lld bytes, requested %lld",
+                  (long long)store->row_bytes, (long long)row_bytes);
+        d_local = store->rows;
+        lhost = store->host_rows;
+    }
     SPP_HIP(hipSetDevice(ctx->device));
     SPP_TRY(device_view(remote, &dremote));
 
@@ -197,7 +223,7 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
     memset(&a, 0, sizeof(a));
     memset(&pro, 0, sizeof(pro));
     int64_t vbound = 0;                 // virtual rows, with padding
-    uintptr_t addr_bits = (uintptr_t)d_local | (uintptr_t)crow | (uintptr_t)dremote;
+    uintptr_t addr_bits = (uintptr_t)d_local | (uintptr_t)crow | (uintptr_t)dremote | (uintptr_t)lhost;
     for (int j = 0; j < n_lists; ++j) {
         SPP_CHECK(lists[j].n >= 0, SPP_E_ARG, "spp_gather_features: list %d has n = %lld", j, (long long)lists[j].n);
         SPP_CHECK(lists[j].n == 0 || (lists[j].d_node_ids && lists[j].d_out), SPP_E_ARG,
@@ -210,7 +236,7 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
         addr_bits |= (uintptr_t)lists[j].d_out;
     }
     SPP_CHECK(vbound < 0x7FFFFFFFll, SPP_E_ARG, "spp_gather_features: %lld rows in one call exceed the 32-bit miss list", (long long)vbound);
-    SPP_CHECK(hi == lo || d_local || vbound == 0, SPP_E_ARG, "spp_gather_features: local shard is null");
+    SPP_CHECK(hi == lo || d_local || store || vbound == 0, SPP_E_ARG, "spp_gather_features: local shard is null");
     a.t.n_lists = pro.n_lists = n_lists;
 
     hipStream_t st = ctx->stream;
@@ -235,6 +261,8 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
         a.tab = cache && cache->limit > 0 ? reinterpret_cast<const unsigned long long*>(cache->table) : nullptr;
         a.mask = cache ? cache->table_mask : 0; a.shift = cache ? cache->table_shift : 0;
         a.limit = cache ? cache->limit : 0;
+        a.local_rank = store ? store->rank : nullptr;
+        a.local_limit = store ? store->limit : 0;
         a.desc = ctx->srcdesc.as<int64_t>(); a.misslist = ctx->misslist.as<int32_t>(); a.counters = counters;
         a.hitlist = a.misslist + vbound;
         a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
@@ -273,23 +301,27 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
                 default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
             }
         }
-        if (dremote) {
+        const bool miss_path = dremote != nullptr || lhost != nullptr;
+        if (miss_path) {
             SPP_HIP(hipEventRecord(ctx->ev_fork, st));
             SPP_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
             {
                 ScopedTimer tm(ctx, SPP_T_GATHER_MISS, ctx->side);
                 const int64_t* miss_count = reinterpret_cast<const int64_t*>(counters + 2);
+                // either store may be null (no remote store given, or no split local store): the
+                // kernel skips rows that would need it and the statistics of the call report them
                 const char* src = static_cast<const char*>(dremote);
+                const char* lh = static_cast<const char*>(lhost);
                 switch (V) {
-                    case 16: gather_miss_kernel<16><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
-                    case 8:  gather_miss_kernel<8><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
-                    case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
-                    default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, a.desc, a.misslist, miss_count, a.t, vpr); break;
+                    case 16: gather_miss_kernel<16><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
+                    case 8:  gather_miss_kernel<8><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
+                    case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
+                    default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
                 }
             }
             SPP_HIP(hipEventRecord(ctx->ev_join, ctx->side));
         }
-        if (dremote) {
+        if (miss_path) {
             if (flags & SPP_NO_JOIN) ctx->join_pending = true;
             else SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
         }
@@ -297,7 +329,7 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
     SPP_HIP(hipGetLastError());
     int64_t* hp = ctx->h_pinned + 40;
     // the counters are final once the classification has run, whether or not the misses have landed
-    SPP_HIP(hipMemcpyAsync(hp, counters, 4 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    SPP_HIP(hipMemcpyAsync(hp, counters, 6 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
     ctx->h_pinned[48] = row_bytes;
     ctx->h_pinned[49] = dremote ? 1 : 0;
     if (flags & SPP_SYNC) {
@@ -306,6 +338,21 @@ extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, c
         return spp_gather_last_stats(ctx, stats);
     }
     return SPP_OK;
+}
+
+extern "C" int spp_gather_features_multi(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
+                                         int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                                         int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
+                                         spp_gather_stats* stats, uint32_t flags) {
+    return gather_lists(ctx, cache, d_local, nullptr, N, lo, hi, remote, D, elem_bytes, lists, n_lists, stats, flags);
+}
+
+extern "C" int spp_gather_features_split(spp_ctx* ctx, const spp_cache* cache, const spp_local_store* store,
+                                         int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                                         int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
+                                         spp_gather_stats* stats, uint32_t flags) {
+    SPP_CHECK(store, SPP_E_ARG, "spp_gather_features_split: store is null");
+    return gather_lists(ctx, cache, nullptr, store, N, lo, hi, remote, D, elem_bytes, lists, n_lists, stats, flags);
 }
 
 extern "C" int spp_gather_join(spp_ctx* ctx) {
@@ -330,11 +377,13 @@ extern "C" int spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats) {
     SPP_CHECK(ctx, SPP_E_ARG, "spp_gather_last_stats: ctx is null");
     const int64_t* hp = ctx->h_pinned + 40;
     if (stats) {
-        stats->n_local = hp[0]; stats->n_cache_hit = hp[1]; stats->n_miss = hp[2];
+        stats->n_local = hp[0]; stats->n_cache_hit = hp[1]; stats->n_miss = hp[2] - hp[5];
+        stats->n_local_host = hp[5];
         stats->miss_bytes = hp[2] * ctx->h_pinned[48];
     }
     SPP_CHECK(hp[3] == 0, SPP_E_ARG, "spp_gather_features: a vertex id lies outside [0, N); its row was left untouched");
-    SPP_CHECK(hp[2] == 0 || ctx->h_pinned[49] != 0, SPP_E_ARG,
-              "spp_gather_features: %lld rows missed but no remote store was given; they were left untouched", (long long)hp[2]);
+    SPP_CHECK(hp[2] - hp[5] == 0 || ctx->h_pinned[49] != 0, SPP_E_ARG,
+              "spp_gather_features: %lld rows missed but no remote store was given; they were left untouched",
+              (long long)(hp[2] - hp[5]));
     return SPP_OK;
 }

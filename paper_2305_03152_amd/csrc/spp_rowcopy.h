@@ -20,11 +20,12 @@ template <> struct VecOf<8>  { typedef u32x2 type; };
 template <> struct VecOf<4>  { typedef uint32_t type; };
 template <> struct VecOf<2>  { typedef uint16_t type; };
 
-// Source descriptor of an output row: tag in the top two bits, row index in the store below.
-constexpr int kTagLocal = 0, kTagCache = 1, kTagMiss = 2, kTagSkip = 3;
-__device__ __host__ __forceinline__ int64_t make_desc(int tag, int64_t row) { return ((int64_t)tag << 62) | row; }
-__device__ __forceinline__ int desc_tag(int64_t d) { return (int)(((uint64_t)d) >> 62); }
-__device__ __forceinline__ int64_t desc_row(int64_t d) { return d & ((1ll << 62) - 1); }
+// Source descriptor of an output row: tag in the top three bits, row index in the store below.
+// kTagLocal: row of the device-resident local rows; kTagLocalHost: row of the host-resident ones.
+constexpr int kTagLocal = 0, kTagCache = 1, kTagMiss = 2, kTagSkip = 3, kTagLocalHost = 4;
+__device__ __host__ __forceinline__ int64_t make_desc(int tag, int64_t row) { return (int64_t)((uint64_t)tag << 61) | row; }
+__device__ __forceinline__ int desc_tag(int64_t d) { return (int)(((uint64_t)d) >> 61); }
+__device__ __forceinline__ int64_t desc_row(int64_t d) { return d & ((1ll << 61) - 1); }
 
 template <int V>
 __device__ __forceinline__ typename VecOf<V>::type load_stream(const void* p) {
@@ -114,9 +115,11 @@ __global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __res
 }
 
 // Miss path: rows read straight from the remote store (pinned host memory over PCIe, or device
-// memory).  misslist[m] is a virtual row; its descriptor holds the row in the store.
+// memory), or from the host-resident part of the local rows.  misslist[m] is a virtual row; its
+// descriptor names the store and the row in it.
 template <int V>
 __global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restrict__ src,
+                                                             const char* __restrict__ local_host,
                                                              const int64_t* __restrict__ desc,
                                                              const int32_t* __restrict__ misslist,
                                                              const int64_t* __restrict__ count_ptr, ListTable t,
@@ -140,9 +143,15 @@ __global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restr
                 const uint32_t k = (uint32_t)(c - m * vpr);
                 const int64_t r = misslist[m];
                 const int j = list_of(ls, t.n_lists, r);
-                const int64_t row = desc_row(desc[r]);
-                v[u] = load_stream<V>(src + ((uint64_t)row * vpr + k) * (uint64_t)V);
-                dst[u] = t.out[j] + ((uint64_t)(r - ls.off[j]) * vpr + k) * (uint64_t)V;
+                const int64_t d = desc[r];
+                const char* from = desc_tag(d) == kTagLocalHost ? local_host : src;
+                // a store the caller did not give: the row is left untouched (the statistics of
+                // the call report it)
+                ok[u] = from != nullptr;
+                if (ok[u]) {
+                    v[u] = load_stream<V>(from + ((uint64_t)desc_row(d) * vpr + k) * (uint64_t)V);
+                    dst[u] = t.out[j] + ((uint64_t)(r - ls.off[j]) * vpr + k) * (uint64_t)V;
+                }
             }
         }
 #pragma unroll

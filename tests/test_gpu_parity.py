@@ -200,7 +200,7 @@ def test_sample_and_gather_tiny(spp, ctx, tiny_case):
     cache_rows = S.feature_rows(cfg, torch.from_numpy(ids_ref)).numpy()
     bufs = spp.MFGBuffers("cuda", cfg.B, cfg.fanouts, cfg.N)
     ctx.totals(reset=True)
-    sums = dict(batches=0, n_nodes=0, n_edges=0, gather_calls=0, n_local=0, n_cache_hit=0, n_miss=0)
+    sums = dict(batches=0, n_nodes=0, n_edges=0, gather_calls=0, n_local=0, n_cache_hit=0, n_miss=0, n_local_host=0)
     for epoch in range(2):
         for bi, seeds in enumerate(S.epoch_batches(cfg, torch.from_numpy(c.Tk), epoch)):
             _say("tiny batch", epoch, bi, "seeds", seeds.numel())
@@ -328,6 +328,113 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
     cache.close()
 
 
+def test_local_store_tiny(spp, ctx, tiny_case):
+    """VIP-ordered local storage: rank array, device prefix, and the gather with the local rows split
+    between device and host (Sec. 3.2 on host-to-device transfers, Sec. 4.1)."""
+    c = tiny_case
+    cfg = c.cfg
+    n_loc = c.hi - c.lo
+    p = spp.vip_propagate(ctx, c.G, c.Tk_d, cfg.B, cfg.fanouts)
+    score = p.cpu().numpy()
+    local = c.local_d.cpu().numpy()
+    local_host = c.local_d.cpu().pin_memory()
+    remote = c.remote.numpy()
+    cache = spp.build_vip_cache(ctx, p, c.lo, c.hi, cfg.K, cfg.alpha, c.remote, cfg.D, cfg.elem_bytes)
+    ids_ref = oracle.cache_select(score, c.lo, c.hi, cfg.K, cfg.alpha)
+    cache_rows = S.feature_rows(cfg, torch.from_numpy(ids_ref)).numpy()
+    probe = torch.arange(-3, cfg.N + 3, dtype=torch.int32, device="cuda")
+    seeds = S.epoch_batches(cfg, torch.from_numpy(c.Tk), 0)[0]
+    ref = oracle.sample_mfg(c.rp, c.col, seeds.numpy(), cfg.fanouts, cfg.seed_sampler, 0)
+    ids_d = torch.from_numpy(ref.node_ids).cuda()
+    weird = score.copy()
+    weird[c.lo:c.lo + 40:3] = -1.0
+    weird[c.lo + 1:c.lo + 40:3] = np.nan
+    weird[c.lo + 100:c.lo + 200] = 0.25                     # a run of ties
+    for name, sc in (("vip", score), ("constant", np.full(cfg.N, 0.5, np.float32)), ("weird", weird)):
+        rank_ref, order_ref = oracle.local_rank(sc, c.lo, c.hi)
+        want_rank = np.full(probe.numel(), -1, dtype=np.int32)
+        want_rank[3 + c.lo:3 + c.hi] = rank_ref
+        for beta in (0.0, 0.05, 0.3, 1.0, 2.5):
+            _say("local store", name, "beta", beta)
+            store = spp.build_local_store(ctx, torch.from_numpy(sc).cuda(), c.lo, c.hi, beta, local_host)
+            n_dev = oracle.local_capacity(beta, n_loc)
+            assert store.n_device_rows == n_dev
+            assert np.array_equal(store.rank(probe).cpu().numpy(), want_rank)
+            out, stats = spp.gather_features(ctx, cache, store, cfg.N, c.lo, c.hi, c.remote, ids_d)
+            want, _, counts = oracle.gather_split(cfg.N, c.lo, c.hi, local[order_ref[:n_dev]], local, rank_ref, n_dev,
+                                                  cache_rows, ids_ref, remote, ref.node_ids)
+            assert np.array_equal(_bits(out.cpu().numpy()), _bits(want))
+            assert (stats["n_local"] - stats["n_local_host"], stats["n_cache_hit"], stats["n_miss"],
+                    stats["n_local_host"]) == counts
+            assert stats["miss_bytes"] == (counts[2] + counts[3]) * cfg.D * cfg.elem_bytes
+            store.close()
+    # a smaller beta is a prefix of a larger one: one store, limits set afterwards; running totals
+    rank_ref, order_ref = oracle.local_rank(score, c.lo, c.hi)
+    store = spp.build_local_store(ctx, p, c.lo, c.hi, 1.0, local_host)
+    ctx.totals(reset=True)
+    host_rows = 0
+    for n_dev in (0, 1, 17, n_loc // 2, n_loc):
+        store.set_limit(n_dev)
+        out, stats = spp.gather_features(ctx, cache, store, cfg.N, c.lo, c.hi, c.remote, ids_d)
+        want, _, counts = oracle.gather_split(cfg.N, c.lo, c.hi, local[order_ref[:n_dev]], local, rank_ref, n_dev,
+                                              cache_rows, ids_ref, remote, ref.node_ids)
+        assert np.array_equal(_bits(out.cpu().numpy()), _bits(want))
+        assert stats["n_local_host"] == counts[3] and stats["n_miss"] == counts[2]
+        host_rows += counts[3]
+    t = ctx.totals()
+    assert t["n_local_host"] == host_rows and t["gather_calls"] == 5
+    with pytest.raises(spp.SppError):
+        store.set_limit(n_loc + 1)
+    # several lists in one call with the join deferred and no cache
+    store.set_limit(n_loc // 5)
+    n_dev = n_loc // 5
+    lists, wants, tot = [], [], [0, 0, 0, 0]
+    for j, take in enumerate((1, 700, 2049, 0, 5000)):
+        ids = np.random.default_rng(j).integers(0, cfg.N, size=take).astype(np.int32)
+        want, _, counts = oracle.gather_split(cfg.N, c.lo, c.hi, local[order_ref[:n_dev]], local, rank_ref, n_dev,
+                                              None, None, remote, ids)
+        out = torch.zeros((take + 2, cfg.D), dtype=torch.float32, device="cuda")
+        lists.append((torch.from_numpy(ids).cuda(), take, None, out))
+        wants.append(want)
+        tot = [a + b for a, b in zip(tot, counts)]
+    assert spp.gather_features_multi(ctx, None, store, cfg.N, c.lo, c.hi, c.remote, lists, sync=False, join=False) is None
+    spp.gather_join(ctx)
+    ctx.sync()
+    st = spp.gather_last_stats(ctx)
+    assert (st["n_local"] - st["n_local_host"], st["n_cache_hit"], st["n_miss"], st["n_local_host"]) == tuple(tot)
+    for (ids, take, _, out), want in zip(lists, wants):
+        assert np.array_equal(_bits(out[:take].cpu().numpy()), _bits(want))
+        assert torch.all(out[take:] == 0)
+    # local ids only and no remote store at all: the host-resident local rows are still served
+    ids = np.arange(c.lo, c.hi, 7, dtype=np.int32)
+    out, stats = spp.gather_features(ctx, None, store, cfg.N, c.lo, c.hi, None, torch.from_numpy(ids).cuda())
+    assert np.array_equal(_bits(out.cpu().numpy()), _bits(local[ids - c.lo]))
+    assert stats["n_miss"] == 0 and stats["n_local"] == ids.size and stats["n_local_host"] > 0
+    # a remote id without a remote store is reported, its row left untouched, nothing else disturbed
+    ids = np.array([c.lo, c.hi + 1 if c.hi + 1 < cfg.N else c.lo - 1, c.lo + 1], dtype=np.int32)
+    out = torch.full((3, cfg.D), 7.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(spp.SppError):
+        spp.gather_features(ctx, None, store, cfg.N, c.lo, c.hi, None, torch.from_numpy(ids).cuda(), out=out)
+    assert torch.all(out[1] == 7.0)
+    assert np.array_equal(_bits(out[[0, 2]].cpu().numpy()), _bits(local[ids[[0, 2]] - c.lo]))
+    # a store built for another range is refused
+    with pytest.raises(spp.SppError):
+        spp.gather_features(ctx, None, store, cfg.N, c.lo, c.hi - 1, c.remote, torch.from_numpy(ids).cuda())
+    store.close()
+    cache.close()
+    # bfloat16 rows (2-byte elements): same split, same bytes
+    half = c.local_d.to(torch.bfloat16)
+    half_host = half.cpu().pin_memory()
+    store = spp.build_local_store(ctx, p, c.lo, c.hi, 0.3, half_host)
+    n_dev = oracle.local_capacity(0.3, n_loc)
+    loc_ids = torch.arange(c.lo, c.hi, 3, dtype=torch.int32, device="cuda")
+    out, stats = spp.gather_features(ctx, None, store, cfg.N, c.lo, c.hi, None, loc_ids)
+    assert torch.equal(out.view(torch.int16).cpu(), half.view(torch.int16).cpu()[(loc_ids - c.lo).cpu().long()])
+    on_dev = rank_ref[(loc_ids - c.lo).cpu().numpy()] < n_dev
+    assert stats["n_local_host"] == int((~on_dev).sum())
+    store.close()
+
+
 # ----------------------------------------------------------------------------------------------
 # scaled copies of the other configs: several tiles, ragged tails, hubs, 16-bit rows
 # ----------------------------------------------------------------------------------------------
@@ -376,5 +483,24 @@ def test_scaled_config_end_to_end(spp, ctx, name, cfg):
         want, _, counts = oracle.gather(cfg.N, c.lo, c.hi, local, cache_rows, ids_ref, remote, ref.node_ids)
         assert np.array_equal(_bits(_np(out)), _bits(want))
         assert (stats["n_local"], stats["n_cache_hit"], stats["n_miss"]) == counts
+    # the same batches with the local rows split between device and host (10 % on the device)
+    _say("local store")
+    local_host = c.local_d.cpu().pin_memory()
+    store = spp.build_local_store(ctx, p, c.lo, c.hi, 0.1, local_host)
+    rank_ref, order_ref = oracle.local_rank(p.cpu().numpy(), c.lo, c.hi)
+    n_dev = oracle.local_capacity(0.1, c.hi - c.lo)
+    assert store.n_device_rows == n_dev
+    probe = torch.arange(c.lo, c.hi, dtype=torch.int32, device="cuda")
+    assert np.array_equal(store.rank(probe).cpu().numpy(), rank_ref)
+    for bi, seeds in enumerate(batches[:2] + batches[-1:]):
+        ref = oracle.sample_mfg(c.rp, c.col, seeds.numpy(), cfg.fanouts, cfg.seed_sampler, bi)
+        ids_d = torch.from_numpy(ref.node_ids).cuda()
+        out, stats = spp.gather_features(ctx, cache, store, cfg.N, c.lo, c.hi, c.remote, ids_d)
+        want, _, counts = oracle.gather_split(cfg.N, c.lo, c.hi, local[order_ref[:n_dev]], local, rank_ref, n_dev,
+                                              cache_rows, ids_ref, remote, ref.node_ids)
+        assert np.array_equal(_bits(_np(out)), _bits(want))
+        assert (stats["n_local"] - stats["n_local_host"], stats["n_cache_hit"], stats["n_miss"],
+                stats["n_local_host"]) == counts
+    store.close()
     cache.close()
     c.G.close()
