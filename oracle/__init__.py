@@ -235,3 +235,16 @@ def gather_split(N, lo, hi, local_dev, local_host, rank, n_dev, cache_rows, cach
     if rc != 0:
         raise ValueError(f"orc_gather_split failed ({rc})")
     return out, tag[:node_ids.size], tuple(int(c) for c in counts)
+
+
+def access_count(N, node_ids, count=None):
+    """count[v] += 1 for every id of the list (float32 counts, exact below 2^24); returns count."""
+    lib = _load()
+    if count is None:
+        count = np.zeros(int(N), dtype=np.float32)
+    assert count.dtype == np.float32 and count.flags.c_contiguous and count.size == int(N)
+    node_ids = _i32(node_ids)
+    rc = lib.orc_access_count(C.c_int64(int(N)), _p(node_ids), C.c_int64(node_ids.size), _p(count))
+    if rc != 0:
+        raise ValueError("orc_access_count: id outside [0, N)")
+    return count

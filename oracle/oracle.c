@@ -377,3 +377,20 @@ int orc_gather_split(int64_t N, int64_t lo, int64_t hi, const void *local_dev, c
     free(slot);
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Empirical access frequencies (Sec. 3.2, the "sim." and "oracle" caching policies): count[v] is
+ * the number of minibatches whose sampled vertex set S_L contains v.  "sim." counts over simulated
+ * epochs before training, "oracle" over the epochs that are evaluated; either count is then ranked
+ * exactly like a VIP score.  One call adds one id list (ids of a minibatch are distinct, so a
+ * vertex gains at most 1 per minibatch; a repeated id would count every time it appears).
+ * ---------------------------------------------------------------------------------------- */
+int orc_access_count(int64_t N, const int32_t *node_ids, int64_t n, float *count)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t g = node_ids[i];
+        if (g < 0 || g >= N) return -1;
+        count[g] += 1.0f;
+    }
+    return 0;
+}
