@@ -74,6 +74,62 @@ def alpha_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, h
                       "rows": rows}), flush=True)
 
 
+def policy_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, lo, hi):
+    """Remote vertices fetched per epoch (communication volume in vertices) over alpha for the caching
+    policies that need nothing but the graph, the sampler and Prop. 1: none, deg., sim. (access counts
+    over 2 simulated epochs), VIP (analytic), oracle (retroactive counts over the evaluated epochs) --
+    the experiment shape of the policy comparison in Sec. 3.2."""
+    alphas = [0.05, 0.1, 0.2, 0.5, 1.0]
+    dev = p.device
+    Gsz = 8
+    bufs = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N) for _ in range(Gsz)]
+
+    def count_epochs(epochs):
+        cnt = torch.zeros(cfg.N, dtype=torch.float32, device=dev)
+        nb = 0
+        for ep in epochs:
+            batches = S.epoch_batches(cfg, Tk, ep)
+            for g0 in range(0, len(batches), Gsz):
+                grp = batches[g0:g0 + Gsz]
+                spp.sample_mfg_multi(ctx, G, [(b, ep * 100000 + g0 + k, bufs[k]) for k, b in enumerate(grp)],
+                                     cfg.fanouts, cfg.seed_sampler, sync=False)
+                spp.access_count(ctx, [(bufs[k].node_ids, bufs[k].nb[-1], bufs[k].n_final_device)
+                                       for k in range(len(grp))], cfg.N, cnt, sync=False)
+                nb += len(grp)
+        ctx.sync()
+        return cnt, nb
+
+    E = args.sweep_epochs
+    t = time.time()
+    sim, nb_sim = count_epochs([1000, 1001])                      # simulated epochs, disjoint from the evaluated ones
+    sim_s = time.time() - t
+    t = time.time()
+    ev, nb_ev = count_epochs(list(range(E)))
+    ev_s = time.time() - t
+    log(f"sim. counts: {nb_sim} minibatches in {sim_s:.2f}s; evaluated: {nb_ev} minibatches in {ev_s:.2f}s")
+    indeg = torch.bincount(g.col.long(), minlength=g.N).to(torch.float32)
+    deg_score = torch.where(p > 0, indeg, torch.zeros_like(indeg))
+    del indeg
+    remote_mask = torch.ones(cfg.N, dtype=torch.bool, device=dev)
+    remote_mask[lo:hi] = False
+    total = float(ev[remote_mask].double().sum().item())
+    rows = [{"policy": "none", "alpha": 0.0, "cached": 0, "remote_vertices_per_epoch": total / E}]
+    for policy, score in (("deg.", deg_score), ("sim.", sim), ("VIP", p), ("oracle", ev)):
+        cache = spp.build_vip_cache(ctx, score, lo, hi, cfg.K, max(alphas), None, cfg.D, cfg.elem_bytes)
+        saved = torch.cumsum(ev[cache.ids.long()].double(), 0)        # accesses absorbed by the first c ranks
+        for a in alphas:
+            c = min(cfg.cache_capacity(a), cache.n_cached)
+            kept = float(saved[c - 1].item()) if c > 0 else 0.0
+            rows.append({"policy": policy, "alpha": a, "cached": c, "remote_vertices_per_epoch": (total - kept) / E})
+        cache.close()
+    best = {r["alpha"]: r["remote_vertices_per_epoch"] for r in rows if r["policy"] == "oracle"}
+    for r in rows:
+        r["vs_oracle"] = (r["remote_vertices_per_epoch"] / best[r["alpha"]]) if best.get(r["alpha"]) else None
+        log(r)
+    print(json.dumps({"phase": "policy-sweep", "workload": cfg.name, "N": g.N, "M": g.M, "epochs": E,
+                      "minibatches": nb_ev, "sim_minibatches": nb_sim, "sim_count_s": sim_s, "rows": rows}), flush=True)
+
+
 def beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi):
     """Host reads for local vertices over the device-resident share beta of the partition's rows:
     VIP order against the id order (Sec. 3.2 on host-to-device transfers; the experiment shape of the
@@ -129,16 +185,19 @@ def main():
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
                          "(pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
-    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "calibrate"],
+    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "policy-sweep", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
                          "alpha-sweep: hit rate and host-miss bytes per batch over alpha in {0,.05,.1,.2,.5}, VIP-ranked "
                          "against degree-ranked cache (the experiment shape of Fig. 2 / Fig. 7), e.g. with --config skew; "
+                         "policy-sweep: remote vertices fetched per epoch over alpha for the policies none / deg. / sim. / "
+                         "VIP / oracle (the policy comparison of Sec. 3.2), counted on the device over --sweep-epochs epochs; "
                          "beta-sweep: local rows read from host memory over the device-resident share beta of the "
                          "partition's rows, VIP order against id order (the experiment shape of the figure on local "
                          "storage on CPU versus GPU); "
                          "calibrate: a plain elementwise pass over 1 GiB (read 1 GiB, write 1 GiB), the known-size kernel "
                          "that scales the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
     ap.add_argument("--sweep-batches", type=int, default=8)
+    ap.add_argument("--sweep-epochs", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one partition's share of the method); "
@@ -176,20 +235,24 @@ def main():
     t = time.time()
     G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True)
     t_inlists = time.time() - t
-    local = S.feature_block(cfg, lo, hi, dev)
     nrem = cfg.N - (hi - lo)
-    if args.phase == "beta-sweep":
-        # this sweep measures host reads of LOCAL rows: the remote store sits in device memory so that
-        # the host's pinning limit is left to the partition's own rows
-        remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype, device=dev)
+    if args.phase in ("policy-sweep", "vip"):
+        local = remote = None                      # these phases move no feature rows
+        log(f"no feature rows for phase {args.phase}; in-lists built in {t_inlists:.2f}s")
     else:
-        remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
-    for a in range(0, nrem, 1 << 19):
-        b = min(nrem, a + (1 << 19))
-        remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
-    torch.cuda.synchronize()
-    log(f"features local {tuple(local.shape)} remote {tuple(remote.shape)} "
-        f"{'pinned' if remote.is_pinned() else 'in device memory'}; in-lists built in {t_inlists:.2f}s")
+        local = S.feature_block(cfg, lo, hi, dev)
+        if args.phase == "beta-sweep":
+            # this sweep measures host reads of LOCAL rows: the remote store sits in device memory so that
+            # the host's pinning limit is left to the partition's own rows
+            remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype, device=dev)
+        else:
+            remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
+        for a in range(0, nrem, 1 << 19):
+            b = min(nrem, a + (1 << 19))
+            remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
+        torch.cuda.synchronize()
+        log(f"features local {tuple(local.shape)} remote {tuple(remote.shape)} "
+            f"{'pinned' if remote.is_pinned() else 'in device memory'}; in-lists built in {t_inlists:.2f}s")
 
     # ---- one-time rows: VIP propagation, cache ranking + fill -------------------------------
     p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts)            # warm-up, allocates workspaces
@@ -221,6 +284,9 @@ def main():
         return
     if args.phase == "beta-sweep":
         beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
+        return
+    if args.phase == "policy-sweep":
+        policy_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, lo, hi)
         return
     t = time.time()
     cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)

@@ -241,6 +241,22 @@ int  spp_gather_features_split(spp_ctx* ctx, const spp_cache* cache, const spp_l
                                int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
                                spp_gather_stats* stats, uint32_t flags);
 
+/* (f) Empirical access frequencies (Sec. 3.2, the "sim." and "oracle" caching policies): d_count[v]
+ *     += 1 for every id of every list, e.g. the sampled vertex sets of the minibatches of simulated
+ *     epochs ("sim.") or of the epochs being evaluated ("oracle", retroactive).  The counts are a
+ *     score like any other: spp_build_vip_cache and spp_build_local_store rank them.
+ *     d_count is device float32[N], not cleared by the call; counts are exact below 2^24.
+ *     List j has n ids, or *d_n of them (device int64, capped at n) when d_n is given.  An id
+ *     outside [0, N) is skipped; with SPP_SYNC the call then returns SPP_E_ARG after counting the
+ *     others (without SPP_SYNC it goes unreported).  At most SPP_MAX_GATHER_LISTS lists. */
+typedef struct {
+    const int32_t* d_ids;
+    int64_t        n;
+    const int64_t* d_n;      /* device int64 count, or NULL */
+} spp_id_list;
+int  spp_access_count(spp_ctx* ctx, const spp_id_list* lists, int32_t n_lists, int64_t N, float* d_count,
+                      uint32_t flags);
+
 /* Device-time accounting.  After spp_ctx_timing(ctx, 1) every call brackets its pieces of device
  * work with events on the stream they run on (vip total and per hop, the whole sampling of a
  * batch, gather classify / hit copy / miss copy).  spp_ctx_times waits for the context's streams,

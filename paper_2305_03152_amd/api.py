@@ -30,7 +30,7 @@ EXPORTS = [
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg", "spp_sample_mfg_multi",
     "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
     "spp_build_local_store", "spp_local_store_destroy", "spp_local_store_set_limit", "spp_local_store_rank",
-    "spp_gather_features_split",
+    "spp_gather_features_split", "spp_access_count",
 ]
 
 
@@ -58,6 +58,10 @@ class _SampleItem(C.Structure):
 
 class _GatherList(C.Structure):
     _fields_ = [("d_node_ids", C.c_void_p), ("n", C.c_int64), ("d_n", C.c_void_p), ("d_out", C.c_void_p)]
+
+
+class _IdList(C.Structure):
+    _fields_ = [("d_ids", C.c_void_p), ("n", C.c_int64), ("d_n", C.c_void_p)]
 
 
 class _GatherStats(C.Structure):
@@ -121,6 +125,7 @@ def load_library():
     lib.spp_gather_features_split.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                               C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_GatherList), C.c_int32,
                                               C.POINTER(_GatherStats), C.c_uint32]
+    lib.spp_access_count.argtypes = [C.c_void_p, C.POINTER(_IdList), C.c_int32, C.c_int64, C.c_void_p, C.c_uint32]
     lib.spp_gather_join.argtypes = [C.c_void_p]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
     lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
@@ -341,6 +346,28 @@ def build_local_store(ctx: Context, score: torch.Tensor, lo: int, hi: int, beta:
                                                 _ptr(local_rows), int(local_rows.shape[1]),
                                                 int(local_rows.element_size()), C.byref(n_rows), C.byref(h)))
     return LocalStore(ctx, h, n_rows.value, score.numel(), lo, hi, local_rows)
+
+
+def access_count(ctx: Context, lists, N: int, count: Optional[torch.Tensor] = None, sync: bool = True) -> torch.Tensor:
+    """count[v] += 1 for every id of every list; `lists` is a sequence of (ids, n, n_device or None).
+
+    The counts (float32, one per vertex) are a score for build_vip_cache / build_local_store.
+    """
+    if count is None:
+        count = torch.zeros(int(N), dtype=torch.float32, device=torch.device("cuda", ctx.device))
+    count = _dev(count, torch.float32, "count")
+    if count.numel() != int(N):
+        raise SppError("count must hold N entries")
+    arr = (_IdList * max(len(lists), 1))()
+    for j, (ids, n, n_dev) in enumerate(lists):
+        ids = _dev(ids, torch.int32, "ids")
+        if int(n) > ids.numel():
+            raise SppError(f"list {j}: n exceeds the id buffer")
+        arr[j].d_ids = ids.data_ptr()
+        arr[j].n = int(n)
+        arr[j].d_n = n_dev.data_ptr() if n_dev is not None else None
+    _check(load_library().spp_access_count(ctx._h, arr, len(lists), int(N), _ptr(count), SPP_SYNC if sync else 0))
+    return count
 
 
 def _stats_dict(st):

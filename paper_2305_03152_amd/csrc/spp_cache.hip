@@ -60,7 +60,66 @@ __global__ void __launch_bounds__(kBlock) cache_lookup_kernel(const unsigned lon
     }
 }
 
+// Empirical access frequencies (Sec. 3.2, "sim." and "oracle" policies): one count per listed id.
+// Ids of one minibatch are distinct and the lists of a call are few, so the float atomics rarely
+// meet on one address.
+struct CountLists {
+    const int32_t* ids[SPP_MAX_GATHER_LISTS];
+    int64_t        n[SPP_MAX_GATHER_LISTS];
+    const int64_t* n_ptr[SPP_MAX_GATHER_LISTS];
+};
+__global__ void clear_flag_kernel(int* flag) { if (threadIdx.x == 0) *flag = 0; }
+
+__global__ void __launch_bounds__(kBlock) access_count_kernel(CountLists l, int64_t N, float* __restrict__ count,
+                                                              int* __restrict__ bad) {
+    const int j = blockIdx.y;
+    int64_t n = l.n_ptr[j] ? *l.n_ptr[j] : l.n[j];
+    if (n > l.n[j]) n = l.n[j];                       // never beyond what the caller's buffer holds
+    const int32_t* __restrict__ ids = l.ids[j];
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        const int64_t g = ids[i];
+        if (g < 0 || g >= N) atomicOr(bad, 1);
+        else unsafeAtomicAdd(&count[g], 1.0f);
+    }
+}
+
 }  // namespace spp
+
+extern "C" int spp_access_count(spp_ctx* ctx, const spp_id_list* lists, int32_t n_lists, int64_t N, float* d_count,
+                                uint32_t flags) {
+    using namespace spp;
+    SPP_CHECK(ctx && d_count && (lists || n_lists == 0), SPP_E_ARG, "spp_access_count: null argument");
+    SPP_CHECK(n_lists >= 0 && n_lists <= SPP_MAX_GATHER_LISTS, SPP_E_ARG, "spp_access_count: %d lists (at most %d)",
+              n_lists, SPP_MAX_GATHER_LISTS);
+    SPP_CHECK(N > 0, SPP_E_ARG, "spp_access_count: N = %lld", (long long)N);
+    if (n_lists == 0) return SPP_OK;
+    CountLists l;
+    memset(&l, 0, sizeof(l));
+    int64_t nmax = 0;
+    for (int j = 0; j < n_lists; ++j) {
+        SPP_CHECK(lists[j].n >= 0 && (lists[j].d_ids || lists[j].n == 0), SPP_E_ARG, "spp_access_count: list %d", j);
+        l.ids[j] = lists[j].d_ids; l.n[j] = lists[j].n; l.n_ptr[j] = lists[j].d_n;
+        if (lists[j].n > nmax) nmax = lists[j].n;
+    }
+    if (nmax == 0) return SPP_OK;
+    SPP_HIP(hipSetDevice(ctx->device));
+    hipStream_t st = ctx->stream;
+    SPP_TRY(ctx->partials.reserve(256));
+    int* d_bad = ctx->partials.as<int>();
+    clear_flag_kernel<<<1, 64, 0, st>>>(d_bad);
+    const int64_t need = (nmax + kBlock - 1) / kBlock;
+    const int64_t lim = (int64_t)ctx->num_cu * 8 / n_lists + 1;
+    access_count_kernel<<<dim3((unsigned)(need < lim ? need : lim), n_lists), kBlock, 0, st>>>(l, N, d_count, d_bad);
+    SPP_HIP(hipGetLastError());
+    if (flags & SPP_SYNC) {
+        int* hb = reinterpret_cast<int*>(ctx->h_pinned + 60);
+        SPP_HIP(hipMemcpyAsync(hb, d_bad, sizeof(int), hipMemcpyDeviceToHost, st));
+        SPP_HIP(hipStreamSynchronize(st));
+        SPP_CHECK(*hb == 0, SPP_E_ARG, "spp_access_count: an id lies outside [0, N); it was skipped");
+    }
+    return SPP_OK;
+}
 
 extern "C" int spp_build_vip_cache(spp_ctx* ctx, const float* d_score, int64_t N, int64_t lo, int64_t hi,
                                    int32_t K, double alpha, const void* remote, int32_t D,

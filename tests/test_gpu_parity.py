@@ -435,6 +435,48 @@ def test_local_store_tiny(spp, ctx, tiny_case):
     store.close()
 
 
+def test_access_counts_and_empirical_policies_tiny(spp, ctx, tiny_case):
+    """Empirical access frequencies (Sec. 3.2, "sim." and "oracle" policies): counts over sampled
+    minibatches, bit for bit, and the caches ranked from them."""
+    c = tiny_case
+    cfg = c.cfg
+    B, fanouts = 64, (5, 5)
+    bufs = [spp.MFGBuffers("cuda", B, fanouts, cfg.N) for _ in range(4)]
+    count_d = torch.zeros(cfg.N, dtype=torch.float32, device="cuda")
+    count_ref = np.zeros(cfg.N, dtype=np.float32)
+    for ep in range(3):
+        perm = np.random.default_rng(50 + ep).permutation(c.Tk)
+        groups = [perm[b:b + B] for b in range(0, perm.size - B + 1, B)]
+        _say("access counts epoch", ep, "minibatches", len(groups))
+        for g0 in range(0, len(groups), 4):
+            grp = groups[g0:g0 + 4]
+            items = [(torch.from_numpy(s_).cuda(), ep * 100 + g0 + k, bufs[k]) for k, s_ in enumerate(grp)]
+            spp.sample_mfg_multi(ctx, c.G, items, fanouts, 11, sync=False)
+            # counts read on the device: no host round trip between sampling and counting
+            spp.access_count(ctx, [(bufs[k].node_ids, bufs[k].nb[-1], bufs[k].n_final_device) for k in range(len(grp))],
+                             cfg.N, count_d, sync=(g0 == 0))
+            for k, s_ in enumerate(grp):
+                ref = oracle.sample_mfg(c.rp, c.col, s_, fanouts, 11, ep * 100 + g0 + k)
+                oracle.access_count(cfg.N, ref.node_ids, count_ref)
+    ctx.sync()
+    assert np.array_equal(count_d.cpu().numpy(), count_ref)
+    for alpha in (0.05, 0.3):
+        cache = spp.build_vip_cache(ctx, count_d, c.lo, c.hi, cfg.K, alpha, None, cfg.D, cfg.elem_bytes)
+        assert np.array_equal(cache.ids.cpu().numpy(), oracle.cache_select(count_ref, c.lo, c.hi, cfg.K, alpha))
+        cache.close()
+    # host counts, repeated ids (each appearance counts), an empty list, and ids out of range
+    ids = torch.tensor([5, 5, 7, 5, cfg.N - 1], dtype=torch.int32, device="cuda")
+    cnt = spp.access_count(ctx, [(ids, 5, None), (ids, 0, None), (ids, 3, None)], cfg.N)
+    want = np.zeros(cfg.N, np.float32)
+    want[5], want[7], want[cfg.N - 1] = 5, 2, 1
+    assert np.array_equal(cnt.cpu().numpy(), want)
+    bad = torch.tensor([1, -1, cfg.N, 2], dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(cfg.N, dtype=torch.float32, device="cuda")
+    with pytest.raises(spp.SppError):
+        spp.access_count(ctx, [(bad, 4, None)], cfg.N, cnt)
+    assert cnt.sum().item() == 2 and cnt[1].item() == 1 and cnt[2].item() == 1
+
+
 # ----------------------------------------------------------------------------------------------
 # scaled copies of the other configs: several tiles, ragged tails, hubs, 16-bit rows
 # ----------------------------------------------------------------------------------------------
