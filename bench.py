@@ -24,10 +24,10 @@ PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
 # same counters on a plain 1 GiB elementwise kernel (factors 2.0 and 1.0): profiles/gather_hit_mid_traffic.txt
-# and profiles/vip_pull_mid_counters.txt.  Keyed by (workload, minibatches per gather launch); other
+# and profiles/vip_tile_mid_counters.txt.  Keyed by (workload, minibatches per gather launch); other
 # shapes report null.
 MEASURED_TRAFFIC = {
-    ("mid", 8): {"gather_hit": 174.0e6 + 134.9e6, "vip_pull": 1.803e9 + 20.5e6},
+    ("mid", 8): {"gather_hit": 174.0e6 + 134.9e6, "vip_tile": None},
 }
 
 
@@ -238,7 +238,7 @@ def main():
     nrem = cfg.N - (hi - lo)
     if args.phase in ("policy-sweep", "vip"):
         local = remote = None                      # these phases move no feature rows
-        log(f"no feature rows for phase {args.phase}; in-lists built in {t_inlists:.2f}s")
+        log(f"no feature rows for phase {args.phase}; transposed structure built in {t_inlists:.2f}s")
     else:
         local = S.feature_block(cfg, lo, hi, dev)
         if args.phase == "beta-sweep":
@@ -252,7 +252,7 @@ def main():
             remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
         torch.cuda.synchronize()
         log(f"features local {tuple(local.shape)} remote {tuple(remote.shape)} "
-            f"{'pinned' if remote.is_pinned() else 'in device memory'}; in-lists built in {t_inlists:.2f}s")
+            f"{'pinned' if remote.is_pinned() else 'in device memory'}; transposed structure built in {t_inlists:.2f}s")
 
     # ---- one-time rows: VIP propagation, cache ranking + fill -------------------------------
     p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts)            # warm-up, allocates workspaces
@@ -263,14 +263,15 @@ def main():
     ctx.timing(False)
     vip_total_ms = ms[0] / max(cnt[0], 1)
     vip_hop_ms = [ms[1 + h] / max(cnt[1 + h], 1) for h in range(cfg.L)]
-    # algorithmic bytes of one hop: one int32 source id per edge, the in-list offsets, y read once,
-    # and the per-vertex result written once
+    # algorithmic bytes of one hop (independent of how the transposed edges are laid out): one int32
+    # source id per edge, one 64-bit offset per destination row, y read once, the per-vertex result
+    # written once
     vip_hop_bytes = 4 * g.M + 8 * (g.N + 1) + 4 * g.N + 4 * g.N
     worst = max(vip_hop_ms)
     measured = MEASURED_TRAFFIC.get((cfg.name, max(1, min(args.group, 16))), {})
     vip_roof = {"bound": "hbm", "achieved": vip_hop_bytes / (worst * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "kernel": "vip_pull_kernel (slowest hop, a dense one: all M edges)",
-                "traffic": measured.get("vip_pull")}
+                "unit": "GB/s", "kernel": "vip_tile_kernel + vip_tile_finish_kernel (slowest hop, a dense one: all M edges)",
+                "traffic": measured.get("vip_tile")}
     vip_roof["frac"] = vip_roof["achieved"] / HBM_PEAK_GBS
     vip_pushed, vip_frontier_edges = spp.vip_last_hops(ctx, cfg.L)
     if args.phase == "vip":

@@ -55,11 +55,12 @@ enum {
 /* flags */
 #define SPP_SYNC              0x1u   /* wait for the stream before returning and fill host outputs */
 #define SPP_VIP_INCLUDE_HOP0  0x2u   /* also multiply (1 - p^[0]) into eq. (1); default: as printed, h = 1..L */
-#define SPP_GRAPH_IN_LISTS    0x4u   /* spp_graph_create: also build the in-lists vip_propagate needs */
+#define SPP_GRAPH_IN_LISTS    0x4u   /* spp_graph_create: also build the transposed edge structure (who can sample u)
+                                        that vip_propagate needs: 6 bytes per edge of device memory */
 #define SPP_NO_JOIN           0x8u   /* gather: leave the miss copy running on the side stream; see spp_gather_join */
 
 typedef struct spp_ctx   spp_ctx;    /* workspaces, side stream, events */
-typedef struct spp_graph spp_graph;  /* refers to the caller's CSR; owns the library-built in-lists */
+typedef struct spp_graph spp_graph;  /* refers to the caller's CSR; owns the library-built transposed structure */
 typedef struct spp_cache spp_cache;  /* owns the id->slot table and the cached rows in HBM */
 
 /* Thread-local description of the last error on this thread; valid until the next call. */
@@ -96,7 +97,7 @@ int  spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t* d_T, int
 
 /* How the last spp_vip_propagate on this context walked each hop: pushed[h-1] = 1 if hop h was done
  * in push form over a sparse frontier (its out-edges were at most M/16), 0 if it was pulled over
- * the in-lists; frontier_edges[h-1] = out-edges of the vertices with a non-zero weight at hop h
+ * the transposed structure; frontier_edges[h-1] = out-edges of the vertices with a non-zero weight at hop h
  * (the edges a hop has to touch at all).  Either array may be NULL. */
 int  spp_vip_last_hops(spp_ctx* ctx, int32_t* pushed, int64_t* frontier_edges, int32_t L);
 

@@ -62,7 +62,7 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     if (c->totals) (void)hipFree(c->totals);
     c->table.release(); c->flat.release(); c->slots.release(); c->partials.release();
     c->srcdesc.release(); c->misslist.release(); c->gcount.release();
-    c->y0.release(); c->y1.release(); c->tot.release(); c->hubacc.release(); c->acc.release(); c->frontier.release();
+    c->y0.release(); c->y1.release(); c->tot.release(); c->acc.release(); c->frontier.release();
     delete c;
 }
 

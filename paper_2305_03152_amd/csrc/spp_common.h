@@ -83,7 +83,8 @@ struct spp_ctx {
     int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
     int64_t*    totals = nullptr;       // device int64[8], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces
-    spp::DevBuf y0, y1, tot, hubacc, acc, frontier;
+    spp::DevBuf y0, y1, tot, acc, frontier;
+    int         tile_lds_set = 0;       // dynamic LDS bytes the dense-hop kernel has been allowed on this device
     int         vip_pushed[SPP_MAX_L] = {};          // last vip_propagate: hop done in push form?
     int64_t     vip_frontier_edges[SPP_MAX_L] = {};  // last vip_propagate: out-edges of each hop's frontier
     // timing: while enabled every timed piece of device work gets its own pair of events
@@ -104,15 +105,15 @@ struct spp_graph {
     int64_t        N = 0, M = 0;
     const int64_t* rowptr = nullptr;    // caller's
     const int32_t* col = nullptr;       // caller's
-    // in-lists (transpose), library-owned
-    bool     has_in = false;
-    int64_t* in_rowptr = nullptr;       // int64[N+1]
-    int32_t* in_col = nullptr;          // int32[M], ascending within a row
-    int32_t* blk_row = nullptr;         // int32[nblk+1]: first in-row starting at or after edge b*kVipChunk
-    int64_t  nblk = 0;
-    int32_t* hub_rows = nullptr;        // in-rows longer than kVipChunk
-    int64_t* hub_slice_ptr = nullptr;   // int64[nhub+1]: prefix of slices per hub
-    int64_t  nhub = 0, nslices = 0;
+    // the same edges once more (library-owned, built on request), grouped by blocks of
+    // 2^tile_rbits destination rows and sorted by source inside a block: the structure the
+    // dense hops of the VIP propagation walk
+    bool      has_in = false;
+    int32_t*  t_src = nullptr;          // int32[M] source vertex
+    uint16_t* t_rl = nullptr;           // uint16[M] destination row inside its block
+    int64_t*  rb_off = nullptr;         // int64[nrb+1] first edge of every row block
+    int       tile_rbits = 0;
+    int64_t   nrb = 0;
 };
 
 struct spp_cache {
@@ -140,8 +141,6 @@ struct spp_local_store {
 
 namespace spp {
 
-constexpr int kVipChunk = 4096;         // in-list edges per workgroup of the pull kernel
-constexpr int kHubSlice = 16384;        // edges per workgroup slice of a hub row
 
 struct ScopedTimer {
     spp_ctx* c; int idx; hipStream_t s; hipEvent_t a = nullptr, b = nullptr;

@@ -77,7 +77,7 @@ def _full_size(name):
     ctx = spp.Context(0)
     t = time.time()
     G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True)
-    _say(f"in-lists built in {time.time() - t:.2f}s; vip on the GPU")
+    _say(f"transposed structure built in {time.time() - t:.2f}s; vip on the GPU")
     p, ph = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts, per_hop=True)
     p_gpu = p.cpu().numpy()
     ph_gpu = ph.cpu().numpy()
