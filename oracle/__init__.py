@@ -248,3 +248,65 @@ def access_count(N, node_ids, count=None):
     if rc != 0:
         raise ValueError("orc_access_count: id outside [0, N)")
     return count
+
+
+def _tlist(t, L, M):
+    """One float32[M] array per hop (a single array serves every hop)."""
+    if isinstance(t, np.ndarray) and t.ndim == 1:
+        t = [t] * L
+    t = [np.ascontiguousarray(a, dtype=np.float32) for a in t]
+    assert len(t) == L and all(a.size == M for a in t)
+    return t
+
+
+def vip_general(rowptr, col, p0, t, L, include_hop0=False):
+    """Proposition 1 with given initial probabilities p0[N] and transition probabilities t[h][M]
+    (aligned with col).  Returns (p_total[N], p_hop[L, N]) in float64."""
+    lib = _load()
+    rowptr, col = _i64(rowptr), _i32(col)
+    N, M = rowptr.size - 1, col.size
+    p0 = np.ascontiguousarray(p0, dtype=np.float32)
+    t = _tlist(t, L, M)
+    tp = (C.c_void_p * L)(*[a.ctypes.data for a in t])
+    p_total = np.empty(N, dtype=np.float64)
+    p_hop = np.empty((L, N), dtype=np.float64)
+    rc = lib.orc_vip_general(C.c_int64(N), _p(rowptr), _p(col), _p(p0), tp, C.c_int32(L),
+                             C.c_int(int(include_hop0)), _p(p_hop), _p(p_total))
+    if rc != 0:
+        raise ValueError(f"orc_vip_general failed ({rc})")
+    return p_total, p_hop
+
+
+def sample_mfg_general(rowptr, col, t, seeds, L, seed, batch):
+    """Independent-inclusion sampler: target v takes col[e] with probability t[h][e].  Returns an MFG."""
+    lib = _load()
+    rowptr, col, seeds = _i64(rowptr), _i32(col), _i32(seeds)
+    N, M = rowptr.size - 1, col.size
+    t = _tlist(t, L, M)
+    tp = (C.c_void_p * L)(*[a.ctypes.data for a in t])
+    n_out = np.zeros(L + 1, dtype=np.int64)
+    e_out = np.zeros(L + 1, dtype=np.int64)
+
+    def call(node_cap, edge_cap, node_ids, ip_arr, sp_arr):
+        rc = lib.orc_sample_mfg_general(C.c_int64(N), _p(rowptr), _p(col), tp, _p(seeds), C.c_int32(seeds.size),
+                                        C.c_int32(L), C.c_uint64(int(seed)), C.c_uint64(int(batch)),
+                                        C.c_int64(node_cap), C.c_int64(edge_cap), node_ids, ip_arr, sp_arr,
+                                        _p(n_out), _p(e_out))
+        if rc != 0:
+            raise ValueError(f"orc_sample_mfg_general failed ({rc})")
+
+    call(0, 0, None, None, None)                                   # sizes only
+    n = [int(x) for x in n_out]
+    e = [int(x) for x in e_out]
+    node_ids = np.empty(max(n[L], 1), dtype=np.int32)
+    indptr = [np.empty(n[h] + 1, dtype=np.int32) for h in range(L)]
+    src = [np.empty(max(e[h + 1], 1), dtype=np.int32) for h in range(L)]
+    ip_arr = (C.c_void_p * L)(*[a.ctypes.data for a in indptr])
+    sp_arr = (C.c_void_p * L)(*[a.ctypes.data for a in src])
+    call(n[L], max(max(e), 1), _p(node_ids), ip_arr, sp_arr)
+    m = MFG()
+    m.n, m.e = n, e
+    m.node_ids = node_ids[:n[L]].copy()
+    m.indptr = indptr
+    m.src = [src[h][:e[h + 1]].copy() for h in range(L)]
+    return m

@@ -394,3 +394,116 @@ int orc_access_count(int64_t N, const int32_t *node_ids, int64_t n, float *count
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Proposition 1 with arbitrary initial and transition probabilities (Sec. 3.1, the paragraph
+ * after the proposition: any initial sampling, any hop-wise transition probability function):
+ *   p0[v]     probability that v is in the minibatch                         (float32[N])
+ *   t[h-1][e] probability that the vertex of CSR row r(e) samples col[e] at hop h  (float32[M])
+ *   p^[h](u) = 1 - prod over edges e with col[e] = u of (1 - t[h-1][e] * p^[h-1](r(e)))   eq. (2)
+ *   p(u)     = 1 - prod_{h=1..L} (1 - p^[h](u))                                          eq. (1)
+ * Products are carried as fp64 sums of log1p.  Every probability must lie in [0, 1].
+ * include_hop0 multiplies (1 - p0) into eq. (1), as for the uniform instantiation.
+ * p_hop: double[L*N] or NULL; p_total: double[N].  Returns 0; -1 bad argument; -3 a value
+ * outside [0, 1] (or not a number).
+ * ---------------------------------------------------------------------------------------- */
+int orc_vip_general(int64_t N, const int64_t *rowptr, const int32_t *col, const float *p0,
+                    const float *const *t, int32_t L, int include_hop0, double *p_hop, double *p_total)
+{
+    if (N <= 0 || L <= 0 || !p0 || !t || !p_total) return -1;
+    const int64_t M = rowptr[N];
+    for (int64_t v = 0; v < N; ++v)
+        if (!(p0[v] >= 0.0f && p0[v] <= 1.0f)) return -3;
+    for (int32_t h = 0; h < L; ++h)
+        for (int64_t e = 0; e < M; ++e)
+            if (!(t[h][e] >= 0.0f && t[h][e] <= 1.0f)) return -3;
+    double *prev = (double *)malloc((size_t)N * sizeof(double));
+    double *S = (double *)malloc((size_t)N * sizeof(double));
+    double *tot = (double *)calloc((size_t)N, sizeof(double));
+    if (!prev || !S || !tot) { free(prev); free(S); free(tot); return -1; }
+    for (int64_t v = 0; v < N; ++v) {
+        prev[v] = (double)p0[v];
+        if (include_hop0) tot[v] = log1p(-prev[v]);
+    }
+    for (int32_t h = 1; h <= L; ++h) {
+        for (int64_t u = 0; u < N; ++u) S[u] = 0.0;
+        for (int64_t v = 0; v < N; ++v) {
+            if (prev[v] == 0.0) continue;
+            for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+                const double x = (double)t[h - 1][e] * prev[v];
+                if (x > 0.0) S[col[e]] += log1p(-x);
+            }
+        }
+        for (int64_t u = 0; u < N; ++u) {
+            prev[u] = -expm1(S[u]);
+            tot[u] += S[u];
+            if (p_hop) p_hop[(int64_t)(h - 1) * N + u] = prev[u];
+        }
+    }
+    for (int64_t u = 0; u < N; ++u) p_total[u] = -expm1(tot[u]);
+    free(prev); free(S); free(tot);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * A sampler whose transition probabilities are exactly t: at hop h a target v takes every member
+ * col[e] of its row independently with probability t[h-1][e] (independent inclusion, so a
+ * target's sample has no fixed size).  Edge e at position k of its row is taken iff
+ *   rand32(seed, batch, h, v, k) < floor(t[h-1][e] * 2^32)      (compared as 64-bit integers),
+ * so the realised probability is t rounded down to a multiple of 2^-32, and t = 1 always takes.
+ * Layout and relabelling as in orc_sample_mfg: taken neighbours of a target in row order,
+ * targets in the order of S_{h-1}, new ids appended in order of first appearance.
+ * With node_ids == NULL only the sizes n_out, e_out are computed (to size the buffers).
+ * Returns 0; -1 bad args/alloc; -2 capacity exceeded.
+ * ---------------------------------------------------------------------------------------- */
+int orc_sample_mfg_general(int64_t N, const int64_t *rowptr, const int32_t *col, const float *const *t,
+                           const int32_t *seeds, int32_t nseeds, int32_t L, uint64_t seed, uint64_t batch,
+                           int64_t node_cap, int64_t edge_cap, int32_t *node_ids, int32_t **indptr,
+                           int32_t **src, int64_t *n_out, int64_t *e_out)
+{
+    if (N <= 0 || nseeds < 0 || L <= 0) return -1;
+    const int count_only = node_ids == NULL;
+    int32_t *local = (int32_t *)malloc((size_t)N * sizeof(int32_t));   /* global id -> index in S */
+    int32_t *S = (int32_t *)malloc((size_t)N * sizeof(int32_t));       /* S_h (at most N ids) */
+    if (!local || !S) { free(local); free(S); return -1; }
+    for (int64_t g = 0; g < N; ++g) local[g] = -1;
+    int64_t n = 0;
+    for (int32_t i = 0; i < nseeds; ++i) {
+        int32_t g = seeds[i];
+        if (g < 0 || g >= N || local[g] >= 0) { free(local); free(S); return -1; }
+        local[g] = (int32_t)n;
+        S[n++] = g;
+    }
+    n_out[0] = n; e_out[0] = 0;
+    int rc = 0;
+    for (int32_t h = 1; h <= L && rc == 0; ++h) {
+        const int64_t n_prev = n;
+        int64_t e = 0;
+        int32_t *ip = count_only ? NULL : indptr[h - 1], *sp = count_only ? NULL : src[h - 1];
+        for (int64_t i = 0; i < n_prev && rc == 0; ++i) {
+            const int32_t v = S[i];
+            if (ip) ip[i] = (int32_t)e;
+            for (int64_t k = 0; k < rowptr[v + 1] - rowptr[v]; ++k) {
+                const int64_t edge = rowptr[v] + k;
+                const uint64_t thr = (uint64_t)((double)t[h - 1][edge] * 4294967296.0);
+                const uint32_t r = orc_rand32(seed, batch, (uint32_t)h, (uint32_t)v, (uint32_t)k);
+                if (!((uint64_t)r < thr)) continue;
+                const int32_t g = col[edge];
+                if (local[g] < 0) { local[g] = (int32_t)n; S[n++] = g; }
+                if (sp) {
+                    if (e >= edge_cap) { rc = -2; break; }
+                    sp[e] = local[g];
+                }
+                ++e;
+            }
+        }
+        if (ip) ip[n_prev] = (int32_t)e;
+        n_out[h] = n; e_out[h] = e;
+    }
+    if (!count_only && rc == 0) {
+        if (n > node_cap) rc = -2;
+        else memcpy(node_ids, S, (size_t)n * sizeof(int32_t));
+    }
+    free(local); free(S);
+    return rc;
+}
