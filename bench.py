@@ -130,6 +130,52 @@ def policy_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, lo, hi):
                       "minibatches": nb_ev, "sim_minibatches": nb_sim, "sim_count_s": sim_s, "rows": rows}), flush=True)
 
 
+def general_phase(args, cfg, spp, S, torch, ctx, G, g, Tk, p):
+    """Proposition 1 and the sampler with given transition probabilities (Sec. 3.1), timed on the
+    uniform instantiation t = min(1, f_h/d(v)) so that the sizes are those of the fanout workload."""
+    dev = p.device
+    deg = (g.rowptr[1:] - g.rowptr[:-1])
+    t = []
+    for f in cfg.fanouts:
+        per_row = torch.clamp(float(f) / deg.clamp(min=1).to(torch.float64), max=1.0).to(torch.float32)
+        t.append(torch.repeat_interleave(per_row, deg))
+    p0 = torch.zeros(cfg.N, dtype=torch.float32, device=dev)
+    p0[Tk.long()] = min(1.0, cfg.B / Tk.numel())
+    pg = spp.vip_propagate_general(ctx, G, p0, t, cfg.L)
+    ctx.timing(True)
+    for _ in range(args.vip_reps):
+        pg = spp.vip_propagate_general(ctx, G, p0, t, cfg.L, sync=False)
+    ms, cnt = ctx.times()
+    ctx.timing(False)
+    rel = ((pg - p).abs() / p.clamp(min=1e-30)).max().item()
+    batches = [b for b in S.epoch_batches(cfg, Tk, 0) if b.numel() == min(cfg.B, Tk.numel())][:8]
+    nb, eb = spp.mfg_bound(cfg.B, cfg.fanouts, cfg.N)
+    caps = (nb[-1], [2 * e for e in eb[1:]])            # independent inclusion: sizes vary around the fanout's
+    bufs = [spp.MFGBuffers(dev, 0, (), cfg.N, capacities=caps) for _ in batches]
+    fb = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N) for _ in batches]
+    items = [(b, i, bufs[i]) for i, b in enumerate(batches)]
+    fitems = [(b, i, fb[i]) for i, b in enumerate(batches)]
+    spp.sample_mfg_general(ctx, G, t, items, cfg.L, cfg.seed_sampler)
+    spp.sample_mfg_multi(ctx, G, fitems, cfg.fanouts, cfg.seed_sampler)
+    res = {}
+    for name, fn in (("general", lambda: spp.sample_mfg_general(ctx, G, t, items, cfg.L, cfg.seed_sampler, sync=False)),
+                     ("fanout", lambda: spp.sample_mfg_multi(ctx, G, fitems, cfg.fanouts, cfg.seed_sampler, sync=False))):
+        ctx.timing(True)
+        for _ in range(10):
+            fn()
+        m2, c2 = ctx.times()
+        ctx.timing(False)
+        res[name] = m2[9] / max(c2[9], 1)
+    print(json.dumps({"phase": "general", "workload": cfg.name, "N": g.N, "M": g.M,
+                      "vip_general_ms_total": ms[0] / max(cnt[0], 1),
+                      "vip_general_ms_per_hop": [ms[1 + h] / max(cnt[1 + h], 1) for h in range(cfg.L)],
+                      "max_rel_diff_to_uniform_entry_point": rel,
+                      "sampler_general_ms_per_8_minibatches": res["general"],
+                      "sampler_fanout_ms_per_8_minibatches": res["fanout"],
+                      "general_nodes_per_batch": sum(b.n[-1] for b in bufs) / len(bufs),
+                      "fanout_nodes_per_batch": sum(b.n[-1] for b in fb) / len(fb)}), flush=True)
+
+
 def beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi):
     """Host reads for local vertices over the device-resident share beta of the partition's rows:
     VIP order against the id order (Sec. 3.2 on host-to-device transfers; the experiment shape of the
@@ -185,12 +231,14 @@ def main():
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
                          "(pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
-    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "policy-sweep", "calibrate"],
+    ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "policy-sweep", "general", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
                          "alpha-sweep: hit rate and host-miss bytes per batch over alpha in {0,.05,.1,.2,.5}, VIP-ranked "
                          "against degree-ranked cache (the experiment shape of Fig. 2 / Fig. 7), e.g. with --config skew; "
                          "policy-sweep: remote vertices fetched per epoch over alpha for the policies none / deg. / sim. / "
                          "VIP / oracle (the policy comparison of Sec. 3.2), counted on the device over --sweep-epochs epochs; "
+                         "general: Prop. 1 and the sampler with given transition probabilities, timed on the uniform "
+                         "instantiation next to the fanout entry points; "
                          "beta-sweep: local rows read from host memory over the device-resident share beta of the "
                          "partition's rows, VIP order against id order (the experiment shape of the figure on local "
                          "storage on CPU versus GPU); "
@@ -236,7 +284,7 @@ def main():
     G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True)
     t_inlists = time.time() - t
     nrem = cfg.N - (hi - lo)
-    if args.phase in ("policy-sweep", "vip"):
+    if args.phase in ("policy-sweep", "vip", "general"):
         local = remote = None                      # these phases move no feature rows
         log(f"no feature rows for phase {args.phase}; transposed structure built in {t_inlists:.2f}s")
     else:
@@ -288,6 +336,9 @@ def main():
         return
     if args.phase == "policy-sweep":
         policy_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, lo, hi)
+        return
+    if args.phase == "general":
+        general_phase(args, cfg, spp, S, torch, ctx, G, g, Tk, p)
         return
     t = time.time()
     cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)

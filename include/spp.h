@@ -242,6 +242,32 @@ int  spp_gather_features_split(spp_ctx* ctx, const spp_cache* cache, const spp_l
                                int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
                                spp_gather_stats* stats, uint32_t flags);
 
+/* (f) Proposition 1 with arbitrary probabilities (Sec. 3.1, paragraph after the proposition: any
+ *     initial sampling and any hop-wise transition probability function):
+ *       d_p0   device fp32[N]: probability that v is in the minibatch
+ *       d_t    HOST array of L device pointers; d_t[h-1] is fp32[M], aligned with the CSR's col:
+ *              the probability that the vertex of the row samples that entry at hop h
+ *       p^[h](u) = 1 - prod over edges e with col[e] = u of (1 - d_t[h-1][e] * p^[h-1](row(e)))
+ *     and p(u) as in eq. (1).  Walked in push form over the CSR (the graph needs no transposed
+ *     structure), fp64 log-sums, fp32 results; no host synchronisation inside.  A probability
+ *     outside [0, 1] (or not a number) counts as 0 and is reported (SPP_E_ARG) when SPP_SYNC is
+ *     set.  flags: SPP_VIP_INCLUDE_HOP0, SPP_SYNC. */
+int  spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const float* d_p0, const float* const* d_t,
+                               int32_t L, float* d_p_total, float* d_p_hop, uint32_t flags);
+
+/*     A sampler whose transition probabilities are exactly d_t: at hop h a target v takes every
+ *     entry of its row independently, entry k (edge e) iff
+ *       rand32(seed, batch_index, h, v, k) < floor(d_t[h-1][e] * 2^32)   (64-bit comparison),
+ *     so a target's sample has no fixed size.  Layout, relabelling, batching over several
+ *     minibatches and the random stream are those of spp_sample_mfg_multi.  Because no fanout
+ *     bounds the sample, the capacities of each spp_mfg decide: d_node_ids holds n_nodes_cap ids,
+ *     d_indptr[h] n_nodes_cap + 1 offsets, d_src[h] n_edges_cap[h] entries.  A minibatch that
+ *     would exceed them is abandoned at that hop (nothing is written out of bounds, its counts
+ *     from that hop on stay 0) and the call reports SPP_E_CAPACITY when SPP_SYNC is set. */
+int  spp_sample_mfg_general(spp_ctx* ctx, const spp_graph* g, const float* const* d_t,
+                            const spp_sample_item* items, int32_t n_items, int32_t L, uint64_t seed,
+                            uint32_t flags);
+
 /* (f) Empirical access frequencies (Sec. 3.2, the "sim." and "oracle" caching policies): d_count[v]
  *     += 1 for every id of every list, e.g. the sampled vertex sets of the minibatches of simulated
  *     epochs ("sim.") or of the epochs being evaluated ("oracle", retroactive).  The counts are a

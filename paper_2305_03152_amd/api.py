@@ -30,7 +30,7 @@ EXPORTS = [
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg", "spp_sample_mfg_multi",
     "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
     "spp_build_local_store", "spp_local_store_destroy", "spp_local_store_set_limit", "spp_local_store_rank",
-    "spp_gather_features_split", "spp_access_count",
+    "spp_gather_features_split", "spp_access_count", "spp_vip_propagate_general", "spp_sample_mfg_general",
 ]
 
 
@@ -126,6 +126,10 @@ def load_library():
                                               C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_GatherList), C.c_int32,
                                               C.POINTER(_GatherStats), C.c_uint32]
     lib.spp_access_count.argtypes = [C.c_void_p, C.POINTER(_IdList), C.c_int32, C.c_int64, C.c_void_p, C.c_uint32]
+    lib.spp_vip_propagate_general.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_int32,
+                                              C.c_void_p, C.c_void_p, C.c_uint32]
+    lib.spp_sample_mfg_general.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(_SampleItem),
+                                           C.c_int32, C.c_int32, C.c_uint64, C.c_uint32]
     lib.spp_gather_join.argtypes = [C.c_void_p]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
     lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
@@ -236,6 +240,34 @@ def vip_propagate(ctx: Context, graph: Graph, T: torch.Tensor, B: int, fanouts: 
     flags = (SPP_SYNC if sync else 0) | (SPP_VIP_INCLUDE_HOP0 if include_hop0 else 0)
     _check(load_library().spp_vip_propagate(ctx._h, graph._h, _ptr(T), T.numel(), int(B), f, L, _ptr(p_total),
                                             _ptr(p_hop), flags))
+    return (p_total, p_hop) if per_hop else p_total
+
+
+def _tptrs(t, L: int, M: int):
+    """Host array of L device pointers to fp32[M] transition probabilities (one tensor serves every hop)."""
+    if isinstance(t, torch.Tensor):
+        t = [t] * L
+    if len(t) != L:
+        raise SppError("one transition-probability tensor per hop is needed")
+    for a in t:
+        _dev(a, torch.float32, "t")
+        if a.numel() != M:
+            raise SppError("a transition-probability tensor must have one entry per edge")
+    return (C.c_void_p * L)(*[a.data_ptr() for a in t]), list(t)
+
+
+def vip_propagate_general(ctx: Context, graph: Graph, p0: torch.Tensor, t, L: int, per_hop: bool = False,
+                          include_hop0: bool = False, sync: bool = True):
+    """Proposition 1 with initial probabilities p0[N] and transition probabilities t[h][M] (aligned with col)."""
+    p0 = _dev(p0, torch.float32, "p0")
+    if p0.numel() != graph.N:
+        raise SppError("p0 must hold N entries")
+    tp, keep = _tptrs(t, L, graph.M)
+    p_total = torch.empty(graph.N, dtype=torch.float32, device=p0.device)
+    p_hop = torch.empty((L, graph.N), dtype=torch.float32, device=p0.device) if per_hop else None
+    flags = (SPP_SYNC if sync else 0) | (SPP_VIP_INCLUDE_HOP0 if include_hop0 else 0)
+    _check(load_library().spp_vip_propagate_general(ctx._h, graph._h, _ptr(p0), tp, L, _ptr(p_total), _ptr(p_hop), flags))
+    del keep
     return (p_total, p_hop) if per_hop else p_total
 
 
@@ -386,10 +418,18 @@ def mfg_bound(nseeds: int, fanouts: Sequence[int], N: int):
 class MFGBuffers:
     """Caller-owned output buffers of sample_mfg, sized once from the bounds and reused."""
 
-    def __init__(self, device, max_seeds: int, fanouts: Sequence[int], N: int):
-        self.fanouts = tuple(int(f) for f in fanouts)
-        self.L = len(self.fanouts)
-        self.nb, self.eb = mfg_bound(max_seeds, self.fanouts, N)
+    def __init__(self, device, max_seeds: int, fanouts: Sequence[int], N: int, capacities=None):
+        """Sized from the fanout bounds, or (capacities = (n_nodes_cap, [edge cap per hop])) as given: the
+        sampler with transition probabilities has no bound of its own and checks these capacities."""
+        if capacities is not None:
+            ncap, ecaps = int(capacities[0]), [int(e) for e in capacities[1]]
+            self.fanouts = ()
+            self.L = len(ecaps)
+            self.nb, self.eb = [ncap] * (self.L + 1), [0] + ecaps
+        else:
+            self.fanouts = tuple(int(f) for f in fanouts)
+            self.L = len(self.fanouts)
+            self.nb, self.eb = mfg_bound(max_seeds, self.fanouts, N)
         self.node_ids = torch.empty(max(self.nb[self.L], 1), dtype=torch.int32, device=device)
         self.indptr = [torch.empty(self.nb[h] + 1, dtype=torch.int32, device=device) for h in range(self.L)]
         self.src = [torch.empty(max(self.eb[h + 1], 1), dtype=torch.int32, device=device) for h in range(self.L)]
@@ -444,6 +484,30 @@ def sample_mfg_multi(ctx: Context, graph: Graph, items, fanouts: Sequence[int], 
         arr[j].io = C.pointer(out._s)
     _check(load_library().spp_sample_mfg_multi(ctx._h, graph._h, arr, len(items), f, L,
                                                C.c_uint64(int(seed) & (2**64 - 1)), SPP_SYNC if sync else 0))
+    if sync:
+        for _, _, out in items:
+            out.n = [int(out._s.n[h]) for h in range(L + 1)]
+            out.e = [int(out._s.e[h]) for h in range(L + 1)]
+    return [out for _, _, out in items]
+
+
+def sample_mfg_general(ctx: Context, graph: Graph, t, items, L: int, seed: int, sync: bool = True):
+    """The sampler with given transition probabilities t[h][M]: a target takes every entry of its row
+    independently with the entry's probability.  `items` as for sample_mfg_multi, with MFGBuffers built
+    from capacities; raises when a minibatch exceeds them (sync only)."""
+    tp, keep = _tptrs(t, L, graph.M)
+    arr = (_SampleItem * max(len(items), 1))()
+    for j, (seeds, batch_index, out) in enumerate(items):
+        seeds = _dev(seeds, torch.int32, "seeds")
+        if out.L != L:
+            raise SppError("the buffers were built for another number of hops")
+        arr[j].d_seeds = seeds.data_ptr()
+        arr[j].nseeds = seeds.numel()
+        arr[j].batch_index = int(batch_index) & (2**64 - 1)
+        arr[j].io = C.pointer(out._s)
+    _check(load_library().spp_sample_mfg_general(ctx._h, graph._h, tp, arr, len(items), L,
+                                                 C.c_uint64(int(seed) & (2**64 - 1)), SPP_SYNC if sync else 0))
+    del keep
     if sync:
         for _, _, out in items:
             out.n = [int(out._s.n[h]) for h in range(L + 1)]

@@ -18,6 +18,12 @@
 // worst-case bound on |S_L| only sizes the allocation: a Mid minibatch reaches 66k of 1.08M
 // possible vertices, and a table laid out for the bound (32 MB per minibatch, touched at random)
 // pushed the feature rows out of the caches (the hit copy ran 20 % slower) besides missing L2 itself.
+//
+// The same machinery serves the sampler with given transition probabilities (Sec. 3.1, paragraph
+// after Prop. 1): a target takes every entry of its row independently with the entry's probability,
+// so step 1 is a counting pass with the random draws (one wavefront per target, ballots) and step 2
+// repeats the draws to place the taken entries; no fanout bounds the sizes, so the counting pass
+// also checks the caller's capacities and abandons a minibatch that would exceed them.
 #include "spp_common.h"
 #include "spp_device.h"
 
@@ -32,7 +38,10 @@ struct BatchDesc {
     int32_t*       indptr[SPP_MAX_L];
     int32_t*       src[SPP_MAX_L];
     int64_t*       counts;              // n[0..MAX_L], e[0..MAX_L]
-    uint32_t*      tinfo;               // [0] mask, [1] shift of the table for the current hop (workspace)
+    uint32_t*      tinfo;               // [0] mask, [1] shift of the table for the current hop, [2] abandoned (workspace)
+    unsigned long long* taken;          // 64-bit count of taken entries of the current hop (given probabilities only)
+    int64_t        ncap;                // capacities of the caller's buffers (checked on the device
+    int64_t        ecap[SPP_MAX_L];     //   only when sizes are not bounded by fanouts)
     int32_t        nseeds;
     uint32_t       batch_lo;
 };
@@ -55,10 +64,15 @@ struct SampleArgs {
     int            h;                   // hop, 1-based
     int            f;                   // fanout of this hop
     uint64_t       seed;
+    const float*   t;                   // this hop's transition probabilities (aligned with col), or null: fanout sampling
+    int32_t*       cnt;                 // one region of `cnt_stride` per-target counts per minibatch (given probabilities)
+    int64_t        cnt_stride;
+    int*           ovf;                 // set when a minibatch was abandoned for lack of capacity
 };
 
 __device__ __forceinline__ unsigned long long* tab_of(const SampleArgs& a, int j) { return a.tab + (int64_t)j * a.cap; }
 __device__ __forceinline__ int32_t* flat_of(const SampleArgs& a, int j) { return a.flat + (int64_t)j * a.flat_stride; }
+__device__ __forceinline__ int32_t* cnt_of(const SampleArgs& a, int j) { return a.cnt + (int64_t)j * a.cnt_stride; }
 constexpr int kE = SPP_MAX_L + 1;      // offset of e[] inside counts
 
 // Zeroes the counts of the new minibatches and copies the seeds into S_0.
@@ -71,6 +85,8 @@ __global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const Batch
         for (int k = 1; k <= SPP_MAX_L; ++k) c[k] = 0;
         for (int k = 0; k <= SPP_MAX_L; ++k) c[kE + k] = 0;
         c[0] = t->b[j].nseeds;
+        t->b[j].tinfo[2] = 0;
+        if (t->b[j].taken) *t->b[j].taken = 0ull;
     }
     if (i >= t->b[j].nseeds) return;
     int32_t v = t->b[j].seeds[i];
@@ -81,8 +97,9 @@ __global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const Batch
 // ---- step 1 ----
 struct CountIn {
     SampleArgs a; const BatchTable* t;
-    __device__ int64_t n(int j) const { return t->b[j].counts[a.h - 1]; }
+    __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[a.h - 1]; }
     __device__ int operator()(int j, int64_t i) const {
+        if (a.t) return cnt_of(a, j)[i];
         const int64_t v = t->b[j].S[i];
         const int64_t d = a.rowptr[v + 1] - a.rowptr[v];
         return (int)(d < a.f ? d : a.f);
@@ -96,6 +113,18 @@ struct CountFin {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int total) const {
         int64_t* c = t->b[j].counts;
+        if (t->b[j].tinfo[2]) return;                        // abandoned at an earlier hop
+        if (a.t) {
+            // sizes are not bounded by fanouts: the 64-bit count of the counting pass decides whether the
+            // caller's buffers (and the table region laid out for them) hold this hop
+            const unsigned long long taken = *t->b[j].taken;
+            *t->b[j].taken = 0ull;
+            if (taken > (unsigned long long)t->b[j].ecap[a.h - 1]) {
+                t->b[j].tinfo[2] = 1;
+                atomicOr(a.ovf, 1);
+                return;
+            }
+        }
         t->b[j].indptr[a.h - 1][c[a.h - 1]] = total;
         c[kE + a.h] = total;
         atomicAdd(&a.totals[2], (unsigned long long)(uint32_t)total);
@@ -115,6 +144,7 @@ struct CountFin {
 __global__ void __launch_bounds__(kBlock) table_clear_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
     const BatchBlock bb = batch_block();
     const int j = bb.j;
+    if (t->b[j].tinfo[2]) return;
     unsigned long long* tab = tab_of(a, j);
     const int64_t capj = (int64_t)t->b[j].tinfo[0] + 1;
     const int64_t stride = (int64_t)gridDim.x * kBlock;
@@ -192,10 +222,90 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
     }
 }
 
+// ---- steps 1 and 2 with given transition probabilities ----
+// Entry k of v's row is taken iff rand32(seed, batch, hop, v, k) < floor(t * 2^32); a probability
+// outside [0, 1] counts as 0 and is reported.
+__device__ __forceinline__ bool general_take(const SampleArgs& a, uint32_t batch_lo, int64_t v, int64_t r0, int64_t k) {
+    const float tt = a.t[r0 + k];
+    if (!(tt >= 0.0f && tt <= 1.0f)) { atomicOr(a.bad, 2); return false; }
+    const uint64_t thr = (uint64_t)((double)tt * 4294967296.0);
+    return (uint64_t)rand32(a.seed, batch_lo, (uint32_t)a.h, (uint32_t)v, (uint32_t)k) < thr;
+}
+
+__global__ void __launch_bounds__(kBlock) general_count_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    __shared__ unsigned long long red[4];
+    const BatchBlock bb = batch_block();
+    const int jb = bb.j;
+    if (t->b[jb].tinfo[2]) return;
+    const int lane = lane_id();
+    const int64_t n_prev = t->b[jb].counts[a.h - 1];
+    const uint32_t batch_lo = t->b[jb].batch_lo;
+    const int64_t wave = ((int64_t)bb.x * kBlock + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+    const int32_t* __restrict__ S = t->b[jb].S;
+    int32_t* __restrict__ cnt = cnt_of(a, jb);
+    unsigned long long mine = 0;
+    for (int64_t i = wave; i < n_prev; i += nwaves) {
+        const int64_t v = S[i];
+        const int64_t r0 = a.rowptr[v], d = a.rowptr[v + 1] - r0;
+        int64_t c = 0;
+        for (int64_t k0 = 0; k0 < d; k0 += kWave) {
+            const int64_t k = k0 + lane;
+            const bool take = k < d && general_take(a, batch_lo, v, r0, k);
+            c += __popcll(__ballot(take));
+        }
+        // a count beyond any capacity is stored saturated; the 64-bit total below decides
+        if (lane == 0) { cnt[i] = (int32_t)(c < 0x7FFFFFFFll ? c : 0x7FFFFFFFll); mine += (unsigned long long)c; }
+    }
+    if (lane == 0) red[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long s4 = red[0] + red[1] + red[2] + red[3];
+        if (s4) atomicAdd(t->b[jb].taken, s4);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const BatchBlock bb = batch_block();
+    const int jb = bb.j;
+    if (t->b[jb].tinfo[2]) return;
+    const int lane = lane_id();
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    const int64_t n_prev = t->b[jb].counts[a.h - 1];
+    const uint32_t batch_lo = t->b[jb].batch_lo;
+    const int64_t wave = ((int64_t)bb.x * kBlock + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+    const int32_t* __restrict__ S = t->b[jb].S;
+    const int32_t* __restrict__ indptr = t->b[jb].indptr[a.h - 1];
+    int32_t* __restrict__ flat = flat_of(a, jb);
+    unsigned long long* tab = tab_of(a, jb);
+    const uint32_t mask = t->b[jb].tinfo[0];
+    const int shift = (int)t->b[jb].tinfo[1];
+    for (int64_t i = wave; i < n_prev; i += nwaves) {
+        const int64_t v = S[i];
+        const int64_t r0 = a.rowptr[v], d = a.rowptr[v + 1] - r0;
+        // the table was emptied for this hop, so the target is offered again with its index
+        if (lane == 0) table_insert_min(tab, mask, shift, (uint32_t)v, (uint32_t)i);
+        int64_t e = indptr[i];
+        for (int64_t k0 = 0; k0 < d; k0 += kWave) {
+            const int64_t k = k0 + lane;
+            const bool take = k < d && general_take(a, batch_lo, v, r0, k);
+            const uint64_t m = __ballot(take);
+            if (take) {
+                const int64_t pos = e + __popcll(m & lt_mask);
+                const int32_t gid = a.col[r0 + k];
+                flat[pos] = gid;
+                table_insert_min(tab, mask, shift, (uint32_t)gid, (uint32_t)(n_prev + pos));
+            }
+            e += __popcll(m);
+        }
+    }
+}
+
 // ---- step 3 ----
 struct NewIn {
     SampleArgs a; const BatchTable* t;
-    __device__ int64_t n(int j) const { return t->b[j].counts[kE + a.h]; }
+    __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[kE + a.h]; }
     __device__ int operator()(int j, int64_t e) const {
         uint32_t val = 0;
         table_find(tab_of(a, j), t->b[j].tinfo[0], (int)t->b[j].tinfo[1], (uint32_t)flat_of(a, j)[e], val);
@@ -205,7 +315,7 @@ struct NewIn {
 struct NewOut {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int64_t e, int ex, int v) const {
-        if (!v) return;
+        if (!v || t->b[j].tinfo[2]) return;
         unsigned long long* tab = tab_of(a, j);
         const uint32_t gid = (uint32_t)flat_of(a, j)[e];
         uint32_t val = 0;
@@ -222,7 +332,14 @@ struct NewFin {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int total) const {
         int64_t* c = t->b[j].counts;
+        if (t->b[j].tinfo[2]) return;
         const int64_t n = c[a.h - 1] + total;
+        if (a.t && n > t->b[j].ncap) {                     // the new ids do not fit the caller's buffer
+            t->b[j].tinfo[2] = 1;
+            atomicOr(a.ovf, 1);
+            c[kE + a.h] = 0;
+            return;
+        }
         c[a.h] = n;
         if (a.h == a.L) { atomicAdd(&a.totals[1], (unsigned long long)n); atomicAdd(&a.totals[0], 1ull); }
     }
@@ -232,6 +349,7 @@ struct NewFin {
 __global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
     const BatchBlock bb = batch_block();
     const int j = bb.j;
+    if (t->b[j].tinfo[2]) return;
     const int64_t e_h = t->b[j].counts[kE + a.h];
     const unsigned long long* tab = tab_of(a, j);
     const int32_t* __restrict__ flat = flat_of(a, j);
@@ -251,7 +369,7 @@ __global__ void __launch_bounds__(kBlock) batch_table_store_kernel(BatchTable sr
     const uint64_t* s = reinterpret_cast<const uint64_t*>(&src);
     uint64_t* d = reinterpret_cast<uint64_t*>(dst);
     for (unsigned i = threadIdx.x; i < sizeof(BatchTable) / sizeof(uint64_t); i += kBlock) d[i] = s[i];
-    if (threadIdx.x == 0) *bad = 0;
+    if (threadIdx.x == 0) { bad[0] = 0; bad[1] = 0; }     // error flag, capacity flag
 }
 static_assert(sizeof(BatchTable) % sizeof(uint64_t) == 0, "copied as 64-bit words");
 
@@ -274,16 +392,23 @@ extern "C" int spp_mfg_bound(int32_t nseeds, const int32_t* fanouts, int32_t L, 
     return SPP_OK;
 }
 
-extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_item* items, int32_t n_items,
-                                    const int32_t* fanouts, int32_t L, uint64_t seed, uint32_t flags) {
+// Both samplers: sizes bounded by `fanouts`, or (d_t given) every entry of a row taken with its
+// own probability and sizes checked against the caller's capacities on the device.
+static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_item* items, int32_t n_items,
+                          const int32_t* fanouts, const float* const* d_t, int32_t L, uint64_t seed, uint32_t flags) {
     using namespace spp;
-    SPP_CHECK(ctx && g && fanouts && (items || n_items == 0), SPP_E_ARG, "spp_sample_mfg: null argument");
+    const bool general = d_t != nullptr;
+    SPP_CHECK(ctx && g && (fanouts || general) && (items || n_items == 0), SPP_E_ARG, "spp_sample_mfg: null argument");
     SPP_CHECK(n_items >= 0 && n_items <= SPP_MAX_SAMPLE_BATCHES, SPP_E_ARG, "spp_sample_mfg: %d minibatches (at most %d)",
               n_items, SPP_MAX_SAMPLE_BATCHES);
+    SPP_CHECK(L >= 1 && L <= SPP_MAX_L, SPP_E_ARG, "spp_sample_mfg: L = %d not in [1, %d]", L, SPP_MAX_L);
+    if (general)
+        for (int h = 0; h < L; ++h)
+            SPP_CHECK(d_t[h] || g->M == 0, SPP_E_ARG, "spp_sample_mfg_general: no transition probabilities for hop %d", h + 1);
     if (n_items == 0) return SPP_OK;
     BatchTable ht;
     memset(&ht, 0, sizeof(ht));
-    int64_t nb[SPP_MAX_L + 1] = {0}, eb[SPP_MAX_L + 1] = {0};       // bounds of the largest minibatch
+    int64_t nb[SPP_MAX_L + 1] = {0}, eb[SPP_MAX_L + 1] = {0};       // bounds (capacities) of the largest minibatch
     int max_seeds = 0;
     for (int j = 0; j < n_items; ++j) {
         const spp_sample_item& it = items[j];
@@ -291,19 +416,34 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
         SPP_CHECK(io, SPP_E_ARG, "spp_sample_mfg: minibatch %d has no output struct", j);
         SPP_CHECK(it.nseeds >= 0 && (it.d_seeds || it.nseeds == 0), SPP_E_ARG, "spp_sample_mfg: seeds of minibatch %d", j);
         SPP_CHECK(it.nseeds <= g->N, SPP_E_ARG, "spp_sample_mfg: more seeds than vertices");
-        int64_t nbj[SPP_MAX_L + 1], ebj[SPP_MAX_L + 1];
-        SPP_TRY(spp_mfg_bound(it.nseeds, fanouts, L, g->N, nbj, ebj));
         SPP_CHECK(io->d_node_ids && io->d_counts, SPP_E_ARG, "spp_sample_mfg: null output buffer");
-        SPP_CHECK(io->n_nodes_cap >= nbj[L] && io->n_nodes_cap >= 1, SPP_E_CAPACITY,
-                  "spp_sample_mfg: d_node_ids holds %lld entries, the bound is %lld", (long long)io->n_nodes_cap, (long long)nbj[L]);
+        int64_t nbj[SPP_MAX_L + 1], ebj[SPP_MAX_L + 1];
+        if (general) {
+            // no fanout bounds the sizes: the capacities are the bounds, enforced on the device
+            SPP_CHECK(io->n_nodes_cap >= it.nseeds && io->n_nodes_cap >= 1, SPP_E_CAPACITY,
+                      "spp_sample_mfg_general: d_node_ids holds %lld entries, the minibatch has %d seeds",
+                      (long long)io->n_nodes_cap, it.nseeds);
+            ebj[0] = 0;
+            for (int h = 0; h <= L; ++h) nbj[h] = io->n_nodes_cap;
+            for (int h = 1; h <= L; ++h) {
+                SPP_CHECK(io->n_edges_cap[h - 1] >= 0, SPP_E_ARG, "spp_sample_mfg_general: negative capacity of hop %d", h);
+                ebj[h] = io->n_edges_cap[h - 1];
+            }
+        } else {
+            SPP_TRY(spp_mfg_bound(it.nseeds, fanouts, L, g->N, nbj, ebj));
+            SPP_CHECK(io->n_nodes_cap >= nbj[L] && io->n_nodes_cap >= 1, SPP_E_CAPACITY,
+                      "spp_sample_mfg: d_node_ids holds %lld entries, the bound is %lld", (long long)io->n_nodes_cap, (long long)nbj[L]);
+        }
+        ht.b[j].ncap = io->n_nodes_cap;
         for (int h = 1; h <= L; ++h) {
             SPP_CHECK(io->d_indptr[h - 1] && io->d_src[h - 1], SPP_E_ARG, "spp_sample_mfg: null buffer of hop %d", h);
             SPP_CHECK(io->n_edges_cap[h - 1] >= ebj[h], SPP_E_CAPACITY,
                       "spp_sample_mfg: d_src of hop %d holds %lld entries, the bound is %lld", h,
                       (long long)io->n_edges_cap[h - 1], (long long)ebj[h]);
-            SPP_CHECK(ebj[h] < 0x7FFFFFFFll && nbj[h] + ebj[h] < 0xFFFFFFFFll, SPP_E_ARG, "spp_sample_mfg: hop %d exceeds 32-bit offsets", h);
+            SPP_CHECK(ebj[h] < 0x3FFFFFFFll && nbj[h] + ebj[h] < 0x3FFFFFFFll, SPP_E_ARG, "spp_sample_mfg: hop %d exceeds 30-bit sizes", h);
             ht.b[j].indptr[h - 1] = io->d_indptr[h - 1];
             ht.b[j].src[h - 1] = io->d_src[h - 1];
+            ht.b[j].ecap[h - 1] = io->n_edges_cap[h - 1];
         }
         for (int h = 0; h <= L; ++h) { if (nbj[h] > nb[h]) nb[h] = nbj[h]; if (ebj[h] > eb[h]) eb[h] = ebj[h]; }
         ht.b[j].seeds = it.d_seeds; ht.b[j].nseeds = it.nseeds; ht.b[j].batch_lo = (uint32_t)it.batch_index;
@@ -315,14 +455,22 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
     SPP_HIP(hipSetDevice(ctx->device));
     hipStream_t st = ctx->stream;
 
-    const uint32_t cap = next_pow2((uint64_t)(2 * nb[L] > 1024 ? 2 * nb[L] : 1024));
+    // table region per minibatch: twice the most keys a hop can hold (all ids so far plus the hop's entries)
+    const int64_t max_keys = general ? nb[L] + emax : nb[L];
+    const uint32_t cap = next_pow2((uint64_t)(2 * max_keys > 1024 ? 2 * max_keys : 1024));
     // workgroups per minibatch in the scans and the table clear: the whole call gets about 4 per CU
     const int per_batch = (ctx->num_cu * 4 + n_items - 1) / n_items;
     const int scan_grid = ((per_batch < 32 ? 32 : per_batch) + 7) & ~7;     // multiples of 8: see batch_block()
     SPP_TRY(ctx->table.reserve((size_t)cap * sizeof(uint64_t) * n_items));
     SPP_TRY(ctx->flat.reserve((size_t)emax * sizeof(int32_t) * n_items));
-    SPP_TRY(ctx->slots.reserve((size_t)2 * sizeof(uint32_t) * n_items));
-    for (int j = 0; j < n_items; ++j) ht.b[j].tinfo = ctx->slots.as<uint32_t>() + 2 * j;
+    SPP_TRY(ctx->slots.reserve((size_t)(4 * sizeof(uint32_t) + sizeof(unsigned long long)) * kMaxBatches + 64 +
+                               (general ? (size_t)nb[L] * sizeof(int32_t) * n_items : 0)));
+    unsigned long long* taken = ctx->slots.as<unsigned long long>();
+    uint32_t* tinfo = reinterpret_cast<uint32_t*>(taken + kMaxBatches);
+    for (int j = 0; j < n_items; ++j) {
+        ht.b[j].tinfo = tinfo + 4 * j;
+        ht.b[j].taken = general ? taken + j : nullptr;
+    }
     SPP_TRY(ctx->partials.reserve((size_t)scan_grid * n_items * sizeof(int) + 64 + sizeof(BatchTable) + 256));
     int* partial = ctx->partials.as<int>();
     int* d_bad = partial + (size_t)scan_grid * n_items;
@@ -335,8 +483,10 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
     a.rowptr = g->rowptr; a.col = g->col; a.N = g->N;
     a.tab = ctx->table.as<unsigned long long>(); a.cap = cap;
     a.flat = ctx->flat.as<int32_t>(); a.flat_stride = emax;
-    a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.bad = d_bad;
+    a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.bad = d_bad; a.ovf = d_bad + 1;
     a.L = L; a.h = 0; a.f = 0; a.seed = seed;
+    a.t = nullptr;
+    a.cnt = reinterpret_cast<int32_t*>(tinfo + 4 * kMaxBatches + 16); a.cnt_stride = nb[L];
 
     auto capped = [&](int64_t need, int64_t lim) {
         const int64_t g = need < 1 ? 1 : (need < lim ? need : lim);
@@ -348,19 +498,25 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
         batch_table_store_kernel<<<1, kBlock, 0, st>>>(ht, dt, d_bad);
         seeds_kernel<<<dim3(capped((max_seeds + kBlock - 1) / kBlock, 1 << 20), n_items), kBlock, 0, st>>>(a, dt);
         for (int h = 1; h <= L; ++h) {
-            a.h = h; a.f = fanouts[h - 1];
+            a.h = h; a.f = general ? 0 : fanouts[h - 1]; a.t = general ? d_t[h - 1] : nullptr;
+            const dim3 wgrid(capped((nb[h - 1] * kWave + kBlock - 1) / kBlock, share), n_items);   // a wavefront per target
+            if (general) general_count_kernel<<<wgrid, kBlock, 0, st>>>(a, dt);
             grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial);
             {   // the hop's table holds at most 2 (n_bound[h-1] + e_bound[h]) keys' worth of slots
                 const int64_t slots_bound = 4 * (nb[h - 1] + eb[h]) < (int64_t)cap ? 4 * (nb[h - 1] + eb[h]) : (int64_t)cap;
                 table_clear_kernel<<<dim3(capped((slots_bound + kBlock * 8 - 1) / (kBlock * 8), share), n_items), kBlock, 0, st>>>(a, dt);
             }
-            const int G = a.f <= 8 ? 8 : a.f <= 16 ? 16 : a.f <= 32 ? 32 : 64;
-            const dim3 sgrid(capped((nb[h - 1] * G + kBlock - 1) / kBlock, share), n_items);
-            switch (G) {
-                case 8:  sample_kernel<8><<<sgrid, kBlock, 0, st>>>(a, dt); break;
-                case 16: sample_kernel<16><<<sgrid, kBlock, 0, st>>>(a, dt); break;
-                case 32: sample_kernel<32><<<sgrid, kBlock, 0, st>>>(a, dt); break;
-                default: sample_kernel<64><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+            if (general) {
+                general_sample_kernel<<<wgrid, kBlock, 0, st>>>(a, dt);
+            } else {
+                const int G = a.f <= 8 ? 8 : a.f <= 16 ? 16 : a.f <= 32 ? 32 : 64;
+                const dim3 sgrid(capped((nb[h - 1] * G + kBlock - 1) / kBlock, share), n_items);
+                switch (G) {
+                    case 8:  sample_kernel<8><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+                    case 16: sample_kernel<16><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+                    case 32: sample_kernel<32><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+                    default: sample_kernel<64><<<sgrid, kBlock, 0, st>>>(a, dt); break;
+                }
             }
             grid_scan_batched(st, scan_grid, n_items, NewIn{a, dt}, NewOut{a, dt}, NewFin{a, dt}, partial);
             relabel_kernel<<<dim3(capped((eb[h] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
@@ -368,19 +524,35 @@ extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_
     }
     SPP_HIP(hipGetLastError());
     if (flags & SPP_SYNC) {
-        int64_t* hp = ctx->h_pinned + 64;            // 16 x 18 counts, then the flag
+        int64_t* hp = ctx->h_pinned + 64;            // 16 x 18 counts, then the flags
         for (int j = 0; j < n_items; ++j)
             SPP_HIP(hipMemcpyAsync(hp + j * 2 * kE, items[j].io->d_counts, 2 * kE * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-        SPP_HIP(hipMemcpyAsync(hp + kMaxBatches * 2 * kE, d_bad, sizeof(int), hipMemcpyDeviceToHost, st));
+        SPP_HIP(hipMemcpyAsync(hp + kMaxBatches * 2 * kE, d_bad, 2 * sizeof(int), hipMemcpyDeviceToHost, st));
         SPP_HIP(hipStreamSynchronize(st));
         for (int j = 0; j < n_items; ++j)
             for (int k = 0; k <= SPP_MAX_L; ++k) {
                 items[j].io->n[k] = hp[j * 2 * kE + k];
                 items[j].io->e[k] = hp[j * 2 * kE + kE + k];
             }
-        SPP_CHECK(*reinterpret_cast<int*>(hp + kMaxBatches * 2 * kE) == 0, SPP_E_ARG, "spp_sample_mfg: a seed lies outside [0, N)");
+        const int* fl = reinterpret_cast<const int*>(hp + kMaxBatches * 2 * kE);
+        SPP_CHECK((fl[0] & 1) == 0, SPP_E_ARG, "spp_sample_mfg: a seed lies outside [0, N)");
+        SPP_CHECK((fl[0] & 2) == 0, SPP_E_ARG, "spp_sample_mfg_general: a transition probability lies outside [0, 1]; it was taken as 0");
+        SPP_CHECK(fl[1] == 0, SPP_E_CAPACITY, "spp_sample_mfg_general: a minibatch exceeded the capacity of its buffers and was abandoned");
     }
     return SPP_OK;
+}
+
+extern "C" int spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_item* items, int32_t n_items,
+                                    const int32_t* fanouts, int32_t L, uint64_t seed, uint32_t flags) {
+    SPP_CHECK(fanouts, SPP_E_ARG, "spp_sample_mfg: null argument");
+    return sample_batches(ctx, g, items, n_items, fanouts, nullptr, L, seed, flags);
+}
+
+extern "C" int spp_sample_mfg_general(spp_ctx* ctx, const spp_graph* g, const float* const* d_t,
+                                      const spp_sample_item* items, int32_t n_items, int32_t L, uint64_t seed,
+                                      uint32_t flags) {
+    SPP_CHECK(d_t, SPP_E_ARG, "spp_sample_mfg_general: null argument");
+    return sample_batches(ctx, g, items, n_items, nullptr, d_t, L, seed, flags);
 }
 
 extern "C" int spp_sample_mfg(spp_ctx* ctx, const spp_graph* g, const int32_t* d_seeds, int32_t nseeds,

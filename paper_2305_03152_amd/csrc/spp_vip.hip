@@ -244,7 +244,119 @@ __global__ void vip_init_kernel(const int32_t* __restrict__ T, int64_t nT, int64
     if (include_hop0) tot[v] = log1p(-p0);
 }
 
+// ---- Proposition 1 with arbitrary initial and transition probabilities (Sec. 3.1) -------------
+// Push form over the CSR, whose edge order the transition probabilities share: every vertex with
+// p^[h-1](v) > 0 adds log1p(-t_h(e) p^[h-1](v)) to the fp64 sum of every member of its row.
+
+__device__ __forceinline__ float unit_or_flag(float x, int* bad) {
+    if (x >= 0.0f && x <= 1.0f) return x;
+    *bad = 1;                                     // also for NaN
+    return 0.0f;
+}
+
+__global__ void __launch_bounds__(kBlock) vipg_init_kernel(const float* __restrict__ p0, int64_t N,
+                                                           float* __restrict__ pcur, double* __restrict__ tot,
+                                                           int include_hop0, int* __restrict__ bad) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < N; v += stride) {
+        const float p = unit_or_flag(p0[v], bad);
+        pcur[v] = p;
+        if (include_hop0) tot[v] = log1p(-(double)p);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) vipg_push_kernel(const int32_t* __restrict__ list,
+                                                           const unsigned long long* __restrict__ nf_ptr,
+                                                           const float* __restrict__ pcur,
+                                                           const int64_t* __restrict__ rowptr,
+                                                           const int32_t* __restrict__ col,
+                                                           const float* __restrict__ t, double* __restrict__ acc,
+                                                           int* __restrict__ bad) {
+    const int lane = lane_id();
+    const int64_t nf = (int64_t)*nf_ptr;
+    const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+    for (int64_t i = wave; i < nf; i += nwaves) {
+        const int64_t v = list[i];
+        const double pv = (double)pcur[v];
+        const int64_t b = rowptr[v], e = rowptr[v + 1];
+        for (int64_t k = b + lane; k < e; k += kWave) {
+            const double x = (double)unit_or_flag(t[k], bad) * pv;
+            if (x > 0.0) unsafeAtomicAdd(&acc[col[k]], log1p(-x));
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) vipg_finish_kernel(const double* __restrict__ acc, double* __restrict__ tot,
+                                                             int first, int last, float* __restrict__ p_hop,
+                                                             float* __restrict__ p_total, float* __restrict__ pnext,
+                                                             int64_t N) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) {
+        const double S = acc[u];
+        const double ph = -expm1(S);
+        if (p_hop) p_hop[u] = (float)ph;
+        const double T = first ? S : tot[u] + S;
+        if (last) p_total[u] = (float)(-expm1(T));
+        else { tot[u] = T; pnext[u] = (float)ph; }
+    }
+}
+
 }  // namespace spp
+
+extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const float* d_p0,
+                                         const float* const* d_t, int32_t L, float* d_p_total, float* d_p_hop,
+                                         uint32_t flags) {
+    using namespace spp;
+    SPP_CHECK(ctx && g && d_p0 && d_t && d_p_total, SPP_E_ARG, "spp_vip_propagate_general: null argument");
+    SPP_CHECK(L >= 1 && L <= SPP_MAX_L, SPP_E_ARG, "spp_vip_propagate_general: L = %d not in [1, %d]", L, SPP_MAX_L);
+    for (int h = 0; h < L; ++h)
+        SPP_CHECK(d_t[h] || g->M == 0, SPP_E_ARG, "spp_vip_propagate_general: no transition probabilities for hop %d", h + 1);
+    SPP_HIP(hipSetDevice(ctx->device));
+    hipStream_t st = ctx->stream;
+    const int64_t N = g->N;
+    SPP_TRY(ctx->y0.reserve((size_t)N * sizeof(float)));
+    SPP_TRY(ctx->y1.reserve((size_t)N * sizeof(float)));
+    SPP_TRY(ctx->tot.reserve((size_t)N * sizeof(double) + sizeof(int)));
+    SPP_TRY(ctx->acc.reserve((size_t)N * sizeof(double)));
+    SPP_TRY(ctx->frontier.reserve((size_t)(N + 2) * sizeof(int32_t) + 4 * sizeof(unsigned long long)));
+    int32_t* flist = ctx->frontier.as<int32_t>();
+    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (N + (N & 1)));
+    float* pcur = ctx->y0.as<float>();
+    float* pnext = ctx->y1.as<float>();
+    double* tot = ctx->tot.as<double>();
+    double* acc = ctx->acc.as<double>();
+    int* d_bad = reinterpret_cast<int*>(tot + N);
+    const int include0 = (flags & SPP_VIP_INCLUDE_HOP0) ? 1 : 0;
+    const int fill_grid = ctx->num_cu * 8;
+    {
+        ScopedTimer tt(ctx, SPP_T_VIP_TOTAL, st);
+        fill_f32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<float*>(d_bad), 1, 0.f);
+        vipg_init_kernel<<<fill_grid, kBlock, 0, st>>>(d_p0, N, pcur, tot, include0, d_bad);
+        for (int h = 1; h <= L; ++h) {
+            ScopedTimer th(ctx, SPP_T_VIP_HOP_FIRST + h - 1, st);
+            fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount), 3, 0.0);
+            fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
+            vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(pcur, N, flist, fcount + 2);
+            vipg_push_kernel<<<ctx->num_cu * 32, kBlock, 0, st>>>(flist, fcount + 2, pcur, g->rowptr, g->col,
+                                                                 d_t[h - 1], acc, d_bad);
+            vipg_finish_kernel<<<fill_grid, kBlock, 0, st>>>(acc, tot, (h == 1 && !include0) ? 1 : 0, h == L ? 1 : 0,
+                                                             d_p_hop ? d_p_hop + (int64_t)(h - 1) * N : nullptr,
+                                                             d_p_total, pnext, N);
+            ctx->vip_pushed[h - 1] = 1;
+            ctx->vip_frontier_edges[h - 1] = -1;
+            float* tmp = pcur; pcur = pnext; pnext = tmp;
+        }
+    }
+    SPP_HIP(hipGetLastError());
+    if (flags & SPP_SYNC) {
+        int bad = 0;
+        SPP_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(int), hipMemcpyDeviceToHost, st));
+        SPP_HIP(hipStreamSynchronize(st));
+        SPP_CHECK(bad == 0, SPP_E_ARG, "spp_vip_propagate_general: a probability lies outside [0, 1]; it was taken as 0");
+    }
+    return SPP_OK;
+}
 
 extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t* d_T, int64_t nT,
                                  int32_t B, const int32_t* fanouts, int32_t L,

@@ -477,6 +477,97 @@ def test_access_counts_and_empirical_policies_tiny(spp, ctx, tiny_case):
     assert cnt.sum().item() == 2 and cnt[1].item() == 1 and cnt[2].item() == 1
 
 
+def _uniform_t(rp, f):
+    d = np.diff(rp)
+    return np.repeat(np.minimum(1.0, f / np.maximum(d, 1)).astype(np.float32), d)
+
+
+def _general_caps(refs, L, slack=1.25):
+    ncap = int(max(r.n[L] for r in refs) * slack) + 8
+    ecaps = [int(max(r.e[h + 1] for r in refs) * slack) + 8 for h in range(L)]
+    return ncap, ecaps
+
+
+def test_general_probabilities_tiny(spp, ctx, tiny_case):
+    """Proposition 1 with arbitrary initial and transition probabilities, and the sampler that takes
+    every entry of a row with its own probability (Sec. 3.1, paragraph after Prop. 1)."""
+    c = tiny_case
+    cfg = c.cfg
+    rng = np.random.default_rng(17)
+    M = c.col.size
+    t_np = [(rng.random(M) * 0.6).astype(np.float32), (rng.random(M) ** 3).astype(np.float32),
+            np.where(rng.random(M) < 0.1, 1.0, rng.random(M) * 0.2).astype(np.float32)]
+    t_d = [torch.from_numpy(a).cuda() for a in t_np]
+    p0 = np.where(rng.random(cfg.N) < 0.05, rng.random(cfg.N), 0.0).astype(np.float32)
+    p0[:3] = [1.0, 0.0, 0.5]
+    for L, hop0 in ((3, False), (2, True), (1, False)):
+        _say("general vip L", L, "hop0", hop0)
+        p, ph = spp.vip_propagate_general(ctx, c.G, torch.from_numpy(p0).cuda(), t_d[:L], L, per_hop=True, include_hop0=hop0)
+        rt, rh = oracle.vip_general(c.rp, c.col, p0, t_np[:L], L, include_hop0=hop0)
+        _check_vip(p, rt)
+        for h in range(L):
+            _check_vip(ph[h], rh[h])
+    # one tensor for every hop; the uniform instantiation agrees with the uniform entry point
+    _say("general vip, uniform instantiation")
+    p0u = np.zeros(cfg.N, np.float32)
+    p0u[c.Tk] = min(1.0, cfg.B / c.Tk.size)
+    tu = [_uniform_t(c.rp, f) for f in cfg.fanouts]
+    pg = spp.vip_propagate_general(ctx, c.G, torch.from_numpy(p0u).cuda(), [torch.from_numpy(a).cuda() for a in tu], cfg.L)
+    _check_vip(pg, oracle.vip(c.rp, c.col, c.Tk, cfg.B, cfg.fanouts)[0])
+    one = spp.vip_propagate_general(ctx, c.G, torch.from_numpy(p0).cuda(), t_d[0], 2)
+    _check_vip(one, oracle.vip_general(c.rp, c.col, p0, t_np[0], 2)[0])
+    # a probability outside [0, 1] is reported and taken as 0
+    bad_t = t_np[0].copy()
+    bad_t[5] = 1.5
+    bad_t[9] = np.nan
+    with pytest.raises(spp.SppError):
+        spp.vip_propagate_general(ctx, c.G, torch.from_numpy(p0).cuda(), torch.from_numpy(bad_t).cuda(), 1)
+    bad_p = p0.copy()
+    bad_p[7] = -0.5
+    with pytest.raises(spp.SppError):
+        spp.vip_propagate_general(ctx, c.G, torch.from_numpy(bad_p).cuda(), t_d[0], 1)
+
+    # ---- the sampler
+    batches = S.epoch_batches(cfg, torch.from_numpy(c.Tk), 0)
+    seeds_list = [b.numpy() for b in batches[:2]] + [c.Tk[:7], np.array([], dtype=np.int32)]
+    for L in (3, 1):
+        refs = [oracle.sample_mfg_general(c.rp, c.col, t_np[:L], s_, L, 99, 40 + j) for j, s_ in enumerate(seeds_list)]
+        ncap, ecaps = _general_caps(refs, L)
+        _say("general sampler L", L, "caps", ncap, ecaps)
+        bufs = [spp.MFGBuffers("cuda", 0, (), cfg.N, capacities=(ncap, ecaps)) for _ in seeds_list]
+        items = [(torch.from_numpy(s_).cuda(), 40 + j, bufs[j]) for j, s_ in enumerate(seeds_list)]
+        spp.sample_mfg_general(ctx, c.G, t_d[:L], items, L, 99)
+        for b, ref in zip(bufs, refs):
+            _check_mfg(b, ref, L)
+    # t = 1 everywhere: full expansion; t = 0: nothing beyond the seeds
+    ones = torch.ones(M, dtype=torch.float32, device="cuda")
+    ref = oracle.sample_mfg_general(c.rp, c.col, np.ones(M, np.float32), c.Tk[:5], 2, 1, 0)
+    b = spp.MFGBuffers("cuda", 0, (), cfg.N, capacities=(ref.n[2], [ref.e[1], ref.e[2]]))      # exact capacities suffice
+    spp.sample_mfg_general(ctx, c.G, ones, [(torch.from_numpy(c.Tk[:5]).cuda(), 0, b)], 2, 1)
+    _check_mfg(b, ref, 2)
+    spp.sample_mfg_general(ctx, c.G, torch.zeros_like(ones), [(torch.from_numpy(c.Tk[:5]).cuda(), 0, b)], 2, 1)
+    assert b.n == [5, 5, 5] and b.e == [0, 0, 0]
+    # capacities one short, for the edges of hop 2 and for the ids: reported, nothing written out of bounds
+    # (the buffers are followed by a guard that must stay untouched), and the next call is not affected
+    for ncap, ecaps in ((ref.n[2], [ref.e[1], ref.e[2] - 1]), (ref.n[2] - 1, [ref.e[1], ref.e[2]])):
+        small = spp.MFGBuffers("cuda", 0, (), cfg.N, capacities=(ncap, ecaps))
+        ok = spp.MFGBuffers("cuda", 0, (), cfg.N, capacities=(ref.n[2] + 3, [ref.e[1] + 3, ref.e[2] + 3]))
+        ok.node_ids.fill_(-7)
+        with pytest.raises(spp.SppError):
+            spp.sample_mfg_general(ctx, c.G, ones, [(torch.from_numpy(c.Tk[:5]).cuda(), 0, small),
+                                                    (torch.from_numpy(c.Tk[:5]).cuda(), 0, ok)], 2, 1)
+        # the minibatch that fitted is complete and correct
+        ctx.sync()
+        cnt = ok.counts.cpu().numpy()
+        assert cnt[2] == ref.n[2] and np.array_equal(ok.node_ids[:ref.n[2]].cpu().numpy(), ref.node_ids)
+        assert torch.all(ok.node_ids[ref.n[2]:] == -7)
+    spp.sample_mfg_general(ctx, c.G, ones, [(torch.from_numpy(c.Tk[:5]).cuda(), 0, b)], 2, 1)
+    _check_mfg(b, ref, 2)
+    # the fanout sampler after the general one on the same context (shared workspaces)
+    m = spp.sample_mfg(ctx, c.G, torch.from_numpy(seeds_list[0]).cuda(), cfg.fanouts, cfg.seed_sampler, 0)
+    _check_mfg(m, oracle.sample_mfg(c.rp, c.col, seeds_list[0], cfg.fanouts, cfg.seed_sampler, 0), cfg.L)
+
+
 # ----------------------------------------------------------------------------------------------
 # scaled copies of the other configs: several tiles, ragged tails, hubs, 16-bit rows
 # ----------------------------------------------------------------------------------------------
@@ -525,6 +616,23 @@ def test_scaled_config_end_to_end(spp, ctx, name, cfg):
         want, _, counts = oracle.gather(cfg.N, c.lo, c.hi, local, cache_rows, ids_ref, remote, ref.node_ids)
         assert np.array_equal(_bits(_np(out)), _bits(want))
         assert (stats["n_local"], stats["n_cache_hit"], stats["n_miss"]) == counts
+    # general probabilities on the same graph: hub rows span many 64-entry chunks of the sampler's ballots
+    _say("general probabilities")
+    rng = np.random.default_rng(5)
+    t_np = (rng.random(c.col.size) * np.repeat(np.minimum(1.0, 6.0 / np.maximum(np.diff(c.rp), 1)), np.diff(c.rp))).astype(np.float32)
+    t_d = torch.from_numpy(t_np).cuda()
+    p0 = np.zeros(cfg.N, np.float32)
+    p0[c.Tk] = min(1.0, cfg.B / c.Tk.size)
+    pg, pgh = spp.vip_propagate_general(ctx, c.G, torch.from_numpy(p0).cuda(), t_d, 2, per_hop=True)
+    rt, rh = oracle.vip_general(c.rp, c.col, p0, t_np, 2)
+    _check_vip(pg, rt)
+    _check_vip(pgh[1], rh[1])
+    grefs = [oracle.sample_mfg_general(c.rp, c.col, t_np, s_.numpy(), 2, 3, bi) for bi, s_ in enumerate(batches[:2])]
+    ncap, ecaps = _general_caps(grefs, 2)
+    gb = [spp.MFGBuffers("cuda", 0, (), cfg.N, capacities=(ncap, ecaps)) for _ in grefs]
+    spp.sample_mfg_general(ctx, c.G, t_d, [(s_.cuda(), bi, gb[bi]) for bi, s_ in enumerate(batches[:2])], 2, 3)
+    for b_, r_ in zip(gb, grefs):
+        _check_mfg(b_, r_, 2)
     # the same batches with the local rows split between device and host (10 % on the device)
     _say("local store")
     local_host = c.local_d.cpu().pin_memory()
