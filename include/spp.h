@@ -181,9 +181,12 @@ int  spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
  *     stats (host, may be NULL) is filled when SPP_SYNC is set; otherwise read it later with
  *     spp_gather_last_stats after synchronising. */
 /* n_local counts every id of the owned range; n_local_host of them were read from host memory
- * (only with a split local store, see spp_build_local_store).  miss_bytes = bytes read from host
- * memory = (n_miss + n_local_host) * row size. */
-typedef struct { int64_t n_local, n_cache_hit, n_miss, miss_bytes, n_local_host; } spp_gather_stats;
+ * (only with a split local store, see spp_build_local_store).  n_miss counts every row that is
+ * neither local nor cached; in a call with several lists a remote vertex that several rows miss
+ * is read from the remote store once and copied to the other rows on the device: n_miss_shared
+ * of the n_miss rows were served that way.  miss_bytes = bytes read from host memory
+ * = (n_miss - n_miss_shared + n_local_host) * row size. */
+typedef struct { int64_t n_local, n_cache_hit, n_miss, miss_bytes, n_local_host, n_miss_shared; } spp_gather_stats;
 int  spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
                          int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D, int32_t elem_bytes,
                          const int32_t* d_node_ids, int64_t n, const int64_t* d_n, void* d_out,
@@ -298,9 +301,11 @@ int  spp_ctx_times(spp_ctx* ctx, float* sum_ms /* [SPP_T_COUNT] */, int64_t* cou
  * that a loop of asynchronous calls can be accounted for without a host round trip per batch:
  *   out[0] minibatches sampled, out[1] sum of |S_L|, out[2] sum of sampled edges over all hops,
  *   out[3] gather calls, out[4] rows from the local shard, out[5] rows from the cache,
- *   out[6] rows missed (served from the remote store), out[7] local rows read from host memory.
+ *   out[6] rows missed (neither local nor cached), out[7] local rows read from host memory,
+ *   out[8] missed rows served by a copy of another row of the same call (n_miss_shared),
+ *   out[9..15] unused.
  * Waits for the context's streams. */
-int  spp_ctx_totals(spp_ctx* ctx, int64_t* out /* [8] */, int reset);
+int  spp_ctx_totals(spp_ctx* ctx, int64_t* out /* [16] */, int reset);
 
 #ifdef __cplusplus
 }

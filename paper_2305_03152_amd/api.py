@@ -66,7 +66,7 @@ class _IdList(C.Structure):
 
 class _GatherStats(C.Structure):
     _fields_ = [("n_local", C.c_int64), ("n_cache_hit", C.c_int64), ("n_miss", C.c_int64),
-                ("miss_bytes", C.c_int64), ("n_local_host", C.c_int64)]
+                ("miss_bytes", C.c_int64), ("n_local_host", C.c_int64), ("n_miss_shared", C.c_int64)]
 
 
 _lib = None
@@ -187,9 +187,10 @@ class Context:
     def totals(self, reset: bool = False):
         """Running sums since the last reset: batches, |S_L|, edges, gather calls, local / cache / missed rows,
         local rows read from host memory (split local store)."""
-        buf = (C.c_int64 * 8)()
+        buf = (C.c_int64 * 16)()
         _check(load_library().spp_ctx_totals(self._h, buf, int(reset)))
-        keys = ("batches", "n_nodes", "n_edges", "gather_calls", "n_local", "n_cache_hit", "n_miss", "n_local_host")
+        keys = ("batches", "n_nodes", "n_edges", "gather_calls", "n_local", "n_cache_hit", "n_miss", "n_local_host",
+                "n_miss_shared")
         return dict(zip(keys, list(buf)))
 
     def close(self):
@@ -404,7 +405,7 @@ def access_count(ctx: Context, lists, N: int, count: Optional[torch.Tensor] = No
 
 def _stats_dict(st):
     return dict(n_local=st.n_local, n_cache_hit=st.n_cache_hit, n_miss=st.n_miss, miss_bytes=st.miss_bytes,
-                n_local_host=st.n_local_host)
+                n_local_host=st.n_local_host, n_miss_shared=st.n_miss_shared)
 
 
 def mfg_bound(nseeds: int, fanouts: Sequence[int], N: int):

@@ -37,8 +37,8 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 512 * sizeof(int64_t), hipHostMallocDefault);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->totals), 8 * sizeof(int64_t));
-    if (e == hipSuccess) e = hipMemset(c->totals, 0, 8 * sizeof(int64_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->totals), 16 * sizeof(int64_t));
+    if (e == hipSuccess) e = hipMemset(c->totals, 0, 16 * sizeof(int64_t));
     if (e != hipSuccess) {
         spp::set_error("spp_ctx_create: %s", hipGetErrorString(e));
         spp_ctx_destroy(c);
@@ -61,7 +61,8 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
     if (c->totals) (void)hipFree(c->totals);
     c->table.release(); c->flat.release(); c->slots.release(); c->partials.release();
-    c->srcdesc.release(); c->misslist.release(); c->gcount.release();
+    c->gtable.release();
+    for (int k = 0; k < 2; ++k) { c->srcdesc[k].release(); c->misslist[k].release(); c->gcount[k].release(); }
     c->y0.release(); c->y1.release(); c->tot.release(); c->acc.release(); c->frontier.release();
     delete c;
 }
@@ -105,8 +106,8 @@ extern "C" int spp_ctx_times(spp_ctx* c, float* sum_ms, int64_t* count) {
 extern "C" int spp_ctx_totals(spp_ctx* c, int64_t* out, int reset) {
     SPP_CHECK(c != nullptr && out != nullptr, SPP_E_ARG, "spp_ctx_totals: null argument");
     SPP_TRY(spp_ctx_sync(c));
-    SPP_HIP(hipMemcpy(out, c->totals, 8 * sizeof(int64_t), hipMemcpyDeviceToHost));
-    if (reset) SPP_HIP(hipMemset(c->totals, 0, 8 * sizeof(int64_t)));
+    SPP_HIP(hipMemcpy(out, c->totals, 16 * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (reset) SPP_HIP(hipMemset(c->totals, 0, 16 * sizeof(int64_t)));
     return SPP_OK;
 }
 

@@ -77,11 +77,15 @@ struct spp_ctx {
     spp::DevBuf slots;                  // per minibatch: mask and shift of the id table of the current hop
     spp::DevBuf partials;               // scan partial sums
     // gather workspaces
-    spp::DevBuf srcdesc;                // int64 per row: where the row comes from
-    spp::DevBuf misslist;               // int32 positions of the rows that miss
-    spp::DevBuf gcount;                 // device counters of the gather (int64[8])
+    // two sets, used alternately: the classification of a call may run while the miss copy of the
+    // call before still reads its own set
+    spp::DevBuf srcdesc[2];             // int64 per row: where the row comes from
+    spp::DevBuf misslist[2];            // int32 positions of the rows that miss, then of the rows that hit
+    spp::DevBuf gcount[2];              // device counters of the gather (int64[8]) and the list layout
+    int         gslot = 0;              // set used by the last gather
+    spp::DevBuf gtable;                 // vertices missed by the current gather call (id -> first row)
     int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
-    int64_t*    totals = nullptr;       // device int64[8], running sums since the last reset (see spp_ctx_totals)
+    int64_t*    totals = nullptr;       // device int64[16], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces
     spp::DevBuf y0, y1, tot, acc, frontier;
     int         tile_lds_set = 0;       // dynamic LDS bytes the dense-hop kernel has been allowed on this device

@@ -279,6 +279,33 @@ __device__ __forceinline__ uint32_t table_insert_min(unsigned long long* tab, ui
     }
 }
 
+// Claims `key` for `value` if no entry holds the key yet.  Returns true to the one thread that
+// placed the entry; every other thread asking for the same key gets false and the claimer's value
+// in `existing` (an entry is never changed once placed, so a stale view is harmless as above).
+__device__ __forceinline__ bool table_claim(unsigned long long* tab, uint32_t mask, int shift, uint32_t key,
+                                            uint32_t value, uint32_t& existing) {
+    const unsigned long long want = ((unsigned long long)key << 32) | value;
+    const uint32_t bmask = mask >> 3;
+    const uint32_t h0 = table_hash(key, shift);
+    uint32_t b = h0 >> 3;
+    for (;;) {
+        unsigned long long s[kBucketSlots];
+        table_load_bucket(tab, b, s);
+#pragma unroll
+        for (int k = 0; k < kBucketSlots; ++k) {
+            const uint32_t idx = (h0 + k) & 7u;
+            unsigned long long cur = table_pick(s, idx);
+            if ((uint32_t)(cur >> 32) == 0xFFFFFFFFu) {
+                const unsigned long long old = atomicCAS(&tab[b * kBucketSlots + idx], (unsigned long long)kEmpty, want);
+                if (old == kEmpty) return true;
+                cur = old;
+            }
+            if ((uint32_t)(cur >> 32) == key) { existing = (uint32_t)cur; return false; }
+        }
+        b = (b + 1) & bmask;
+    }
+}
+
 // Returns the slot index of `key`, or -1; `value` receives the stored value.
 __device__ __forceinline__ int64_t table_find(const unsigned long long* tab, uint32_t mask, int shift,
                                               uint32_t key, uint32_t& value) {

@@ -7,6 +7,11 @@
 //                            output walked flat so that stores are dense
 //   miss copy (side stream)  rows read straight from pinned host memory over PCIe, started as
 //                            soon as the classification is done and joined before the call ends
+// A vertex that several rows of one call miss (several minibatches of a pipeline sampling the same
+// remote vertex) is fetched once: after the classification a pass over the miss list claims every
+// missed vertex in a table that lives for the call (sized for the misses, so a few MB); the row
+// that wins the claim stays in the miss list, the others are struck from it and copied from the
+// winner's output row after the miss copy.
 // With a split local store (Sec. 3.2 on host-to-device transfers, Sec. 4.1) a local id is looked up
 // in the store's rank array: below the limit it is a hit on the device rows (stored in rank order),
 // else it joins the miss list and is read from the host-resident local rows.
@@ -33,7 +38,7 @@ struct ClassifyArgs {
     int32_t*       misslist;           // virtual rows that miss
     int32_t*       hitlist;            // virtual rows served from the shard or the cache
     unsigned long long* counters;      // [0] local, [1] cache hit, [2] rows in misslist, [3] bad id, [4] rows in hitlist,
-                                       // [5] local rows read from the host (part of [0] and of [2])
+                                       // [5] local rows read from the host (part of [0] and of [2]), [6] rows in duplist
     unsigned long long* totals;        // context-wide running sums: [3] calls, [4] local, [5] cache hit,
                                        // [6] remote miss, [7] local rows read from the host
 };
@@ -58,6 +63,60 @@ __global__ void gather_prologue_kernel(PrologueArgs p, unsigned long long* count
             o = (o + c + kListAlign - 1) / kListAlign * kListAlign;
         }
         off[p.n_lists] = o;
+    }
+}
+
+// Table of the call's missed vertices: the smallest power of two >= twice the miss list (>= 1024
+// slots, at most max_slots, which the host sized for the bound), emptied.
+__global__ void __launch_bounds__(kBlock) gather_table_clear_kernel(unsigned long long* tab,
+                                                                    const unsigned long long* __restrict__ counters,
+                                                                    int64_t max_slots, int64_t* minfo) {
+    const int64_t want = 2 * (int64_t)counters[2];
+    int64_t slots = 1024, shift = 22;
+    while (slots < want && slots < max_slots) { slots <<= 1; --shift; }
+    if (blockIdx.x == 0 && threadIdx.x == 0) { minfo[0] = slots - 1; minfo[1] = shift; }
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < slots; i += stride) tab[i] = ~0ull;
+}
+
+// Every remote row of the miss list claims its vertex; a row that finds the vertex claimed is struck
+// from the list (the miss copy skips negative entries), gets the claimer's virtual row as its
+// source, and joins the copy list.
+__global__ void __launch_bounds__(kBlock) gather_share_kernel(unsigned long long* tab, const int64_t* __restrict__ minfo,
+                                                              int64_t* __restrict__ desc, int32_t* __restrict__ misslist,
+                                                              int32_t* __restrict__ duplist,
+                                                              unsigned long long* __restrict__ counters,
+                                                              unsigned long long* __restrict__ totals) {
+    __shared__ int scan_lds[4];
+    __shared__ unsigned long long base_lds;
+    const int64_t n = (int64_t)counters[2];
+    const uint32_t mask = (uint32_t)minfo[0];
+    const int shift = (int)minfo[1];
+    const int64_t n_round = (n + kBlock - 1) / kBlock * kBlock;            // whole workgroups reach the scan
+    for (int64_t m = (int64_t)blockIdx.x * kBlock + threadIdx.x; m < n_round; m += (int64_t)gridDim.x * kBlock) {
+        int32_t r = -1;
+        bool dup = false;
+        if (m < n) {
+            r = misslist[m];
+            const int64_t d = desc[r];
+            uint32_t first = 0;
+            if (desc_tag(d) == kTagMiss && !table_claim(tab, mask, shift, (uint32_t)desc_row(d), (uint32_t)r, first)) {
+                dup = true;
+                desc[r] = make_desc(kTagDup, first);
+                misslist[m] = -1;
+            }
+        }
+        int total;
+        const int ex = block_exclusive_scan(dup ? 1 : 0, scan_lds, total);
+        if (total) {                                                       // uniform over the workgroup
+            if (threadIdx.x == 0) {
+                base_lds = atomicAdd(&counters[6], (unsigned long long)total);
+                atomicAdd(&totals[8], (unsigned long long)total);
+            }
+            __syncthreads();
+            if (dup) duplist[base_lds + (unsigned long long)ex] = r;
+            __syncthreads();
+        }
     }
 }
 
@@ -240,20 +299,28 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     a.t.n_lists = pro.n_lists = n_lists;
 
     hipStream_t st = ctx->stream;
-    // a miss copy left running by an earlier SPP_NO_JOIN call still reads this context's
-    // descriptors and miss list: the stream waits for it before they are overwritten
-    if (ctx->join_pending) {
-        SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
-        ctx->join_pending = false;
-    }
-    SPP_TRY(ctx->gcount.reserve((8 + 2 * (kMaxLists + 1)) * sizeof(int64_t)));
-    unsigned long long* counters = ctx->gcount.as<unsigned long long>();
-    int64_t* off = ctx->gcount.as<int64_t>() + 8;
+    // A miss copy left running by the call before (SPP_NO_JOIN) still reads that call's descriptors,
+    // lists and counters, so calls alternate between two sets of them: this call's classification
+    // runs beside that miss copy, and the stream waits for it only before the hit copy below.  (The
+    // set used two calls ago is free: the call before waited for its miss copy at the same place.)
+    const int slot = ctx->gslot ^= 1;
+    SPP_TRY(ctx->gcount[slot].reserve((8 + 2 * (kMaxLists + 1) + 2) * sizeof(int64_t)));
+    unsigned long long* counters = ctx->gcount[slot].as<unsigned long long>();
+    int64_t* off = ctx->gcount[slot].as<int64_t>() + 8;
     int64_t* cnt = off + kMaxLists + 1;
+    int64_t* minfo = cnt + kMaxLists + 1;
     a.t.off = off; a.t.cnt = cnt;
+    // several lists make it worth claiming missed vertices: one list of a sampler's distinct ids
+    // has nothing to share
+    const bool share_misses = dremote != nullptr && n_lists > 1 && vbound > 0;
+    uint32_t mcap = 0;
+    if (share_misses) {
+        mcap = next_pow2((uint64_t)(2 * vbound > 1024 ? 2 * vbound : 1024));
+        SPP_TRY(ctx->gtable.reserve((size_t)mcap * sizeof(uint64_t)));
+    }
     if (vbound > 0) {
-        SPP_TRY(ctx->srcdesc.reserve((size_t)vbound * sizeof(int64_t)));
-        SPP_TRY(ctx->misslist.reserve((size_t)vbound * sizeof(int32_t) * 2));     // miss list, then hit list
+        SPP_TRY(ctx->srcdesc[slot].reserve((size_t)vbound * sizeof(int64_t)));
+        SPP_TRY(ctx->misslist[slot].reserve((size_t)vbound * sizeof(int32_t) * 3));     // miss list, hit list, copy list
     }
     gather_prologue_kernel<<<1, 64, 0, st>>>(pro, counters, off, cnt);
     if (vbound > 0) {
@@ -263,14 +330,21 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         a.limit = cache ? cache->limit : 0;
         a.local_rank = store ? store->rank : nullptr;
         a.local_limit = store ? store->limit : 0;
-        a.desc = ctx->srcdesc.as<int64_t>(); a.misslist = ctx->misslist.as<int32_t>(); a.counters = counters;
+        a.desc = ctx->srcdesc[slot].as<int64_t>(); a.misslist = ctx->misslist[slot].as<int32_t>(); a.counters = counters;
         a.hitlist = a.misslist + vbound;
+        int32_t* duplist = a.hitlist + vbound;
         a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
         const int64_t cneed = vbound / kListAlign;
         const int cgrid = (int)(cneed < (int64_t)ctx->num_cu * 8 ? cneed : (int64_t)ctx->num_cu * 8);
         {
             ScopedTimer tc(ctx, SPP_T_GATHER_CLASSIFY, st);
             classify_kernel<<<cgrid, kBlock, 0, st>>>(a);
+            if (share_misses) {
+                unsigned long long* mtab = ctx->gtable.as<unsigned long long>();
+                const int sgrid = ctx->num_cu * 4;
+                gather_table_clear_kernel<<<sgrid, kBlock, 0, st>>>(mtab, counters, (int64_t)mcap, minfo);
+                gather_share_kernel<<<sgrid, kBlock, 0, st>>>(mtab, minfo, a.desc, a.misslist, duplist, counters, a.totals);
+            }
         }
         const int V = pick_vec(row_bytes, addr_bits);
         const uint32_t vpr = (uint32_t)(row_bytes / V);
@@ -283,6 +357,12 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         // the PCIe link, and every CU that hosts host-memory loads serves other kernels slowly.
         const int64_t mneed = (vecs + kBlock * kCopyUnroll - 1) / (kBlock * kCopyUnroll);
         const int mgrid = (int)(mneed < kMissBlocks ? mneed : kMissBlocks);
+        // the rows of the call before are complete from here on, and the PCIe link is idle: the hit
+        // copy runs alone
+        if (ctx->join_pending) {
+            SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
+            ctx->join_pending = false;
+        }
         // Order on purpose: the hit copy runs first and alone, the miss copy starts on the side
         // stream when it is done.  Run together, the host-memory loads of the miss kernel held up
         // the hit copy on every CU they shared (it then ran at a third of its rate), and the hit
@@ -318,6 +398,16 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
                     case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
                     default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
                 }
+                if (share_misses) {     // rows that share a fetched vertex, from the fetched row's output
+                    const int64_t* dup_count = reinterpret_cast<const int64_t*>(counters + 6);
+                    const int dgrid = ctx->num_cu * 4;
+                    switch (V) {
+                        case 16: gather_dup_kernel<16><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
+                        case 8:  gather_dup_kernel<8><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
+                        case 4:  gather_dup_kernel<4><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
+                        default: gather_dup_kernel<2><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
+                    }
+                }
             }
             SPP_HIP(hipEventRecord(ctx->ev_join, ctx->side));
         }
@@ -329,7 +419,7 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     SPP_HIP(hipGetLastError());
     int64_t* hp = ctx->h_pinned + 40;
     // the counters are final once the classification has run, whether or not the misses have landed
-    SPP_HIP(hipMemcpyAsync(hp, counters, 6 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    SPP_HIP(hipMemcpyAsync(hp, counters, 7 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
     ctx->h_pinned[48] = row_bytes;
     ctx->h_pinned[49] = dremote ? 1 : 0;
     if (flags & SPP_SYNC) {
@@ -379,7 +469,8 @@ extern "C" int spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats) {
     if (stats) {
         stats->n_local = hp[0]; stats->n_cache_hit = hp[1]; stats->n_miss = hp[2] - hp[5];
         stats->n_local_host = hp[5];
-        stats->miss_bytes = hp[2] * ctx->h_pinned[48];
+        stats->n_miss_shared = hp[6];
+        stats->miss_bytes = (hp[2] - hp[6]) * ctx->h_pinned[48];
     }
     SPP_CHECK(hp[3] == 0, SPP_E_ARG, "spp_gather_features: a vertex id lies outside [0, N); its row was left untouched");
     SPP_CHECK(hp[2] - hp[5] == 0 || ctx->h_pinned[49] != 0, SPP_E_ARG,

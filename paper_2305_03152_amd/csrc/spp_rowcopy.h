@@ -21,8 +21,10 @@ template <> struct VecOf<4>  { typedef uint32_t type; };
 template <> struct VecOf<2>  { typedef uint16_t type; };
 
 // Source descriptor of an output row: tag in the top three bits, row index in the store below.
-// kTagLocal: row of the device-resident local rows; kTagLocalHost: row of the host-resident ones.
-constexpr int kTagLocal = 0, kTagCache = 1, kTagMiss = 2, kTagSkip = 3, kTagLocalHost = 4;
+// kTagLocal: row of the device-resident local rows; kTagLocalHost: row of the host-resident ones;
+// kTagDup: the same remote vertex is fetched for another output row of this call, whose virtual
+// row is stored: this row is copied from that one once it has arrived.
+constexpr int kTagLocal = 0, kTagCache = 1, kTagMiss = 2, kTagSkip = 3, kTagLocalHost = 4, kTagDup = 5;
 __device__ __host__ __forceinline__ int64_t make_desc(int tag, int64_t row) { return (int64_t)((uint64_t)tag << 61) | row; }
 __device__ __forceinline__ int desc_tag(int64_t d) { return (int)(((uint64_t)d) >> 61); }
 __device__ __forceinline__ int64_t desc_row(int64_t d) { return d & ((1ll << 61) - 1); }
@@ -142,12 +144,12 @@ __global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restr
                 const uint64_t m = small ? (uint64_t)((uint32_t)c / vpr) : c / vpr;
                 const uint32_t k = (uint32_t)(c - m * vpr);
                 const int64_t r = misslist[m];
-                const int j = list_of(ls, t.n_lists, r);
-                const int64_t d = desc[r];
+                const int64_t d = r >= 0 ? desc[r] : 0;
+                const int j = r >= 0 ? list_of(ls, t.n_lists, r) : 0;
                 const char* from = desc_tag(d) == kTagLocalHost ? local_host : src;
-                // a store the caller did not give: the row is left untouched (the statistics of
-                // the call report it)
-                ok[u] = from != nullptr;
+                // struck from the list (another row fetches the vertex), or a store the caller did
+                // not give: the row is left to the copy pass, or untouched (the statistics report it)
+                ok[u] = r >= 0 && from != nullptr;
                 if (ok[u]) {
                     v[u] = load_stream<V>(from + ((uint64_t)desc_row(d) * vpr + k) * (uint64_t)V);
                     dst[u] = t.out[j] + ((uint64_t)(r - ls.off[j]) * vpr + k) * (uint64_t)V;
@@ -157,6 +159,29 @@ __global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restr
 #pragma unroll
         for (int u = 0; u < kCopyUnroll; ++u)
             if (ok[u]) store_stream<V>(dst[u], v[u]);
+    }
+}
+
+// Rows whose vertex another row of the same call fetches from the host: copied from that row's
+// output (device memory) after the miss copy, so a vertex that several minibatches of the call
+// miss crosses PCIe once.
+template <int V>
+__global__ void __launch_bounds__(kBlock) gather_dup_kernel(const int64_t* __restrict__ desc,
+                                                            const int32_t* __restrict__ duplist,
+                                                            const int64_t* __restrict__ count_ptr, ListTable t,
+                                                            uint32_t vpr) {
+    typedef typename VecOf<V>::type vec_t;
+    __shared__ ListLds ls;
+    load_lists(t, ls);
+    const uint64_t total = (uint64_t)(*count_ptr) * vpr;
+    for (uint64_t c = (uint64_t)blockIdx.x * kBlock + threadIdx.x; c < total; c += (uint64_t)gridDim.x * kBlock) {
+        const uint64_t m = c / vpr;
+        const uint32_t k = (uint32_t)(c - m * vpr);
+        const int64_t r = duplist[m];
+        const int64_t rs = desc_row(desc[r]);
+        const int j = list_of(ls, t.n_lists, r), js = list_of(ls, t.n_lists, rs);
+        const vec_t v = *reinterpret_cast<const vec_t*>(t.out[js] + ((uint64_t)(rs - ls.off[js]) * vpr + k) * (uint64_t)V);
+        store_stream<V>(t.out[j] + ((uint64_t)(r - ls.off[j]) * vpr + k) * (uint64_t)V, v);
     }
 }
 

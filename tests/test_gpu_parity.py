@@ -200,7 +200,8 @@ def test_sample_and_gather_tiny(spp, ctx, tiny_case):
     cache_rows = S.feature_rows(cfg, torch.from_numpy(ids_ref)).numpy()
     bufs = spp.MFGBuffers("cuda", cfg.B, cfg.fanouts, cfg.N)
     ctx.totals(reset=True)
-    sums = dict(batches=0, n_nodes=0, n_edges=0, gather_calls=0, n_local=0, n_cache_hit=0, n_miss=0, n_local_host=0)
+    sums = dict(batches=0, n_nodes=0, n_edges=0, gather_calls=0, n_local=0, n_cache_hit=0, n_miss=0, n_local_host=0,
+                n_miss_shared=0)
     for epoch in range(2):
         for bi, seeds in enumerate(S.epoch_batches(cfg, torch.from_numpy(c.Tk), epoch)):
             _say("tiny batch", epoch, bi, "seeds", seeds.numel())
@@ -305,12 +306,30 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
             tot[key] += st[key]
     st = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists)
     assert {k: st[k] for k in tot} == tot
+    # a remote vertex that several rows of the call miss crosses PCIe once: the other rows are copies
+    all_ids = np.concatenate([l[0][:n0].cpu().numpy() for l, n0 in zip(lists, sizes)])
+    cached = set(cache.ids.cpu().numpy().tolist())
+    missed = np.array([g_ for g_ in all_ids if not (c.lo <= g_ < c.hi) and g_ not in cached])
+    assert missed.size == tot["n_miss"]
+    assert st["n_miss_shared"] == missed.size - np.unique(missed).size and st["n_miss_shared"] > 0
+    assert st["miss_bytes"] == np.unique(missed).size * cfg.D * cfg.elem_bytes
     for (ids, n, n_dev, out), ref, n0 in zip(lists, singles, sizes):
         assert torch.equal(out[:n0], ref[:n0])
         assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
         assert torch.all(out[n0:] == 0)
     with pytest.raises(spp.SppError):
         spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists * 3)   # 18 lists
+    # maximal sharing: 16 lists of the same ids, no cache: every remote row but the first of a vertex is a copy
+    _say("gather multi: 16 identical lists")
+    ids = torch.randint(0, cfg.N, (3000,), device="cuda", generator=g, dtype=torch.int32)
+    outs = [torch.zeros((3000, cfg.D), dtype=torch.float32, device="cuda") for _ in range(16)]
+    st16 = spp.gather_features_multi(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, [(ids, 3000, None, o) for o in outs])
+    want = S.feature_rows(cfg, ids.cpu())
+    for o in outs:
+        assert torch.equal(o.cpu(), want)
+    idn = ids.cpu().numpy()
+    rem = idn[(idn < c.lo) | (idn >= c.hi)]
+    assert st16["n_miss"] == 16 * rem.size and st16["n_miss_shared"] == 16 * rem.size - np.unique(rem).size
     # miss copy left running on the side stream while the stream samples the next minibatch, joined later
     _say("gather multi: deferred join")
     for (_, _, _, out) in lists:
