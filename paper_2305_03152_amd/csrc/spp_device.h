@@ -149,11 +149,17 @@ inline void grid_scan(hipStream_t st, int grid, const int64_t* n_ptr, In in, Out
 //   Out: void operator()(int j, int64_t i, int ex, int v) const
 //   Fin: void operator()(int j, int total) const
 // `partial` holds gridDim.x ints per sequence.
-template <class In>
-__global__ void __launch_bounds__(kBlock) bscan_reduce_kernel(In in, int* partial) {
+// Two hooks let independent work ride in the same launches (a launch costs more than most of
+// these steps): Head: void operator()(int j, unsigned x, unsigned gx) const runs before the
+// reduction, Tail after the write pass; x is the workgroup's index among the gx of sequence j.
+struct NoHook { __device__ void operator()(int, unsigned, unsigned) const {} };
+
+template <class In, class Head>
+__global__ void __launch_bounds__(kBlock) bscan_reduce_kernel(In in, int* partial, Head head) {
     __shared__ int lds[4];
     const BatchBlock bb = batch_block();
     const int j = bb.j;
+    head(j, bb.x, gridDim.x);
     int64_t b, e;
     scan_range(in.n(j), bb.x, b, e);
     int acc = 0;
@@ -179,8 +185,8 @@ __global__ void __launch_bounds__(kBlock) bscan_partials_kernel(int* partial, in
     if (threadIdx.x == 0) fin(j, carry);
 }
 
-template <class In, class Out>
-__global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, const int* partial) {
+template <class In, class Out, class Tail>
+__global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, const int* partial, Tail tail) {
     __shared__ int lds[4];
     const BatchBlock bb = batch_block();
     const int j = bb.j;
@@ -195,13 +201,15 @@ __global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, con
         if (i < e) out(j, i, uadd(carry, ex), v);
         carry = uadd(carry, total);
     }
+    tail(j, bb.x, gridDim.x);
 }
 
-template <class In, class Out, class Fin>
-inline void grid_scan_batched(hipStream_t st, int grid, int nbatch, In in, Out out, Fin fin, int* partial) {
-    bscan_reduce_kernel<In><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, partial);
+template <class In, class Out, class Fin, class Head = NoHook, class Tail = NoHook>
+inline void grid_scan_batched(hipStream_t st, int grid, int nbatch, In in, Out out, Fin fin, int* partial,
+                              Head head = Head(), Tail tail = Tail()) {
+    bscan_reduce_kernel<In, Head><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, partial, head);
     bscan_partials_kernel<Fin><<<nbatch, kBlock, 0, st>>>(partial, grid, fin);
-    bscan_write_kernel<In, Out><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, out, partial);
+    bscan_write_kernel<In, Out, Tail><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, out, partial, tail);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -140,16 +140,18 @@ struct CountFin {
 };
 
 // ---- step 2 ----
-// Empties the part of the region that this hop's table occupies.
-__global__ void __launch_bounds__(kBlock) table_clear_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    const BatchBlock bb = batch_block();
-    const int j = bb.j;
-    if (t->b[j].tinfo[2]) return;
-    unsigned long long* tab = tab_of(a, j);
-    const int64_t capj = (int64_t)t->b[j].tinfo[0] + 1;
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t i = (int64_t)bb.x * kBlock + threadIdx.x; i < capj; i += stride) tab[i] = ~0ull;
-}
+// Empties the part of the region that this hop's table occupies.  Rides at the end of the launch
+// that writes the hop's offsets: CountFin has fixed the table's size in the launch before.
+struct TableClear {
+    SampleArgs a; const BatchTable* t;
+    __device__ void operator()(int j, unsigned x, unsigned gx) const {
+        if (t->b[j].tinfo[2]) return;
+        unsigned long long* tab = tab_of(a, j);
+        const int64_t capj = (int64_t)t->b[j].tinfo[0] + 1;
+        const int64_t stride = (int64_t)gx * kBlock;
+        for (int64_t i = (int64_t)x * kBlock + threadIdx.x; i < capj; i += stride) tab[i] = ~0ull;
+    }
+};
 
 template <int G>
 __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
@@ -346,9 +348,8 @@ struct NewFin {
 };
 
 // ---- step 4 ----
-__global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    const BatchBlock bb = batch_block();
-    const int j = bb.j;
+__device__ __forceinline__ void relabel_rows(const SampleArgs& a, const BatchTable* __restrict__ t, int j, unsigned x,
+                                             unsigned gx) {
     if (t->b[j].tinfo[2]) return;
     const int64_t e_h = t->b[j].counts[kE + a.h];
     const unsigned long long* tab = tab_of(a, j);
@@ -356,13 +357,23 @@ __global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const Bat
     int32_t* __restrict__ src = t->b[j].src[a.h - 1];
     const uint32_t mask = t->b[j].tinfo[0];
     const int shift = (int)t->b[j].tinfo[1];
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t e = (int64_t)bb.x * kBlock + threadIdx.x; e < e_h; e += stride) {
+    const int64_t stride = (int64_t)gx * kBlock;
+    for (int64_t e = (int64_t)x * kBlock + threadIdx.x; e < e_h; e += stride) {
         uint32_t val = 0;
         table_find(tab, mask, shift, (uint32_t)flat[e], val);
         src[e] = (int32_t)val;
     }
 }
+__global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const BatchBlock bb = batch_block();
+    relabel_rows(a, t, bb.j, bb.x, gridDim.x);
+}
+// The relabel of hop h-1 riding at the head of hop h's first scan launch (it reads the table, the
+// flat ids and the counts of hop h-1, which that launch only reads too).
+struct RelabelPrev {
+    SampleArgs a; const BatchTable* t;         // a.h = the hop to relabel
+    __device__ void operator()(int j, unsigned x, unsigned gx) const { relabel_rows(a, t, j, x, gx); }
+};
 
 // Stores the call's table of per-minibatch pointers in device memory and clears the error flag.
 __global__ void __launch_bounds__(kBlock) batch_table_store_kernel(BatchTable src, BatchTable* dst, int* bad) {
@@ -501,10 +512,15 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
             a.h = h; a.f = general ? 0 : fanouts[h - 1]; a.t = general ? d_t[h - 1] : nullptr;
             const dim3 wgrid(capped((nb[h - 1] * kWave + kBlock - 1) / kBlock, share), n_items);   // a wavefront per target
             if (general) general_count_kernel<<<wgrid, kBlock, 0, st>>>(a, dt);
-            grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial);
-            {   // the hop's table holds at most 2 (n_bound[h-1] + e_bound[h]) keys' worth of slots
-                const int64_t slots_bound = 4 * (nb[h - 1] + eb[h]) < (int64_t)cap ? 4 * (nb[h - 1] + eb[h]) : (int64_t)cap;
-                table_clear_kernel<<<dim3(capped((slots_bound + kBlock * 8 - 1) / (kBlock * 8), share), n_items), kBlock, 0, st>>>(a, dt);
+            // the relabel of the hop before and the emptying of this hop's table ride in the scan's launches
+            if (h > 1 && !general) {
+                SampleArgs ap = a;
+                ap.h = h - 1;
+                grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial,
+                                  RelabelPrev{ap, dt}, TableClear{a, dt});
+            } else {
+                grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial,
+                                  NoHook(), TableClear{a, dt});
             }
             if (general) {
                 general_sample_kernel<<<wgrid, kBlock, 0, st>>>(a, dt);
@@ -519,7 +535,8 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
                 }
             }
             grid_scan_batched(st, scan_grid, n_items, NewIn{a, dt}, NewOut{a, dt}, NewFin{a, dt}, partial);
-            relabel_kernel<<<dim3(capped((eb[h] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
+            if (h == L || general)
+                relabel_kernel<<<dim3(capped((eb[h] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
         }
     }
     SPP_HIP(hipGetLastError());
