@@ -28,6 +28,7 @@ PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 # shapes report null.
 MEASURED_TRAFFIC = {
     ("mid", 16): {"gather_hit": 346.3e6 + 269.9e6, "vip_tile": 1.329e9 + 134.9e6},
+    ("mid", 32): {"gather_hit": 692.0e6 + 536.5e6, "vip_tile": 1.329e9 + 134.9e6},
 }
 
 
@@ -221,15 +222,15 @@ def beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=320)
+    ap.add_argument("--steps", type=int, default=640)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--config", default="mid", help="workload: tiny | mid (default, the metric's configuration)")
     ap.add_argument("--vip-reps", type=int, default=5)
     ap.add_argument("--pipeline", type=int, default=1,
                     help="lanes: contexts (each with its own stream and buffers) used round-robin")
-    ap.add_argument("--group", type=int, default=16,
+    ap.add_argument("--group", type=int, default=32,
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
-                         "(pipeline x group minibatches are in flight; the paper keeps ten)")
+                         "(2 x pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
     ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "policy-sweep", "general", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
@@ -272,7 +273,7 @@ def main():
     K, W = args.steps, args.warmup
     P = max(1, args.pipeline)
     # groups of `group` minibatches, but at least about four groups in the timed region
-    Gsz = max(1, min(args.group, 16, max(1, K // (4 * P))))
+    Gsz = max(1, min(args.group, 32, max(1, K // (4 * P))))
     lo, hi = cfg.bounds()
     row_bytes = cfg.D * cfg.elem_bytes
 

@@ -41,8 +41,8 @@ extern "C" {
 
 #define SPP_MAX_L       8      /* most hops / GNN layers */
 #define SPP_MAX_FANOUT  64     /* largest fanout (one wavefront lane per slot) */
-#define SPP_MAX_GATHER_LISTS 16 /* most id lists in one spp_gather_features_multi call */
-#define SPP_MAX_SAMPLE_BATCHES 16 /* most minibatches in one spp_sample_mfg_multi call */
+#define SPP_MAX_GATHER_LISTS 32 /* most id lists in one spp_gather_features_multi call */
+#define SPP_MAX_SAMPLE_BATCHES 32 /* most minibatches in one spp_sample_mfg_multi call */
 
 enum {
     SPP_OK          =  0,

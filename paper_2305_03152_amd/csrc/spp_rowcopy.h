@@ -67,9 +67,12 @@ __device__ __forceinline__ void load_lists(const ListTable& t, ListLds& s) {
 }
 // Index of the list that owns virtual row r (r < off[n_lists]).
 __device__ __forceinline__ int list_of(const ListLds& s, int n_lists, int64_t r) {
-    int j = 0;
-    while (j + 1 < n_lists && r >= s.off[j + 1]) ++j;
-    return j;
+    int lo = 0, hi = n_lists - 1;                 // last j with off[j] <= r
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (r >= s.off[mid]) lo = mid; else hi = mid - 1;
+    }
+    return lo;
 }
 
 // Hit path: rows served from the local shard or the cache.  hitlist[m] is a virtual row whose

@@ -1,6 +1,6 @@
 // Node-wise fanout sampling into per-layer message-flow graphs (Sec. 2.3; the process of Sec. 3.1).
 //
-// Up to 16 minibatches are sampled by one set of launches: every kernel has a second grid dimension
+// Up to 32 minibatches are sampled by one set of launches: every kernel has a second grid dimension
 // that names the minibatch, and each minibatch has its own id table, flat-id buffer and counts, so
 // the minibatches never interact.  Per hop h, all on the context's stream with every count kept on
 // the device:
@@ -375,14 +375,20 @@ struct RelabelPrev {
     __device__ void operator()(int j, unsigned x, unsigned gx) const { relabel_rows(a, t, j, x, gx); }
 };
 
-// Stores the call's table of per-minibatch pointers in device memory and clears the error flag.
-__global__ void __launch_bounds__(kBlock) batch_table_store_kernel(BatchTable src, BatchTable* dst, int* bad) {
+// Stores the call's table of per-minibatch pointers in device memory, sixteen entries per launch
+// (a launch's argument block holds 4 KB), and clears the flags.
+constexpr int kStoreChunk = 16;
+struct BatchTableChunk { BatchDesc b[kStoreChunk]; };
+__global__ void __launch_bounds__(kBlock) batch_table_store_kernel(BatchTableChunk src, BatchTable* dst, int first, int* bad) {
     const uint64_t* s = reinterpret_cast<const uint64_t*>(&src);
-    uint64_t* d = reinterpret_cast<uint64_t*>(dst);
-    for (unsigned i = threadIdx.x; i < sizeof(BatchTable) / sizeof(uint64_t); i += kBlock) d[i] = s[i];
-    if (threadIdx.x == 0) { bad[0] = 0; bad[1] = 0; }     // error flag, capacity flag
+    uint64_t* d = reinterpret_cast<uint64_t*>(&dst->b[first]);
+    for (unsigned i = threadIdx.x; i < sizeof(BatchTableChunk) / sizeof(uint64_t); i += kBlock) d[i] = s[i];
+    // [0] error flag, [1] capacity flag
+    if (first == 0 && threadIdx.x < 2) bad[threadIdx.x] = 0;
 }
-static_assert(sizeof(BatchTable) % sizeof(uint64_t) == 0, "copied as 64-bit words");
+static_assert(sizeof(BatchTableChunk) % sizeof(uint64_t) == 0, "copied as 64-bit words");
+static_assert(sizeof(BatchTableChunk) <= 4000, "must fit a launch's argument block");
+static_assert(kMaxBatches % kStoreChunk == 0, "the table is stored in whole chunks");
 
 }  // namespace spp
 
@@ -417,7 +423,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
         for (int h = 0; h < L; ++h)
             SPP_CHECK(d_t[h] || g->M == 0, SPP_E_ARG, "spp_sample_mfg_general: no transition probabilities for hop %d", h + 1);
     if (n_items == 0) return SPP_OK;
-    BatchTable ht;
+    BatchTable ht = {};
     memset(&ht, 0, sizeof(ht));
     int64_t nb[SPP_MAX_L + 1] = {0}, eb[SPP_MAX_L + 1] = {0};       // bounds (capacities) of the largest minibatch
     int max_seeds = 0;
@@ -506,7 +512,11 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
     const int64_t share = (int64_t)ctx->num_cu * 16 / n_items + 1;    // workgroups per minibatch in the wide kernels
     {
         ScopedTimer tt(ctx, SPP_T_SAMPLE, st);
-        batch_table_store_kernel<<<1, kBlock, 0, st>>>(ht, dt, d_bad);
+        for (int first = 0; first < n_items; first += kStoreChunk) {
+            BatchTableChunk chunk;
+            memcpy(&chunk, &ht.b[first], sizeof(chunk));
+            batch_table_store_kernel<<<1, kBlock, 0, st>>>(chunk, dt, first, d_bad);
+        }
         seeds_kernel<<<dim3(capped((max_seeds + kBlock - 1) / kBlock, 1 << 20), n_items), kBlock, 0, st>>>(a, dt);
         for (int h = 1; h <= L; ++h) {
             a.h = h; a.f = general ? 0 : fanouts[h - 1]; a.t = general ? d_t[h - 1] : nullptr;
@@ -541,7 +551,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
     }
     SPP_HIP(hipGetLastError());
     if (flags & SPP_SYNC) {
-        int64_t* hp = ctx->h_pinned + 64;            // 16 x 18 counts, then the flags
+        int64_t* hp = ctx->h_pinned + 64;            // kMaxBatches x 18 counts, then the flags
         for (int j = 0; j < n_items; ++j)
             SPP_HIP(hipMemcpyAsync(hp + j * 2 * kE, items[j].io->d_counts, 2 * kE * sizeof(int64_t), hipMemcpyDeviceToHost, st));
         SPP_HIP(hipMemcpyAsync(hp + kMaxBatches * 2 * kE, d_bad, 2 * sizeof(int), hipMemcpyDeviceToHost, st));

@@ -281,7 +281,15 @@ def test_sample_multi_batches(spp, ctx, tiny_case):
         ref = oracle.sample_mfg(c.rp, c.col, s_, cfg.fanouts, cfg.seed_sampler, bi)
         _check_mfg(m, ref, cfg.L)
     with pytest.raises(spp.SppError):
-        spp.sample_mfg_multi(ctx, c.G, items * 4, cfg.fanouts, cfg.seed_sampler)       # 20 minibatches
+        spp.sample_mfg_multi(ctx, c.G, items * 7, cfg.fanouts, cfg.seed_sampler)       # 35 minibatches
+    _say("sample multi: 21 and 32 minibatches in one call")
+    for count in (21, 32):
+        seeds = [rng.permutation(c.Tk)[:rng.integers(1, 60)] for _ in range(count)]
+        items = [(torch.from_numpy(np.ascontiguousarray(s_)).cuda(), 900 + k, spp.MFGBuffers("cuda", 64, cfg.fanouts, cfg.N))
+                 for k, s_ in enumerate(seeds)]
+        spp.sample_mfg_multi(ctx, c.G, items, cfg.fanouts, cfg.seed_sampler)
+        for (sd, bi, m), s_ in zip(items, seeds):
+            _check_mfg(m, oracle.sample_mfg(c.rp, c.col, s_, cfg.fanouts, cfg.seed_sampler, bi), cfg.L)
 
 
 def test_gather_multi_lists(spp, ctx, tiny_case):
@@ -318,18 +326,18 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
         assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
         assert torch.all(out[n0:] == 0)
     with pytest.raises(spp.SppError):
-        spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists * 3)   # 18 lists
-    # maximal sharing: 16 lists of the same ids, no cache: every remote row but the first of a vertex is a copy
-    _say("gather multi: 16 identical lists")
+        spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists * 6)   # 36 lists
+    # maximal sharing: 32 lists of the same ids, no cache: every remote row but the first of a vertex is a copy
+    _say("gather multi: 32 identical lists")
     ids = torch.randint(0, cfg.N, (3000,), device="cuda", generator=g, dtype=torch.int32)
-    outs = [torch.zeros((3000, cfg.D), dtype=torch.float32, device="cuda") for _ in range(16)]
-    st16 = spp.gather_features_multi(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, [(ids, 3000, None, o) for o in outs])
+    outs = [torch.zeros((3000, cfg.D), dtype=torch.float32, device="cuda") for _ in range(32)]
+    st32 = spp.gather_features_multi(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, [(ids, 3000, None, o) for o in outs])
     want = S.feature_rows(cfg, ids.cpu())
     for o in outs:
         assert torch.equal(o.cpu(), want)
     idn = ids.cpu().numpy()
     rem = idn[(idn < c.lo) | (idn >= c.hi)]
-    assert st16["n_miss"] == 16 * rem.size and st16["n_miss_shared"] == 16 * rem.size - np.unique(rem).size
+    assert st32["n_miss"] == 32 * rem.size and st32["n_miss_shared"] == 32 * rem.size - np.unique(rem).size
     # miss copy left running on the side stream while the stream samples the next minibatch, joined later
     _say("gather multi: deferred join")
     for (_, _, _, out) in lists:
