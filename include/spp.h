@@ -176,7 +176,8 @@ int  spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
  *     and joined back before the call returns to the stream.  cache may be NULL (alpha = 0).
  *     n is the number of ids, or an upper bound when d_n (device int64, e.g. &d_counts[L]) is
  *     given, in which case the count is read on the device.  Row size D*elem_bytes must be a
- *     multiple of 2; 16-byte multiples take the widest path.  Duplicate ids are allowed.
+ *     multiple of 2 and every store and output 2-byte aligned (SPP_E_ARG otherwise); 16-byte
+ *     multiples and alignments take the widest path.  Duplicate ids are allowed.
  *     `remote` is pinned host memory (or device memory); it may be NULL only if no id misses.
  *     stats (host, may be NULL) is filled when SPP_SYNC is set; otherwise read it later with
  *     spp_gather_last_stats after synchronising. */

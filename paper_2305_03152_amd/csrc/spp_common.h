@@ -171,9 +171,11 @@ int device_view(const void* p, const void** out);
 int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, int64_t n,
                       int64_t row_bytes, void* d_out, int num_cu);
 
+// Slots of an id table for x/2 keys: the smallest power of two >= x, at most 2^31 (a table index
+// has 32 bits; key counts stay below 2^31, so such a table still has a free slot).
 static inline uint32_t next_pow2(uint64_t x) {
     uint64_t p = 1;
-    while (p < x) p <<= 1;
+    while (p < x && p < (1ull << 31)) p <<= 1;
     return (uint32_t)p;
 }
 

@@ -224,6 +224,10 @@ int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, 
     if (n <= 0) return SPP_OK;
     const void* dsrc = nullptr;
     SPP_TRY(device_view(src, &dsrc));
+    if ((((uintptr_t)dsrc | (uintptr_t)d_out | (uintptr_t)row_bytes) & 1) != 0) {
+        set_error("row copy: odd row size or address");
+        return SPP_E_ARG;
+    }
     const int V = pick_vec(row_bytes, (uintptr_t)dsrc | (uintptr_t)d_out);
     const uint32_t vpr = (uint32_t)(row_bytes / V);
     const int64_t vecs = n * vpr;
@@ -294,6 +298,7 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         vbound = (vbound + lists[j].n + kListAlign - 1) / kListAlign * kListAlign;
         addr_bits |= (uintptr_t)lists[j].d_out;
     }
+    SPP_CHECK((addr_bits & 1) == 0, SPP_E_ARG, "spp_gather_features: a row store or an output has an odd address");
     SPP_CHECK(vbound < 0x7FFFFFFFll, SPP_E_ARG, "spp_gather_features: %lld rows in one call exceed the 32-bit miss list", (long long)vbound);
     SPP_CHECK(hi == lo || d_local || store || vbound == 0, SPP_E_ARG, "spp_gather_features: local shard is null");
     a.t.n_lists = pro.n_lists = n_lists;

@@ -424,7 +424,6 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
             SPP_CHECK(d_t[h] || g->M == 0, SPP_E_ARG, "spp_sample_mfg_general: no transition probabilities for hop %d", h + 1);
     if (n_items == 0) return SPP_OK;
     BatchTable ht = {};
-    memset(&ht, 0, sizeof(ht));
     int64_t nb[SPP_MAX_L + 1] = {0}, eb[SPP_MAX_L + 1] = {0};       // bounds (capacities) of the largest minibatch
     int max_seeds = 0;
     for (int j = 0; j < n_items; ++j) {

@@ -265,6 +265,14 @@ def test_gather_edge_cases(spp, ctx, tiny_case):
     out, st = spp.gather_features(ctx, None, loc, 40, 0, 10, rem, ids)
     full = torch.cat([loc.cpu(), rem])
     assert torch.equal(out.cpu(), full[ids.cpu().long()])
+    # byte rows at an even address are served, an output at an odd address is refused
+    loc8 = torch.arange(60, dtype=torch.uint8, device="cuda").reshape(10, 6)
+    rem8 = (100 + torch.arange(180, dtype=torch.uint8)).reshape(30, 6).pin_memory()
+    buf = torch.zeros(5 * 6 + 2, dtype=torch.uint8, device="cuda")
+    out8, _ = spp.gather_features(ctx, None, loc8, 40, 0, 10, rem8, ids, out=buf[2:32].view(5, 6))
+    assert torch.equal(out8.cpu(), torch.cat([loc8.cpu(), rem8])[ids.cpu().long()])
+    with pytest.raises(spp.SppError):
+        spp.gather_features(ctx, None, loc8, 40, 0, 10, rem8, ids, out=buf[1:31].view(5, 6))
 
 
 def test_sample_multi_batches(spp, ctx, tiny_case):
