@@ -29,6 +29,7 @@ PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 MEASURED_TRAFFIC = {
     ("mid", 16): {"gather_hit": 346.3e6 + 269.9e6, "vip_tile": 1.329e9 + 134.9e6},
     ("mid", 32): {"gather_hit": 692.0e6 + 536.5e6, "vip_tile": 1.329e9 + 134.9e6},
+    ("mid", 64): {"gather_hit": 1382.6e6 + 1068.8e6, "vip_tile": 1.329e9 + 134.9e6},
 }
 
 
@@ -222,13 +223,13 @@ def beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=640)
-    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--steps", type=int, default=1280)
+    ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--config", default="mid", help="workload: tiny | mid (default, the metric's configuration)")
     ap.add_argument("--vip-reps", type=int, default=5)
     ap.add_argument("--pipeline", type=int, default=1,
                     help="lanes: contexts (each with its own stream and buffers) used round-robin")
-    ap.add_argument("--group", type=int, default=32,
+    ap.add_argument("--group", type=int, default=64,
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
                          "(2 x pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
@@ -273,7 +274,7 @@ def main():
     K, W = args.steps, args.warmup
     P = max(1, args.pipeline)
     # groups of `group` minibatches, but at least about four groups in the timed region
-    Gsz = max(1, min(args.group, 32, max(1, K // (4 * P))))
+    Gsz = max(1, min(args.group, 64, max(1, K // (4 * P))))
     lo, hi = cfg.bounds()
     row_bytes = cfg.D * cfg.elem_bytes
 
@@ -444,7 +445,7 @@ def main():
     miss_bytes = (tot["n_miss"] - tot["n_miss_shared"]) / max(cnt[T_MISS], 1) * row_bytes
     pcie = {"bound": "pcie", "achieved": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms > 0 else 0.0,
             "peak": PCIE_PEAK_GBS, "unit": "GB/s",
-            "kernel": "gather_miss_kernel<16> + gather_dup_kernel<16> (miss path, side stream)",
+            "kernel": "gather_miss_kernel<16> (side stream)",
             "bytes_per_launch": miss_bytes, "avg_launch_ms": miss_ms,
             "rows_missed_per_launch": tot["n_miss"] / max(cnt[T_MISS], 1),
             "rows_shared_per_launch": tot["n_miss_shared"] / max(cnt[T_MISS], 1)}

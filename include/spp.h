@@ -41,8 +41,8 @@ extern "C" {
 
 #define SPP_MAX_L       8      /* most hops / GNN layers */
 #define SPP_MAX_FANOUT  64     /* largest fanout (one wavefront lane per slot) */
-#define SPP_MAX_GATHER_LISTS 32 /* most id lists in one spp_gather_features_multi call */
-#define SPP_MAX_SAMPLE_BATCHES 32 /* most minibatches in one spp_sample_mfg_multi call */
+#define SPP_MAX_GATHER_LISTS 64 /* most id lists in one spp_gather_features_multi call */
+#define SPP_MAX_SAMPLE_BATCHES 64 /* most minibatches in one spp_sample_mfg_multi call */
 
 enum {
     SPP_OK          =  0,
@@ -196,8 +196,9 @@ int  spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats);
 /* With SPP_NO_JOIN a gather returns to the context's stream as soon as the hit copy is enqueued,
  * while the missed rows are still arriving on the side stream; work enqueued next on the stream
  * (the sampling of the following minibatches) overlaps the PCIe transfer.  spp_gather_join makes
- * the stream wait for that miss copy: call it before anything that reads the gathered rows.  The
- * next gather on the same context, spp_ctx_sync and SPP_SYNC join by themselves. */
+ * the stream wait for that miss copy and then copies the rows that share a fetched vertex with
+ * another row of the call: call it before anything that reads the gathered rows.  The next
+ * gather on the same context, spp_ctx_sync and SPP_SYNC join by themselves. */
 int  spp_gather_join(spp_ctx* ctx);
 
 /* The same gather for up to SPP_MAX_GATHER_LISTS id lists in one set of launches (one

@@ -35,7 +35,8 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
     // default priority on purpose: streams of mixed priority are not used anywhere in this library
     hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join[0], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join[1], hipEventDisableTiming);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 2048 * sizeof(int64_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->totals), 16 * sizeof(int64_t));
     if (e == hipSuccess) e = hipMemset(c->totals, 0, 16 * sizeof(int64_t));
@@ -55,7 +56,7 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     (void)hipStreamSynchronize(c->stream);
     if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    for (hipEvent_t e : c->ev_join) if (e) (void)hipEventDestroy(e);
     for (auto& sp : c->spans) { (void)hipEventDestroy(sp.t0); (void)hipEventDestroy(sp.t1); }
     for (hipEvent_t e : c->ev_free) (void)hipEventDestroy(e);
     if (c->h_pinned) (void)hipHostFree(c->h_pinned);
@@ -69,9 +70,9 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
 
 extern "C" int spp_ctx_sync(spp_ctx* c) {
     SPP_CHECK(c != nullptr, SPP_E_ARG, "spp_ctx_sync: ctx is null");
+    SPP_TRY(spp_gather_join(c));          // a gather left unjoined still owes its shared rows
     SPP_HIP(hipStreamSynchronize(c->stream));
     SPP_HIP(hipStreamSynchronize(c->side));
-    c->join_pending = false;
     return SPP_OK;
 }
 

@@ -62,14 +62,40 @@ struct DevBuf {
 
 constexpr int kNumTimers = SPP_T_COUNT;
 
+// Several id lists gathered by one set of launches.  List j owns the virtual rows
+// [off[j], off[j] + cnt[j]); off[] is padded to multiples of kListAlign so that one workgroup's
+// chunk of rows (or of vectors) never straddles two lists.
+constexpr int kMaxLists = SPP_MAX_GATHER_LISTS;
+struct ListTable {
+    const int32_t* ids[kMaxLists];
+    char*          out[kMaxLists];
+    const int64_t* off;     // device int64[n_lists + 1]
+    const int64_t* cnt;     // device int64[n_lists]
+    int            n_lists;
+};
+
+// What is left to do for a gather whose miss copy was left running on the side stream: wait for
+// it, then copy the rows that share a fetched vertex from the rows that fetched them.
+struct PendingGather {
+    bool           active = false;
+    int            slot = 0;            // which join event the miss copy records
+    bool           has_dup = false;
+    int            V = 0;               // vector width of the copy
+    uint32_t       vpr = 0;
+    const int64_t* desc = nullptr;
+    const int32_t* duplist = nullptr;
+    const int64_t* dup_count = nullptr;
+    ListTable      t;
+};
+
 }  // namespace spp
 
 struct spp_ctx {
     int         device = 0;
     hipStream_t stream = nullptr;       // caller's stream
     hipStream_t side = nullptr;         // miss path
-    hipEvent_t  ev_fork = nullptr, ev_join = nullptr;
-    bool        join_pending = false;   // a miss copy was left running on the side stream (SPP_NO_JOIN)
+    hipEvent_t  ev_fork = nullptr, ev_join[2] = {nullptr, nullptr};   // one join event per workspace set
+    spp::PendingGather pending;         // the gather whose miss copy is still running on the side stream
     int         num_cu = 256;
     // sampling workspaces
     spp::DevBuf table;                  // uint64 hash table: global id -> local id / first position

@@ -5,13 +5,14 @@
 //                            source descriptor per row and the compacted list of missing rows
 //   hit copy  (main stream)  rows from the local shard or the replica cache, 128-bit vectors,
 //                            output walked flat so that stores are dense
-//   miss copy (side stream)  rows read straight from pinned host memory over PCIe, started as
-//                            soon as the classification is done and joined before the call ends
+//   miss copy (side stream)  rows read straight from pinned host memory over PCIe, started
+//                            after the hit copy and joined before the call ends, or (SPP_NO_JOIN)
+//                            by the next gather, which classifies its own ids in the meantime
 // A vertex that several rows of one call miss (several minibatches of a pipeline sampling the same
 // remote vertex) is fetched once: after the classification a pass over the miss list claims every
 // missed vertex in a table that lives for the call (sized for the misses, so a few MB); the row
 // that wins the claim stays in the miss list, the others are struck from it and copied from the
-// winner's output row after the miss copy.
+// winner's output row at the join, on the main stream (beside the next miss copy, if there is one).
 // With a split local store (Sec. 3.2 on host-to-device transfers, Sec. 4.1) a local id is looked up
 // in the store's rank array: below the limit it is a hit on the device rows (stored in rank order),
 // else it joins the miss list and is read from the host-resident local rows.
@@ -22,6 +23,7 @@
 namespace spp {
 
 constexpr int kMissBlocks = 64;        // workgroups of the miss kernel (see gather_lists)
+constexpr bool kHitBesideMiss = false; // see the order of the copies in gather_lists
 constexpr int kClsPer = 8;             // ids per thread: a workgroup classifies 2048 consecutive ids per round
 static_assert(kBlock * kClsPer == kListAlign, "a classification chunk must not straddle two lists");
 
@@ -243,6 +245,22 @@ int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, 
     return SPP_OK;
 }
 
+// Rows that share a fetched vertex, copied from the fetched row's output once the miss copy of
+// their call has landed (the caller has made the stream wait for it).
+int launch_dup(spp_ctx* ctx, const PendingGather& pg) {
+    if (!pg.has_dup) return SPP_OK;
+    const int dgrid = ctx->num_cu * 4;
+    hipStream_t st = ctx->stream;
+    switch (pg.V) {
+        case 16: gather_dup_kernel<16><<<dgrid, kBlock, 0, st>>>(pg.desc, pg.duplist, pg.dup_count, pg.t, pg.vpr); break;
+        case 8:  gather_dup_kernel<8><<<dgrid, kBlock, 0, st>>>(pg.desc, pg.duplist, pg.dup_count, pg.t, pg.vpr); break;
+        case 4:  gather_dup_kernel<4><<<dgrid, kBlock, 0, st>>>(pg.desc, pg.duplist, pg.dup_count, pg.t, pg.vpr); break;
+        default: gather_dup_kernel<2><<<dgrid, kBlock, 0, st>>>(pg.desc, pg.duplist, pg.dup_count, pg.t, pg.vpr); break;
+    }
+    SPP_HIP(hipGetLastError());
+    return SPP_OK;
+}
+
 }  // namespace spp
 
 // The gather behind both entry points: the local shard is either d_local (all rows in device
@@ -306,9 +324,10 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     hipStream_t st = ctx->stream;
     // A miss copy left running by the call before (SPP_NO_JOIN) still reads that call's descriptors,
     // lists and counters, so calls alternate between two sets of them: this call's classification
-    // runs beside that miss copy, and the stream waits for it only before the hit copy below.  (The
-    // set used two calls ago is free: the call before waited for its miss copy at the same place.)
+    // runs beside that miss copy.  The set used two calls ago is free: the call before joined that
+    // gather before its own hit copy (if it had no rows and joined nothing, it is joined here).
     const int slot = ctx->gslot ^= 1;
+    if (ctx->pending.active && ctx->pending.slot == slot) SPP_TRY(spp_gather_join(ctx));
     SPP_TRY(ctx->gcount[slot].reserve((8 + 2 * (kMaxLists + 1) + 2) * sizeof(int64_t)));
     unsigned long long* counters = ctx->gcount[slot].as<unsigned long long>();
     int64_t* off = ctx->gcount[slot].as<int64_t>() + 8;
@@ -362,32 +381,8 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         // the PCIe link, and every CU that hosts host-memory loads serves other kernels slowly.
         const int64_t mneed = (vecs + kBlock * kCopyUnroll - 1) / (kBlock * kCopyUnroll);
         const int mgrid = (int)(mneed < kMissBlocks ? mneed : kMissBlocks);
-        // the rows of the call before are complete from here on, and the PCIe link is idle: the hit
-        // copy runs alone
-        if (ctx->join_pending) {
-            SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
-            ctx->join_pending = false;
-        }
-        // Order on purpose: the hit copy runs first and alone, the miss copy starts on the side
-        // stream when it is done.  Run together, the host-memory loads of the miss kernel held up
-        // the hit copy on every CU they shared (it then ran at a third of its rate), and the hit
-        // copy is short next to the PCIe transfer, so nothing is gained by overlapping the two.
-        // The side stream still lets the caller's stream go on with independent work (the next
-        // minibatch's sampling) while the misses arrive.
-        {
-            ScopedTimer th(ctx, SPP_T_GATHER_HIT, st);
-            const char* loc = static_cast<const char*>(d_local);
-            const char* cr = static_cast<const char*>(crow);
-            const int64_t* hit_count = reinterpret_cast<const int64_t*>(counters + 4);
-            switch (V) {
-                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
-                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
-                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
-                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
-            }
-        }
         const bool miss_path = dremote != nullptr || lhost != nullptr;
-        if (miss_path) {
+        auto launch_miss = [&]() -> int {
             SPP_HIP(hipEventRecord(ctx->ev_fork, st));
             SPP_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
             {
@@ -403,22 +398,51 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
                     case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
                     default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
                 }
-                if (share_misses) {     // rows that share a fetched vertex, from the fetched row's output
-                    const int64_t* dup_count = reinterpret_cast<const int64_t*>(counters + 6);
-                    const int dgrid = ctx->num_cu * 4;
-                    switch (V) {
-                        case 16: gather_dup_kernel<16><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
-                        case 8:  gather_dup_kernel<8><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
-                        case 4:  gather_dup_kernel<4><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
-                        default: gather_dup_kernel<2><<<dgrid, kBlock, 0, ctx->side>>>(a.desc, duplist, dup_count, a.t, vpr); break;
-                    }
-                }
             }
-            SPP_HIP(hipEventRecord(ctx->ev_join, ctx->side));
+            SPP_HIP(hipEventRecord(ctx->ev_join[slot], ctx->side));
+            return SPP_OK;
+        };
+        auto launch_hit = [&]() {
+            ScopedTimer th(ctx, SPP_T_GATHER_HIT, st);
+            const char* loc = static_cast<const char*>(d_local);
+            const char* cr = static_cast<const char*>(crow);
+            const int64_t* hit_count = reinterpret_cast<const int64_t*>(counters + 4);
+            switch (V) {
+                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+            }
+        };
+        // Order of the copies.  The PCIe link is the scarce resource.  The stream waits for the miss
+        // copy of the call before (its rows are complete from there on), runs the hit copy alone,
+        // queues this call's miss copy on the side stream, and only then copies the rows that shared
+        // a vertex of the earlier miss copy (device to device), beside the new miss copy.
+        // kHitBesideMiss queues the new miss copy first instead, so that the link never idles and
+        // the hit copy runs beside it as well: measured on 64 minibatches of 66k rows, the link was
+        // then busy 99 % of the time instead of 94 %, but the host-memory loads held up the hit copy
+        // on the CUs they shared (0.57 ms instead of 0.40) and were held up themselves (9.17 ms
+        // instead of 8.92), and the whole pipeline gained 1.8 %.
+        if (kHitBesideMiss) {
+            if (miss_path) SPP_TRY(launch_miss());
+            SPP_TRY(spp_gather_join(ctx));
+            launch_hit();
+        } else {
+            const PendingGather before = ctx->pending;
+            if (before.active) {
+                SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join[before.slot], 0));
+                ctx->pending.active = false;
+            }
+            launch_hit();
+            if (miss_path) SPP_TRY(launch_miss());
+            if (before.active) SPP_TRY(launch_dup(ctx, before));
         }
         if (miss_path) {
-            if (flags & SPP_NO_JOIN) ctx->join_pending = true;
-            else SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join, 0));
+            PendingGather& pg = ctx->pending;
+            pg.active = true; pg.slot = slot; pg.has_dup = share_misses; pg.V = V; pg.vpr = vpr;
+            pg.desc = a.desc; pg.duplist = duplist; pg.dup_count = reinterpret_cast<const int64_t*>(counters + 6);
+            pg.t = a.t;
+            if (!(flags & SPP_NO_JOIN)) SPP_TRY(spp_gather_join(ctx));
         }
     }
     SPP_HIP(hipGetLastError());
@@ -452,9 +476,12 @@ extern "C" int spp_gather_features_split(spp_ctx* ctx, const spp_cache* cache, c
 
 extern "C" int spp_gather_join(spp_ctx* ctx) {
     SPP_CHECK(ctx, SPP_E_ARG, "spp_gather_join: ctx is null");
-    if (ctx->join_pending) {
-        SPP_HIP(hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
-        ctx->join_pending = false;
+    if (ctx->pending.active) {
+        const spp::PendingGather pg = ctx->pending;
+        ctx->pending.active = false;
+        SPP_HIP(hipSetDevice(ctx->device));
+        SPP_HIP(hipStreamWaitEvent(ctx->stream, ctx->ev_join[pg.slot], 0));
+        SPP_TRY(spp::launch_dup(ctx, pg));
     }
     return SPP_OK;
 }

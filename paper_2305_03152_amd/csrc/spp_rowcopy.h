@@ -7,7 +7,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "../../include/spp.h"
+#include "spp_common.h"
 #include "spp_device.h"
 
 namespace spp {
@@ -40,19 +40,7 @@ __device__ __forceinline__ void store_stream(void* p, typename VecOf<V>::type v)
 
 constexpr int kCopyUnroll = 4;          // vectors in flight per lane, indexed (PCIe) copy
 constexpr int kHitUnroll = 2;           // vectors in flight per lane, hit copy
-constexpr int kMaxLists = SPP_MAX_GATHER_LISTS;
 constexpr int64_t kListAlign = 2048;    // every list starts at a multiple of this in the virtual row space
-
-// Several id lists gathered by one set of launches.  List j owns the virtual rows
-// [off[j], off[j] + cnt[j]); off[] is padded to multiples of kListAlign so that one workgroup's
-// chunk of rows (or of vectors) never straddles two lists.
-struct ListTable {
-    const int32_t* ids[kMaxLists];
-    char*          out[kMaxLists];
-    const int64_t* off;     // device int64[n_lists + 1]
-    const int64_t* cnt;     // device int64[n_lists]
-    int            n_lists;
-};
 
 // The offsets and counts are read many times by every workgroup: a copy in LDS keeps the search for
 // a row's list off the global-memory latency path.

@@ -1,6 +1,6 @@
 // Node-wise fanout sampling into per-layer message-flow graphs (Sec. 2.3; the process of Sec. 3.1).
 //
-// Up to 32 minibatches are sampled by one set of launches: every kernel has a second grid dimension
+// Up to 64 minibatches are sampled by one set of launches: every kernel has a second grid dimension
 // that names the minibatch, and each minibatch has its own id table, flat-id buffer and counts, so
 // the minibatches never interact.  Per hop h, all on the context's stream with every count kept on
 // the device:

@@ -1,5 +1,5 @@
 """Parity at the full size of the Mid workload (2.4M vertices, ~121M edges, fp32 D=100, K=8,
-alpha=0.16), in the launch configuration bench.py times: groups of 32 minibatches sampled by one
+alpha=0.16), in the launch configuration bench.py times: groups of 64 minibatches sampled by one
 call and gathered by one set of launches, asynchronous calls with the join of the miss copy
 deferred, |S_L| read on the device; then the local-storage split, the access counts and the
 general-probability entry points at the same size."""
@@ -55,9 +55,9 @@ def test_mid_full_size():
     assert np.array_equal(cache.ids.cpu().numpy(), ids_ref) and ids_ref.size == cfg.cache_capacity()
     cache_rows = S.feature_rows(cfg, torch.from_numpy(ids_ref)).numpy()
 
-    _say("batches: groups of 32 per call, join deferred, two buffer sets (the benchmark's launch configuration)")
-    G8 = 32
-    batches = [b for ep in range(3) for b in S.epoch_batches(cfg, Tk, ep)][:2 * G8]       # 24 per epoch
+    _say("batches: groups of 64 per call, join deferred, two buffer sets (the benchmark's launch configuration)")
+    G8 = 64
+    batches = [b for ep in range(6) for b in S.epoch_batches(cfg, Tk, ep)][:2 * G8]       # 24 per epoch
     assert len(batches) == 2 * G8
     sets = []
     for _ in range(2):

@@ -289,9 +289,9 @@ def test_sample_multi_batches(spp, ctx, tiny_case):
         ref = oracle.sample_mfg(c.rp, c.col, s_, cfg.fanouts, cfg.seed_sampler, bi)
         _check_mfg(m, ref, cfg.L)
     with pytest.raises(spp.SppError):
-        spp.sample_mfg_multi(ctx, c.G, items * 7, cfg.fanouts, cfg.seed_sampler)       # 35 minibatches
-    _say("sample multi: 21 and 32 minibatches in one call")
-    for count in (21, 32):
+        spp.sample_mfg_multi(ctx, c.G, items * 13, cfg.fanouts, cfg.seed_sampler)       # 65 minibatches
+    _say("sample multi: 21, 40 and 64 minibatches in one call")
+    for count in (21, 40, 64):
         seeds = [rng.permutation(c.Tk)[:rng.integers(1, 60)] for _ in range(count)]
         items = [(torch.from_numpy(np.ascontiguousarray(s_)).cuda(), 900 + k, spp.MFGBuffers("cuda", 64, cfg.fanouts, cfg.N))
                  for k, s_ in enumerate(seeds)]
@@ -334,18 +334,18 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
         assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
         assert torch.all(out[n0:] == 0)
     with pytest.raises(spp.SppError):
-        spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists * 6)   # 36 lists
-    # maximal sharing: 32 lists of the same ids, no cache: every remote row but the first of a vertex is a copy
-    _say("gather multi: 32 identical lists")
+        spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists * 11)   # 66 lists
+    # maximal sharing: 64 lists of the same ids, no cache: every remote row but the first of a vertex is a copy
+    _say("gather multi: 64 identical lists")
     ids = torch.randint(0, cfg.N, (3000,), device="cuda", generator=g, dtype=torch.int32)
-    outs = [torch.zeros((3000, cfg.D), dtype=torch.float32, device="cuda") for _ in range(32)]
-    st32 = spp.gather_features_multi(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, [(ids, 3000, None, o) for o in outs])
+    outs = [torch.zeros((3000, cfg.D), dtype=torch.float32, device="cuda") for _ in range(64)]
+    st64 = spp.gather_features_multi(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, [(ids, 3000, None, o) for o in outs])
     want = S.feature_rows(cfg, ids.cpu())
     for o in outs:
         assert torch.equal(o.cpu(), want)
     idn = ids.cpu().numpy()
     rem = idn[(idn < c.lo) | (idn >= c.hi)]
-    assert st32["n_miss"] == 32 * rem.size and st32["n_miss_shared"] == 32 * rem.size - np.unique(rem).size
+    assert st64["n_miss"] == 64 * rem.size and st64["n_miss_shared"] == 64 * rem.size - np.unique(rem).size
     # miss copy left running on the side stream while the stream samples the next minibatch, joined later
     _say("gather multi: deferred join")
     for (_, _, _, out) in lists:
@@ -360,6 +360,21 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
     spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists[3:], sync=False, join=False)
     st2 = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists[:3])
     assert st2["n_local"] + st2["n_cache_hit"] + st2["n_miss"] == sum(sizes[:3])
+    # three unjoined gathers in a row, the middle one without rows: the third takes the workspace
+    # of the first, so it must join the first itself; shared rows are copied at the join
+    _say("gather multi: deferred joins around an empty call")
+    for (_, _, _, out) in lists:
+        out.zero_()
+    same = [(lists[5][0], sizes[5], None, torch.zeros_like(lists[5][3])) for _ in range(3)]
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, same, sync=False, join=False)
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, [], sync=False, join=False)
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists, sync=False, join=False)
+    ctx.sync()
+    want5 = S.feature_rows(cfg, lists[5][0][:sizes[5]].cpu())
+    for (_, _, _, out) in same:
+        assert torch.equal(out[:sizes[5]].cpu(), want5)
+    for (ids, n, n_dev, out), n0 in zip(lists, sizes):
+        assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
     cache.close()
 
 
