@@ -232,6 +232,9 @@ def main():
     ap.add_argument("--group", type=int, default=64,
                     help="minibatches a lane samples back to back and then gathers with ONE set of launches "
                          "(2 x pipeline x group minibatches are in flight; the paper keeps ten)")
+    ap.add_argument("--store-order", default="auto", choices=["auto", "on", "off"],
+                    help="fetch a group's missed rows in the order of the remote store (SPP_STORE_ORDER); auto: when "
+                         "the set-up groups fetched an eighth or more of the store's rows per group")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
     ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "policy-sweep", "general", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
@@ -389,15 +392,25 @@ def main():
             # copy (the previous group's rows are complete from there on), then copies the hits
             spp.gather_features_multi(c, cache, local, cfg.N, lo, hi, remote,
                                       [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(len(idx))],
-                                      sync=False, join=False)
+                                      sync=False, join=False, store_order=store_order)
         for c, _, _ in lanes:
             spp.gather_join(c)
 
     # set-up, not a step: every lane runs two full groups once, so that both buffer sets and both sets of
     # library workspaces exist before the warm-up (an allocation inside the timed region would stall it)
+    store_order = args.store_order == "on"
     torch.cuda.synchronize()
-    run(0, min(len(batches), 2 * P * Gsz))
+    for c, _, _ in lanes:
+        c.totals(reset=True)
+    n_setup = min(len(batches), 2 * P * Gsz)
+    run(0, n_setup)
     torch.cuda.synchronize()
+    # share of the remote store's rows that one group fetches: decides the order of the fetches
+    fetched = sum(t_["n_miss"] - t_["n_miss_shared"] for t_ in (c.totals(reset=True) for c, _, _ in lanes))
+    fetched_share = fetched / max(1, -(-n_setup // Gsz)) / max(nrem, 1)
+    if args.store_order == "auto":
+        store_order = fetched_share >= 0.125
+    log(f"a group fetches {fetched_share:.3f} of the remote store's rows; store order: {store_order}")
     run(0, W)
     torch.cuda.synchronize()
     for c, _, _ in lanes:
@@ -497,6 +510,8 @@ def main():
         "config": {"workload": f"{cfg.name}: N={g.N} M={g.M} D={cfg.D} {cfg.dtype} fanouts={list(cfg.fanouts)} "
                                f"B={cfg.B} K={cfg.K} alpha={cfg.alpha} owned partition {cfg.owned_partition}",
                    "lanes": P, "minibatches_per_gather_launch": Gsz, "minibatches_in_flight": 2 * P * Gsz,
+                   "misses_fetched_in": "store order" if store_order else "list order",
+                   "share_of_remote_store_fetched_per_launch": round(fetched_share, 4),
                    "avg_per_batch": {k: round(v, 1) for k, v in avg.items()},
                    "hit_rate_of_remote": avg["n_cache_hit"] / max(avg["n_cache_hit"] + avg["n_miss"], 1e-9)},
         "roofline": roof,

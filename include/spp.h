@@ -58,6 +58,8 @@ enum {
 #define SPP_GRAPH_IN_LISTS    0x4u   /* spp_graph_create: also build the transposed edge structure (who can sample u)
                                         that vip_propagate needs: 6 bytes per edge of device memory */
 #define SPP_NO_JOIN           0x8u   /* gather: leave the miss copy running on the side stream; see spp_gather_join */
+#define SPP_STORE_ORDER       0x10u  /* gather: fetch the call's missed remote rows in the order of the remote store;
+                                        see spp_gather_features_multi */
 
 typedef struct spp_ctx   spp_ctx;    /* workspaces, side stream, events */
 typedef struct spp_graph spp_graph;  /* refers to the caller's CSR; owns the library-built transposed structure */
@@ -205,7 +207,15 @@ int  spp_gather_join(spp_ctx* ctx);
  * classification, one hit copy, one miss copy), e.g. the minibatches a pipeline keeps in flight
  * (Sec. 4.3 keeps ten): each kernel then moves several minibatches' worth of rows per launch.
  * List j: d_out[i,:] = row of vertex d_node_ids[i], i < n (n an upper bound when d_n is given).
- * The statistics are summed over the lists. */
+ * The statistics are summed over the lists.
+ * A remote vertex that several rows of the call miss is read from the remote store once
+ * (n_miss_shared counts the other rows, which are copied on the device).
+ * SPP_STORE_ORDER changes how that is done, never the result: the missed vertices are marked in an
+ * array with one entry per row of the remote store (4 bytes each, cleared and scanned per call)
+ * and fetched in the store's order, so that rows that are neighbours in the store share the
+ * memory lines they straddle.  It pays when a call misses a sizeable share of the store (an
+ * eighth or more: then the fetch is 3 to 15 % faster) and costs a pass over that array
+ * otherwise. */
 typedef struct {
     const int32_t* d_node_ids;
     int64_t        n;

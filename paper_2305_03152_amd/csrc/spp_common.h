@@ -110,6 +110,7 @@ struct spp_ctx {
     spp::DevBuf gcount[2];              // device counters of the gather (int64[8]) and the list layout
     int         gslot = 0;              // set used by the last gather
     spp::DevBuf gtable;                 // vertices missed by the current gather call (id -> first row)
+    spp::DevBuf gfirst;                 // the same per row of the remote store (SPP_STORE_ORDER): first row that misses it
     int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
     int64_t*    totals = nullptr;       // device int64[16], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces

@@ -40,7 +40,8 @@ struct ClassifyArgs {
     int32_t*       misslist;           // virtual rows that miss
     int32_t*       hitlist;            // virtual rows served from the shard or the cache
     unsigned long long* counters;      // [0] local, [1] cache hit, [2] rows in misslist, [3] bad id, [4] rows in hitlist,
-                                       // [5] local rows read from the host (part of [0] and of [2]), [6] rows in duplist
+                                       // [5] local rows read from the host (part of [0] and of [2]), [6] rows in duplist,
+                                       // [7] rows in the store-ordered list
     unsigned long long* totals;        // context-wide running sums: [3] calls, [4] local, [5] cache hit,
                                        // [6] remote miss, [7] local rows read from the host
 };
@@ -49,12 +50,15 @@ struct PrologueArgs {
     int64_t        n[kMaxLists];       // host counts (upper bounds when n_ptr is given)
     const int64_t* n_ptr[kMaxLists];   // device counts or null
     int            n_lists;
+    int64_t        n_remote;           // rows of the remote store
 };
 
 // Zeroes the per-call counters and lays the lists out in the virtual row space.
-__global__ void gather_prologue_kernel(PrologueArgs p, unsigned long long* counters, int64_t* off, int64_t* cnt) {
+__global__ void gather_prologue_kernel(PrologueArgs p, unsigned long long* counters, int64_t* off, int64_t* cnt,
+                                       int64_t* minfo) {
     if (threadIdx.x < 8) counters[threadIdx.x] = 0ull;
     if (threadIdx.x == 0) {
+        minfo[2] = p.n_remote;
         int64_t o = 0;
         for (int j = 0; j < p.n_lists; ++j) {
             int64_t c = p.n_ptr[j] ? *p.n_ptr[j] : p.n[j];
@@ -121,6 +125,65 @@ __global__ void __launch_bounds__(kBlock) gather_share_kernel(unsigned long long
         }
     }
 }
+
+// The same with one entry per row of the remote store instead of a hashed table (SPP_STORE_ORDER):
+// every remote row of the miss list leaves the list; the row that claims its vertex is found again
+// by the scan over the store's rows that follows, which lists the claimers in store order.
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;
+__global__ void __launch_bounds__(kBlock) fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+__global__ void __launch_bounds__(kBlock) gather_share_direct_kernel(uint32_t* __restrict__ first,
+                                                                     int64_t* __restrict__ desc,
+                                                                     int32_t* __restrict__ misslist,
+                                                                     int32_t* __restrict__ duplist,
+                                                                     unsigned long long* __restrict__ counters,
+                                                                     unsigned long long* __restrict__ totals) {
+    __shared__ int scan_lds[4];
+    __shared__ unsigned long long base_lds;
+    const int64_t n = (int64_t)counters[2];
+    const int64_t n_round = (n + kBlock - 1) / kBlock * kBlock;            // whole workgroups reach the scan
+    for (int64_t m = (int64_t)blockIdx.x * kBlock + threadIdx.x; m < n_round; m += (int64_t)gridDim.x * kBlock) {
+        int32_t r = -1;
+        bool dup = false;
+        if (m < n) {
+            r = misslist[m];
+            const int64_t d = desc[r];
+            if (desc_tag(d) == kTagMiss) {
+                const uint32_t old = atomicCAS(&first[desc_row(d)], kNoRow, (uint32_t)r);
+                misslist[m] = -1;
+                if (old != kNoRow) {
+                    dup = true;
+                    desc[r] = make_desc(kTagDup, old);
+                }
+            }
+        }
+        int total;
+        const int ex = block_exclusive_scan(dup ? 1 : 0, scan_lds, total);
+        if (total) {                                                       // uniform over the workgroup
+            if (threadIdx.x == 0) {
+                base_lds = atomicAdd(&counters[6], (unsigned long long)total);
+                atomicAdd(&totals[8], (unsigned long long)total);
+            }
+            __syncthreads();
+            if (dup) duplist[base_lds + (unsigned long long)ex] = r;
+            __syncthreads();
+        }
+    }
+}
+struct ClaimedIn {
+    const uint32_t* first;
+    __device__ int operator()(int64_t i) const { return first[i] != kNoRow ? 1 : 0; }
+};
+struct ClaimedOut {
+    const uint32_t* first; int32_t* sorted;
+    __device__ void operator()(int64_t i, int ex, int v) const { if (v) sorted[(uint32_t)ex] = (int32_t)first[i]; }
+};
+struct ClaimedFin {
+    unsigned long long* count;
+    __device__ void operator()(int total) const { *count = (unsigned long long)(uint32_t)total; }
+};
 
 // One workgroup classifies a run of 2048 consecutive ids of one list, then reserves room for all of
 // its misses in the miss list with a single atomic (ranks inside the workgroup come from a scan),
@@ -328,7 +391,7 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     // gather before its own hit copy (if it had no rows and joined nothing, it is joined here).
     const int slot = ctx->gslot ^= 1;
     if (ctx->pending.active && ctx->pending.slot == slot) SPP_TRY(spp_gather_join(ctx));
-    SPP_TRY(ctx->gcount[slot].reserve((8 + 2 * (kMaxLists + 1) + 2) * sizeof(int64_t)));
+    SPP_TRY(ctx->gcount[slot].reserve((8 + 2 * (kMaxLists + 1) + 4) * sizeof(int64_t)));
     unsigned long long* counters = ctx->gcount[slot].as<unsigned long long>();
     int64_t* off = ctx->gcount[slot].as<int64_t>() + 8;
     int64_t* cnt = off + kMaxLists + 1;
@@ -336,17 +399,25 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     a.t.off = off; a.t.cnt = cnt;
     // several lists make it worth claiming missed vertices: one list of a sampler's distinct ids
     // has nothing to share
-    const bool share_misses = dremote != nullptr && n_lists > 1 && vbound > 0;
+    const int64_t n_remote = N - (hi - lo);
+    const bool store_order = (flags & SPP_STORE_ORDER) && dremote != nullptr && vbound > 0 && n_remote > 0;
+    const bool share_misses = dremote != nullptr && vbound > 0 && (n_lists > 1 || store_order);
+    const int order_grid = 256;         // workgroups of the scan over the store's rows
     uint32_t mcap = 0;
-    if (share_misses) {
+    if (store_order) {
+        SPP_TRY(ctx->gfirst.reserve((size_t)n_remote * sizeof(uint32_t)));
+        SPP_TRY(ctx->partials.reserve((size_t)order_grid * sizeof(int) + 64));
+    } else if (share_misses) {
         mcap = next_pow2((uint64_t)(2 * vbound > 1024 ? 2 * vbound : 1024));
         SPP_TRY(ctx->gtable.reserve((size_t)mcap * sizeof(uint64_t)));
     }
     if (vbound > 0) {
         SPP_TRY(ctx->srcdesc[slot].reserve((size_t)vbound * sizeof(int64_t)));
-        SPP_TRY(ctx->misslist[slot].reserve((size_t)vbound * sizeof(int32_t) * 3));     // miss list, hit list, copy list
+        // miss list, hit list, copy list, misses in store order
+        SPP_TRY(ctx->misslist[slot].reserve((size_t)vbound * sizeof(int32_t) * 4));
     }
-    gather_prologue_kernel<<<1, 64, 0, st>>>(pro, counters, off, cnt);
+    pro.n_remote = n_remote;
+    gather_prologue_kernel<<<1, 64, 0, st>>>(pro, counters, off, cnt, minfo);
     if (vbound > 0) {
         a.N = N; a.lo = lo; a.hi = hi;
         a.tab = cache && cache->limit > 0 ? reinterpret_cast<const unsigned long long*>(cache->table) : nullptr;
@@ -357,15 +428,22 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         a.desc = ctx->srcdesc[slot].as<int64_t>(); a.misslist = ctx->misslist[slot].as<int32_t>(); a.counters = counters;
         a.hitlist = a.misslist + vbound;
         int32_t* duplist = a.hitlist + vbound;
+        int32_t* ordered = duplist + vbound;
         a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
         const int64_t cneed = vbound / kListAlign;
         const int cgrid = (int)(cneed < (int64_t)ctx->num_cu * 8 ? cneed : (int64_t)ctx->num_cu * 8);
         {
             ScopedTimer tc(ctx, SPP_T_GATHER_CLASSIFY, st);
             classify_kernel<<<cgrid, kBlock, 0, st>>>(a);
-            if (share_misses) {
+            const int sgrid = ctx->num_cu * 4;
+            if (store_order) {
+                uint32_t* first = ctx->gfirst.as<uint32_t>();
+                fill_u32_kernel<<<sgrid, kBlock, 0, st>>>(first, n_remote, kNoRow);
+                gather_share_direct_kernel<<<sgrid, kBlock, 0, st>>>(first, a.desc, a.misslist, duplist, counters, a.totals);
+                grid_scan(st, order_grid, minfo + 2, ClaimedIn{first}, ClaimedOut{first, ordered}, ClaimedFin{counters + 7},
+                          ctx->partials.as<int>());
+            } else if (share_misses) {
                 unsigned long long* mtab = ctx->gtable.as<unsigned long long>();
-                const int sgrid = ctx->num_cu * 4;
                 gather_table_clear_kernel<<<sgrid, kBlock, 0, st>>>(mtab, counters, (int64_t)mcap, minfo);
                 gather_share_kernel<<<sgrid, kBlock, 0, st>>>(mtab, minfo, a.desc, a.misslist, duplist, counters, a.totals);
             }
@@ -387,17 +465,22 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
             SPP_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
             {
                 ScopedTimer tm(ctx, SPP_T_GATHER_MISS, ctx->side);
-                const int64_t* miss_count = reinterpret_cast<const int64_t*>(counters + 2);
                 // either store may be null (no remote store given, or no split local store): the
                 // kernel skips rows that would need it and the statistics of the call report them
                 const char* src = static_cast<const char*>(dremote);
                 const char* lh = static_cast<const char*>(lhost);
-                switch (V) {
-                    case 16: gather_miss_kernel<16><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
-                    case 8:  gather_miss_kernel<8><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
-                    case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
-                    default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, a.misslist, miss_count, a.t, vpr); break;
-                }
+                auto run = [&](const int32_t* list, const int64_t* count) {
+                    switch (V) {
+                        case 16: gather_miss_kernel<16><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                        case 8:  gather_miss_kernel<8><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                        case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                        default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                    }
+                };
+                // in store order: the claimed remote rows from the scan's list; the miss list then
+                // only holds local rows that live in host memory (a split local store)
+                if (store_order) run(ordered, reinterpret_cast<const int64_t*>(counters + 7));
+                if (!store_order || lhost) run(a.misslist, reinterpret_cast<const int64_t*>(counters + 2));
             }
             SPP_HIP(hipEventRecord(ctx->ev_join[slot], ctx->side));
             return SPP_OK;

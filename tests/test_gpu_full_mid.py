@@ -78,7 +78,7 @@ def test_mid_full_size():
         spp.gather_join(ctx)
         spp.gather_features_multi(ctx, cache, local, cfg.N, lo, hi, remote,
                                   [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(G8)],
-                                  sync=False, join=False)
+                                  sync=False, join=False, store_order=(gi == 1))     # both miss orders
     spp.gather_join(ctx)
     ctx.sync()
     count_ref = np.zeros(cfg.N, dtype=np.float32)

@@ -378,6 +378,73 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
     cache.close()
 
 
+def test_gather_in_store_order(spp, ctx, tiny_case):
+    """Missed rows fetched in the order of the remote store: same rows and statistics as the hashed path,
+    for several lists, one list with repeated ids, a split local store, unjoined calls in a row."""
+    c = tiny_case
+    cfg = c.cfg
+    p = spp.vip_propagate(ctx, c.G, c.Tk_d, cfg.B, cfg.fanouts)
+    cache = spp.build_vip_cache(ctx, p, c.lo, c.hi, cfg.K, cfg.alpha, c.remote, cfg.D, cfg.elem_bytes)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(17)
+    sizes = [0, 1, 2047, 2048, 2049, 7000, 3]
+    lists = []
+    for k, n in enumerate(sizes):
+        ids = torch.randint(0, cfg.N, (n + 5,), device="cuda", generator=g, dtype=torch.int32)
+        n_dev = torch.tensor([n], dtype=torch.int64, device="cuda") if k == 4 else None
+        lists.append((ids, n + 5 if n_dev is not None else n, n_dev, torch.zeros((n + 5, cfg.D), dtype=torch.float32, device="cuda")))
+    _say("store order: seven lists")
+    ref = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists)
+    outs_ref = [l[3].clone() for l in lists]
+    for l in lists:
+        l[3].zero_()
+    st = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists, store_order=True)
+    assert st == ref and st["n_miss_shared"] > 0
+    for (ids, n, n_dev, out), want, n0 in zip(lists, outs_ref, sizes):
+        assert torch.equal(out, want)
+        assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
+        assert torch.all(out[n0:] == 0)
+    _say("store order: one list, every id three times, no cache")
+    ids = torch.randint(0, cfg.N, (1500,), device="cuda", generator=g, dtype=torch.int32).repeat(3)
+    out, st1 = spp.gather_features(ctx, None, c.local_d, cfg.N, c.lo, c.hi, c.remote, ids, store_order=True)
+    assert torch.equal(out.cpu(), S.feature_rows(cfg, ids.cpu()))
+    idn = ids.cpu().numpy()
+    rem = idn[(idn < c.lo) | (idn >= c.hi)]
+    assert st1["n_miss"] == rem.size and st1["n_miss_shared"] == rem.size - np.unique(rem).size
+    assert st1["miss_bytes"] == np.unique(rem).size * cfg.D * cfg.elem_bytes
+    _say("store order: split local store, local rows from host memory beside the ordered remote rows")
+    local_host = c.local_d.cpu().pin_memory()
+    store = spp.build_local_store(ctx, p, c.lo, c.hi, 0.25, local_host)
+    for l in lists:
+        l[3].zero_()
+    ref_s = spp.gather_features_multi(ctx, cache, store, cfg.N, c.lo, c.hi, c.remote, lists)
+    for l in lists:
+        l[3].zero_()
+    st_s = spp.gather_features_multi(ctx, cache, store, cfg.N, c.lo, c.hi, c.remote, lists, store_order=True)
+    assert st_s == ref_s and st_s["n_local_host"] > 0
+    for (ids, n, n_dev, out), want in zip(lists, outs_ref):
+        assert torch.equal(out, want)
+    store.close()
+    _say("store order: unjoined calls in a row, then a call without the flag")
+    for l in lists:
+        l[3].zero_()
+    other = [(l[0], l[1], l[2], torch.zeros_like(l[3])) for l in lists]
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists, sync=False, join=False, store_order=True)
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, other, sync=False, join=False, store_order=True)
+    third = [(l[0], l[1], l[2], torch.zeros_like(l[3])) for l in lists]
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, third, sync=False, join=False)
+    ctx.sync()
+    for group in (lists, other, third):
+        for (ids, n, n_dev, out), want in zip(group, outs_ref):
+            assert torch.equal(out, want)
+    # nothing to order: no remote store and no remote id, an empty call
+    loc_ids = torch.arange(c.lo, c.lo + 50, dtype=torch.int32, device="cuda")
+    out, st0 = spp.gather_features(ctx, None, c.local_d, cfg.N, c.lo, c.hi, None, loc_ids, store_order=True)
+    assert torch.equal(out, c.local_d[:50]) and st0["n_miss"] == 0
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, [], store_order=True)
+    cache.close()
+
+
 def test_local_store_tiny(spp, ctx, tiny_case):
     """VIP-ordered local storage: rank array, device prefix, and the gather with the local rows split
     between device and host (Sec. 3.2 on host-to-device transfers, Sec. 4.1)."""
