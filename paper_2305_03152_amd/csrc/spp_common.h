@@ -109,6 +109,7 @@ struct spp_ctx {
     spp::DevBuf misslist[2];            // int32 positions of the rows that miss, then of the rows that hit
     spp::DevBuf gcount[2];              // device counters of the gather (int64[8]) and the list layout
     int         gslot = 0;              // set used by the last gather
+    int         miss_lds = 0;           // dynamic LDS bytes of the miss kernel
     spp::DevBuf gtable;                 // vertices missed by the current gather call (id -> first row)
     spp::DevBuf gfirst;                 // the same per row of the remote store (SPP_STORE_ORDER): first row that misses it
     int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters

@@ -5,14 +5,18 @@
 //                            source descriptor per row and the compacted list of missing rows
 //   hit copy  (main stream)  rows from the local shard or the replica cache, 128-bit vectors,
 //                            output walked flat so that stores are dense
-//   miss copy (side stream)  rows read straight from pinned host memory over PCIe, started
-//                            after the hit copy and joined before the call ends, or (SPP_NO_JOIN)
-//                            by the next gather, which classifies its own ids in the meantime
+//   miss copy (side stream)  rows read straight from pinned host memory over PCIe, queued
+//                            before the hit copy (on CUs of its own) and joined before the call
+//                            ends, or (SPP_NO_JOIN) by the next gather, which classifies its own
+//                            ids and queues its own miss copy in the meantime
 // A vertex that several rows of one call miss (several minibatches of a pipeline sampling the same
 // remote vertex) is fetched once: after the classification a pass over the miss list claims every
 // missed vertex in a table that lives for the call (sized for the misses, so a few MB); the row
 // that wins the claim stays in the miss list, the others are struck from it and copied from the
 // winner's output row at the join, on the main stream (beside the next miss copy, if there is one).
+// On request (SPP_STORE_ORDER) the claim uses one entry per row of the remote store instead of the
+// hashed table, and a scan over those entries lists the claimed rows in the store's order: rows
+// that are neighbours in the store then share the memory lines they straddle on their way over PCIe.
 // With a split local store (Sec. 3.2 on host-to-device transfers, Sec. 4.1) a local id is looked up
 // in the store's rank array: below the limit it is a hit on the device rows (stored in rank order),
 // else it joins the miss list and is read from the host-resident local rows.
@@ -23,7 +27,7 @@
 namespace spp {
 
 constexpr int kMissBlocks = 64;        // workgroups of the miss kernel (see gather_lists)
-constexpr bool kHitBesideMiss = false; // see the order of the copies in gather_lists
+constexpr int kMissThreads = 256;      // threads of each
 constexpr int kClsPer = 8;             // ids per thread: a workgroup classifies 2048 consecutive ids per round
 static_assert(kBlock * kClsPer == kListAlign, "a classification chunk must not straddle two lists");
 
@@ -455,11 +459,27 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         // dispatcher balance the copy around CUs that are busy with slow host-memory loads
         const int64_t hneed = (vecs + kBlock * kHitUnroll - 1) / (kBlock * kHitUnroll);
         const int grid = (int)(hneed < (int64_t)ctx->num_cu * 64 ? hneed : (int64_t)ctx->num_cu * 64);
-        // The miss kernel is kept to a few workgroups on purpose: 64 of them already saturate
-        // the PCIe link, and every CU that hosts host-memory loads serves other kernels slowly.
-        const int64_t mneed = (vecs + kBlock * kCopyUnroll - 1) / (kBlock * kCopyUnroll);
+        // The miss kernel is kept to 64 workgroups of 256 threads: they saturate the PCIe link (32
+        // workgroups of 512 threads or 16 of 1024 reach 95 % of their rate, 64 of 512 less).  A CU
+        // that hosts host-memory loads serves every other wavefront on it slowly, so each of these
+        // workgroups asks for nearly all of a CU's LDS, which keeps the hit copy (whose workgroups
+        // need a KB of LDS) and most other kernels off its CU: with the 64 CUs set aside like this
+        // the sampler beside a miss copy ran 25 % faster and the hit copy lost only the CUs' share.
+        const int64_t mneed = (vecs + kMissThreads * kCopyUnroll - 1) / (kMissThreads * kCopyUnroll);
         const int mgrid = (int)(mneed < kMissBlocks ? mneed : kMissBlocks);
         const bool miss_path = dremote != nullptr || lhost != nullptr;
+        if (miss_path && ctx->miss_lds == 0) {
+            int lds_max = 0;
+            SPP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, ctx->device));
+            // what is left beside this and the kernel's own KB is less than the hit copy needs
+            const int want = lds_max - 2048;
+            SPP_CHECK(want > 0, SPP_E_HIP, "spp_gather_features: the device reports %d bytes of LDS per workgroup", lds_max);
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_miss_kernel<16, kMissThreads>), hipFuncAttributeMaxDynamicSharedMemorySize, want));
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_miss_kernel<8, kMissThreads>), hipFuncAttributeMaxDynamicSharedMemorySize, want));
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_miss_kernel<4, kMissThreads>), hipFuncAttributeMaxDynamicSharedMemorySize, want));
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_miss_kernel<2, kMissThreads>), hipFuncAttributeMaxDynamicSharedMemorySize, want));
+            ctx->miss_lds = want;
+        }
         auto launch_miss = [&]() -> int {
             SPP_HIP(hipEventRecord(ctx->ev_fork, st));
             SPP_HIP(hipStreamWaitEvent(ctx->side, ctx->ev_fork, 0));
@@ -470,11 +490,12 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
                 const char* src = static_cast<const char*>(dremote);
                 const char* lh = static_cast<const char*>(lhost);
                 auto run = [&](const int32_t* list, const int64_t* count) {
+                    const size_t lds = (size_t)ctx->miss_lds;
                     switch (V) {
-                        case 16: gather_miss_kernel<16><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
-                        case 8:  gather_miss_kernel<8><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
-                        case 4:  gather_miss_kernel<4><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
-                        default: gather_miss_kernel<2><<<mgrid, kBlock, 0, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                        case 16: gather_miss_kernel<16, kMissThreads><<<mgrid, kMissThreads, lds, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                        case 8:  gather_miss_kernel<8, kMissThreads><<<mgrid, kMissThreads, lds, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                        case 4:  gather_miss_kernel<4, kMissThreads><<<mgrid, kMissThreads, lds, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
+                        default: gather_miss_kernel<2, kMissThreads><<<mgrid, kMissThreads, lds, ctx->side>>>(src, lh, a.desc, list, count, a.t, vpr); break;
                     }
                 };
                 // in store order: the claimed remote rows from the scan's list; the miss list then
@@ -497,29 +518,17 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
                 default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
             }
         };
-        // Order of the copies.  The PCIe link is the scarce resource.  The stream waits for the miss
-        // copy of the call before (its rows are complete from there on), runs the hit copy alone,
-        // queues this call's miss copy on the side stream, and only then copies the rows that shared
-        // a vertex of the earlier miss copy (device to device), beside the new miss copy.
-        // kHitBesideMiss queues the new miss copy first instead, so that the link never idles and
-        // the hit copy runs beside it as well: measured on 64 minibatches of 66k rows, the link was
-        // then busy 99 % of the time instead of 94 %, but the host-memory loads held up the hit copy
-        // on the CUs they shared (0.57 ms instead of 0.40) and were held up themselves (9.17 ms
-        // instead of 8.92), and the whole pipeline gained 1.8 %.
-        if (kHitBesideMiss) {
-            if (miss_path) SPP_TRY(launch_miss());
-            SPP_TRY(spp_gather_join(ctx));
-            launch_hit();
-        } else {
-            const PendingGather before = ctx->pending;
-            if (before.active) {
-                SPP_HIP(hipStreamWaitEvent(st, ctx->ev_join[before.slot], 0));
-                ctx->pending.active = false;
-            }
-            launch_hit();
-            if (miss_path) SPP_TRY(launch_miss());
-            if (before.active) SPP_TRY(launch_dup(ctx, before));
-        }
+        // Order of the copies.  The PCIe link is the scarce resource, so this call's miss copy is
+        // queued on the side stream as soon as its lists are final: it starts the moment the miss
+        // copy of the call before ends, and the link never idles.  The stream then waits for that
+        // earlier miss copy, copies the rows that shared one of its vertices (device to device: the
+        // call before is complete from there on) and runs the hit copy, both beside the new miss
+        // copy, on the CUs it leaves free.  (Hit copy first and alone, then the miss copy: the hit
+        // copy runs a fifth faster with the whole chip, the link idles meanwhile, and the pipeline
+        // was 3 to 5 % slower.)
+        if (miss_path) SPP_TRY(launch_miss());
+        SPP_TRY(spp_gather_join(ctx));
+        launch_hit();
         if (miss_path) {
             PendingGather& pg = ctx->pending;
             pg.active = true; pg.slot = slot; pg.has_dup = share_misses; pg.V = V; pg.vpr = vpr;

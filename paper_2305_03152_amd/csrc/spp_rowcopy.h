@@ -110,8 +110,8 @@ __global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __res
 // Miss path: rows read straight from the remote store (pinned host memory over PCIe, or device
 // memory), or from the host-resident part of the local rows.  misslist[m] is a virtual row; its
 // descriptor names the store and the row in it.
-template <int V>
-__global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restrict__ src,
+template <int V, int BS = kBlock>
+__global__ void __launch_bounds__(BS) gather_miss_kernel(const char* __restrict__ src,
                                                              const char* __restrict__ local_host,
                                                              const int64_t* __restrict__ desc,
                                                              const int32_t* __restrict__ misslist,
@@ -122,14 +122,14 @@ __global__ void __launch_bounds__(kBlock) gather_miss_kernel(const char* __restr
     load_lists(t, ls);
     const uint64_t total = (uint64_t)(*count_ptr) * vpr;
     const bool small = total <= 0xFFFFFFFFull;
-    const uint64_t span = (uint64_t)kBlock * kCopyUnroll;
+    const uint64_t span = (uint64_t)BS * kCopyUnroll;
     for (uint64_t base = (uint64_t)blockIdx.x * span; base < total; base += (uint64_t)gridDim.x * span) {
         vec_t v[kCopyUnroll];
         char* dst[kCopyUnroll];
         bool ok[kCopyUnroll];
 #pragma unroll
         for (int u = 0; u < kCopyUnroll; ++u) {
-            const uint64_t c = base + (uint64_t)u * kBlock + threadIdx.x;
+            const uint64_t c = base + (uint64_t)u * BS + threadIdx.x;
             ok[u] = c < total;
             if (ok[u]) {
                 const uint64_t m = small ? (uint64_t)((uint32_t)c / vpr) : c / vpr;
