@@ -7,7 +7,8 @@
 //   1. grid scan of c_i = min(f_h, d(S_{h-1}[i]))            -> indptr of MFG h, e_h
 //   2. sample: a group of G lanes (G = 8/16/32/64 >= f_h) per target draws its slots in parallel
 //      (one Philox block per lane), resolves Floyd's "already taken" rule with ballots, reads the
-//      neighbour ids and offers (id, n_{h-1} + flat position) to the id table with atomic min
+//      neighbour ids, offers (id, n_{h-1} + flat position) to the id table with atomic min and
+//      keeps the table slot of every sampled id, so that the later steps read the entry directly
 //   3. grid scan of "this flat entry is the first appearance of a new id"
 //                                                            -> S_h appended in order, n_h, table value := local id
 //   4. relabel: src[e] = table value of the e-th sampled id
@@ -56,7 +57,8 @@ struct SampleArgs {
     int64_t        N;
     unsigned long long* tab;            // one region of `cap` entries per minibatch
     int64_t        cap;                 // slots per region (a power of two, sized for the bound on |S_L|)
-    int32_t*       flat;                // one region of `flat_stride` sampled global ids per minibatch (current hop)
+    int32_t*       flat;                // one region of `flat_stride` entries per minibatch: the id-table slot of
+                                        // every sampled id of the current hop, in flat (edge) order
     int64_t        flat_stride;
     unsigned long long* totals;         // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
     int*           bad;
@@ -210,16 +212,19 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
         // its neighbour
         const bool spare = c < G;
         uint32_t key = 0, val = 0;
+        int64_t e = -1;                            // flat position of this lane's sampled id, if it has one
         bool ins = false;
         if (valid && j < c) {
             const int32_t gid = a.col[r0 + pos];
-            const int64_t e = (int64_t)off + j;
-            flat[e] = gid;
+            e = (int64_t)off + j;
             key = (uint32_t)gid; val = (uint32_t)(n_prev + e); ins = true;
         } else if (valid && spare && j == G - 1) {
             key = (uint32_t)v; val = (uint32_t)i; ins = true;
         }
-        if (ins) table_insert_min(tab, mask, shift, key, val);
+        if (ins) {
+            const uint32_t slot = table_insert_min(tab, mask, shift, key, val);
+            if (e >= 0) flat[e] = (int32_t)slot;
+        }
         if (valid && !spare && j == 0) table_insert_min(tab, mask, shift, (uint32_t)v, (uint32_t)i);
     }
 }
@@ -296,8 +301,7 @@ __global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, co
             if (take) {
                 const int64_t pos = e + __popcll(m & lt_mask);
                 const int32_t gid = a.col[r0 + k];
-                flat[pos] = gid;
-                table_insert_min(tab, mask, shift, (uint32_t)gid, (uint32_t)(n_prev + pos));
+                flat[pos] = (int32_t)table_insert_min(tab, mask, shift, (uint32_t)gid, (uint32_t)(n_prev + pos));
             }
             e += __popcll(m);
         }
@@ -309,8 +313,7 @@ struct NewIn {
     SampleArgs a; const BatchTable* t;
     __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[kE + a.h]; }
     __device__ int operator()(int j, int64_t e) const {
-        uint32_t val = 0;
-        table_find(tab_of(a, j), t->b[j].tinfo[0], (int)t->b[j].tinfo[1], (uint32_t)flat_of(a, j)[e], val);
+        const uint32_t val = (uint32_t)tab_of(a, j)[(uint32_t)flat_of(a, j)[e]];
         return (int64_t)val == t->b[j].counts[a.h - 1] + e ? 1 : 0;
     }
 };
@@ -319,9 +322,8 @@ struct NewOut {
     __device__ void operator()(int j, int64_t e, int ex, int v) const {
         if (!v || t->b[j].tinfo[2]) return;
         unsigned long long* tab = tab_of(a, j);
-        const uint32_t gid = (uint32_t)flat_of(a, j)[e];
-        uint32_t val = 0;
-        const int64_t slot = table_find(tab, t->b[j].tinfo[0], (int)t->b[j].tinfo[1], gid, val);
+        const uint32_t slot = (uint32_t)flat_of(a, j)[e];
+        const uint32_t gid = (uint32_t)(tab[slot] >> 32);            // a slot's key never changes
         const int64_t id = t->b[j].counts[a.h - 1] + ex;
         t->b[j].S[id] = (int32_t)gid;
         // the new value is <= the old one and is never equal to another entry's own position, so
@@ -355,14 +357,8 @@ __device__ __forceinline__ void relabel_rows(const SampleArgs& a, const BatchTab
     const unsigned long long* tab = tab_of(a, j);
     const int32_t* __restrict__ flat = flat_of(a, j);
     int32_t* __restrict__ src = t->b[j].src[a.h - 1];
-    const uint32_t mask = t->b[j].tinfo[0];
-    const int shift = (int)t->b[j].tinfo[1];
     const int64_t stride = (int64_t)gx * kBlock;
-    for (int64_t e = (int64_t)x * kBlock + threadIdx.x; e < e_h; e += stride) {
-        uint32_t val = 0;
-        table_find(tab, mask, shift, (uint32_t)flat[e], val);
-        src[e] = (int32_t)val;
-    }
+    for (int64_t e = (int64_t)x * kBlock + threadIdx.x; e < e_h; e += stride) src[e] = (int32_t)(uint32_t)tab[(uint32_t)flat[e]];
 }
 __global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
     const BatchBlock bb = batch_block();
@@ -508,7 +504,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
         const int64_t g = need < 1 ? 1 : (need < lim ? need : lim);
         return (unsigned)((g + 7) & ~(int64_t)7);
     };
-    const int64_t share = (int64_t)ctx->num_cu * 16 / n_items + 1;    // workgroups per minibatch in the wide kernels
+    const int64_t share = (int64_t)ctx->num_cu * 64 / n_items + 1;    // workgroups per minibatch in the wide kernels
     {
         ScopedTimer tt(ctx, SPP_T_SAMPLE, st);
         for (int first = 0; first < n_items; first += kStoreChunk) {
