@@ -158,7 +158,7 @@ int  spp_sample_mfg(spp_ctx* ctx, const spp_graph* g, const int32_t* d_seeds, in
 /* The same sampling for up to SPP_MAX_SAMPLE_BATCHES minibatches in one set of launches (every kernel
  * gets a second grid dimension that names the minibatch; each minibatch has its own id table and
  * counts and its own caller-provided spp_mfg, so results are those of one call per minibatch).
- * A single minibatch of B = 1024 seeds cannot fill 256 CUs, and its two dozen launches are latency-bound;
+ * A single minibatch of B = 1024 seeds cannot fill 256 CUs, and its dependent launches are latency-bound;
  * sampling the minibatches a pipeline keeps in flight together spreads that latency over all of them. */
 typedef struct {
     const int32_t* d_seeds;

@@ -1,5 +1,6 @@
-// Device-side building blocks shared by the kernels: wavefront (64-lane) scans, a three-launch
-// grid scan whose length is read on the device, the open-addressing id table, Philox-4x32-10.
+// Device-side building blocks shared by the kernels: wavefront (64-lane) scans, grid scans whose
+// length is read on the device (three launches; two for several sequences at once), the
+// open-addressing id table, Philox-4x32-10.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -144,15 +145,24 @@ inline void grid_scan(hipStream_t st, int grid, const int64_t* n_ptr, In in, Out
     scan_write_kernel<In, Out><<<grid, kBlock, 0, st>>>(n_ptr, in, out, partial);
 }
 
-// The same scan for several independent sequences at once; batch_block() names the sequence ("batch") j.
+// The same scan for several independent sequences at once, in two launches; batch_block() names the
+// sequence ("batch") j.
 //   In:  int64_t n(int j) const (length, read on the device); int operator()(int j, int64_t i) const
-//   Out: void operator()(int j, int64_t i, int ex, int v) const
-//   Fin: void operator()(int j, int total) const
-// `partial` holds gridDim.x ints per sequence.
+//   Out: void operator()(int j, int64_t i, int ex, int v, int total) const
+//   Fin: void operator()(int j, int total) const      called once per sequence, by one thread
+// `partial` holds gridDim.x ints per sequence.  Every workgroup of the second launch adds up the
+// partial sums of its sequence itself (there are a few dozen), so no launch stands between the two
+// passes; Fin runs at the start of the second launch, in workgroup 0 of the sequence, which means
+// that the other workgroups of that launch must not read what Fin writes: Out and Tail get the
+// sequence's total and derive what they need from it.
 // Two hooks let independent work ride in the same launches (a launch costs more than most of
 // these steps): Head: void operator()(int j, unsigned x, unsigned gx) const runs before the
-// reduction, Tail after the write pass; x is the workgroup's index among the gx of sequence j.
-struct NoHook { __device__ void operator()(int, unsigned, unsigned) const {} };
+// reduction, Tail: void operator()(int j, unsigned x, unsigned gx, int total) const after the write
+// pass; x is the workgroup's index among the gx of sequence j.
+struct NoHook {
+    __device__ void operator()(int, unsigned, unsigned) const {}
+    __device__ void operator()(int, unsigned, unsigned, int) const {}
+};
 
 template <class In, class Head>
 __global__ void __launch_bounds__(kBlock) bscan_reduce_kernel(In in, int* partial, Head head) {
@@ -168,48 +178,39 @@ __global__ void __launch_bounds__(kBlock) bscan_reduce_kernel(In in, int* partia
     if (threadIdx.x == 0) partial[(int64_t)j * gridDim.x + bb.x] = t;
 }
 
-template <class Fin>
-__global__ void __launch_bounds__(kBlock) bscan_partials_kernel(int* partial, int nparts, Fin fin) {
-    __shared__ int lds[4];
-    const int j = blockIdx.x;                       // one workgroup per sequence
-    int* p = partial + (int64_t)j * nparts;
-    int carry = 0;
-    for (int base = 0; base < nparts; base += kBlock) {
-        int i = base + threadIdx.x;
-        int v = i < nparts ? p[i] : 0;
-        int total;
-        int ex = block_exclusive_scan(v, lds, total);
-        if (i < nparts) p[i] = uadd(carry, ex);
-        carry = uadd(carry, total);
-    }
-    if (threadIdx.x == 0) fin(j, carry);
-}
-
-template <class In, class Out, class Tail>
-__global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, const int* partial, Tail tail) {
+template <class In, class Out, class Fin, class Tail>
+__global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, Fin fin, const int* partial, Tail tail) {
     __shared__ int lds[4];
     const BatchBlock bb = batch_block();
     const int j = bb.j;
+    // this workgroup's prefix and the sequence's total, from the partial sums of the first launch
+    const int* p = partial + (int64_t)j * gridDim.x;
+    int carry = 0, seq_total = 0;
+    for (unsigned base = 0; base < gridDim.x; base += kBlock) {
+        const unsigned i = base + threadIdx.x;
+        const int v = i < gridDim.x ? p[i] : 0;
+        seq_total = uadd(seq_total, block_reduce_sum(v, lds));
+        carry = uadd(carry, block_reduce_sum(i < bb.x ? v : 0, lds));
+    }
+    if (bb.x == 0 && threadIdx.x == 0) fin(j, seq_total);
     int64_t b, e;
     scan_range(in.n(j), bb.x, b, e);
-    int carry = partial[(int64_t)j * gridDim.x + bb.x];
     for (int64_t base = b; base < e; base += kBlock) {
         int64_t i = base + threadIdx.x;
         int v = i < e ? in(j, i) : 0;
         int total;
         int ex = block_exclusive_scan(v, lds, total);
-        if (i < e) out(j, i, uadd(carry, ex), v);
+        if (i < e) out(j, i, uadd(carry, ex), v, seq_total);
         carry = uadd(carry, total);
     }
-    tail(j, bb.x, gridDim.x);
+    tail(j, bb.x, gridDim.x, seq_total);
 }
 
 template <class In, class Out, class Fin, class Head = NoHook, class Tail = NoHook>
 inline void grid_scan_batched(hipStream_t st, int grid, int nbatch, In in, Out out, Fin fin, int* partial,
                               Head head = Head(), Tail tail = Tail()) {
     bscan_reduce_kernel<In, Head><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, partial, head);
-    bscan_partials_kernel<Fin><<<nbatch, kBlock, 0, st>>>(partial, grid, fin);
-    bscan_write_kernel<In, Out, Tail><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, out, partial, tail);
+    bscan_write_kernel<In, Out, Fin, Tail><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, out, fin, partial, tail);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -109,33 +109,39 @@ struct CountIn {
 };
 struct CountOut {
     SampleArgs a; const BatchTable* t;
-    __device__ void operator()(int j, int64_t i, int ex, int) const { t->b[j].indptr[a.h - 1][i] = ex; }
+    __device__ void operator()(int j, int64_t i, int ex, int, int) const { t->b[j].indptr[a.h - 1][i] = ex; }
 };
+// With given probabilities sizes are not bounded by fanouts: the 64-bit count of the counting pass
+// decides whether the caller's buffers (and the table region laid out for them) hold this hop.
+// The count stays as it is until the hop's last scan resets it, so every workgroup of a launch
+// reads the same decision.
+__device__ __forceinline__ bool hop_overflows(const SampleArgs& a, const BatchDesc& b) {
+    return a.t != nullptr && *b.taken > (unsigned long long)b.ecap[a.h - 1];
+}
+// This hop's table: the smallest power of two >= 2 (n_{h-1} + e_h), at least 1024 slots, never more
+// than the region (the host sized it for the bound, which dominates).
+__device__ __forceinline__ void hop_table(const SampleArgs& a, int64_t n_prev, int e_h, uint32_t& capj, int& shift) {
+    const uint64_t want = 2ull * (uint64_t)(n_prev + (int64_t)(uint32_t)e_h);
+    capj = 1024;
+    shift = 22;
+    while (capj < want && (int64_t)capj < a.cap) { capj <<= 1; --shift; }
+}
 struct CountFin {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int total) const {
         int64_t* c = t->b[j].counts;
         if (t->b[j].tinfo[2]) return;                        // abandoned at an earlier hop
-        if (a.t) {
-            // sizes are not bounded by fanouts: the 64-bit count of the counting pass decides whether the
-            // caller's buffers (and the table region laid out for them) hold this hop
-            const unsigned long long taken = *t->b[j].taken;
-            *t->b[j].taken = 0ull;
-            if (taken > (unsigned long long)t->b[j].ecap[a.h - 1]) {
-                t->b[j].tinfo[2] = 1;
-                atomicOr(a.ovf, 1);
-                return;
-            }
+        if (hop_overflows(a, t->b[j])) {
+            t->b[j].tinfo[2] = 1;
+            atomicOr(a.ovf, 1);
+            return;
         }
         t->b[j].indptr[a.h - 1][c[a.h - 1]] = total;
         c[kE + a.h] = total;
         atomicAdd(&a.totals[2], (unsigned long long)(uint32_t)total);
-        // this hop's table: the smallest power of two >= 2 (n_{h-1} + e_h), at least 1024 slots,
-        // never more than the region (the host sized it for the bound, which dominates)
-        const uint64_t want = 2ull * (uint64_t)(c[a.h - 1] + total);
-        uint32_t capj = 1024;
-        int shift = 22;
-        while (capj < want && (int64_t)capj < a.cap) { capj <<= 1; --shift; }
+        uint32_t capj;
+        int shift;
+        hop_table(a, c[a.h - 1], total, capj, shift);
         t->b[j].tinfo[0] = capj - 1;
         t->b[j].tinfo[1] = (uint32_t)shift;
     }
@@ -143,15 +149,18 @@ struct CountFin {
 
 // ---- step 2 ----
 // Empties the part of the region that this hop's table occupies.  Rides at the end of the launch
-// that writes the hop's offsets: CountFin has fixed the table's size in the launch before.
+// that writes the hop's offsets; the table's size follows from the scan's total, which every
+// workgroup of that launch has.
 struct TableClear {
     SampleArgs a; const BatchTable* t;
-    __device__ void operator()(int j, unsigned x, unsigned gx) const {
-        if (t->b[j].tinfo[2]) return;
+    __device__ void operator()(int j, unsigned x, unsigned gx, int total) const {
+        if (t->b[j].tinfo[2] || hop_overflows(a, t->b[j])) return;
         unsigned long long* tab = tab_of(a, j);
-        const int64_t capj = (int64_t)t->b[j].tinfo[0] + 1;
+        uint32_t capj;
+        int shift;
+        hop_table(a, t->b[j].counts[a.h - 1], total, capj, shift);
         const int64_t stride = (int64_t)gx * kBlock;
-        for (int64_t i = (int64_t)x * kBlock + threadIdx.x; i < capj; i += stride) tab[i] = ~0ull;
+        for (int64_t i = (int64_t)x * kBlock + threadIdx.x; i < (int64_t)capj; i += stride) tab[i] = ~0ull;
     }
 };
 
@@ -319,12 +328,14 @@ struct NewIn {
 };
 struct NewOut {
     SampleArgs a; const BatchTable* t;
-    __device__ void operator()(int j, int64_t e, int ex, int v) const {
+    __device__ void operator()(int j, int64_t e, int ex, int v, int total) const {
         if (!v || t->b[j].tinfo[2]) return;
+        const int64_t n_prev = t->b[j].counts[a.h - 1];
+        if (a.t && n_prev + (int64_t)(uint32_t)total > t->b[j].ncap) return;      // NewFin abandons the minibatch
         unsigned long long* tab = tab_of(a, j);
         const uint32_t slot = (uint32_t)flat_of(a, j)[e];
         const uint32_t gid = (uint32_t)(tab[slot] >> 32);            // a slot's key never changes
-        const int64_t id = t->b[j].counts[a.h - 1] + ex;
+        const int64_t id = n_prev + ex;
         t->b[j].S[id] = (int32_t)gid;
         // the new value is <= the old one and is never equal to another entry's own position, so
         // threads still testing "first appearance" read either value with the same outcome
@@ -336,8 +347,9 @@ struct NewFin {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int total) const {
         int64_t* c = t->b[j].counts;
+        if (a.t) *t->b[j].taken = 0ull;                    // the next hop counts from zero
         if (t->b[j].tinfo[2]) return;
-        const int64_t n = c[a.h - 1] + total;
+        const int64_t n = c[a.h - 1] + (int64_t)(uint32_t)total;
         if (a.t && n > t->b[j].ncap) {                     // the new ids do not fit the caller's buffer
             t->b[j].tinfo[2] = 1;
             atomicOr(a.ovf, 1);
