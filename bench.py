@@ -452,7 +452,8 @@ def main():
     roof = {"bound": "hbm", "achieved": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms > 0 else 0.0,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>",
             "traffic": measured.get("gather_hit") if P == 1 else None,
-            "bytes_per_launch": hit_bytes, "avg_launch_ms": hit_ms}
+            "bytes_per_launch": hit_bytes, "avg_launch_ms": hit_ms,
+            "note": "runs beside the group's PCIe miss copy, whose 64 workgroups hold 64 of the 256 CUs"}
     roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
     # bytes that cross PCIe: a vertex missed by several minibatches of a group is read once and copied on the device
     miss_bytes = (tot["n_miss"] - tot["n_miss_shared"]) / max(cnt[T_MISS], 1) * row_bytes
