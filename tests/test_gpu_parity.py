@@ -138,6 +138,50 @@ def test_sampler_mini(spp, ctx):
         _check_mfg(m, ref, len(fan))
 
 
+def _random_graph(rng, N, degrees):
+    """CSR with the given out-degree per vertex, neighbours drawn without repetition, sorted."""
+    rp = np.zeros(N + 1, dtype=np.int64)
+    cols = []
+    for v in range(N):
+        d = int(degrees[v])
+        cols.append(np.sort(rng.choice(N, size=d, replace=False)).astype(np.int32))
+        rp[v + 1] = rp[v] + d
+    return rp, (np.concatenate(cols) if cols else np.zeros(0, np.int32))
+
+
+@pytest.mark.parametrize("fanouts", [(64,), (63, 2), (33, 3), (32, 2), (17, 9, 1), (16, 16), (9, 8, 7), (8, 1, 8), (1,) * 8,
+                                     (2,) * 8, (3, 1, 2, 1, 3, 1, 2, 1)])
+def test_sampler_and_vip_shape_sweep(spp, ctx, fanouts):
+    """Every lane-group width of the sampler (8/16/32/64), the largest fanout and the largest number
+    of hops, on a graph whose degrees sit at and around each fanout (0, 1, f-1, f, f+1, hubs);
+    vertex-inclusion probabilities on the same graph."""
+    rng = np.random.default_rng(sum(fanouts) * 131 + len(fanouts))
+    N = 700
+    marks = sorted({0, 1, 2, 600} | {max(0, f + d) for f in fanouts for d in (-1, 0, 1)})
+    degrees = rng.choice(np.asarray(marks), size=N)
+    degrees[:8] = [0, 1, 600, 65, 64, 63, 2, 0]
+    rp, col = _random_graph(rng, N, degrees)
+    dev = torch.device("cuda:0")
+    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), in_lists=True)
+    L = len(fanouts)
+    seeds = np.concatenate([np.arange(8), 8 + rng.permutation(N - 8)[:43]]).astype(np.int32)    # distinct, as a minibatch is
+    _say("shape sweep: fanouts", fanouts, "M", col.size)
+    for bi in (0, 7):
+        m = spp.sample_mfg(ctx, G, torch.from_numpy(seeds).to(dev), fanouts, 99, bi)
+        _check_mfg(m, oracle.sample_mfg(rp, col, seeds, fanouts, 99, bi), L)
+    items = [(torch.from_numpy(seeds[:k]).to(dev), 20 + k, spp.MFGBuffers("cuda", 64, fanouts, N)) for k in (51, 1, 17)]
+    spp.sample_mfg_multi(ctx, G, items, fanouts, 5)
+    for (sd, bi, m), k in zip(items, (51, 1, 17)):
+        _check_mfg(m, oracle.sample_mfg(rp, col, seeds[:k], fanouts, 5, bi), L)
+    T = np.sort(seeds)
+    p, ph = spp.vip_propagate(ctx, G, torch.from_numpy(T).to(dev), 16, fanouts, per_hop=True)
+    ref_t, ref_h = oracle.vip(rp, col, T, 16, fanouts)
+    _check_vip(p, ref_t)
+    for h in range(L):
+        _check_vip(ph[h], ref_h[h])
+    G.close()
+
+
 # ----------------------------------------------------------------------------------------------
 # Tiny config, all four calls
 # ----------------------------------------------------------------------------------------------
