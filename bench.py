@@ -276,8 +276,9 @@ def main():
         return
     K, W = args.steps, args.warmup
     P = max(1, args.pipeline)
-    # groups of `group` minibatches, but at least about four groups in the timed region
-    Gsz = max(1, min(args.group, 64, max(1, K // (4 * P))))
+    # groups of `group` minibatches; a short run is one group per lane (the larger the group, the more of its
+    # missed rows are shared, and PCIe is what bounds the step)
+    Gsz = max(1, min(args.group, 64, -(-K // P)))
     lo, hi = cfg.bounds()
     row_bytes = cfg.D * cfg.elem_bytes
 
