@@ -466,7 +466,9 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         // need a KB of LDS) and most other kernels off its CU: with the 64 CUs set aside like this
         // the sampler beside a miss copy ran 25 % faster and the hit copy lost only the CUs' share.
         const int64_t mneed = (vecs + kMissThreads * kCopyUnroll - 1) / (kMissThreads * kCopyUnroll);
-        const int mgrid = (int)(mneed < kMissBlocks ? mneed : kMissBlocks);
+        const int quarter = ctx->num_cu / 4 > 0 ? ctx->num_cu / 4 : 1;
+        const int mmax = quarter < kMissBlocks ? quarter : kMissBlocks;        // a quarter of the CUs at most
+        const int mgrid = (int)(mneed < mmax ? mneed : mmax);
         const bool miss_path = dremote != nullptr || lhost != nullptr;
         if (miss_path && ctx->miss_lds == 0) {
             int lds_max = 0;
