@@ -56,7 +56,7 @@ enum {
 #define SPP_SYNC              0x1u   /* wait for the stream before returning and fill host outputs */
 #define SPP_VIP_INCLUDE_HOP0  0x2u   /* also multiply (1 - p^[0]) into eq. (1); default: as printed, h = 1..L */
 #define SPP_GRAPH_IN_LISTS    0x4u   /* spp_graph_create: also build the transposed edge structure (who can sample u)
-                                        that vip_propagate needs: 6 bytes per edge of device memory */
+                                        that vip_propagate needs: 4 bytes per edge of device memory */
 #define SPP_NO_JOIN           0x8u   /* gather: leave the miss copy running on the side stream; see spp_gather_join */
 #define SPP_STORE_ORDER       0x10u  /* gather: fetch the call's missed remote rows in the order of the remote store;
                                         see spp_gather_features_multi */
@@ -76,9 +76,10 @@ void spp_ctx_destroy(spp_ctx* ctx);
 int  spp_ctx_sync(spp_ctx* ctx);
 
 /* Wraps a device CSR (not copied; must outlive the handle).  With SPP_GRAPH_IN_LISTS it also
- * builds, once, the transposed structure (for every u the ascending list of v with u in
- * adj(v)), which costs about 4*M + 8*N bytes of device memory plus 16*M bytes of temporary
- * space while it is built.  Synchronous. */
+ * builds, once, the transposed structure (the edges v -> u grouped by blocks of destination
+ * vertices u and sorted by v inside a block: who can sample u), which costs about
+ * 4*M + N/64 bytes of device memory plus 16*M bytes of temporary space while it is built.
+ * Synchronous. */
 int  spp_graph_create(spp_ctx* ctx, int64_t N, int64_t M, const int64_t* d_rowptr,
                       const int32_t* d_col, uint32_t flags, spp_graph** out);
 void spp_graph_destroy(spp_graph* g);

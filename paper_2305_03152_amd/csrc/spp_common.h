@@ -139,13 +139,15 @@ struct spp_graph {
     const int32_t* col = nullptr;       // caller's
     // the same edges once more (library-owned, built on request), grouped by blocks of
     // 2^tile_rbits destination rows and sorted by source inside a block: the structure the
-    // dense hops of the VIP propagation walk
+    // dense hops of the VIP propagation walk.  One 32-bit word per edge: the low kTileSrcLoBits of
+    // the source above the destination row inside its block; the high bits of the source are the
+    // index of the "source chunk", and tile_first says where each chunk starts inside each block.
     bool      has_in = false;
-    int32_t*  t_src = nullptr;          // int32[M] source vertex
-    uint16_t* t_rl = nullptr;           // uint16[M] destination row inside its block
-    int64_t*  rb_off = nullptr;         // int64[nrb+1] first edge of every row block
+    uint32_t* t_edge = nullptr;         // uint32[M]
+    int64_t*  tile_first = nullptr;     // int64[nrb * nch + 1]: first edge of (row block, source chunk), ascending
     int       tile_rbits = 0;
-    int64_t   nrb = 0;
+    int64_t   nrb = 0;                  // row blocks
+    int       nch = 0;                  // source chunks (of 2^kTileSrcLoBits vertices)
 };
 
 struct spp_cache {

@@ -336,6 +336,29 @@ __device__ __forceinline__ int64_t table_find(const unsigned long long* tab, uin
 }
 
 // ---------------------------------------------------------------------------------------------
+// Edges grouped by blocks of destination rows and sorted by source inside a block, one 32-bit word
+// per edge: (source & (2^18 - 1)) << 14 | row inside the block.  The source's high bits are the
+// index of its "source chunk"; bound[c] is the position inside the block of the first edge whose
+// chunk is >= c (bound[0] = 0, bound[nch] = edges of the block), so the chunk of the edge at
+// position p is the largest c with bound[c] <= p.
+// ---------------------------------------------------------------------------------------------
+constexpr int kTileSrcLoBits = 18;
+constexpr int kTileRowBits = 14;
+constexpr uint32_t kTileRowMask = (1u << kTileRowBits) - 1u;
+
+__device__ __forceinline__ int tile_chunk_of(const uint32_t* bound, int nch, uint32_t p) {
+    int lo = 0, hi = nch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (bound[mid] <= p) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+__device__ __forceinline__ uint32_t tile_source(uint32_t word, int chunk) {
+    return ((uint32_t)chunk << kTileSrcLoBits) | (word >> kTileRowBits);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Philox-4x32 with 10 rounds (Salmon et al., SC'11), from the published round function:
 // two 32x32->64 multiplies per round, key bumped by the Weyl constants between rounds.
 // ---------------------------------------------------------------------------------------------

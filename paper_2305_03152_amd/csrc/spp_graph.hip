@@ -1,7 +1,9 @@
 // Graph handle: wraps the caller's CSR and, on request, builds the transposed structure that the
 // pull form of Proposition 1, eq. (2), walks: the edges v -> u grouped by blocks of 2^14
-// destination rows u and, inside a block, sorted by source v, as two arrays (source: 4 bytes,
-// row inside the block: 2 bytes).  Built once per graph by a radix sort of the packed edge keys.
+// destination rows u and, inside a block, sorted by source v, 4 bytes per edge (the low 18 bits of
+// the source and the row inside the block; a table says where each run of 2^18 sources starts in
+// each block).  Built once per graph by a radix sort of the packed edge keys, then read back and
+// compared with the keys before anything gathers through it.
 #include "spp_common.h"
 #include "spp_device.h"
 
@@ -47,20 +49,51 @@ __global__ void __launch_bounds__(kBlock) tile_keys_kernel(int64_t N, const int6
     }
 }
 
-// From the sorted keys: t_src, t_rl, and rb_off[b] = first e whose row block is >= b (blocks after
-// the last one keep the value M they were filled with).
+// From the sorted keys: the edge words, and first[g] = first e whose (row block, source chunk)
+// index g = block * nch + chunk is >= g (indices after the last one keep the value M they were
+// filled with).
 __global__ void __launch_bounds__(kBlock) tile_lists_kernel(const uint64_t* __restrict__ keys, int64_t M, int rbits,
-                                                            int vbits, int32_t* __restrict__ t_src,
-                                                            uint16_t* __restrict__ t_rl, int64_t* __restrict__ rb_off) {
+                                                            int vbits, int nch, uint32_t* __restrict__ t_edge,
+                                                            int64_t* __restrict__ first) {
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     const uint64_t rmask = (1ull << rbits) - 1, vmask = (1ull << vbits) - 1;
+    auto index_of = [&](uint64_t k) {
+        return (int64_t)(k >> (vbits + rbits)) * nch + (int64_t)(((k >> rbits) & vmask) >> kTileSrcLoBits);
+    };
     for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < M; e += stride) {
         const uint64_t k = keys[e];
-        t_src[e] = (int32_t)((k >> rbits) & vmask);
-        t_rl[e] = (uint16_t)(k & rmask);
-        const int64_t rb = (int64_t)(k >> (vbits + rbits));
-        const int64_t prev = e > 0 ? (int64_t)(keys[e - 1] >> (vbits + rbits)) : -1;
-        for (int64_t r = prev + 1; r <= rb; ++r) rb_off[r] = e;
+        const uint32_t v = (uint32_t)((k >> rbits) & vmask);
+        t_edge[e] = ((v & ((1u << kTileSrcLoBits) - 1u)) << kTileRowBits) | (uint32_t)(k & rmask);
+        const int64_t g = index_of(k);
+        const int64_t prev = e > 0 ? index_of(keys[e - 1]) : -1;
+        for (int64_t r = prev + 1; r <= g; ++r) first[r] = e;
+    }
+}
+
+// Reads the structure back the way the propagation kernel does and compares every edge with the
+// sorted key it was made from, so that a kernel that gathers through it never sees a source or a
+// row out of range.  One workgroup per row block; the block's chunk bounds sit in LDS.
+__global__ void __launch_bounds__(kBlock) tile_verify_kernel(const uint64_t* __restrict__ keys, int rbits, int vbits,
+                                                             int nch, const uint32_t* __restrict__ t_edge,
+                                                             const int64_t* __restrict__ first, int64_t N, int64_t M,
+                                                             int* __restrict__ bad) {
+    extern __shared__ uint32_t bound[];
+    const uint64_t rmask = (1ull << rbits) - 1, vmask = (1ull << vbits) - 1;
+    for (int64_t rb = blockIdx.x; rb * ((int64_t)1 << rbits) < N; rb += gridDim.x) {
+        const int64_t b0 = first[rb * nch], len = first[(rb + 1) * nch] - b0;
+        if (b0 < 0 || len < 0 || b0 + len > M || len > 0xFFFFFFFFll) { if (threadIdx.x == 0) *bad = 1; continue; }
+        __syncthreads();
+        for (int c = threadIdx.x; c <= nch; c += kBlock) bound[c] = (uint32_t)(first[rb * nch + c] - b0);
+        __syncthreads();
+        for (int64_t p = threadIdx.x; p < len; p += kBlock) {
+            const uint64_t k = keys[b0 + p];
+            const uint32_t w = t_edge[b0 + p];
+            const int c = tile_chunk_of(bound, nch, (uint32_t)p);
+            const bool ok = (int64_t)(k >> (vbits + rbits)) == rb && tile_source(w, c) == (uint32_t)((k >> rbits) & vmask) &&
+                            (w & kTileRowMask) == (uint32_t)(k & rmask) && (int64_t)tile_source(w, c) < N &&
+                            (rb << rbits) + (int64_t)(w & kTileRowMask) < N;
+            if (!ok) *bad = 1;
+        }
     }
 }
 
@@ -71,30 +104,50 @@ static int build_tiles(spp_ctx* ctx, spp_graph* g) {
     const int grid = ctx->num_cu * 8;
     int lds = 0;
     SPP_HIP(hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, ctx->device));
-    const int rbits = lds >= (int)((sizeof(double) << 14) + 1024) ? 14 : 13;      // fp64 accumulators of a block in LDS
+    const int nch = (int)((N + ((int64_t)1 << kTileSrcLoBits) - 1) >> kTileSrcLoBits);
+    // the fp64 sums of a block and the block's chunk bounds share the LDS of a workgroup
+    const size_t bound_bytes = (size_t)(nch + 1) * sizeof(uint32_t);
+    const int rbits = (size_t)lds >= (sizeof(double) << kTileRowBits) + bound_bytes + 1024 ? kTileRowBits : kTileRowBits - 1;
+    SPP_CHECK((size_t)lds >= (sizeof(double) << rbits) + bound_bytes + 1024, SPP_E_HIP,
+              "row blocks: %d bytes of LDS per workgroup do not hold a block's sums and chunk bounds", lds);
     int vbits = 1;
     while (((int64_t)1 << vbits) < N) ++vbits;
     const int64_t nrb = (N + ((int64_t)1 << rbits) - 1) >> rbits;
     int bbits = 1;
     while (((int64_t)1 << bbits) < nrb) ++bbits;
-    g->tile_rbits = rbits; g->nrb = nrb;
-    SPP_HIP(hipMalloc(&g->rb_off, (size_t)(nrb + 1) * sizeof(int64_t)));
-    SPP_HIP(hipMalloc(&g->t_src, (size_t)(M > 0 ? M : 1) * sizeof(int32_t)));
-    SPP_HIP(hipMalloc(&g->t_rl, (size_t)(M > 0 ? M : 1) * sizeof(uint16_t)));
-    fill_i64_kernel<<<grid, kBlock, 0, st>>>(g->rb_off, nrb + 1, M);
+    g->tile_rbits = rbits; g->nrb = nrb; g->nch = nch;
+    const int64_t nfirst = nrb * nch + 1;
+    SPP_HIP(hipMalloc(&g->tile_first, (size_t)nfirst * sizeof(int64_t)));
+    SPP_HIP(hipMalloc(&g->t_edge, (size_t)(M > 0 ? M : 1) * sizeof(uint32_t)));
+    fill_i64_kernel<<<grid, kBlock, 0, st>>>(g->tile_first, nfirst, M);
     if (M > 0) {
         uint64_t *ka = nullptr, *kb = nullptr, *sorted = nullptr;
+        int* d_bad = nullptr;
         SPP_HIP(hipMalloc(&ka, (size_t)M * sizeof(uint64_t)));
         hipError_t e = hipMalloc(&kb, (size_t)M * sizeof(uint64_t));
-        if (e != hipSuccess) { (void)hipFree(ka); set_error("row blocks: out of device memory for sort keys"); return SPP_E_OOM; }
+        if (e == hipSuccess) e = hipMalloc(&d_bad, sizeof(int));
+        if (e != hipSuccess) {
+            (void)hipFree(ka); if (kb) (void)hipFree(kb);
+            set_error("row blocks: out of device memory for sort keys");
+            return SPP_E_OOM;
+        }
         tile_keys_kernel<<<grid, kBlock, 0, st>>>(N, g->rowptr, g->col, rbits, vbits, ka);
         int rc = radix_sort_u64(ctx, ka, kb, M, rbits, rbits + vbits + bbits, &sorted);
         if (rc == SPP_OK) {
-            tile_lists_kernel<<<grid, kBlock, 0, st>>>(sorted, M, rbits, vbits, g->t_src, g->t_rl, g->rb_off);
-            hipError_t e2 = hipStreamSynchronize(st);
+            int bad = 0;
+            tile_lists_kernel<<<grid, kBlock, 0, st>>>(sorted, M, rbits, vbits, nch, g->t_edge, g->tile_first);
+            hipError_t e2 = hipMemsetAsync(d_bad, 0, sizeof(int), st);
+            if (e2 == hipSuccess) {
+                const int vgrid = (int)(nrb < (int64_t)ctx->num_cu * 8 ? nrb : (int64_t)ctx->num_cu * 8);
+                tile_verify_kernel<<<vgrid, kBlock, bound_bytes, st>>>(sorted, rbits, vbits, nch, g->t_edge, g->tile_first,
+                                                                       N, M, d_bad);
+                e2 = hipMemcpyAsync(&bad, d_bad, sizeof(int), hipMemcpyDeviceToHost, st);
+            }
+            if (e2 == hipSuccess) e2 = hipStreamSynchronize(st);
             if (e2 != hipSuccess) { set_error("row blocks: %s", hipGetErrorString(e2)); rc = SPP_E_HIP; }
+            else if (bad) { set_error("row blocks: the structure does not read back as the edges it was built from"); rc = SPP_E_HIP; }
         }
-        (void)hipFree(ka); (void)hipFree(kb);
+        (void)hipFree(ka); (void)hipFree(kb); (void)hipFree(d_bad);
         SPP_TRY(rc);
     }
     return SPP_OK;
@@ -150,8 +203,7 @@ extern "C" void spp_graph_destroy(spp_graph* g) {
     if (!g) return;
     (void)hipSetDevice(g->device);
     (void)hipDeviceSynchronize();      // work that still reads the row blocks may be in flight
-    if (g->t_src) (void)hipFree(g->t_src);
-    if (g->t_rl) (void)hipFree(g->t_rl);
-    if (g->rb_off) (void)hipFree(g->rb_off);
+    if (g->t_edge) (void)hipFree(g->t_edge);
+    if (g->tile_first) (void)hipFree(g->tile_first);
     delete g;
 }

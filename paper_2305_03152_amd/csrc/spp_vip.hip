@@ -8,7 +8,7 @@
 //
 // Dense hops: the edges are stored grouped by blocks of 2^14 destination rows and sorted by source
 // inside a block.  A workgroup keeps the block's fp64 sums in LDS (128 KB), streams a share of the
-// block's edges (6 bytes each, read as 128-bit vectors) and adds y[source] to the row's sum with an
+// block's edges (4 bytes each, read as 128-bit vectors) and adds y[source] to the row's sum with an
 // LDS atomic; because the sources ascend, neighbouring lanes gather from neighbouring lines of y and
 // a line fetched from L2 serves every edge of the block that needs it.  (A pull that walks one
 // row's in-list at a time fetches a line per edge: it ran at a third of this rate on every graph
@@ -141,76 +141,96 @@ __global__ void __launch_bounds__(kBlock) vip_push_finish_kernel(VipHop a, const
 // neighbouring lines, and a line fetched from L2 serves every edge of the block that needs it
 // (in a row-ordered pull every edge fetches a line of its own).  The share's sums are written
 // to part[j][row]; the finish kernel adds the shares.
+// An edge is one 32-bit word (low 18 bits of the source, row inside the block); the source's high
+// bits follow from the edge's position: the block's chunk bounds sit in LDS next to the sums, a
+// lane finds the chunk of the first of its four consecutive edges by bisection and steps forward
+// for the other three.
 constexpr int kTileBlock = 1024;
-constexpr int kTileUnroll = 2;          // 128-bit id vectors per lane and round (8 edges)
-__global__ void __launch_bounds__(kTileBlock) vip_tile_kernel(const int32_t* __restrict__ t_src,
-                                                              const uint16_t* __restrict__ t_rl,
-                                                              const int64_t* __restrict__ rb_off, int parts, int rbits,
-                                                              const float* __restrict__ y, double* __restrict__ part,
-                                                              int64_t part_stride) {
+constexpr int kTileUnroll = 2;          // 128-bit vectors (four edges) per lane and round
+__global__ void __launch_bounds__(kTileBlock) vip_tile_kernel(const uint32_t* __restrict__ t_edge,
+                                                              const int64_t* __restrict__ first, int nch, int parts,
+                                                              int rbits, const float* __restrict__ y,
+                                                              double* __restrict__ part, int64_t part_stride) {
     extern __shared__ double acc[];
     const int R = 1 << rbits;
+    uint32_t* bound = reinterpret_cast<uint32_t*>(acc + R);
     const int64_t rb = blockIdx.x / parts;
     const int j = blockIdx.x % parts;
+    const int64_t b0 = first[rb * nch], len = first[(rb + 1) * nch] - b0;
     for (int i = threadIdx.x; i < R; i += kTileBlock) acc[i] = 0.0;
+    for (int c = threadIdx.x; c <= nch; c += kTileBlock) bound[c] = (uint32_t)(first[rb * nch + c] - b0);
     __syncthreads();
-    const int64_t b0 = rb_off[rb], len = rb_off[rb + 1] - b0;
     const int64_t beg = b0 + len * j / parts, end = b0 + len * (j + 1) / parts;
-    // The edge stream is read four edges per lane (one 128-bit load of sources, one 64-bit load of
-    // rows): a CU keeps a limited number of misses in flight, so the bytes per request decide the
-    // streaming rate.  Software pipeline: the ids of the next round are in flight while this
-    // round's gathers and LDS adds run.
-    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
-    typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+    // The edge stream is read four edges per lane (one 128-bit load): a CU keeps a limited number
+    // of misses in flight, so the bytes per request decide the streaming rate.  Software pipeline:
+    // the words of the next round are in flight while this round's gathers and LDS adds run.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     int64_t a4 = (beg + 3) & ~(int64_t)3, e4 = end & ~(int64_t)3;
     if (a4 > end) a4 = end;
     if (e4 < a4) e4 = a4;
-    for (int64_t e = beg + threadIdx.x; e < a4; e += kTileBlock) {            // unaligned head
-        const float v = y[t_src[e]];
-        if (v != 0.0f) unsafeAtomicAdd(&acc[t_rl[e]], (double)v);
-    }
-    for (int64_t e = e4 + threadIdx.x; e < end; e += kTileBlock) {            // tail
-        const float v = y[t_src[e]];
-        if (v != 0.0f) unsafeAtomicAdd(&acc[t_rl[e]], (double)v);
-    }
-    const i32x4* __restrict__ vs = reinterpret_cast<const i32x4*>(t_src + a4);
-    const u16x4* __restrict__ vr = reinterpret_cast<const u16x4*>(t_rl + a4);
+    auto one = [&](int64_t e) {
+        const uint32_t w = t_edge[e];
+        const float v = y[tile_source(w, tile_chunk_of(bound, nch, (uint32_t)(e - b0)))];
+        if (v != 0.0f) unsafeAtomicAdd(&acc[w & kTileRowMask], (double)v);
+    };
+    for (int64_t e = beg + threadIdx.x; e < a4; e += kTileBlock) one(e);      // unaligned head
+    for (int64_t e = e4 + threadIdx.x; e < end; e += kTileBlock) one(e);      // tail
+    const u32x4* __restrict__ vs = reinterpret_cast<const u32x4*>(t_edge + a4);
     const int64_t nvec = (e4 - a4) >> 2;
+    const uint32_t p0 = (uint32_t)(a4 - b0);                                   // position of the first vector's first edge
     constexpr int64_t kRound = (int64_t)kTileUnroll * kTileBlock;
-    i32x4 s[kTileUnroll];
-    u16x4 r[kTileUnroll];
+    u32x4 s[kTileUnroll];
+    int ch[kTileUnroll];                 // chunk of the lane's current vector and where that chunk ends;
+    uint32_t ch_end[kTileUnroll];        // a lane's positions only grow, so both only move forward
     int64_t q = threadIdx.x;
 #pragma unroll
-    for (int u = 0; u < kTileUnroll; ++u)
+    for (int u = 0; u < kTileUnroll; ++u) {
+        ch[u] = 0; ch_end[u] = 0;
         if (q + u * kTileBlock < nvec) {
             s[u] = __builtin_nontemporal_load(vs + q + u * kTileBlock);
-            r[u] = __builtin_nontemporal_load(vr + q + u * kTileBlock);
+            ch[u] = tile_chunk_of(bound, nch, p0 + 4u * (uint32_t)(q + u * kTileBlock));
+            ch_end[u] = bound[ch[u] + 1];
         }
+    }
     for (; q < nvec; q += kRound) {
-        i32x4 sn[kTileUnroll];
-        u16x4 rn[kTileUnroll];
+        u32x4 sn[kTileUnroll];
 #pragma unroll
         for (int u = 0; u < kTileUnroll; ++u)
-            if (q + kRound + u * kTileBlock < nvec) {
-                sn[u] = __builtin_nontemporal_load(vs + q + kRound + u * kTileBlock);
-                rn[u] = __builtin_nontemporal_load(vr + q + kRound + u * kTileBlock);
-            }
+            if (q + kRound + u * kTileBlock < nvec) sn[u] = __builtin_nontemporal_load(vs + q + kRound + u * kTileBlock);
         float v[kTileUnroll][4];
 #pragma unroll
         for (int u = 0; u < kTileUnroll; ++u)
             if (q + u * kTileBlock < nvec) {
-                v[u][0] = y[s[u].x]; v[u][1] = y[s[u].y]; v[u][2] = y[s[u].z]; v[u][3] = y[s[u].w];
+                const uint32_t p = p0 + 4u * (uint32_t)(q + u * kTileBlock);
+                int c = ch[u];
+                uint32_t ce = ch_end[u];
+                while (p >= ce) { ++c; ce = bound[c + 1]; }      // p + 3 < len = bound[nch]: c stays below nch
+                if (p + 3 < ce) {                                  // the four edges share a chunk
+                    v[u][0] = y[tile_source(s[u].x, c)];
+                    v[u][1] = y[tile_source(s[u].y, c)];
+                    v[u][2] = y[tile_source(s[u].z, c)];
+                    v[u][3] = y[tile_source(s[u].w, c)];
+                } else {
+                    v[u][0] = y[tile_source(s[u].x, c)];
+                    while (p + 1 >= ce) { ++c; ce = bound[c + 1]; }
+                    v[u][1] = y[tile_source(s[u].y, c)];
+                    while (p + 2 >= ce) { ++c; ce = bound[c + 1]; }
+                    v[u][2] = y[tile_source(s[u].z, c)];
+                    while (p + 3 >= ce) { ++c; ce = bound[c + 1]; }
+                    v[u][3] = y[tile_source(s[u].w, c)];
+                }
+                ch[u] = c; ch_end[u] = ce;
             }
 #pragma unroll
         for (int u = 0; u < kTileUnroll; ++u)
             if (q + u * kTileBlock < nvec) {
-                if (v[u][0] != 0.0f) unsafeAtomicAdd(&acc[r[u].x], (double)v[u][0]);
-                if (v[u][1] != 0.0f) unsafeAtomicAdd(&acc[r[u].y], (double)v[u][1]);
-                if (v[u][2] != 0.0f) unsafeAtomicAdd(&acc[r[u].z], (double)v[u][2]);
-                if (v[u][3] != 0.0f) unsafeAtomicAdd(&acc[r[u].w], (double)v[u][3]);
+                if (v[u][0] != 0.0f) unsafeAtomicAdd(&acc[s[u].x & kTileRowMask], (double)v[u][0]);
+                if (v[u][1] != 0.0f) unsafeAtomicAdd(&acc[s[u].y & kTileRowMask], (double)v[u][1]);
+                if (v[u][2] != 0.0f) unsafeAtomicAdd(&acc[s[u].z & kTileRowMask], (double)v[u][2]);
+                if (v[u][3] != 0.0f) unsafeAtomicAdd(&acc[s[u].w & kTileRowMask], (double)v[u][3]);
             }
 #pragma unroll
-        for (int u = 0; u < kTileUnroll; ++u) { s[u] = sn[u]; r[u] = rn[u]; }
+        for (int u = 0; u < kTileUnroll; ++u) s[u] = sn[u];
     }
     __syncthreads();
     double* __restrict__ out = part + (int64_t)j * part_stride + (rb << rbits);
@@ -386,7 +406,7 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
         const size_t push_bytes = (size_t)N * sizeof(double);
         SPP_TRY(ctx->acc.reserve(tile_bytes > push_bytes ? tile_bytes : push_bytes));
     }
-    const size_t lds_bytes = sizeof(double) << g->tile_rbits;
+    const size_t lds_bytes = (sizeof(double) << g->tile_rbits) + (size_t)(g->nch + 1) * sizeof(uint32_t);
     if (ctx->tile_lds_set < (int)lds_bytes) {        // more than the 64 KB a launch may ask for by default
         SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vip_tile_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
@@ -440,7 +460,7 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
                 vip_push_finish_kernel<<<fill_grid, kBlock, 0, st>>>(a, acc, N);
             } else {
                 vip_tile_kernel<<<(unsigned)(g->nrb * parts), kTileBlock, lds_bytes, st>>>(
-                    g->t_src, g->t_rl, g->rb_off, parts, g->tile_rbits, ycur, ctx->acc.as<double>(), part_stride);
+                    g->t_edge, g->tile_first, g->nch, parts, g->tile_rbits, ycur, ctx->acc.as<double>(), part_stride);
                 vip_tile_finish_kernel<<<fill_grid, kBlock, 0, st>>>(a, ctx->acc.as<double>(), parts, part_stride, N);
             }
             ctx->vip_pushed[h - 1] = push ? 1 : 0;
