@@ -379,21 +379,23 @@ def main():
         lanes.append((c, sets, None))
     bufs, out = lanes[0][1][0][0][0], lanes[0][1][0][1][0]
 
-    def run(first, count):
+    def run(first, count, gsz=None, order=None):
         """Enqueue minibatches first .. first+count-1 (no host synchronisation inside)."""
+        gsz = Gsz if gsz is None else gsz
+        order = store_order if order is None else order
         gi = 0
-        for g0 in range(first, first + count, Gsz):
+        for g0 in range(first, first + count, gsz):
             c, sets, _ = lanes[gi % P]
             b, o = sets[(gi // P) % 2]
             gi += 1
-            idx = range(g0, min(g0 + Gsz, first + count))
+            idx = range(g0, min(g0 + gsz, first + count))
             spp.sample_mfg_multi(c, G, [(batches[i], i, b[k]) for k, i in enumerate(idx)], cfg.fanouts,
                                  cfg.seed_sampler, sync=False)
             # the gather classifies this group beside the previous group's miss copy, waits for that
             # copy (the previous group's rows are complete from there on), then copies the hits
             spp.gather_features_multi(c, cache, local, cfg.N, lo, hi, remote,
                                       [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(len(idx))],
-                                      sync=False, join=False, store_order=store_order)
+                                      sync=False, join=False, store_order=order)
         for c, _, _ in lanes:
             spp.gather_join(c)
 
@@ -440,6 +442,22 @@ def main():
         for k in tot:
             tot[k] += t_[k]
     avg = {k: v / K for k, v in tot.items()}
+
+    # the same steps at the pipeline depth the paper keeps (ten minibatches in flight: groups of five on
+    # the two buffer sets), for comparison: reported beside `value`, never as it
+    depth = None
+    if P == 1 and Gsz > 5 and K >= 40:
+        kd = min(K, 320) // 5 * 5
+        run(W, 20, gsz=5, order=False)
+        torch.cuda.synchronize()
+        td = time.perf_counter()
+        run(W, kd, gsz=5, order=False)
+        for c, _, _ in lanes:
+            c.sync()
+        torch.cuda.synchronize()
+        td = time.perf_counter() - td
+        depth = {"minibatches_per_gather_launch": 5, "minibatches_in_flight": 10, "steps": kd,
+                 "value": kd / td, "ms_per_step": td / kd * 1e3}
 
     T_HIT, T_MISS, T_CLS, T_SAMPLE = 10, 11, 12, 9
     hit_ms = ms[T_HIT] / max(cnt[T_HIT], 1)
@@ -512,6 +530,7 @@ def main():
         "config": {"workload": f"{cfg.name}: N={g.N} M={g.M} D={cfg.D} {cfg.dtype} fanouts={list(cfg.fanouts)} "
                                f"B={cfg.B} K={cfg.K} alpha={cfg.alpha} owned partition {cfg.owned_partition}",
                    "lanes": P, "minibatches_per_gather_launch": Gsz, "minibatches_in_flight": 2 * P * Gsz,
+                   "at_ten_minibatches_in_flight": depth,
                    "misses_fetched_in": "store order" if store_order else "list order",
                    "share_of_remote_store_fetched_per_launch": round(fetched_share, 4),
                    "avg_per_batch": {k: round(v, 1) for k, v in avg.items()},
