@@ -201,7 +201,9 @@ int  spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats);
  * (the sampling of the following minibatches) overlaps the PCIe transfer.  spp_gather_join makes
  * the stream wait for that miss copy and then copies the rows that share a fetched vertex with
  * another row of the call: call it before anything that reads the gathered rows.  The next
- * gather on the same context, spp_ctx_sync and SPP_SYNC join by themselves. */
+ * gather on the same context, spp_ctx_sync and SPP_SYNC join by themselves.  Until the join
+ * has run, the id lists and the outputs of the call must stay allocated: the side stream and
+ * the join still write them. */
 int  spp_gather_join(spp_ctx* ctx);
 
 /* The same gather for up to SPP_MAX_GATHER_LISTS id lists in one set of launches (one
