@@ -240,12 +240,37 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
 
 // ---- steps 1 and 2 with given transition probabilities ----
 // Entry k of v's row is taken iff rand32(seed, batch, hop, v, k) < floor(t * 2^32); a probability
-// outside [0, 1] counts as 0 and is reported.
-__device__ __forceinline__ bool general_take(const SampleArgs& a, uint32_t batch_lo, int64_t v, int64_t r0, int64_t k) {
-    const float tt = a.t[r0 + k];
-    if (!(tt >= 0.0f && tt <= 1.0f)) { atomicOr(a.bad, 2); return false; }
-    const uint64_t thr = (uint64_t)((double)tt * 4294967296.0);
-    return (uint64_t)rand32(a.seed, batch_lo, (uint32_t)a.h, (uint32_t)v, (uint32_t)k) < thr;
+// outside [0, 1] counts as 0 and is reported.  A lane decides four consecutive entries at a time:
+// their draws are the four words of one Philox block (that is how rand32 numbers them).
+// Returns the 4-bit mask of the taken ones among entries k4 .. k4+3 (k4 a multiple of 4) of a row of d.
+__device__ __forceinline__ uint32_t general_take4(const SampleArgs& a, uint32_t batch_lo, int64_t v, int64_t r0, int64_t k4,
+                                                  int64_t d) {
+    if (k4 >= d) return 0u;
+    const Philox4 p = philox4x32_10((uint32_t)v, (uint32_t)(k4 >> 2), (uint32_t)a.h, batch_lo, (uint32_t)a.seed,
+                                    (uint32_t)(a.seed >> 32));
+    uint32_t m = 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (k4 + i < d) {
+            const float tt = a.t[r0 + k4 + i];
+            if (!(tt >= 0.0f && tt <= 1.0f)) { atomicOr(a.bad, 2); continue; }
+            const uint64_t thr = (uint64_t)((double)tt * 4294967296.0);
+            if ((uint64_t)p.w[i] < thr) m |= 1u << i;
+        }
+    }
+    return m;
+}
+// Taken entries of the 256 entries a wavefront decides in one step: in all lanes, and in the lanes below this one.
+__device__ __forceinline__ int taken_in_wave(uint32_t m, uint64_t lt_mask, int& below) {
+    int all = 0;
+    below = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint64_t b = __ballot((m >> i) & 1u);
+        all += __popcll(b);
+        below += __popcll(b & lt_mask);
+    }
+    return all;
 }
 
 __global__ void __launch_bounds__(kBlock) general_count_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
@@ -265,10 +290,9 @@ __global__ void __launch_bounds__(kBlock) general_count_kernel(SampleArgs a, con
         const int64_t v = S[i];
         const int64_t r0 = a.rowptr[v], d = a.rowptr[v + 1] - r0;
         int64_t c = 0;
-        for (int64_t k0 = 0; k0 < d; k0 += kWave) {
-            const int64_t k = k0 + lane;
-            const bool take = k < d && general_take(a, batch_lo, v, r0, k);
-            c += __popcll(__ballot(take));
+        for (int64_t k0 = 0; k0 < d; k0 += 4 * kWave) {
+            int below;
+            c += taken_in_wave(general_take4(a, batch_lo, v, r0, k0 + 4 * lane, d), 0ull, below);
         }
         // a count beyond any capacity is stored saturated; the 64-bit total below decides
         if (lane == 0) { cnt[i] = (int32_t)(c < 0x7FFFFFFFll ? c : 0x7FFFFFFFll); mine += (unsigned long long)c; }
@@ -303,16 +327,21 @@ __global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, co
         // the table was emptied for this hop, so the target is offered again with its index
         if (lane == 0) table_insert_min(tab, mask, shift, (uint32_t)v, (uint32_t)i);
         int64_t e = indptr[i];
-        for (int64_t k0 = 0; k0 < d; k0 += kWave) {
-            const int64_t k = k0 + lane;
-            const bool take = k < d && general_take(a, batch_lo, v, r0, k);
-            const uint64_t m = __ballot(take);
-            if (take) {
-                const int64_t pos = e + __popcll(m & lt_mask);
-                const int32_t gid = a.col[r0 + k];
-                flat[pos] = (int32_t)table_insert_min(tab, mask, shift, (uint32_t)gid, (uint32_t)(n_prev + pos));
+        for (int64_t k0 = 0; k0 < d; k0 += 4 * kWave) {
+            const int64_t k4 = k0 + 4 * lane;
+            const uint32_t m = general_take4(a, batch_lo, v, r0, k4, d);
+            int below;
+            const int all = taken_in_wave(m, lt_mask, below);
+            int64_t pos = e + below;                   // entries ascend with the lane, then inside the lane
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if ((m >> q) & 1u) {
+                    const int32_t gid = a.col[r0 + k4 + q];
+                    flat[pos] = (int32_t)table_insert_min(tab, mask, shift, (uint32_t)gid, (uint32_t)(n_prev + pos));
+                    ++pos;
+                }
             }
-            e += __popcll(m);
+            e += all;
         }
     }
 }
