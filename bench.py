@@ -235,6 +235,9 @@ def main():
     ap.add_argument("--store-order", default="auto", choices=["auto", "on", "off"],
                     help="fetch a group's missed rows in the order of the remote store (SPP_STORE_ORDER); auto: when "
                          "the set-up groups fetched an eighth or more of the store's rows per group")
+    ap.add_argument("--depth-leg", default="on", choices=["on", "off"],
+                    help="after the timed steps, also time the pipeline at ten minibatches in flight (the paper's depth); "
+                         "off keeps a kernel trace of the run to the launches of the timed configuration")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
     ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "policy-sweep", "general", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
@@ -446,7 +449,7 @@ def main():
     # the same steps at the pipeline depth the paper keeps (ten minibatches in flight: groups of five on
     # the two buffer sets), for comparison: reported beside `value`, never as it
     depth = None
-    if P == 1 and Gsz > 5 and K >= 40:
+    if args.depth_leg == "on" and P == 1 and Gsz > 5 and K >= 40:
         kd = min(K, 320) // 5 * 5
         run(W, 20, gsz=5, order=False)
         torch.cuda.synchronize()
