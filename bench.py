@@ -29,7 +29,7 @@ PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 MEASURED_TRAFFIC = {
     ("mid", 16): {"gather_hit": 346.3e6 + 269.9e6, "vip_tile": 1.039e9 + 134.9e6},
     ("mid", 32): {"gather_hit": 692.0e6 + 536.5e6, "vip_tile": 1.039e9 + 134.9e6},
-    ("mid", 64): {"gather_hit": 1382.6e6 + 1068.8e6, "vip_tile": 1.039e9 + 134.9e6},
+    ("mid", 64): {"gather_hit": 1262.4e6 + 1056.3e6, "vip_tile": 1.039e9 + 134.9e6},
 }
 
 

@@ -106,7 +106,7 @@ struct spp_ctx {
     // two sets, used alternately: the classification of a call may run while the miss copy of the
     // call before still reads its own set
     spp::DevBuf srcdesc[2];             // int64 per row: where the row comes from
-    spp::DevBuf misslist[2];            // int32 positions of the rows that miss, then of the rows that hit
+    spp::DevBuf misslist[2];            // the lists of a call: rows that hit (64-bit entries), miss, share a fetch, miss in store order
     spp::DevBuf gcount[2];              // device counters of the gather (int64[8]) and the list layout
     int         gslot = 0;              // set used by the last gather
     int         miss_lds = 0;           // dynamic LDS bytes of the miss kernel

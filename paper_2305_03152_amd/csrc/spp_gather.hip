@@ -42,7 +42,7 @@ struct ClassifyArgs {
     int64_t        local_limit;        // ranks below this are in device memory (row = rank)
     int64_t*       desc;               // per virtual row
     int32_t*       misslist;           // virtual rows that miss
-    int32_t*       hitlist;            // virtual rows served from the shard or the cache
+    int64_t*       hitlist;            // rows served from the shard or the cache: source and virtual row (make_hit)
     unsigned long long* counters;      // [0] local, [1] cache hit, [2] rows in misslist, [3] bad id, [4] rows in hitlist,
                                        // [5] local rows read from the host (part of [0] and of [2]), [6] rows in duplist,
                                        // [7] rows in the store-ordered list
@@ -204,8 +204,10 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
         const int64_t lbeg = ls.off[j], n = ls.cnt[j];
         const int32_t* __restrict__ ids = a.t.ids[j];
         uint32_t missbits = 0, hitbits = 0;
+        int64_t dk[kClsPer];
 #pragma unroll
         for (int k = 0; k < kClsPer; ++k) {
+            dk[k] = 0;
             const int64_t i = base - lbeg + (int64_t)k * kBlock + threadIdx.x;
             if (i >= n) continue;
             const int64_t g = ids[i];
@@ -231,6 +233,7 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
                 else       { d = make_desc(kTagMiss, g < a.lo ? g : g - (a.hi - a.lo)); ++n_rmiss; missbits |= 1u << k; }
             }
             a.desc[lbeg + i] = d;
+            dk[k] = d;
         }
         // both lists are compacted with one scan: misses in the low half-word, hits in the high one
         // (a workgroup's totals are at most 2048 each)
@@ -248,7 +251,7 @@ __global__ void __launch_bounds__(kBlock) classify_kernel(ClassifyArgs a) {
         for (int k = 0; k < kClsPer; ++k) {
             const int32_t r = (int32_t)(base + (int64_t)k * kBlock + threadIdx.x);
             if (missbits & (1u << k)) a.misslist[mpos++] = r;
-            if (hitbits & (1u << k)) a.hitlist[hpos++] = r;
+            if (hitbits & (1u << k)) a.hitlist[hpos++] = make_hit(desc_tag(dk[k]) == kTagCache, desc_row(dk[k]), r);
         }
         __syncthreads();                          // base_lds is reused by the next round
     }
@@ -417,8 +420,8 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     }
     if (vbound > 0) {
         SPP_TRY(ctx->srcdesc[slot].reserve((size_t)vbound * sizeof(int64_t)));
-        // miss list, hit list, copy list, misses in store order
-        SPP_TRY(ctx->misslist[slot].reserve((size_t)vbound * sizeof(int32_t) * 4));
+        // hit list (64-bit entries), miss list, copy list, misses in store order
+        SPP_TRY(ctx->misslist[slot].reserve((size_t)vbound * sizeof(int32_t) * 5));
     }
     pro.n_remote = n_remote;
     gather_prologue_kernel<<<1, 64, 0, st>>>(pro, counters, off, cnt, minfo);
@@ -429,9 +432,10 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         a.limit = cache ? cache->limit : 0;
         a.local_rank = store ? store->rank : nullptr;
         a.local_limit = store ? store->limit : 0;
-        a.desc = ctx->srcdesc[slot].as<int64_t>(); a.misslist = ctx->misslist[slot].as<int32_t>(); a.counters = counters;
-        a.hitlist = a.misslist + vbound;
-        int32_t* duplist = a.hitlist + vbound;
+        a.desc = ctx->srcdesc[slot].as<int64_t>(); a.counters = counters;
+        a.hitlist = ctx->misslist[slot].as<int64_t>();
+        a.misslist = ctx->misslist[slot].as<int32_t>() + 2 * vbound;
+        int32_t* duplist = a.misslist + vbound;
         int32_t* ordered = duplist + vbound;
         a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
         const int64_t cneed = vbound / kListAlign;
@@ -514,10 +518,10 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
             const char* cr = static_cast<const char*>(crow);
             const int64_t* hit_count = reinterpret_cast<const int64_t*>(counters + 4);
             switch (V) {
-                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
-                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
-                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
-                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.desc, a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.hitlist, hit_count, a.t, loc, cr, vpr); break;
+                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.hitlist, hit_count, a.t, loc, cr, vpr); break;
             }
         };
         // Order of the copies.  The PCIe link is the scarce resource, so this call's miss copy is

@@ -63,16 +63,19 @@ __device__ __forceinline__ int list_of(const ListLds& s, int n_lists, int64_t r)
     return lo;
 }
 
-// Hit path: rows served from the local shard or the cache.  hitlist[m] is a virtual row whose
-// descriptor names the store and the row in it; the kernel walks the n_hit * vpr vectors of those
-// rows flat, so every lane copies (no lane idles on a row that missed).
+// Hit path: rows served from the local shard or the cache.  A hit-list entry names the output row
+// and its source in one 64-bit word (bit 63: cache instead of local shard, bits 32-62: row in that
+// store, bits 0-31: virtual row), so a lane reaches the source row with one dependent load; the
+// kernel walks the n_hit * vpr vectors of those rows flat, so every lane copies (no lane idles on
+// a row that missed).
 // Source rows are read with ordinary loads (hot rows of the shard and the cache stay in L2 and
 // the Infinity Cache across batches), the output is written with streaming stores (it is not read
-// again by this path).  Measured at 1M-4M rows: 6.1-6.3 TB/s for 400-byte rows of a 120 MB shard,
-// 5.7 TB/s for 256-byte rows of a 3.5 GB shard, 6.0 TB/s for 1536-byte rows.
+// again by this path).
+__device__ __forceinline__ int64_t make_hit(bool from_cache, int64_t src_row, int64_t vrow) {
+    return (int64_t)(((uint64_t)(from_cache ? 1 : 0) << 63) | ((uint64_t)src_row << 32) | (uint64_t)(uint32_t)vrow);
+}
 template <int V, int U = kHitUnroll>
-__global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __restrict__ desc,
-                                                            const int32_t* __restrict__ hitlist,
+__global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __restrict__ hitlist,
                                                             const int64_t* __restrict__ count_ptr, ListTable t,
                                                             const char* __restrict__ local,
                                                             const char* __restrict__ cache, uint32_t vpr) {
@@ -93,11 +96,12 @@ __global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __res
             if (ok[u]) {
                 const uint64_t m = small ? (uint64_t)((uint32_t)c / vpr) : c / vpr;
                 const uint32_t k = (uint32_t)(c - m * vpr);
-                const int64_t r = hitlist[m];
-                const int j = list_of(ls, t.n_lists, r);
-                const int64_t d = desc[r];
-                const char* src = (desc_tag(d) == kTagLocal ? local : cache) + (desc_row(d) * vpr + k) * (int64_t)V;
+                const uint64_t h = (uint64_t)hitlist[m];
+                const int64_t r = (int64_t)(uint32_t)h;
+                const uint64_t srow = (h >> 32) & 0x7FFFFFFFull;
+                const char* src = ((h >> 63) ? cache : local) + (srow * vpr + k) * (uint64_t)V;
                 v[u] = *reinterpret_cast<const vec_t*>(src);
+                const int j = list_of(ls, t.n_lists, r);
                 dst[u] = t.out[j] + ((uint64_t)(r - ls.off[j]) * vpr + k) * (uint64_t)V;
             }
         }
