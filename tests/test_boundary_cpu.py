@@ -60,3 +60,36 @@ def test_product_path_fails_loudly_without_a_gpu():
         pytest.skip("a GPU is visible")
     with pytest.raises(spp.SppError):
         spp.Context(0)
+
+
+def test_binding_constants_match_the_header():
+    """Flags, limits and timer indices are typed twice (C header, ctypes binding): they must agree."""
+    from paper_2305_03152_amd import api
+    text = open(os.path.join(ROOT, "include", "spp.h")).read()
+    defines = {k: int(v.rstrip("u"), 0) for k, v in re.findall(r"#define\s+(SPP_[A-Z0-9_]+)\s+(0x[0-9a-fA-F]+u?|\d+)\b", text)}
+    for name in ("SPP_MAX_L", "SPP_MAX_FANOUT", "SPP_SYNC", "SPP_VIP_INCLUDE_HOP0", "SPP_GRAPH_IN_LISTS", "SPP_NO_JOIN",
+                 "SPP_STORE_ORDER"):
+        assert defines[name] == getattr(api, name), name
+    assert defines["SPP_MAX_GATHER_LISTS"] == 64 and defines["SPP_MAX_SAMPLE_BATCHES"] == 64
+    enums = {k: int(v) for k, v in re.findall(r"\b(SPP_T_[A-Z_]+)\s*=\s*(\d+)", text)}
+    for name in ("SPP_T_VIP_TOTAL", "SPP_T_VIP_HOP_FIRST", "SPP_T_SAMPLE", "SPP_T_GATHER_HIT", "SPP_T_GATHER_MISS",
+                 "SPP_T_GATHER_CLASSIFY", "SPP_T_COUNT"):
+        assert enums[name] == getattr(api, name), name
+    # struct layouts the binding mirrors: sizes as the C compiler sees them
+    import subprocess, tempfile
+    src = '#include "spp.h"\n#include <stdio.h>\nint main(void){printf("%zu %zu %zu %zu %zu\\n", sizeof(spp_mfg), ' \
+          'sizeof(spp_gather_stats), sizeof(spp_gather_list), sizeof(spp_sample_item), sizeof(spp_id_list));return 0;}\n'
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "s.c")
+        open(c, "w").write(src)
+        exe = os.path.join(d, "s")
+        subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), c, "-o", exe], check=True)
+        sizes = [int(x) for x in subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()]
+    assert sizes == [C.sizeof(api._MfgStruct), C.sizeof(api._GatherStats), C.sizeof(api._GatherList), C.sizeof(api._SampleItem),
+                     C.sizeof(api._IdList)]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
