@@ -777,6 +777,26 @@ def test_scaled_config_end_to_end(spp, ctx, name, cfg):
         want, _, counts = oracle.gather(cfg.N, c.lo, c.hi, local, cache_rows, ids_ref, remote, ref.node_ids)
         assert np.array_equal(_bits(_np(out)), _bits(want))
         assert (stats["n_local"], stats["n_cache_hit"], stats["n_miss"]) == counts
+    # the same minibatches through the batched calls, misses fetched in store order (this workload's row width and type)
+    _say("batched calls, store order")
+    group = batches[:2] + batches[-1:]
+    mb = [spp.MFGBuffers("cuda", cfg.B, cfg.fanouts, cfg.N) for _ in group]
+    spp.sample_mfg_multi(ctx, c.G, [(s_.cuda(), bi, mb[bi]) for bi, s_ in enumerate(group)], cfg.fanouts, cfg.seed_sampler, sync=False)
+    outs = [torch.zeros((b_.nb[-1], cfg.D), dtype=cfg.torch_dtype, device="cuda") for b_ in mb]
+    st = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote,
+                                   [(b_.node_ids, b_.nb[-1], b_.n_final_device, o_) for b_, o_ in zip(mb, outs)], store_order=True)
+    tot = [0, 0, 0]
+    ids_all = []
+    for bi, (seeds, b_, o_) in enumerate(zip(group, mb, outs)):
+        ref = oracle.sample_mfg(c.rp, c.col, seeds.numpy(), cfg.fanouts, cfg.seed_sampler, bi)
+        want, tag, counts = oracle.gather(cfg.N, c.lo, c.hi, local, cache_rows, ids_ref, remote, ref.node_ids)
+        assert np.array_equal(_bits(_np(o_[:ref.n[-1]])), _bits(want))
+        assert not bool(o_[ref.n[-1]:].any())
+        tot = [x + y for x, y in zip(tot, counts)]
+        ids_all.append(ref.node_ids[tag == 2])
+    assert (st["n_local"], st["n_cache_hit"], st["n_miss"]) == tuple(tot)
+    missed = np.concatenate(ids_all)
+    assert st["n_miss_shared"] == missed.size - np.unique(missed).size
     # general probabilities on the same graph: hub rows span many 64-entry chunks of the sampler's ballots
     _say("general probabilities")
     rng = np.random.default_rng(5)
