@@ -177,8 +177,8 @@ int  spp_sample_mfg_multi(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
  *     Hits are copied by one kernel on the context's stream; the compacted miss list is served
  *     by a second kernel on the context's side stream reading the pinned host rows directly,
  *     and joined back before the call returns to the stream.  cache may be NULL (alpha = 0).
- *     n is the number of ids, or an upper bound when d_n (device int64, e.g. &d_counts[L]) is
- *     given, in which case the count is read on the device.  Row size D*elem_bytes must be a
+ *     n (at most 2^26) is the number of ids, or an upper bound when d_n (device int64, e.g.
+ *     &d_counts[L]) is given, in which case the count is read on the device.  Row size D*elem_bytes must be a
  *     multiple of 2 and every store and output 2-byte aligned (SPP_E_ARG otherwise); 16-byte
  *     multiples and alignments take the widest path.  Duplicate ids are allowed.
  *     `remote` is pinned host memory (or device memory); it may be NULL only if no id misses.
