@@ -78,7 +78,7 @@ __device__ __forceinline__ int list_of(const ListLds& s, int n_lists, int64_t r)
 // the Infinity Cache across batches), the output is written with streaming stores (it is not read
 // again by this path).
 constexpr int kHitRowBits = 26;         // rows of one list that a hit-list entry can name
-constexpr int kHitSlices = 8;           // parts a chunk's copy is cut into
+constexpr int kHitSlices = 16;          // parts a chunk's copy is cut into
 static_assert(SPP_MAX_GATHER_LISTS <= (1 << (32 - kHitRowBits)), "the list index has 32 - kHitRowBits bits");
 __device__ __forceinline__ int64_t make_hit(bool from_cache, int64_t src_row, int list, int64_t row_in_list) {
     return (int64_t)(((uint64_t)(from_cache ? 1 : 0) << 63) | ((uint64_t)src_row << 32) |
