@@ -37,7 +37,7 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join[0], hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join[1], hipEventDisableTiming);
-    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 2048 * sizeof(int64_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_pinned), 8192 * sizeof(int64_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->totals), 16 * sizeof(int64_t));
     if (e == hipSuccess) e = hipMemset(c->totals, 0, 16 * sizeof(int64_t));
     if (e != hipSuccess) {
@@ -45,7 +45,7 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
         spp_ctx_destroy(c);
         return SPP_E_HIP;
     }
-    memset(c->h_pinned, 0, 2048 * sizeof(int64_t));
+    memset(c->h_pinned, 0, 8192 * sizeof(int64_t));
     *out = c;
     return SPP_OK;
 }

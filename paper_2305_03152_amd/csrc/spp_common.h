@@ -112,7 +112,8 @@ struct spp_ctx {
     int         miss_lds = 0;           // dynamic LDS bytes of the miss kernel
     spp::DevBuf gtable;                 // vertices missed by the current gather call (id -> first row)
     spp::DevBuf gfirst;                 // the same per row of the remote store (SPP_STORE_ORDER): first row that misses it
-    int64_t*    h_pinned = nullptr;     // pinned host mirror: [0..15] mfg counts, [16..23] gather counters
+    int64_t*    h_pinned = nullptr;     // pinned host mirror (8192 int64): gather counters from 40, sampler counts from 64,
+                                        // per-workgroup frontier sizes of the VIP propagation from 2048
     int64_t*    totals = nullptr;       // device int64[16], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces
     spp::DevBuf y0, y1, tot, acc, frontier;

@@ -15,16 +15,19 @@
 // measured, from 2.4M to 134M vertices.)  A second kernel adds the shares and finishes the vertex
 // (p^[h], running total, next hop's y).
 //
-// Early hops touch few edges (hop 1 only the rows of T), so before each hop the vertices with
-// y != 0 are compacted into a frontier and their out-edges counted; when that is a small share of
-// the graph the hop is done in push form instead: each frontier vertex adds its y to the fp64
-// accumulator of every member of its row (atomic adds), and one pass finishes all vertices.
+// Early hops touch few edges (hop 1 only the rows of T), so the kernel that writes a hop's y also
+// counts the hop's frontier (vertices with y != 0) and its out-edges; when that is a small share of
+// the graph the frontier is compacted into a list and the hop is done in push form instead: each
+// frontier vertex adds its y to the fp64 accumulator of every member of its row (atomic adds), and
+// one pass finishes all vertices.
 #include "spp_common.h"
 #include "spp_device.h"
 
 namespace spp {
 
 constexpr int64_t kPushShare = 16;       // push when the frontier's out-edges are at most M/16
+constexpr int kStatBlocks = 2048;        // most workgroups that report a part of the next frontier's size
+constexpr int kStatMirror = 2048;        // where those reports land in the context's pinned mirror (int64 index)
 
 struct VipHop {
     const int64_t* rowptr;     // forward CSR, for d(u)
@@ -36,9 +39,11 @@ struct VipHop {
     double         f_next;     // f_{h+1}
     int            first;      // first hop and hop 0 not included: tot is not read
     int            last;
+    unsigned long long* stat;  // per workgroup: vertices and out-edges of the next hop's frontier (unused at the last hop)
 };
 
-__device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, double S) {
+__device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, double S, unsigned long long& verts,
+                                                  unsigned long long& edges) {
     const double ph = -expm1(S);
     if (a.p_hop) a.p_hop[u] = (float)ph;
     const double T = a.first ? S : a.tot[u] + S;
@@ -54,6 +59,26 @@ __device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, do
             yn = (float)log1p(-(t * ph));
         }
         a.y_next[u] = yn;
+        if (yn != 0.0f) { ++verts; edges += (unsigned long long)d; }
+    }
+}
+
+// The next hop is pushed or pulled depending on the size of its frontier (vertices with y != 0 and
+// their out-edges); the kernel that writes the next hop's y counts both on the way, one pair per
+// workgroup (no atomics: same-address atomics cost about 15 ns each), and the host adds the pairs.
+__device__ __forceinline__ void write_frontier_stat(unsigned long long* stat, unsigned long long verts,
+                                                    unsigned long long edges) {
+    __shared__ unsigned long long red[2][kBlock / kWave];
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        verts += __shfl_down((long long)verts, off, kWave);
+        edges += __shfl_down((long long)edges, off, kWave);
+    }
+    if (lane_id() == 0) { red[0][threadIdx.x >> 6] = verts; red[1][threadIdx.x >> 6] = edges; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        stat[2 * blockIdx.x] = red[0][0] + red[0][1] + red[0][2] + red[0][3];
+        stat[2 * blockIdx.x + 1] = red[1][0] + red[1][1] + red[1][2] + red[1][3];
     }
 }
 
@@ -64,31 +89,6 @@ __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
 __global__ void fill_f64_kernel(double* p, int64_t n, double v) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
-}
-
-// Size of a hop's frontier: counters[0] = vertices whose y is not zero, counters[1] = their out-edges.
-__global__ void __launch_bounds__(kBlock) vip_frontier_stats_kernel(const float* __restrict__ y,
-                                                                    const int64_t* __restrict__ rowptr, int64_t N,
-                                                                    unsigned long long* __restrict__ counters) {
-    unsigned long long verts = 0, edges = 0;
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < N; v += stride) {
-        if (y[v] != 0.0f) { ++verts; edges += (unsigned long long)(rowptr[v + 1] - rowptr[v]); }
-    }
-    // one pair of atomics per workgroup: atomics on one address cost ~15 ns each, back to back
-    __shared__ unsigned long long red[2][4];
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        verts += __shfl_down((long long)verts, off, kWave);
-        edges += __shfl_down((long long)edges, off, kWave);
-    }
-    if (lane_id() == 0) { red[0][threadIdx.x >> 6] = verts; red[1][threadIdx.x >> 6] = edges; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned long long tv = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-        const unsigned long long te = red[1][0] + red[1][1] + red[1][2] + red[1][3];
-        if (tv) { atomicAdd(&counters[0], tv); atomicAdd(&counters[1], te); }
-    }
 }
 
 // The frontier itself (any order): list[0 .. *cursor) = vertices whose y is not zero.
@@ -132,7 +132,9 @@ __global__ void __launch_bounds__(kBlock) vip_push_kernel(const int32_t* __restr
 
 __global__ void __launch_bounds__(kBlock) vip_push_finish_kernel(VipHop a, const double* __restrict__ acc, int64_t N) {
     const int64_t stride = (int64_t)gridDim.x * kBlock;
-    for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) vip_finish_vertex(a, u, acc[u]);
+    unsigned long long verts = 0, edges = 0;
+    for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) vip_finish_vertex(a, u, acc[u], verts, edges);
+    if (!a.last) write_frontier_stat(a.stat, verts, edges);
 }
 
 // Dense hops, blocked: one workgroup takes the j-th of `parts` equal shares of the edges that end
@@ -240,28 +242,37 @@ __global__ void __launch_bounds__(kTileBlock) vip_tile_kernel(const uint32_t* __
 __global__ void __launch_bounds__(kBlock) vip_tile_finish_kernel(VipHop a, const double* __restrict__ part, int parts,
                                                                  int64_t part_stride, int64_t N) {
     const int64_t stride = (int64_t)gridDim.x * kBlock;
+    unsigned long long verts = 0, edges = 0;
     for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) {
         double S = part[u];
         for (int j = 1; j < parts; ++j) S += part[(int64_t)j * part_stride + u];
-        vip_finish_vertex(a, u, S);
+        vip_finish_vertex(a, u, S, verts, edges);
     }
+    if (!a.last) write_frontier_stat(a.stat, verts, edges);
 }
 
-// y_1(v) for the training vertices (p^[0] = min(1, B/|T|), Sec. 3.1); optionally hop 0 into the total.
-__global__ void vip_init_kernel(const int32_t* __restrict__ T, int64_t nT, int64_t N, double p0, double f1,
-                                const int64_t* __restrict__ rowptr, float* __restrict__ y,
-                                double* __restrict__ tot, int include_hop0, int* __restrict__ bad) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= nT) return;
-    const int64_t v = T[i];
-    if (v < 0 || v >= N) { *bad = 1; return; }
-    const int64_t d = rowptr[v + 1] - rowptr[v];
-    if (d > 0) {
-        double t = f1 / (double)d;
-        if (t > 1.0) t = 1.0;
-        y[v] = (float)log1p(-(t * p0));
+// y_1(v) for the training vertices (p^[0] = min(1, B/|T|), Sec. 3.1); optionally hop 0 into the
+// total; counts hop 1's frontier on the way.
+__global__ void __launch_bounds__(kBlock) vip_init_kernel(const int32_t* __restrict__ T, int64_t nT, int64_t N, double p0,
+                                                          double f1, const int64_t* __restrict__ rowptr,
+                                                          float* __restrict__ y, double* __restrict__ tot, int include_hop0,
+                                                          int* __restrict__ bad, unsigned long long* __restrict__ stat) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    unsigned long long verts = 0, edges = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nT; i += stride) {
+        const int64_t v = T[i];
+        if (v < 0 || v >= N) { *bad = 1; continue; }
+        const int64_t d = rowptr[v + 1] - rowptr[v];
+        if (d > 0) {
+            double t = f1 / (double)d;
+            if (t > 1.0) t = 1.0;
+            const float yv = (float)log1p(-(t * p0));
+            y[v] = yv;
+            if (yv != 0.0f) { ++verts; edges += (unsigned long long)d; }
+        }
+        if (include_hop0) tot[v] = log1p(-p0);
     }
-    if (include_hop0) tot[v] = log1p(-p0);
+    write_frontier_stat(stat, verts, edges);
 }
 
 // ---- Proposition 1 with arbitrary initial and transition probabilities (Sec. 3.1) -------------
@@ -412,15 +423,18 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         ctx->tile_lds_set = (int)lds_bytes;
     }
-    SPP_TRY(ctx->frontier.reserve((size_t)(N + 2) * sizeof(int32_t) + 4 * sizeof(unsigned long long)));
+    // the kernels that write a hop's y run this many workgroups; each leaves the size of the part of
+    // the next frontier it saw (at most kStatBlocks pairs fit the pinned mirror)
+    const int fill_grid = ctx->num_cu * 8 < kStatBlocks ? ctx->num_cu * 8 : kStatBlocks;
+    SPP_TRY(ctx->frontier.reserve((size_t)(N + 2) * sizeof(int32_t) + (4 + 2 * (size_t)kStatBlocks) * sizeof(unsigned long long)));
     int32_t* flist = ctx->frontier.as<int32_t>();
-    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (N + (N & 1)));
+    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (N + (N & 1)));    // [2]: cursor of the list
+    unsigned long long* fstat = fcount + 4;
     float* ycur = ctx->y0.as<float>();
     float* ynext = ctx->y1.as<float>();
     double* tot = ctx->tot.as<double>();
     int* d_bad = reinterpret_cast<int*>(tot + N);
     const int include0 = (flags & SPP_VIP_INCLUDE_HOP0) ? 1 : 0;
-    const int fill_grid = ctx->num_cu * 8;
     double p0 = (double)B / (double)nT;
     if (p0 > 1.0) p0 = 1.0;
 
@@ -429,8 +443,8 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
         fill_f32_kernel<<<fill_grid, kBlock, 0, st>>>(ycur, N, 0.f);
         if (include0) fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(tot, N, 0.0);
         fill_f32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<float*>(d_bad), 1, 0.f);
-        vip_init_kernel<<<(unsigned)((nT + kBlock - 1) / kBlock), kBlock, 0, st>>>(
-            d_T, nT, N, p0, (double)fanouts[0], g->rowptr, ycur, tot, include0, d_bad);
+        vip_init_kernel<<<fill_grid, kBlock, 0, st>>>(d_T, nT, N, p0, (double)fanouts[0], g->rowptr, ycur, tot, include0,
+                                                      d_bad, fstat);
         for (int h = 1; h <= L; ++h) {
             ScopedTimer th(ctx, SPP_T_VIP_HOP_FIRST + h - 1, st);
             VipHop a;
@@ -441,17 +455,23 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
             a.f_next = h < L ? (double)fanouts[h] : 0.0;
             a.first = (h == 1 && !include0) ? 1 : 0;
             a.last = (h == L) ? 1 : 0;
-            // frontier of this hop and its out-edges; a small frontier is pushed, a large one pulled
-            fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount), 3, 0.0);
-            vip_frontier_stats_kernel<<<ctx->num_cu * 2, kBlock, 0, st>>>(ycur, g->rowptr, N, fcount);
-            volatile unsigned long long* fc = reinterpret_cast<volatile unsigned long long*>(ctx->h_pinned + 56);
-            SPP_HIP(hipMemcpyAsync(ctx->h_pinned + 56, fcount, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
-            SPP_HIP(hipStreamSynchronize(st));
+            a.stat = fstat;
+            // frontier of this hop and its out-edges, as counted by the kernel that wrote this hop's y;
+            // a small frontier is pushed, a large one pulled
+            unsigned long long fc[2] = {0, 0};
+            {
+                const unsigned long long* hs = reinterpret_cast<const unsigned long long*>(ctx->h_pinned + kStatMirror);
+                SPP_HIP(hipMemcpyAsync(ctx->h_pinned + kStatMirror, fstat, 2 * (size_t)fill_grid * sizeof(unsigned long long),
+                                       hipMemcpyDeviceToHost, st));
+                SPP_HIP(hipStreamSynchronize(st));
+                for (int b = 0; b < fill_grid; ++b) { fc[0] += hs[2 * b]; fc[1] += hs[2 * b + 1]; }
+            }
             const bool push = (int64_t)fc[1] * kPushShare <= g->M;
             if (push) {
                 double* acc = ctx->acc.as<double>();
                 fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
                 if (fc[0] > 0) {
+                    fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount + 2), 1, 0.0);
                     vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(ycur, N, flist, fcount + 2);
                     const int64_t need = ((int64_t)fc[0] * kWave + kBlock - 1) / kBlock;
                     const int pgrid = (int)(need < (int64_t)ctx->num_cu * 32 ? need : (int64_t)ctx->num_cu * 32);
