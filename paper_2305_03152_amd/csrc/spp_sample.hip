@@ -260,78 +260,122 @@ __device__ __forceinline__ uint32_t general_take4(const SampleArgs& a, uint32_t 
     }
     return m;
 }
-// Taken entries of the 256 entries a wavefront decides in one step: in all lanes, and in the lanes below this one.
-__device__ __forceinline__ int taken_in_wave(uint32_t m, uint64_t lt_mask, int& below) {
+// A row is walked by a group of G lanes (G = 16: four targets per wavefront; G = 64: one), 4 G
+// entries per step.  Most rows hold a handful of entries, a few tens of thousands: rows of at most
+// kShortRow entries are taken four per wavefront in a first sweep over the targets, longer ones by
+// a whole wavefront in a second sweep.
+constexpr int kShortRow = 256;
+constexpr int kShortGroup = 16;
+
+// Taken entries among the 4 G entries a group decides in one step: in all of the group's lanes, and
+// in its lanes below this one.  gmask = the group's lanes, lt_mask = the wavefront's lanes below this one.
+__device__ __forceinline__ int taken_in_group(uint32_t m, uint64_t gmask, uint64_t lt_mask, int& below) {
     int all = 0;
     below = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const uint64_t b = __ballot((m >> i) & 1u);
+        const uint64_t b = __ballot((m >> i) & 1u) & gmask;
         all += __popcll(b);
         below += __popcll(b & lt_mask);
     }
     return all;
 }
 
-__global__ void __launch_bounds__(kBlock) general_count_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    __shared__ unsigned long long red[4];
-    const BatchBlock bb = batch_block();
-    const int jb = bb.j;
-    if (t->b[jb].tinfo[2]) return;
+// Which target a lane group works on in sweep `longer` (0: short rows, G = kShortGroup; 1: long rows, G = 64).
+struct GroupWalk {
+    int64_t first, stride;      // first target of this group and the step to its next one
+    uint32_t glane;             // lane inside the group
+    uint64_t gmask;             // the group's lanes
+};
+template <int G>
+__device__ __forceinline__ GroupWalk group_walk(const BatchBlock& bb) {
     const int lane = lane_id();
-    const int64_t n_prev = t->b[jb].counts[a.h - 1];
-    const uint32_t batch_lo = t->b[jb].batch_lo;
     const int64_t wave = ((int64_t)bb.x * kBlock + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
-    const int32_t* __restrict__ S = t->b[jb].S;
-    int32_t* __restrict__ cnt = cnt_of(a, jb);
-    unsigned long long mine = 0;
-    for (int64_t i = wave; i < n_prev; i += nwaves) {
-        const int64_t v = S[i];
-        const int64_t r0 = a.rowptr[v], d = a.rowptr[v + 1] - r0;
-        int64_t c = 0;
-        for (int64_t k0 = 0; k0 < d; k0 += 4 * kWave) {
-            int below;
-            c += taken_in_wave(general_take4(a, batch_lo, v, r0, k0 + 4 * lane, d), 0ull, below);
+    GroupWalk w;
+    w.first = wave * (kWave / G) + lane / G;
+    w.stride = nwaves * (kWave / G);
+    w.glane = (uint32_t)(lane % G);
+    w.gmask = G == kWave ? ~0ull : ((1ull << (G & 63)) - 1ull) << (lane - lane % G);
+    return w;
+}
+
+template <int G>
+__device__ __forceinline__ void general_count_rows(const SampleArgs& a, const BatchDesc& b, const BatchBlock& bb,
+                                                   int32_t* __restrict__ cnt, unsigned long long& mine) {
+    const GroupWalk w = group_walk<G>(bb);
+    const int64_t n_prev = b.counts[a.h - 1];
+    const int64_t rounds = (n_prev + w.stride - 1) / w.stride;           // whole wavefronts reach the ballots
+    for (int64_t it = 0; it < rounds; ++it) {
+        const int64_t i = w.first + it * w.stride;
+        int64_t v = 0, r0 = 0, d = 0;
+        if (i < n_prev) {
+            v = b.S[i];
+            r0 = a.rowptr[v];
+            d = a.rowptr[v + 1] - r0;
+            if ((d > kShortRow) != (G == kWave)) d = 0;                  // the other sweep's row
         }
-        // a count beyond any capacity is stored saturated; the 64-bit total below decides
-        if (lane == 0) { cnt[i] = (int32_t)(c < 0x7FFFFFFFll ? c : 0x7FFFFFFFll); mine += (unsigned long long)c; }
-    }
-    if (lane == 0) red[threadIdx.x >> 6] = mine;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned long long s4 = red[0] + red[1] + red[2] + red[3];
-        if (s4) atomicAdd(t->b[jb].taken, s4);
+        int64_t c = 0;
+        // groups of one wavefront walk rows of different lengths: all step until the longest is done
+        for (int64_t k0 = 0; __any(k0 < d); k0 += 4 * G) {
+            int below;
+            c += taken_in_group(k0 < d ? general_take4(a, b.batch_lo, v, r0, k0 + 4 * w.glane, d) : 0u, w.gmask, 0ull, below);
+        }
+        // a count beyond any capacity is stored saturated; the 64-bit total decides
+        if (i < n_prev && w.glane == 0 && ((a.rowptr[v + 1] - a.rowptr[v] > kShortRow) == (G == kWave))) {
+            cnt[i] = (int32_t)(c < 0x7FFFFFFFll ? c : 0x7FFFFFFFll);
+            mine += (unsigned long long)c;
+        }
     }
 }
 
-__global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+__global__ void __launch_bounds__(kBlock) general_count_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    __shared__ unsigned long long red[kBlock];
     const BatchBlock bb = batch_block();
     const int jb = bb.j;
     if (t->b[jb].tinfo[2]) return;
+    unsigned long long mine = 0;
+    general_count_rows<kShortGroup>(a, t->b[jb], bb, cnt_of(a, jb), mine);
+    general_count_rows<kWave>(a, t->b[jb], bb, cnt_of(a, jb), mine);
+    red[threadIdx.x] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long s = 0;
+        for (int k = 0; k < kBlock; ++k) s += red[k];
+        if (s) atomicAdd(t->b[jb].taken, s);
+    }
+}
+
+template <int G>
+__device__ __forceinline__ void general_sample_rows(const SampleArgs& a, const BatchDesc& b, const BatchBlock& bb,
+                                                    int32_t* __restrict__ flat, unsigned long long* tab) {
+    const GroupWalk w = group_walk<G>(bb);
     const int lane = lane_id();
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    const int64_t n_prev = t->b[jb].counts[a.h - 1];
-    const uint32_t batch_lo = t->b[jb].batch_lo;
-    const int64_t wave = ((int64_t)bb.x * kBlock + threadIdx.x) >> 6;
-    const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
-    const int32_t* __restrict__ S = t->b[jb].S;
-    const int32_t* __restrict__ indptr = t->b[jb].indptr[a.h - 1];
-    int32_t* __restrict__ flat = flat_of(a, jb);
-    unsigned long long* tab = tab_of(a, jb);
-    const uint32_t mask = t->b[jb].tinfo[0];
-    const int shift = (int)t->b[jb].tinfo[1];
-    for (int64_t i = wave; i < n_prev; i += nwaves) {
-        const int64_t v = S[i];
-        const int64_t r0 = a.rowptr[v], d = a.rowptr[v + 1] - r0;
-        // the table was emptied for this hop, so the target is offered again with its index
-        if (lane == 0) table_insert_min(tab, mask, shift, (uint32_t)v, (uint32_t)i);
-        int64_t e = indptr[i];
-        for (int64_t k0 = 0; k0 < d; k0 += 4 * kWave) {
-            const int64_t k4 = k0 + 4 * lane;
-            const uint32_t m = general_take4(a, batch_lo, v, r0, k4, d);
+    const int64_t n_prev = b.counts[a.h - 1];
+    const int32_t* __restrict__ indptr = b.indptr[a.h - 1];
+    const uint32_t mask = b.tinfo[0];
+    const int shift = (int)b.tinfo[1];
+    const int64_t rounds = (n_prev + w.stride - 1) / w.stride;
+    for (int64_t it = 0; it < rounds; ++it) {
+        const int64_t i = w.first + it * w.stride;
+        int64_t v = 0, r0 = 0, d = 0, e = 0;
+        if (i < n_prev) {
+            v = b.S[i];
+            r0 = a.rowptr[v];
+            d = a.rowptr[v + 1] - r0;
+            if ((d > kShortRow) != (G == kWave)) d = 0;
+            else {
+                e = indptr[i];
+                // the table was emptied for this hop, so the target is offered again with its index
+                if (w.glane == 0) table_insert_min(tab, mask, shift, (uint32_t)v, (uint32_t)i);
+            }
+        }
+        for (int64_t k0 = 0; __any(k0 < d); k0 += 4 * G) {
+            const int64_t k4 = k0 + 4 * w.glane;
+            const uint32_t m = k0 < d ? general_take4(a, b.batch_lo, v, r0, k4, d) : 0u;
             int below;
-            const int all = taken_in_wave(m, lt_mask, below);
+            const int all = taken_in_group(m, w.gmask, lt_mask, below);
             int64_t pos = e + below;                   // entries ascend with the lane, then inside the lane
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -344,6 +388,14 @@ __global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, co
             e += all;
         }
     }
+}
+
+__global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    const BatchBlock bb = batch_block();
+    const int jb = bb.j;
+    if (t->b[jb].tinfo[2]) return;
+    general_sample_rows<kShortGroup>(a, t->b[jb], bb, flat_of(a, jb), tab_of(a, jb));
+    general_sample_rows<kWave>(a, t->b[jb], bb, flat_of(a, jb), tab_of(a, jb));
 }
 
 // ---- step 3 ----
