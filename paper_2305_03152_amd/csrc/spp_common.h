@@ -117,6 +117,8 @@ struct spp_ctx {
     int64_t*    totals = nullptr;       // device int64[16], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces
     spp::DevBuf y0, y1, tot, acc, frontier;
+    spp::DevBuf bins;                   // general propagation: per row block the (row, weight) entries of a hop, and the fill counts
+    int         bin_lds_set = 0, sum_lds_set = 0;   // dynamic LDS bytes its two kernels have been allowed
     int         tile_lds_set = 0;       // dynamic LDS bytes the dense-hop kernel has been allowed on this device
     int         vip_pushed[SPP_MAX_L] = {};          // last vip_propagate: hop done in push form?
     int64_t     vip_frontier_edges[SPP_MAX_L] = {};  // last vip_propagate: out-edges of each hop's frontier

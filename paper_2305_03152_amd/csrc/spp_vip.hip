@@ -91,24 +91,32 @@ __global__ void fill_f64_kernel(double* p, int64_t n, double v) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
 }
 
-// The frontier itself (any order): list[0 .. *cursor) = vertices whose y is not zero.
+// The frontier itself (any order): list[0 .. *cursor) = vertices whose y is not zero.  A thread
+// looks at kListPer consecutive vertices and a workgroup reserves its part of the list with one
+// atomic per round (same-address atomics cost about 15 ns each: one per wavefront of 64 vertices
+// took 0.45 ms on a frontier of 2.4M vertices).
+constexpr int kListPer = 8;
 __global__ void __launch_bounds__(kBlock) vip_frontier_list_kernel(const float* __restrict__ y, int64_t N,
                                                                    int32_t* __restrict__ list,
                                                                    unsigned long long* __restrict__ cursor) {
-    const int lane = lane_id();
-    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    const int64_t n_round = (N + kWave - 1) / kWave * kWave;      // whole wavefronts reach the ballot
-    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n_round; v += stride) {
-        const bool in = v < N && y[v] != 0.0f;
-        const uint64_t m = __ballot(in);
-        if (m) {
-            const int leader = __ffsll((unsigned long long)m) - 1;
-            unsigned long long base = 0;
-            if (lane == leader) base = atomicAdd(cursor, (unsigned long long)__popcll(m));
-            base = __shfl((long long)base, leader, kWave);
-            if (in) list[base + __popcll(m & lt_mask)] = (int32_t)v;
-        }
+    __shared__ int scan_lds[4];
+    __shared__ unsigned long long start;
+    const int64_t round = (int64_t)kBlock * kListPer;
+    for (int64_t r0 = (int64_t)blockIdx.x * round; r0 < N; r0 += (int64_t)gridDim.x * round) {
+        const int64_t v0 = r0 + (int64_t)threadIdx.x * kListPer;
+        unsigned in = 0;
+#pragma unroll
+        for (int k = 0; k < kListPer; ++k)
+            if (v0 + k < N && y[v0 + k] != 0.0f) in |= 1u << k;
+        int total;
+        int at = block_exclusive_scan(__popc(in), scan_lds, total);
+        if (threadIdx.x == 0 && total) start = atomicAdd(cursor, (unsigned long long)total);
+        __syncthreads();
+        const unsigned long long base = start;
+#pragma unroll
+        for (int k = 0; k < kListPer; ++k)
+            if (in >> k & 1u) list[base + at++] = (int32_t)(v0 + k);
+        __syncthreads();
     }
 }
 
@@ -318,13 +326,269 @@ __global__ void __launch_bounds__(kBlock) vipg_push_kernel(const int32_t* __rest
     }
 }
 
+// Push without global atomics, for graphs that carry the row-block structure: the fp64 global
+// atomic adds of vipg_push_kernel run at about 21 G/s whatever the walk, so a dense hop of 121M
+// edges takes 5.7 ms.  Here every frontier edge v -> u becomes an entry (fp32 weight, row of u
+// inside its block) in the bin of u's row block, and a second kernel adds a bin's entries into the
+// block's fp64 sums in LDS, as the pull over row blocks does.  A bin has room for every edge that
+// ends in its block (its base and size are the block's range in the transposed structure), so no
+// counting pass over the hop is needed.  A workgroup takes a portion of the frontier and lays the
+// rows of its vertices end to end (prefix sums of their lengths in LDS; a thread takes kBinPer
+// consecutive edges of that sequence whatever the row lengths).  One walk over col[] counts the
+// portion's entries per bin, and one global atomic per bin reserves their range (one per chunk
+// instead serialised on the bins' counters: 59k same-address atomics, 0.9 ms).  A second walk, in
+// chunks, forms the entries, sorts a chunk's entries by bin in LDS and writes them out with
+// neighbouring threads writing neighbouring entries of a bin (scattered stores, one per edge, ran
+// slower).  The weight is log1p in fp32: it is stored as fp32 anyway, and the fp64 routine was
+// 117 of the walk's 300 instructions per edge.
+constexpr int kBinBlock = 256;           // threads per workgroup, and most frontier vertices per portion
+constexpr int kBinPer = 8;               // consecutive edges per thread and chunk
+constexpr int kBinChunk = kBinBlock * kBinPer;
+constexpr int64_t kBinMaxBlocks = 8192;  // row blocks whose three counters each fit the LDS of a workgroup
+
+struct BinPortion {
+    uint32_t prefix[kBinBlock + 1];      // edges of the portion before vertex i
+    int64_t  row[kBinBlock];             // where vertex i's row starts in col[] and t[]
+    float    p[kBinBlock];               // p^[h-1] of vertex i
+    uint32_t wave_sum[kBinBlock / kWave];
+    uint2    stage[kBinChunk];           // a chunk's entries sorted by bin: (weight bits, block << 14 | row)
+};
+
+// Exclusive prefix sums over a workgroup of kBinBlock threads; ends with a barrier.
+__device__ __forceinline__ uint32_t bin_block_scan(uint32_t v, uint32_t* wave_sum, uint32_t& total) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t inc = (uint32_t)wave_inclusive_scan((int)v);
+    if (lane == kWave - 1) wave_sum[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kBinBlock / kWave; ++w) {
+        const uint32_t x = wave_sum[w];
+        if (w < wave) before += x;
+        all += x;
+    }
+    total = all;
+    __syncthreads();
+    return before + inc - v;
+}
+
+// The vertex of the portion whose row holds edge x of the sequence (x < prefix[nv]): the last i
+// with prefix[i] <= x.
+__device__ __forceinline__ int bin_vertex_of(const BinPortion& po, int nv, uint32_t x) {
+    int lo = 0, hi = nv;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (po.prefix[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// A thread's walk over consecutive edges of the portion's sequence: where edge x sits in col[] and
+// t[], and the probability of its source.  Rows are entered by comparison with the row's end, so an
+// edge inside a row costs an add.
+struct BinCursor {
+    int      i;          // vertex of the portion
+    uint32_t row_end;    // first x beyond its row
+    int64_t  k;          // position of the next edge
+    float    p;
+    __device__ __forceinline__ void start(const BinPortion& po, int nv, uint32_t x) {
+        i = bin_vertex_of(po, nv, x);
+        row_end = po.prefix[i + 1];
+        k = po.row[i] + (int64_t)(x - po.prefix[i]);
+        p = po.p[i];
+    }
+    __device__ __forceinline__ int64_t next(const BinPortion& po, uint32_t x) {   // x < prefix[nv]
+        if (x >= row_end) {
+            do { ++i; row_end = po.prefix[i + 1]; } while (x >= row_end);
+            k = po.row[i] + (int64_t)(x - po.prefix[i]);
+            p = po.p[i];
+        }
+        return k++;
+    }
+};
+
+// log1p(-x) for 0 < x <= 1 to a few fp32 ulp.  All terms of a vertex's sum have one sign, so the
+// sum's relative error is at most the largest of its terms'; the library's fp32 and fp64 routines
+// carry extended precision that is of no use here and were 90 and 117 of the walk's instructions per
+// edge.  Below 1/4 the atanh series in s = x / (2 - x) <= 1/7 (six terms: the next is below 2^-33
+// of the first); above, the logarithm of 1 - x, whose rounding error is at most 2^-25 against a
+// result of at least 0.28.
+__device__ __forceinline__ float bin_log1p_neg(float x) {
+    const float s = __fdividef(x, 2.0f - x);
+    const float z = s * s;
+    float q = 1.0f / 11.0f;
+    q = __fmaf_rn(q, z, 1.0f / 9.0f);
+    q = __fmaf_rn(q, z, 1.0f / 7.0f);
+    q = __fmaf_rn(q, z, 1.0f / 5.0f);
+    q = __fmaf_rn(q, z, 1.0f / 3.0f);
+    q = __fmaf_rn(q, z, 1.0f);
+    const float small = -2.0f * s * q;
+    const float large = __logf(1.0f - x);
+    return x < 0.25f ? small : large;
+}
+
+__global__ void __launch_bounds__(kBinBlock) vipg_bin_fill_kernel(const int32_t* __restrict__ list,
+                                                                  const unsigned long long* __restrict__ nf_ptr,
+                                                                  const float* __restrict__ pcur,
+                                                                  const int64_t* __restrict__ rowptr,
+                                                                  const int32_t* __restrict__ col,
+                                                                  const float* __restrict__ t, int rbits, int nrb,
+                                                                  const int64_t* __restrict__ first, int nch,
+                                                                  uint32_t* __restrict__ cursor,
+                                                                  uint2* __restrict__ bins, int* __restrict__ bad) {
+    __shared__ BinPortion po;
+    extern __shared__ uint32_t lds_u32[];
+    uint32_t* off = lds_u32;             // a chunk's entries per row block, then where the block's entries start in stage[]
+    uint32_t* base = lds_u32 + nrb;      // entry (index into bins[], below 2^32) where the chunk's entries of a block start
+    uint32_t* prev = lds_u32 + 2 * nrb;  // entries of the chunk before, which move base on
+    uint32_t* dest = lds_u32 + 3 * nrb;  // base - off: entry j of stage[] goes to dest + j
+    const int64_t nf = (int64_t)*nf_ptr;
+    // small frontiers are cut into small portions so that they still spread over the chip
+    int64_t per = (nf + gridDim.x - 1) / gridDim.x;
+    per = per < kWave ? kWave : (per > kBinBlock ? kBinBlock : per);
+    const uint32_t rmask = (1u << rbits) - 1u;
+    const int bins_per_thread = (nrb + kBinBlock - 1) / kBinBlock;
+    const int r0 = threadIdx.x * bins_per_thread;
+    const int r1 = r0 + bins_per_thread < nrb ? r0 + bins_per_thread : nrb;
+    // Portions are handed out through a counter (the slot after the bins' cursors): their sizes
+    // differ by the degrees of their vertices, and with fixed shares half of the wavefronts had
+    // left before the kernel's end.
+    __shared__ uint32_t portion;
+    for (;;) {
+        if (threadIdx.x == 0) portion = atomicAdd(&cursor[nrb], 1u);
+        __syncthreads();
+        const int64_t beg = (int64_t)portion * per;
+        if (beg >= nf) break;
+        const int nv = (int)(beg + per < nf ? per : nf - beg);
+        uint32_t deg = 0;
+        if ((int)threadIdx.x < nv) {
+            const int64_t v = list[beg + threadIdx.x];
+            const int64_t b = rowptr[v];
+            deg = (uint32_t)(rowptr[v + 1] - b);
+            po.row[threadIdx.x] = b;
+            po.p[threadIdx.x] = pcur[v];
+        }
+        uint32_t total;
+        const uint32_t ex = bin_block_scan(deg, po.wave_sum, total);
+        if ((int)threadIdx.x < nv) po.prefix[threadIdx.x] = ex;
+        if (threadIdx.x == 0) po.prefix[nv] = total;
+        for (int r = threadIdx.x; r < nrb; r += kBinBlock) base[r] = 0u;
+        __syncthreads();                                   // publishes prefix[], row[], p[]
+        // first walk: the portion's entries per bin
+        for (uint32_t x0 = threadIdx.x * kBinPer; x0 < total; x0 += kBinChunk) {
+            BinCursor cu;
+            cu.start(po, nv, x0);
+            uint32_t u[kBinPer];
+#pragma unroll
+            for (int q = 0; q < kBinPer; ++q) u[q] = x0 + (uint32_t)q < total ? (uint32_t)col[cu.next(po, x0 + (uint32_t)q)] : ~0u;
+#pragma unroll
+            for (int q = 0; q < kBinPer; ++q)
+                if (u[q] != ~0u) atomicAdd(&base[u[q] >> rbits], 1u);
+        }
+        __syncthreads();
+        for (int r = r0; r < r1; ++r) {
+            const uint32_t c = base[r];
+            base[r] = (uint32_t)first[(int64_t)r * nch] + (c ? atomicAdd(&cursor[r], c) : 0u);
+            prev[r] = 0u;
+        }
+        // second walk, in chunks
+        for (uint32_t c0 = 0; c0 < total; c0 += kBinChunk) {
+            for (int r = threadIdx.x; r < nrb; r += kBinBlock) off[r] = 0u;
+            __syncthreads();
+            // the thread's entries of the chunk, kept in registers with their rank inside their bin
+            uint32_t key[kBinPer], wbits[kBinPer], rank[kBinPer];
+            const uint32_t x0 = c0 + threadIdx.x * kBinPer;
+            float pv[kBinPer], tv[kBinPer];
+            if (x0 < total) {
+                BinCursor cu;
+                cu.start(po, nv, x0);
+#pragma unroll
+                for (int q = 0; q < kBinPer; ++q) {
+                    key[q] = ~0u;
+                    if (x0 + (uint32_t)q < total) {
+                        const int64_t k = cu.next(po, x0 + (uint32_t)q);
+                        key[q] = (uint32_t)col[k];
+                        tv[q] = t[k];
+                        pv[q] = cu.p;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < kBinPer; ++q) key[q] = ~0u;
+            }
+#pragma unroll
+            for (int q = 0; q < kBinPer; ++q) {
+                if (key[q] != ~0u) {
+                    const uint32_t u = key[q];
+                    const float xw = unit_or_flag(tv[q], bad) * pv[q];
+                    const uint32_t rb = u >> rbits;
+                    key[q] = (rb << kTileRowBits) | (u & rmask);
+                    wbits[q] = __float_as_uint(xw > 0.0f ? bin_log1p_neg(xw) : 0.0f);
+                    rank[q] = atomicAdd(&off[rb], 1u);
+                }
+            }
+            __syncthreads();
+            // off[] becomes the exclusive prefix of the chunk's counts; base[] moves past the chunk before
+            uint32_t mine = 0;
+            for (int r = r0; r < r1; ++r) mine += off[r];
+            uint32_t n_chunk;
+            uint32_t run = bin_block_scan(mine, po.wave_sum, n_chunk);
+            for (int r = r0; r < r1; ++r) {
+                const uint32_t c = off[r];
+                const uint32_t b = base[r] + prev[r];
+                off[r] = run;
+                base[r] = b;
+                dest[r] = b - run;
+                prev[r] = c;
+                run += c;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < kBinPer; ++q)
+                if (key[q] != ~0u) po.stage[off[key[q] >> kTileRowBits] + rank[q]] = make_uint2(wbits[q], key[q]);
+            __syncthreads();
+            for (uint32_t j = threadIdx.x; j < n_chunk; j += kBinBlock) {
+                const uint2 e = po.stage[j];
+                bins[dest[e.y >> kTileRowBits] + j] = make_uint2(e.x, e.y & kTileRowMask);
+            }
+            __syncthreads();
+        }
+        __syncthreads();
+    }
+}
+
+// Adds the entries of one share of one bin into the block's fp64 sums (LDS) and writes them to
+// part[j][row], like vip_tile_kernel but with the weights already in place.
+__global__ void __launch_bounds__(kTileBlock) vip_bin_sum_kernel(const uint2* __restrict__ bins,
+                                                                 const uint32_t* __restrict__ cursor,
+                                                                 const int64_t* __restrict__ first, int nch, int parts,
+                                                                 int rbits, double* __restrict__ part, int64_t part_stride) {
+    extern __shared__ double acc[];
+    const int R = 1 << rbits;
+    const int64_t rb = blockIdx.x / parts;
+    const int j = blockIdx.x % parts;
+    for (int i = threadIdx.x; i < R; i += kTileBlock) acc[i] = 0.0;
+    __syncthreads();
+    const int64_t b0 = first[rb * nch], len = (int64_t)cursor[rb];
+    const int64_t beg = b0 + len * j / parts, end = b0 + len * (j + 1) / parts;
+    for (int64_t e = beg + threadIdx.x; e < end; e += kTileBlock) {
+        const unsigned long long x = __builtin_nontemporal_load(reinterpret_cast<const unsigned long long*>(bins) + e);
+        const uint32_t w = (uint32_t)x;                    // .x of the entry
+        if (w != 0u) unsafeAtomicAdd(&acc[(uint32_t)(x >> 32)], (double)__uint_as_float(w));
+    }
+    __syncthreads();
+    double* __restrict__ out = part + (int64_t)j * part_stride + (rb << rbits);
+    for (int i = threadIdx.x; i < R; i += kTileBlock) out[i] = acc[i];
+}
+
 __global__ void __launch_bounds__(kBlock) vipg_finish_kernel(const double* __restrict__ acc, double* __restrict__ tot,
                                                              int first, int last, float* __restrict__ p_hop,
                                                              float* __restrict__ p_total, float* __restrict__ pnext,
-                                                             int64_t N) {
+                                                             int64_t N, int parts, int64_t part_stride) {
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) {
-        const double S = acc[u];
+        double S = acc[u];
+        for (int j = 1; j < parts; ++j) S += acc[(int64_t)j * part_stride + u];
         const double ph = -expm1(S);
         if (p_hop) p_hop[u] = (float)ph;
         const double T = first ? S : tot[u] + S;
@@ -360,6 +624,33 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
     int* d_bad = reinterpret_cast<int*>(tot + N);
     const int include0 = (flags & SPP_VIP_INCLUDE_HOP0) ? 1 : 0;
     const int fill_grid = ctx->num_cu * 8;
+    // With the row-block structure at hand the push goes through bins (no global fp64 atomics).
+    const bool binned = g->has_in && g->nrb > 0 && g->nrb <= kBinMaxBlocks && g->M > 0;
+    int parts = 1;
+    const int64_t part_stride = binned ? g->nrb << g->tile_rbits : N;
+    uint2* bins = nullptr;
+    uint32_t* cursor = nullptr;
+    const size_t fill_lds = binned ? 4 * (size_t)g->nrb * sizeof(uint32_t) : 0;
+    const size_t sum_lds = binned ? sizeof(double) << g->tile_rbits : 0;
+    if (binned) {
+        const int64_t want = ((int64_t)ctx->num_cu * 4 + g->nrb - 1) / g->nrb;
+        parts = (int)(want < 1 ? 1 : (want > 16 ? 16 : want));
+        SPP_TRY(ctx->acc.reserve((size_t)parts * (size_t)part_stride * sizeof(double)));
+        acc = ctx->acc.as<double>();
+        SPP_TRY(ctx->bins.reserve(((size_t)g->M + (size_t)g->nrb + 1) * sizeof(uint2)));
+        bins = ctx->bins.as<uint2>();
+        cursor = reinterpret_cast<uint32_t*>(bins + g->M);
+        if (ctx->bin_lds_set < (int)fill_lds) {
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vipg_bin_fill_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)fill_lds));
+            ctx->bin_lds_set = (int)fill_lds;
+        }
+        if (ctx->sum_lds_set < (int)sum_lds) {
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vip_bin_sum_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)sum_lds));
+            ctx->sum_lds_set = (int)sum_lds;
+        }
+    }
     {
         ScopedTimer tt(ctx, SPP_T_VIP_TOTAL, st);
         fill_f32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<float*>(d_bad), 1, 0.f);
@@ -367,13 +658,23 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
         for (int h = 1; h <= L; ++h) {
             ScopedTimer th(ctx, SPP_T_VIP_HOP_FIRST + h - 1, st);
             fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount), 3, 0.0);
-            fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
             vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(pcur, N, flist, fcount + 2);
-            vipg_push_kernel<<<ctx->num_cu * 32, kBlock, 0, st>>>(flist, fcount + 2, pcur, g->rowptr, g->col,
-                                                                 d_t[h - 1], acc, d_bad);
+            if (binned) {
+                fill_f32_kernel<<<(unsigned)((g->nrb + kBlock) / kBlock), kBlock, 0, st>>>(
+                    reinterpret_cast<float*>(cursor), g->nrb + 1, 0.f);         // all-zero bits either way
+                vipg_bin_fill_kernel<<<ctx->num_cu * 6, kBinBlock, fill_lds, st>>>(
+                    flist, fcount + 2, pcur, g->rowptr, g->col, d_t[h - 1], g->tile_rbits, (int)g->nrb,
+                    g->tile_first, g->nch, cursor, bins, d_bad);
+                vip_bin_sum_kernel<<<(unsigned)(g->nrb * parts), kTileBlock, sum_lds, st>>>(
+                    bins, cursor, g->tile_first, g->nch, parts, g->tile_rbits, acc, part_stride);
+            } else {
+                fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
+                vipg_push_kernel<<<ctx->num_cu * 32, kBlock, 0, st>>>(flist, fcount + 2, pcur, g->rowptr, g->col,
+                                                                     d_t[h - 1], acc, d_bad);
+            }
             vipg_finish_kernel<<<fill_grid, kBlock, 0, st>>>(acc, tot, (h == 1 && !include0) ? 1 : 0, h == L ? 1 : 0,
                                                              d_p_hop ? d_p_hop + (int64_t)(h - 1) * N : nullptr,
-                                                             d_p_total, pnext, N);
+                                                             d_p_total, pnext, N, parts, part_stride);
             ctx->vip_pushed[h - 1] = 1;
             ctx->vip_frontier_edges[h - 1] = -1;
             float* tmp = pcur; pcur = pnext; pnext = tmp;

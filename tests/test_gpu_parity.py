@@ -661,13 +661,16 @@ def test_general_probabilities_tiny(spp, ctx, tiny_case):
     t_d = [torch.from_numpy(a).cuda() for a in t_np]
     p0 = np.where(rng.random(cfg.N) < 0.05, rng.random(cfg.N), 0.0).astype(np.float32)
     p0[:3] = [1.0, 0.0, 0.5]
+    # a graph with the row-block structure takes the binned push, one without it the atomic push
+    G_plain = spp.Graph(ctx, c.rowptr_d, c.col_d, in_lists=False)
     for L, hop0 in ((3, False), (2, True), (1, False)):
-        _say("general vip L", L, "hop0", hop0)
-        p, ph = spp.vip_propagate_general(ctx, c.G, torch.from_numpy(p0).cuda(), t_d[:L], L, per_hop=True, include_hop0=hop0)
         rt, rh = oracle.vip_general(c.rp, c.col, p0, t_np[:L], L, include_hop0=hop0)
-        _check_vip(p, rt)
-        for h in range(L):
-            _check_vip(ph[h], rh[h])
+        for G in (c.G, G_plain):
+            _say("general vip L", L, "hop0", hop0, "row blocks", G is c.G)
+            p, ph = spp.vip_propagate_general(ctx, G, torch.from_numpy(p0).cuda(), t_d[:L], L, per_hop=True, include_hop0=hop0)
+            _check_vip(p, rt)
+            for h in range(L):
+                _check_vip(ph[h], rh[h])
     # one tensor for every hop; the uniform instantiation agrees with the uniform entry point
     _say("general vip, uniform instantiation")
     p0u = np.zeros(cfg.N, np.float32)
