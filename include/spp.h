@@ -267,9 +267,13 @@ int  spp_gather_features_split(spp_ctx* ctx, const spp_cache* cache, const spp_l
  *              the probability that the vertex of the row samples that entry at hop h
  *       p^[h](u) = 1 - prod over edges e with col[e] = u of (1 - d_t[h-1][e] * p^[h-1](row(e)))
  *     and p(u) as in eq. (1).  Walked in push form over the CSR (the graph needs no transposed
- *     structure), fp64 log-sums, fp32 results; no host synchronisation inside.  A probability
- *     outside [0, 1] (or not a number) counts as 0 and is reported (SPP_E_ARG) when SPP_SYNC is
- *     set.  flags: SPP_VIP_INCLUDE_HOP0, SPP_SYNC. */
+ *     structure), fp64 log-sums, fp32 results; no host synchronisation inside.  On a graph
+ *     created with SPP_GRAPH_IN_LISTS the edges' terms go through per-row-block bins instead of
+ *     global atomic adds (about four times faster); the terms are then formed and held in fp32
+ *     (a few ulp each, all of one sign, so the sums keep that relative accuracy) and the context
+ *     keeps 8*M bytes of device memory for the bins.  A probability outside [0, 1] (or not a
+ *     number) counts as 0 and is reported (SPP_E_ARG) when SPP_SYNC is set.
+ *     flags: SPP_VIP_INCLUDE_HOP0, SPP_SYNC. */
 int  spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const float* d_p0, const float* const* d_t,
                                int32_t L, float* d_p_total, float* d_p_hop, uint32_t flags);
 

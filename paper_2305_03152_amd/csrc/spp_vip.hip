@@ -333,25 +333,24 @@ __global__ void __launch_bounds__(kBlock) vipg_push_kernel(const int32_t* __rest
 // block's fp64 sums in LDS, as the pull over row blocks does.  A bin has room for every edge that
 // ends in its block (its base and size are the block's range in the transposed structure), so no
 // counting pass over the hop is needed.  A workgroup takes a portion of the frontier and lays the
-// rows of its vertices end to end (prefix sums of their lengths in LDS; a thread takes kBinPer
-// consecutive edges of that sequence whatever the row lengths).  One walk over col[] counts the
-// portion's entries per bin, and one global atomic per bin reserves their range (one per chunk
-// instead serialised on the bins' counters: 59k same-address atomics, 0.9 ms).  A second walk, in
-// chunks, forms the entries, sorts a chunk's entries by bin in LDS and writes them out with
-// neighbouring threads writing neighbouring entries of a bin (scattered stores, one per edge, ran
-// slower).  The weight is log1p in fp32: it is stored as fp32 anyway, and the fp64 routine was
-// 117 of the walk's 300 instructions per edge.
+// rows of its vertices end to end (prefix sums of their lengths in LDS; a wavefront takes runs of
+// 64 consecutive edges of that sequence whatever the row lengths, so its loads are contiguous).
+// One walk over col[] counts the portion's entries per bin in LDS, one global atomic per bin
+// reserves their range (reserving per 2048 edges instead serialised on the bins' counters: 59k
+// same-address atomics, 0.9 ms), and a second walk forms the entries and stores them, the slot
+// inside the range coming from an LDS atomic.  (Sorting 2048 entries at a time by bin in LDS, so
+// that neighbouring threads store neighbouring entries, was slower: 1.2 ms against 0.9 ms per
+// dense hop; a thread taking 8 consecutive edges instead of a wavefront taking 64: 1.25 ms.)
 constexpr int kBinBlock = 256;           // threads per workgroup, and most frontier vertices per portion
-constexpr int kBinPer = 8;               // consecutive edges per thread and chunk
+constexpr int kBinPer = 8;               // edges per thread and round
 constexpr int kBinChunk = kBinBlock * kBinPer;
-constexpr int64_t kBinMaxBlocks = 8192;  // row blocks whose three counters each fit the LDS of a workgroup
+constexpr int64_t kBinMaxBlocks = 16384; // row blocks whose two counters each fit the LDS of a workgroup
 
 struct BinPortion {
     uint32_t prefix[kBinBlock + 1];      // edges of the portion before vertex i
     int64_t  row[kBinBlock];             // where vertex i's row starts in col[] and t[]
     float    p[kBinBlock];               // p^[h-1] of vertex i
     uint32_t wave_sum[kBinBlock / kWave];
-    uint2    stage[kBinChunk];           // a chunk's entries sorted by bin: (weight bits, block << 14 | row)
 };
 
 // Exclusive prefix sums over a workgroup of kBinBlock threads; ends with a barrier.
@@ -383,29 +382,37 @@ __device__ __forceinline__ int bin_vertex_of(const BinPortion& po, int nv, uint3
     return lo;
 }
 
-// A thread's walk over consecutive edges of the portion's sequence: where edge x sits in col[] and
+// A thread's walk over ascending edges of the portion's sequence: where edge x sits in col[] and
 // t[], and the probability of its source.  Rows are entered by comparison with the row's end, so an
-// edge inside a row costs an add.
+// edge inside the row of the edge before costs an add.
 struct BinCursor {
     int      i;          // vertex of the portion
     uint32_t row_end;    // first x beyond its row
-    int64_t  k;          // position of the next edge
+    int64_t  shift;      // position in col[] minus x, inside this row
     float    p;
     __device__ __forceinline__ void start(const BinPortion& po, int nv, uint32_t x) {
         i = bin_vertex_of(po, nv, x);
+        enter(po);
+    }
+    __device__ __forceinline__ void enter(const BinPortion& po) {
         row_end = po.prefix[i + 1];
-        k = po.row[i] + (int64_t)(x - po.prefix[i]);
+        shift = po.row[i] - (int64_t)po.prefix[i];
         p = po.p[i];
     }
-    __device__ __forceinline__ int64_t next(const BinPortion& po, uint32_t x) {   // x < prefix[nv]
+    __device__ __forceinline__ int64_t at(const BinPortion& po, uint32_t x) {     // x < prefix[nv], not below the x before
         if (x >= row_end) {
-            do { ++i; row_end = po.prefix[i + 1]; } while (x >= row_end);
-            k = po.row[i] + (int64_t)(x - po.prefix[i]);
-            p = po.p[i];
+            do { ++i; } while (x >= po.prefix[i + 1]);
+            enter(po);
         }
-        return k++;
+        return shift + (int64_t)x;
     }
 };
+
+// Edge q of a thread in the round that starts at edge c0: a wavefront takes kBinPer runs of 64
+// consecutive edges, so that its loads from col[] and t[] are contiguous.
+__device__ __forceinline__ uint32_t bin_edge(uint32_t c0, int q) {
+    return c0 + (threadIdx.x >> 6) * (kWave * kBinPer) + (uint32_t)q * kWave + (threadIdx.x & (kWave - 1));
+}
 
 // log1p(-x) for 0 < x <= 1 to a few fp32 ulp.  All terms of a vertex's sum have one sign, so the
 // sum's relative error is at most the largest of its terms'; the library's fp32 and fp64 routines
@@ -438,10 +445,8 @@ __global__ void __launch_bounds__(kBinBlock) vipg_bin_fill_kernel(const int32_t*
                                                                   uint2* __restrict__ bins, int* __restrict__ bad) {
     __shared__ BinPortion po;
     extern __shared__ uint32_t lds_u32[];
-    uint32_t* off = lds_u32;             // a chunk's entries per row block, then where the block's entries start in stage[]
-    uint32_t* base = lds_u32 + nrb;      // entry (index into bins[], below 2^32) where the chunk's entries of a block start
-    uint32_t* prev = lds_u32 + 2 * nrb;  // entries of the chunk before, which move base on
-    uint32_t* dest = lds_u32 + 3 * nrb;  // base - off: entry j of stage[] goes to dest + j
+    uint32_t* base = lds_u32;            // the portion's entries per row block, then the entry (index into bins[], below 2^32) where they start
+    uint32_t* filled = lds_u32 + nrb;    // entries of the block written so far
     const int64_t nf = (int64_t)*nf_ptr;
     // small frontiers are cut into small portions so that they still spread over the chip
     int64_t per = (nf + gridDim.x - 1) / gridDim.x;
@@ -475,12 +480,13 @@ __global__ void __launch_bounds__(kBinBlock) vipg_bin_fill_kernel(const int32_t*
         for (int r = threadIdx.x; r < nrb; r += kBinBlock) base[r] = 0u;
         __syncthreads();                                   // publishes prefix[], row[], p[]
         // first walk: the portion's entries per bin
-        for (uint32_t x0 = threadIdx.x * kBinPer; x0 < total; x0 += kBinChunk) {
+        for (uint32_t c0 = 0; c0 < total; c0 += kBinChunk) {
+            if (bin_edge(c0, 0) >= total) continue;
             BinCursor cu;
-            cu.start(po, nv, x0);
+            cu.start(po, nv, bin_edge(c0, 0));
             uint32_t u[kBinPer];
 #pragma unroll
-            for (int q = 0; q < kBinPer; ++q) u[q] = x0 + (uint32_t)q < total ? (uint32_t)col[cu.next(po, x0 + (uint32_t)q)] : ~0u;
+            for (int q = 0; q < kBinPer; ++q) u[q] = bin_edge(c0, q) < total ? (uint32_t)col[cu.at(po, bin_edge(c0, q))] : ~0u;
 #pragma unroll
             for (int q = 0; q < kBinPer; ++q)
                 if (u[q] != ~0u) atomicAdd(&base[u[q] >> rbits], 1u);
@@ -489,32 +495,25 @@ __global__ void __launch_bounds__(kBinBlock) vipg_bin_fill_kernel(const int32_t*
         for (int r = r0; r < r1; ++r) {
             const uint32_t c = base[r];
             base[r] = (uint32_t)first[(int64_t)r * nch] + (c ? atomicAdd(&cursor[r], c) : 0u);
-            prev[r] = 0u;
+            filled[r] = 0u;
         }
-        // second walk, in chunks
+        __syncthreads();
+        // second walk: the entries
         for (uint32_t c0 = 0; c0 < total; c0 += kBinChunk) {
-            for (int r = threadIdx.x; r < nrb; r += kBinBlock) off[r] = 0u;
-            __syncthreads();
-            // the thread's entries of the chunk, kept in registers with their rank inside their bin
-            uint32_t key[kBinPer], wbits[kBinPer], rank[kBinPer];
-            const uint32_t x0 = c0 + threadIdx.x * kBinPer;
+            if (bin_edge(c0, 0) >= total) continue;
+            BinCursor cu;
+            cu.start(po, nv, bin_edge(c0, 0));
+            uint32_t key[kBinPer];
             float pv[kBinPer], tv[kBinPer];
-            if (x0 < total) {
-                BinCursor cu;
-                cu.start(po, nv, x0);
 #pragma unroll
-                for (int q = 0; q < kBinPer; ++q) {
-                    key[q] = ~0u;
-                    if (x0 + (uint32_t)q < total) {
-                        const int64_t k = cu.next(po, x0 + (uint32_t)q);
-                        key[q] = (uint32_t)col[k];
-                        tv[q] = t[k];
-                        pv[q] = cu.p;
-                    }
+            for (int q = 0; q < kBinPer; ++q) {
+                key[q] = ~0u;
+                if (bin_edge(c0, q) < total) {
+                    const int64_t k = cu.at(po, bin_edge(c0, q));
+                    key[q] = (uint32_t)col[k];
+                    tv[q] = t[k];
+                    pv[q] = cu.p;
                 }
-            } else {
-#pragma unroll
-                for (int q = 0; q < kBinPer; ++q) key[q] = ~0u;
             }
 #pragma unroll
             for (int q = 0; q < kBinPer; ++q) {
@@ -522,36 +521,10 @@ __global__ void __launch_bounds__(kBinBlock) vipg_bin_fill_kernel(const int32_t*
                     const uint32_t u = key[q];
                     const float xw = unit_or_flag(tv[q], bad) * pv[q];
                     const uint32_t rb = u >> rbits;
-                    key[q] = (rb << kTileRowBits) | (u & rmask);
-                    wbits[q] = __float_as_uint(xw > 0.0f ? bin_log1p_neg(xw) : 0.0f);
-                    rank[q] = atomicAdd(&off[rb], 1u);
+                    const uint32_t slot = atomicAdd(&filled[rb], 1u);
+                    bins[base[rb] + slot] = make_uint2(__float_as_uint(xw > 0.0f ? bin_log1p_neg(xw) : 0.0f), u & rmask);
                 }
             }
-            __syncthreads();
-            // off[] becomes the exclusive prefix of the chunk's counts; base[] moves past the chunk before
-            uint32_t mine = 0;
-            for (int r = r0; r < r1; ++r) mine += off[r];
-            uint32_t n_chunk;
-            uint32_t run = bin_block_scan(mine, po.wave_sum, n_chunk);
-            for (int r = r0; r < r1; ++r) {
-                const uint32_t c = off[r];
-                const uint32_t b = base[r] + prev[r];
-                off[r] = run;
-                base[r] = b;
-                dest[r] = b - run;
-                prev[r] = c;
-                run += c;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int q = 0; q < kBinPer; ++q)
-                if (key[q] != ~0u) po.stage[off[key[q] >> kTileRowBits] + rank[q]] = make_uint2(wbits[q], key[q]);
-            __syncthreads();
-            for (uint32_t j = threadIdx.x; j < n_chunk; j += kBinBlock) {
-                const uint2 e = po.stage[j];
-                bins[dest[e.y >> kTileRowBits] + j] = make_uint2(e.x, e.y & kTileRowMask);
-            }
-            __syncthreads();
         }
         __syncthreads();
     }
@@ -630,7 +603,7 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
     const int64_t part_stride = binned ? g->nrb << g->tile_rbits : N;
     uint2* bins = nullptr;
     uint32_t* cursor = nullptr;
-    const size_t fill_lds = binned ? 4 * (size_t)g->nrb * sizeof(uint32_t) : 0;
+    const size_t fill_lds = binned ? 2 * (size_t)g->nrb * sizeof(uint32_t) : 0;
     const size_t sum_lds = binned ? sizeof(double) << g->tile_rbits : 0;
     if (binned) {
         const int64_t want = ((int64_t)ctx->num_cu * 4 + g->nrb - 1) / g->nrb;
@@ -662,7 +635,7 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
             if (binned) {
                 fill_f32_kernel<<<(unsigned)((g->nrb + kBlock) / kBlock), kBlock, 0, st>>>(
                     reinterpret_cast<float*>(cursor), g->nrb + 1, 0.f);         // all-zero bits either way
-                vipg_bin_fill_kernel<<<ctx->num_cu * 6, kBinBlock, fill_lds, st>>>(
+                vipg_bin_fill_kernel<<<ctx->num_cu * 8, kBinBlock, fill_lds, st>>>(
                     flist, fcount + 2, pcur, g->rowptr, g->col, d_t[h - 1], g->tile_rbits, (int)g->nrb,
                     g->tile_first, g->nch, cursor, bins, d_bad);
                 vip_bin_sum_kernel<<<(unsigned)(g->nrb * parts), kTileBlock, sum_lds, st>>>(
