@@ -671,6 +671,15 @@ def test_general_probabilities_tiny(spp, ctx, tiny_case):
             _check_vip(p, rt)
             for h in range(L):
                 _check_vip(ph[h], rh[h])
+    # degenerate inputs: nobody in the minibatch (empty frontier at every hop); nothing ever sampled
+    for G in (c.G, G_plain):
+        _say("general vip, empty frontier / zero transitions, row blocks", G is c.G)
+        z, zh = spp.vip_propagate_general(ctx, G, torch.zeros(cfg.N, device="cuda"), t_d[:2], 2, per_hop=True)
+        assert not bool(z.any()) and not bool(zh.any())
+        zt = torch.zeros(M, device="cuda")
+        p, ph = spp.vip_propagate_general(ctx, G, torch.from_numpy(p0).cuda(), zt, 2, per_hop=True, include_hop0=True)
+        assert not bool(ph.any())
+        _check_vip(p, oracle.vip_general(c.rp, c.col, p0, np.zeros(M, np.float32), 2, include_hop0=True)[0])
     # one tensor for every hop; the uniform instantiation agrees with the uniform entry point
     _say("general vip, uniform instantiation")
     p0u = np.zeros(cfg.N, np.float32)
