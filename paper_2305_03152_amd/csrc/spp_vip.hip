@@ -146,8 +146,11 @@ __global__ void __launch_bounds__(kTileBlock) vip_tile_kernel(const uint32_t* __
     extern __shared__ double acc[];
     const int R = 1 << rbits;
     uint32_t* bound = reinterpret_cast<uint32_t*>(acc + R);
-    const int64_t rb = blockIdx.x / parts;
-    const int j = blockIdx.x % parts;
+    // share-major order: the workgroups that run at the same time take the same share of different
+    // blocks, i.e. the same part of y (block-major order: 228 us instead of 214)
+    const int64_t nrb = gridDim.x / parts;
+    const int64_t rb = blockIdx.x % nrb;
+    const int j = (int)(blockIdx.x / nrb);
     const int64_t b0 = first[rb * nch], len = first[(rb + 1) * nch] - b0;
     for (int i = threadIdx.x; i < R; i += kTileBlock) acc[i] = 0.0;
     for (int c = threadIdx.x; c <= nch; c += kTileBlock) bound[c] = (uint32_t)(first[rb * nch + c] - b0);
@@ -709,7 +712,8 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
     SPP_TRY(ctx->y1.reserve((size_t)N * sizeof(float)));
     SPP_TRY(ctx->tot.reserve((size_t)N * sizeof(double) + sizeof(int)));
     // dense hops over row blocks: shares per block for at most four workgroups per CU (on 147 blocks
-    // and 256 CUs: 6 shares 224 + 31 us for the kernel and the finish, 7 shares 234 + 34, 8 shares 279 + 38)
+    // and 256 CUs, in block-major order: 6 shares 224 + 31 us for the kernel and the finish, 7 shares 234 + 34,
+    // 8 shares 279 + 38; in share-major order 6 shares 214 + 31, 8 shares 209 + 37)
     int parts = 1;
     if (g->nrb > 0) {
         const int64_t want = (int64_t)ctx->num_cu * 4 / g->nrb;
