@@ -27,9 +27,9 @@ PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 # and profiles/vip_tile_mid_counters.txt.  Keyed by (workload, minibatches per gather launch); other
 # shapes report null.
 MEASURED_TRAFFIC = {
-    ("mid", 16): {"gather_hit": 346.3e6 + 269.9e6, "vip_tile": 0.747e9 + 115.6e6},
-    ("mid", 32): {"gather_hit": 692.0e6 + 536.5e6, "vip_tile": 0.747e9 + 115.6e6},
-    ("mid", 64): {"gather_hit": 2266.4e6, "vip_tile": 0.747e9 + 115.6e6},
+    ("mid", 16): {"gather_hit": 346.3e6 + 269.9e6, "vip_tile": 0.730e9 + 115.6e6},
+    ("mid", 32): {"gather_hit": 692.0e6 + 536.5e6, "vip_tile": 0.730e9 + 115.6e6},
+    ("mid", 64): {"gather_hit": 2266.4e6, "vip_tile": 0.730e9 + 115.6e6},
 }
 
 
