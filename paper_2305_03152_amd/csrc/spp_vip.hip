@@ -91,12 +91,18 @@ __global__ void fill_f64_kernel(double* p, int64_t n, double v) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
 }
 
-// The frontier itself (any order): list[0 .. *cursor) = vertices whose y is not zero.  A thread
-// looks at kListPer consecutive vertices and a workgroup reserves its part of the list with one
-// atomic per round (same-address atomics cost about 15 ns each: one per wavefront of 64 vertices
-// took 0.45 ms on a frontier of 2.4M vertices).
+// The frontier itself (any order): list[0 .. *cursor) = vertices whose y is not zero and whose row
+// is not empty; a row of more than kPieceEdges entries is listed once per piece of that many
+// entries (adjacent in the list), so that the kernels that walk the frontier's rows can hand the
+// pieces of a long row to different workgroups.  A thread looks at kListPer consecutive vertices
+// and a workgroup reserves its part of the list with one atomic per round (same-address atomics
+// cost about 15 ns each: one per wavefront of 64 vertices took 0.45 ms on a frontier of 2.4M).
 constexpr int kListPer = 8;
-__global__ void __launch_bounds__(kBlock) vip_frontier_list_kernel(const float* __restrict__ y, int64_t N,
+constexpr int64_t kPieceEdges = 4096;
+__host__ __device__ inline int64_t frontier_list_capacity(int64_t N, int64_t M) { return N + M / kPieceEdges; }
+
+__global__ void __launch_bounds__(kBlock) vip_frontier_list_kernel(const float* __restrict__ y,
+                                                                   const int64_t* __restrict__ rowptr, int64_t N,
                                                                    int32_t* __restrict__ list,
                                                                    unsigned long long* __restrict__ cursor) {
     __shared__ int scan_lds[4];
@@ -104,20 +110,43 @@ __global__ void __launch_bounds__(kBlock) vip_frontier_list_kernel(const float* 
     const int64_t round = (int64_t)kBlock * kListPer;
     for (int64_t r0 = (int64_t)blockIdx.x * round; r0 < N; r0 += (int64_t)gridDim.x * round) {
         const int64_t v0 = r0 + (int64_t)threadIdx.x * kListPer;
-        unsigned in = 0;
+        int cnt[kListPer], mine = 0;
 #pragma unroll
-        for (int k = 0; k < kListPer; ++k)
-            if (v0 + k < N && y[v0 + k] != 0.0f) in |= 1u << k;
+        for (int k = 0; k < kListPer; ++k) {
+            cnt[k] = 0;
+            if (v0 + k < N && y[v0 + k] != 0.0f)
+                cnt[k] = (int)((rowptr[v0 + k + 1] - rowptr[v0 + k] + kPieceEdges - 1) / kPieceEdges);
+            mine += cnt[k];
+        }
         int total;
-        int at = block_exclusive_scan(__popc(in), scan_lds, total);
+        int at = block_exclusive_scan(mine, scan_lds, total);
         if (threadIdx.x == 0 && total) start = atomicAdd(cursor, (unsigned long long)total);
         __syncthreads();
         const unsigned long long base = start;
 #pragma unroll
         for (int k = 0; k < kListPer; ++k)
-            if (in >> k & 1u) list[base + at++] = (int32_t)(v0 + k);
+            for (int c = 0; c < cnt[k]; ++c) list[base + at++] = (int32_t)(v0 + k);
         __syncthreads();
     }
+}
+
+// Entry i of that list: where its piece of the row starts in col[] and how many entries it has.
+// The pieces of a row are adjacent and in order, so the number of the piece is the distance to
+// the first entry with the same vertex (found by galloping, then bisection).
+__device__ __forceinline__ int32_t frontier_entry(const int32_t* __restrict__ list, int64_t i,
+                                                  const int64_t* __restrict__ rowptr, int64_t& row, uint32_t& deg) {
+    const int32_t v = list[i];
+    int64_t lo = i, step = 1;                               // list[lo] == v
+    while (lo - step >= 0 && list[lo - step] == v) { lo -= step; step <<= 1; }
+    int64_t a = lo - step < 0 ? -1 : lo - step;             // a == -1 or list[a] != v
+    while (lo - a > 1) {
+        const int64_t mid = (a + lo) >> 1;
+        if (list[mid] == v) lo = mid; else a = mid;
+    }
+    const int64_t b = rowptr[v] + (i - lo) * kPieceEdges, e = rowptr[v + 1];
+    row = b;
+    deg = (uint32_t)(e - b < kPieceEdges ? e - b : kPieceEdges);
+    return v;
 }
 
 __global__ void __launch_bounds__(kBlock) vip_push_finish_kernel(VipHop a, const double* __restrict__ acc, int64_t N) {
@@ -301,9 +330,11 @@ __global__ void __launch_bounds__(kBlock) vipg_push_kernel(const int32_t* __rest
     const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
     for (int64_t i = wave; i < nf; i += nwaves) {
-        const int64_t v = list[i];
+        int64_t b;
+        uint32_t deg;
+        const int64_t v = frontier_entry(list, i, rowptr, b, deg);
         const double pv = (double)pcur[v];
-        const int64_t b = rowptr[v], e = rowptr[v + 1];
+        const int64_t e = b + deg;
         for (int64_t k = b + lane; k < e; k += kWave) {
             const double x = (double)unit_or_flag(t[k], bad) * pv;
             if (x > 0.0) unsafeAtomicAdd(&acc[col[k]], log1p(-x));
@@ -330,6 +361,36 @@ constexpr int kBinBlock = 256;           // threads per workgroup, and most fron
 constexpr int kBinPer = 8;               // edges per thread and round
 constexpr int kBinChunk = kBinBlock * kBinPer;
 constexpr int64_t kBinMaxBlocks = 16384; // row blocks whose two counters each fit the LDS of a workgroup
+
+// Frontier entries per portion: small frontiers are cut into small portions so that they still
+// spread over the chip.
+__device__ __forceinline__ int64_t bin_portion_size(int64_t nf) {
+    const int64_t per = (nf + gridDim.x - 1) / gridDim.x;
+    return per < kWave ? kWave : (per > kBinBlock ? kBinBlock : per);
+}
+
+// Which list entries make up a portion.  A small frontier (at most two portions per workgroup) is
+// dealt out entry by entry, so that the pieces of a long row, adjacent in the list, land in
+// different portions; a large one is cut into runs of consecutive entries, whose rows lie
+// side by side in col[] (dealt out entry by entry, the dense hop of the general propagation took
+// 1.00 ms instead of 0.88).
+struct PortionMap {
+    int64_t nf, per, nportions;
+    bool dealt;
+    __device__ __forceinline__ explicit PortionMap(int64_t nf_) : nf(nf_) {
+        per = bin_portion_size(nf);
+        nportions = (nf + per - 1) / per;
+        dealt = nportions <= 2 * (int64_t)gridDim.x;
+    }
+    __device__ __forceinline__ int count(int64_t portion) const {
+        if (dealt) return (int)((nf - portion + nportions - 1) / nportions);
+        const int64_t rest = nf - portion * per;
+        return (int)(rest < per ? rest : per);
+    }
+    __device__ __forceinline__ int64_t entry(int64_t portion, int t) const {
+        return dealt ? portion + (int64_t)t * nportions : portion * per + t;
+    }
+};
 
 struct BinPortion {
     uint32_t prefix[kBinBlock + 1];      // edges of the portion before vertex i
@@ -403,19 +464,22 @@ __device__ __forceinline__ uint32_t bin_edge(uint32_t c0, int q) {
 // accumulator of every member of adj(v) (fp64 global atomics).  Portions of `per` frontier vertices
 // walked as one edge sequence, as above: with one wavefront per vertex the longest row set the
 // kernel's duration (138 us for the 1.2M out-edges of 24k training vertices, degrees up to 20k).
-__global__ void __launch_bounds__(kBinBlock) vip_push_flat_kernel(const int32_t* __restrict__ list, int64_t nf, int per,
+__global__ void __launch_bounds__(kBinBlock) vip_push_flat_kernel(const int32_t* __restrict__ list,
+                                                                  const unsigned long long* __restrict__ nf_ptr,
                                                                   const float* __restrict__ y,
                                                                   const int64_t* __restrict__ rowptr,
                                                                   const int32_t* __restrict__ col,
                                                                   double* __restrict__ acc) {
     __shared__ BinPortion po;
-    for (int64_t beg = (int64_t)blockIdx.x * per; beg < nf; beg += (int64_t)gridDim.x * per) {
-        const int nv = (int)(beg + per < nf ? per : nf - beg);
+    const int64_t nf = (int64_t)*nf_ptr;
+    const PortionMap pm(nf);
+    for (int64_t portion = blockIdx.x; portion < pm.nportions; portion += gridDim.x) {
+        const int nv = pm.count(portion);
+        const int64_t mine = pm.entry(portion, threadIdx.x);
         uint32_t deg = 0;
         if ((int)threadIdx.x < nv) {
-            const int64_t v = list[beg + threadIdx.x];
-            const int64_t b = rowptr[v];
-            deg = (uint32_t)(rowptr[v + 1] - b);
+            int64_t b;
+            const int32_t v = frontier_entry(list, mine, rowptr, b, deg);
             po.row[threadIdx.x] = b;
             po.p[threadIdx.x] = y[v];
         }
@@ -480,9 +544,7 @@ __global__ void __launch_bounds__(kBinBlock) vipg_bin_fill_kernel(const int32_t*
     uint32_t* base = lds_u32;            // the portion's entries per row block, then the entry (index into bins[], below 2^32) where they start
     uint32_t* filled = lds_u32 + nrb;    // entries of the block written so far
     const int64_t nf = (int64_t)*nf_ptr;
-    // small frontiers are cut into small portions so that they still spread over the chip
-    int64_t per = (nf + gridDim.x - 1) / gridDim.x;
-    per = per < kWave ? kWave : (per > kBinBlock ? kBinBlock : per);
+    const PortionMap pm(nf);
     const uint32_t rmask = (1u << rbits) - 1u;
     const int bins_per_thread = (nrb + kBinBlock - 1) / kBinBlock;
     const int r0 = threadIdx.x * bins_per_thread;
@@ -494,14 +556,13 @@ __global__ void __launch_bounds__(kBinBlock) vipg_bin_fill_kernel(const int32_t*
     for (;;) {
         if (threadIdx.x == 0) portion = atomicAdd(&cursor[nrb], 1u);
         __syncthreads();
-        const int64_t beg = (int64_t)portion * per;
-        if (beg >= nf) break;
-        const int nv = (int)(beg + per < nf ? per : nf - beg);
+        if ((int64_t)portion >= pm.nportions) break;
+        const int nv = pm.count(portion);
+        const int64_t mine = pm.entry(portion, threadIdx.x);
         uint32_t deg = 0;
         if ((int)threadIdx.x < nv) {
-            const int64_t v = list[beg + threadIdx.x];
-            const int64_t b = rowptr[v];
-            deg = (uint32_t)(rowptr[v + 1] - b);
+            int64_t b;
+            const int32_t v = frontier_entry(list, mine, rowptr, b, deg);
             po.row[threadIdx.x] = b;
             po.p[threadIdx.x] = pcur[v];
         }
@@ -619,9 +680,10 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
     SPP_TRY(ctx->y1.reserve((size_t)N * sizeof(float)));
     SPP_TRY(ctx->tot.reserve((size_t)N * sizeof(double) + sizeof(int)));
     SPP_TRY(ctx->acc.reserve((size_t)N * sizeof(double)));
-    SPP_TRY(ctx->frontier.reserve((size_t)(N + 2) * sizeof(int32_t) + 4 * sizeof(unsigned long long)));
+    const int64_t lcap = frontier_list_capacity(N, g->M);
+    SPP_TRY(ctx->frontier.reserve((size_t)(lcap + 2) * sizeof(int32_t) + 4 * sizeof(unsigned long long)));
     int32_t* flist = ctx->frontier.as<int32_t>();
-    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (N + (N & 1)));
+    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (lcap + (lcap & 1)));
     float* pcur = ctx->y0.as<float>();
     float* pnext = ctx->y1.as<float>();
     double* tot = ctx->tot.as<double>();
@@ -663,7 +725,7 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
         for (int h = 1; h <= L; ++h) {
             ScopedTimer th(ctx, SPP_T_VIP_HOP_FIRST + h - 1, st);
             fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount), 3, 0.0);
-            vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(pcur, N, flist, fcount + 2);
+            vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(pcur, g->rowptr, N, flist, fcount + 2);
             if (binned) {
                 fill_f32_kernel<<<(unsigned)((g->nrb + kBlock) / kBlock), kBlock, 0, st>>>(
                     reinterpret_cast<float*>(cursor), g->nrb + 1, 0.f);         // all-zero bits either way
@@ -734,9 +796,10 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
     // the kernels that write a hop's y run this many workgroups; each leaves the size of the part of
     // the next frontier it saw (at most kStatBlocks pairs fit the pinned mirror)
     const int fill_grid = ctx->num_cu * 8 < kStatBlocks ? ctx->num_cu * 8 : kStatBlocks;
-    SPP_TRY(ctx->frontier.reserve((size_t)(N + 2) * sizeof(int32_t) + (4 + 2 * (size_t)kStatBlocks) * sizeof(unsigned long long)));
+    const int64_t lcap = frontier_list_capacity(N, g->M);
+    SPP_TRY(ctx->frontier.reserve((size_t)(lcap + 2) * sizeof(int32_t) + (4 + 2 * (size_t)kStatBlocks) * sizeof(unsigned long long)));
     int32_t* flist = ctx->frontier.as<int32_t>();
-    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (N + (N & 1)));    // [2]: cursor of the list
+    unsigned long long* fcount = reinterpret_cast<unsigned long long*>(flist + (lcap + (lcap & 1)));    // [2]: cursor of the list
     unsigned long long* fstat = fcount + 4;
     float* ycur = ctx->y0.as<float>();
     float* ynext = ctx->y1.as<float>();
@@ -780,14 +843,12 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
                 fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
                 if (fc[0] > 0) {
                     fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount + 2), 1, 0.0);
-                    vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(ycur, N, flist, fcount + 2);
-                    // small frontiers in small portions, so that they still spread over the chip
-                    const int64_t pgrid = (int64_t)ctx->num_cu * 8;
-                    int64_t per = ((int64_t)fc[0] + pgrid - 1) / pgrid;
-                    per = per < kWave ? kWave : (per > kBinBlock ? kBinBlock : per);
-                    const int64_t need = ((int64_t)fc[0] + per - 1) / per;
+                    vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(ycur, g->rowptr, N, flist, fcount + 2);
+                    // at most this many list entries (vertices and pieces of long rows); the kernel reads the count itself
+                    const int64_t entries = (int64_t)fc[0] + (int64_t)fc[1] / kPieceEdges;
+                    const int64_t pgrid = (int64_t)ctx->num_cu * 8, need = (entries + kWave - 1) / kWave;
                     vip_push_flat_kernel<<<(unsigned)(need < pgrid ? need : pgrid), kBinBlock, 0, st>>>(
-                        flist, (int64_t)fc[0], (int)per, ycur, g->rowptr, g->col, acc);
+                        flist, fcount + 2, ycur, g->rowptr, g->col, acc);
                 }
                 vip_push_finish_kernel<<<fill_grid, kBlock, 0, st>>>(a, acc, N);
             } else {

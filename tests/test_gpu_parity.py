@@ -182,6 +182,47 @@ def test_sampler_and_vip_shape_sweep(spp, ctx, fanouts):
     G.close()
 
 
+def test_vip_long_rows_in_the_frontier(spp, ctx):
+    """Frontier rows of 4095 to 12000 entries: the push hops list such a row in pieces of 4096 entries
+    that different workgroups walk (both entry points, with and without the row-block structure)."""
+    rng = np.random.default_rng(77)
+    N = 20000
+    degrees = np.full(N, 28)         # M large enough for a hop-1 frontier of 34k out-edges to count as sparse
+    hubs = {5: 12000, 300: 4096, 301: 4097, 7000: 4095, 19999: 9000}
+    for v, d in hubs.items():
+        degrees[v] = d
+    rp = np.zeros(N + 1, dtype=np.int64)
+    rp[1:] = np.cumsum(degrees)
+    col = np.empty(rp[-1], dtype=np.int32)
+    for v in range(N):
+        d = int(degrees[v])
+        col[rp[v]:rp[v + 1]] = np.sort(rng.choice(N, size=d, replace=False)) if d > 100 else np.unique(rng.integers(0, N, 4 * d))[:d]
+    assert all(np.all(np.diff(col[rp[v]:rp[v + 1]]) > 0) for v in (0, 5, 300, 19999))
+    dev = torch.device("cuda:0")
+    rp_d, col_d = torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev)
+    T = np.sort(np.concatenate([np.fromiter(hubs, dtype=np.int64), 40 + 97 * np.arange(20)])).astype(np.int32)
+    fanouts = (4000, 3)        # hop 1 takes most of the long rows
+    ref_t, ref_h = oracle.vip(rp, col, T, 8, fanouts)
+    t_np = [np.repeat(np.minimum(1.0, f / np.maximum(degrees, 1)).astype(np.float32), degrees) for f in fanouts]
+    t_np[1] = (t_np[1] * rng.random(col.size)).astype(np.float32)
+    p0 = np.zeros(N, np.float32)
+    p0[T] = 8 / T.size
+    gen_t, gen_h = oracle.vip_general(rp, col, p0, t_np, 2)
+    for in_lists in (True, False):
+        _say("long rows in the frontier, row blocks", in_lists)
+        G = spp.Graph(ctx, rp_d, col_d, in_lists=in_lists)
+        if in_lists:
+            p, ph = spp.vip_propagate(ctx, G, torch.from_numpy(T).to(dev), 8, fanouts, per_hop=True)
+            assert spp.vip_last_hops(ctx, 2)[0][0], "hop 1 was meant to be pushed"
+            _check_vip(p, ref_t)
+            _check_vip(ph[0], ref_h[0])
+        pg, pgh = spp.vip_propagate_general(ctx, G, torch.from_numpy(p0).to(dev), [torch.from_numpy(a).to(dev) for a in t_np], 2,
+                                            per_hop=True)
+        _check_vip(pg, gen_t)
+        _check_vip(pgh[0], gen_h[0])
+        G.close()
+
+
 # ----------------------------------------------------------------------------------------------
 # Tiny config, all four calls
 # ----------------------------------------------------------------------------------------------
