@@ -410,13 +410,18 @@ struct NewIn {
 struct NewOut {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int64_t e, int ex, int v, int total) const {
-        if (!v || t->b[j].tinfo[2]) return;
+        if (t->b[j].tinfo[2]) return;
+        // A first appearance knows its local id here; the relabel pass looks up only the entries
+        // marked -1 (every look-up is a random 8-byte read that moves a whole line).
+        int32_t* __restrict__ src = t->b[j].src[a.h - 1];
+        if (!v) { src[e] = -1; return; }
         const int64_t n_prev = t->b[j].counts[a.h - 1];
         if (a.t && n_prev + (int64_t)(uint32_t)total > t->b[j].ncap) return;      // NewFin abandons the minibatch
         unsigned long long* tab = tab_of(a, j);
         const uint32_t slot = (uint32_t)flat_of(a, j)[e];
         const uint32_t gid = (uint32_t)(tab[slot] >> 32);            // a slot's key never changes
         const int64_t id = n_prev + ex;
+        src[e] = (int32_t)id;
         t->b[j].S[id] = (int32_t)gid;
         // the new value is <= the old one and is never equal to another entry's own position, so
         // threads still testing "first appearance" read either value with the same outcome
@@ -451,7 +456,8 @@ __device__ __forceinline__ void relabel_rows(const SampleArgs& a, const BatchTab
     const int32_t* __restrict__ flat = flat_of(a, j);
     int32_t* __restrict__ src = t->b[j].src[a.h - 1];
     const int64_t stride = (int64_t)gx * kBlock;
-    for (int64_t e = (int64_t)x * kBlock + threadIdx.x; e < e_h; e += stride) src[e] = (int32_t)(uint32_t)tab[(uint32_t)flat[e]];
+    for (int64_t e = (int64_t)x * kBlock + threadIdx.x; e < e_h; e += stride)
+        if (src[e] < 0) src[e] = (int32_t)(uint32_t)tab[(uint32_t)flat[e]];      // first appearances were numbered by the scan
 }
 __global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
     const BatchBlock bb = batch_block();
