@@ -213,6 +213,15 @@ inline void grid_scan_batched(hipStream_t st, int grid, int nbatch, In in, Out o
     bscan_write_kernel<In, Out, Fin, Tail><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, out, fin, partial, tail);
 }
 
+// The same with a value function of its own for the second launch (one that reads what the first
+// launch's function left behind instead of computing the value again).
+template <class In, class In2, class Out, class Fin, class Head = NoHook, class Tail = NoHook>
+inline void grid_scan_batched_two(hipStream_t st, int grid, int nbatch, In in, In2 in2, Out out, Fin fin, int* partial,
+                                  Head head = Head(), Tail tail = Tail()) {
+    bscan_reduce_kernel<In, Head><<<dim3(grid, nbatch), kBlock, 0, st>>>(in, partial, head);
+    bscan_write_kernel<In2, Out, Fin, Tail><<<dim3(grid, nbatch), kBlock, 0, st>>>(in2, out, fin, partial, tail);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Open-addressing table of 64-bit entries (key << 32 | value), empty = all ones.  Keys are vertex
 // ids (below 2^31).  The capacity is a power of two >= 1024 and at least twice the number of keys.

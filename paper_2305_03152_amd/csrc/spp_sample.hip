@@ -402,19 +402,27 @@ __global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, co
 struct NewIn {
     SampleArgs a; const BatchTable* t;
     __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[kE + a.h]; }
+    // The look-up is a random 8-byte read that moves a whole line, so the outcome is left in the
+    // entry's place in the hop's src array (-2 first appearance, -1 repeat) for the second pass.
     __device__ int operator()(int j, int64_t e) const {
         const uint32_t val = (uint32_t)tab_of(a, j)[(uint32_t)flat_of(a, j)[e]];
-        return (int64_t)val == t->b[j].counts[a.h - 1] + e ? 1 : 0;
+        const int first = (int64_t)val == t->b[j].counts[a.h - 1] + e ? 1 : 0;
+        t->b[j].src[a.h - 1][e] = first ? -2 : -1;
+        return first;
     }
+};
+struct NewInKept {
+    SampleArgs a; const BatchTable* t;
+    __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[kE + a.h]; }
+    __device__ int operator()(int j, int64_t e) const { return t->b[j].src[a.h - 1][e] == -2 ? 1 : 0; }
 };
 struct NewOut {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int64_t e, int ex, int v, int total) const {
-        if (t->b[j].tinfo[2]) return;
+        if (!v || t->b[j].tinfo[2]) return;
         // A first appearance knows its local id here; the relabel pass looks up only the entries
-        // marked -1 (every look-up is a random 8-byte read that moves a whole line).
+        // still marked -1.
         int32_t* __restrict__ src = t->b[j].src[a.h - 1];
-        if (!v) { src[e] = -1; return; }
         const int64_t n_prev = t->b[j].counts[a.h - 1];
         if (a.t && n_prev + (int64_t)(uint32_t)total > t->b[j].ncap) return;      // NewFin abandons the minibatch
         unsigned long long* tab = tab_of(a, j);
@@ -423,8 +431,7 @@ struct NewOut {
         const int64_t id = n_prev + ex;
         src[e] = (int32_t)id;
         t->b[j].S[id] = (int32_t)gid;
-        // the new value is <= the old one and is never equal to another entry's own position, so
-        // threads still testing "first appearance" read either value with the same outcome
+        // (no other thread reads the slot in this launch: "first appearance" was decided in the launch before)
         __hip_atomic_store(&tab[slot], ((unsigned long long)gid << 32) | (uint32_t)id, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -638,7 +645,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
                     default: sample_kernel<64><<<sgrid, kBlock, 0, st>>>(a, dt); break;
                 }
             }
-            grid_scan_batched(st, scan_grid, n_items, NewIn{a, dt}, NewOut{a, dt}, NewFin{a, dt}, partial);
+            grid_scan_batched_two(st, scan_grid, n_items, NewIn{a, dt}, NewInKept{a, dt}, NewOut{a, dt}, NewFin{a, dt}, partial);
             if (h == L || general)
                 relabel_kernel<<<dim3(capped((eb[h] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
         }
