@@ -274,8 +274,21 @@ def main():
         for _ in range(5):
             torch.add(x, 1.0, out=y)
         torch.cuda.synchronize()
+        # what plain library kernels reach on this machine, by direction (the published peak counts both)
+        rates = {}
+        for name, fn, nbytes in (("read_only_sum", lambda: x.sum(), 4 * x.numel()),
+                                 ("read_write_add", lambda: torch.add(x, 1.0, out=y), 8 * x.numel()),
+                                 ("write_only_fill", lambda: y.fill_(2.0), 4 * x.numel())):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            rates[name + "_GBps"] = round(nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         print(json.dumps({"phase": "calibrate", "kernel": "elementwise add", "bytes_read": x.numel() * 4,
-                          "bytes_written": y.numel() * 4, "launches": 5}), flush=True)
+                          "bytes_written": y.numel() * 4, "launches": 5, "library_kernels_over_1GiB": rates}), flush=True)
         return
     K, W = args.steps, args.warmup
     P = max(1, args.pipeline)
