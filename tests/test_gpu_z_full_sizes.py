@@ -91,7 +91,35 @@ def _full_size(name):
         assert np.all(a[b == 0] == 0)
         _say("vip", nm, "ok; nonzero", int((b > 0).sum()), "max rel err",
              float(np.max(np.abs(a - b)[b > 1e-30] / b[b > 1e-30])))
-    del ref_h, ph_gpu
+    del ph_gpu
+
+    # Proposition 1 with given probabilities, in its uniform instantiation t_h = min(1, f_h/d(v)): the same
+    # numbers by the other entry point (thousands of row blocks for the binned push, rows of 50k entries)
+    _say("general propagation, uniform instantiation")
+    deg = g.rowptr[1:] - g.rowptr[:-1]
+    t_list = []
+    for f in cfg.fanouts:
+        t_h = torch.empty(M, dtype=torch.float32, device=dev)
+        for a in range(0, N, 1 << 22):                       # in pieces: one repeat_interleave stays below 2^31 outputs
+            b = min(N, a + (1 << 22))
+            d = deg[a:b]
+            per_row = torch.clamp(float(f) / d.clamp(min=1).to(torch.float64), max=1.0).to(torch.float32)
+            t_h[int(g.rowptr[a]):int(g.rowptr[b])] = torch.repeat_interleave(per_row, d)
+        t_list.append(t_h)
+    del deg, d, per_row, t_h
+    p0 = torch.zeros(N, dtype=torch.float32, device=dev)
+    p0[Tk.long()] = min(1.0, cfg.B / Tk.numel())
+    pg, pgh = spp.vip_propagate_general(ctx, G, p0, t_list, cfg.L, per_hop=True)
+    pg_np, pgh_np = pg.cpu().numpy(), pgh.cpu().numpy()
+    del pg, pgh, t_list, p0
+    torch.cuda.empty_cache()
+    for nm, a, b in [("total", pg_np, ref_t)] + [(f"hop{h + 1}", pgh_np[h], ref_h[h]) for h in range(cfg.L)]:
+        a = a.astype(np.float64)
+        bad = np.flatnonzero(np.abs(a - b) > 1e-5 * b + 1e-37)
+        assert bad.size == 0, ("general", nm, bad[:5], a[bad[:5]], b[bad[:5]])
+        assert np.all(a[b == 0] == 0)
+        _say("general vip", nm, "ok; max rel err", float(np.max(np.abs(a - b)[b > 1e-30] / b[b > 1e-30])))
+    del ref_h, pg_np, pgh_np
 
     _say("cache ranking (membership only) vs oracle sort")
     cache0 = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, None, cfg.D, cfg.elem_bytes)
