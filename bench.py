@@ -446,11 +446,13 @@ def main():
         c.sync()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms, cnt = [0.0] * 16, [0] * 16
-    for c, _, _ in lanes:
-        m_, c_ = c.times()
+    ms, cnt, shortest, median = [0.0] * 16, [0] * 16, [0.0] * 16, [0.0] * 16
+    for li, (c, _, _) in enumerate(lanes):
+        m_, c_, mn_, med_ = c.time_stats()
         ms = [a + b for a, b in zip(ms, m_)]
         cnt = [a + b for a, b in zip(cnt, c_)]
+        if li == 0:
+            shortest, median = mn_, med_           # of the first lane's launches
         c.timing(False)
     elapsed = t1 - t0
     ms_per_step = elapsed / K * 1e3
@@ -492,6 +494,7 @@ def main():
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>",
             "traffic": measured.get("gather_hit") if P == 1 else None,
             "bytes_per_launch": hit_bytes, "avg_launch_ms": hit_ms,
+            "median_launch_ms": median[T_HIT], "min_launch_ms": shortest[T_HIT], "launches": cnt[T_HIT],
             "note": "runs between two PCIe miss copies, with the whole chip"}
     roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
     # bytes that cross PCIe: a vertex missed by several minibatches of a group is read once and copied on the device
@@ -559,7 +562,11 @@ def main():
         "cpu_baseline": cpu,
         "pcie": pcie,
         "kernels_ms": {"sample_mfg_per_launch": sample_ms, "gather_classify_per_launch": cls_ms,
-                       "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms},
+                       "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms,
+                       "median": {"sample_mfg": median[T_SAMPLE], "gather_classify": median[T_CLS],
+                                  "gather_hit": median[T_HIT], "gather_miss": median[T_MISS]},
+                       "min": {"sample_mfg": shortest[T_SAMPLE], "gather_classify": shortest[T_CLS],
+                               "gather_hit": shortest[T_HIT], "gather_miss": shortest[T_MISS]}},
         "vip": {"ms_total": vip_total_ms, "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
                 "hop_pushed_over_sparse_frontier": vip_pushed, "frontier_out_edges_per_hop": vip_frontier_edges,
                 "in_lists_build_s": t_inlists, "cache_build_s": cache_s, "n_cached": cache.n_cached},

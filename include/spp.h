@@ -315,6 +315,9 @@ enum { SPP_T_VIP_TOTAL = 0, SPP_T_VIP_HOP_FIRST = 1 /* .. +L-1 */, SPP_T_SAMPLE 
        SPP_T_GATHER_HIT = 10, SPP_T_GATHER_MISS = 11, SPP_T_GATHER_CLASSIFY = 12, SPP_T_COUNT = 16 };
 int  spp_ctx_timing(spp_ctx* ctx, int enable);
 int  spp_ctx_times(spp_ctx* ctx, float* sum_ms /* [SPP_T_COUNT] */, int64_t* count /* [SPP_T_COUNT] */);
+/*     The same with the shortest and the median piece per index (0 where there was none); any of the
+ *     four arrays may be null. */
+int  spp_ctx_time_stats(spp_ctx* ctx, float* sum_ms, int64_t* count, float* min_ms, float* median_ms);
 
 /* Running sums over the calls made on this context since the last reset, kept on the device so
  * that a loop of asynchronous calls can be accounted for without a host round trip per batch:

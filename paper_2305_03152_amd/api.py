@@ -29,7 +29,7 @@ EXPORTS = [
     "spp_last_error", "spp_ctx_create", "spp_ctx_destroy", "spp_ctx_sync", "spp_graph_create",
     "spp_graph_destroy", "spp_vip_propagate", "spp_vip_last_hops", "spp_build_vip_cache", "spp_cache_destroy",
     "spp_cache_set_limit", "spp_cache_lookup", "spp_mfg_bound", "spp_sample_mfg", "spp_sample_mfg_multi",
-    "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_totals",
+    "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_time_stats", "spp_ctx_totals",
     "spp_build_local_store", "spp_local_store_destroy", "spp_local_store_set_limit", "spp_local_store_rank",
     "spp_gather_features_split", "spp_access_count", "spp_vip_propagate_general", "spp_sample_mfg_general",
 ]
@@ -134,6 +134,8 @@ def load_library():
     lib.spp_gather_join.argtypes = [C.c_void_p]
     lib.spp_ctx_timing.argtypes = [C.c_void_p, C.c_int]
     lib.spp_ctx_times.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64)]
+    lib.spp_ctx_time_stats.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_float),
+                                       C.POINTER(C.c_float)]
     lib.spp_ctx_totals.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_int]
     _lib = lib
     return lib
@@ -184,6 +186,13 @@ class Context:
         cnt = (C.c_int64 * SPP_T_COUNT)()
         _check(load_library().spp_ctx_times(self._h, ms, cnt))
         return list(ms), list(cnt)
+
+    def time_stats(self):
+        """(sum_ms, count, min_ms, median_ms) per SPP_T_* index, like times()."""
+        ms, mn, med = (C.c_float * SPP_T_COUNT)(), (C.c_float * SPP_T_COUNT)(), (C.c_float * SPP_T_COUNT)()
+        cnt = (C.c_int64 * SPP_T_COUNT)()
+        _check(load_library().spp_ctx_time_stats(self._h, ms, cnt, mn, med))
+        return list(ms), list(cnt), list(mn), list(med)
 
     def totals(self, reset: bool = False):
         """Running sums since the last reset: batches, |S_L|, edges, gather calls, local / cache / missed rows,

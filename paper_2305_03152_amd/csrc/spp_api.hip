@@ -1,7 +1,9 @@
 // Context, error text and timing of the library; see include/spp.h for the contract.
 #include "spp_common.h"
 
+#include <algorithm>
 #include <new>
+#include <vector>
 
 namespace spp {
 
@@ -89,19 +91,32 @@ extern "C" int spp_ctx_timing(spp_ctx* c, int enable) {
     return SPP_OK;
 }
 
-extern "C" int spp_ctx_times(spp_ctx* c, float* sum_ms, int64_t* count) {
-    SPP_CHECK(c != nullptr && sum_ms != nullptr && count != nullptr, SPP_E_ARG, "spp_ctx_times: null argument");
+extern "C" int spp_ctx_time_stats(spp_ctx* c, float* sum_ms, int64_t* count, float* min_ms, float* median_ms) {
+    SPP_CHECK(c != nullptr, SPP_E_ARG, "spp_ctx_time_stats: ctx is null");
     SPP_TRY(spp_ctx_sync(c));
-    for (int i = 0; i < spp::kNumTimers; ++i) { sum_ms[i] = 0.f; count[i] = 0; }
+    std::vector<float> pieces[spp::kNumTimers];
     for (auto& sp : c->spans) {
         float ms = 0.f;
-        if (hipEventElapsedTime(&ms, sp.t0, sp.t1) == hipSuccess && sp.idx >= 0 && sp.idx < spp::kNumTimers) {
-            sum_ms[sp.idx] += ms;
-            count[sp.idx] += 1;
-        }
+        if (hipEventElapsedTime(&ms, sp.t0, sp.t1) == hipSuccess && sp.idx >= 0 && sp.idx < spp::kNumTimers)
+            pieces[sp.idx].push_back(ms);
+    }
+    for (int i = 0; i < spp::kNumTimers; ++i) {
+        std::vector<float>& v = pieces[i];
+        std::sort(v.begin(), v.end());
+        float sum = 0.f;
+        for (float x : v) sum += x;
+        if (sum_ms) sum_ms[i] = sum;
+        if (count) count[i] = (int64_t)v.size();
+        if (min_ms) min_ms[i] = v.empty() ? 0.f : v.front();
+        if (median_ms) median_ms[i] = v.empty() ? 0.f : 0.5f * (v[(v.size() - 1) / 2] + v[v.size() / 2]);
     }
     recycle_spans(c);
     return SPP_OK;
+}
+
+extern "C" int spp_ctx_times(spp_ctx* c, float* sum_ms, int64_t* count) {
+    SPP_CHECK(c != nullptr && sum_ms != nullptr && count != nullptr, SPP_E_ARG, "spp_ctx_times: null argument");
+    return spp_ctx_time_stats(c, sum_ms, count, nullptr, nullptr);
 }
 
 extern "C" int spp_ctx_totals(spp_ctx* c, int64_t* out, int reset) {
