@@ -313,6 +313,17 @@ def test_sample_and_gather_tiny(spp, ctx, tiny_case):
     assert torch.equal(out[:m.n[-1]].cpu(), S.feature_rows(cfg, ids))
     assert torch.all(out[m.n[-1]:] == 0)
     assert st["n_cache_hit"] == 0 and st["n_local"] + st["n_miss"] == m.n[-1]
+    # device-time accounting: one piece per call and kind, shortest <= median <= longest
+    ctx.timing(True)
+    for _ in range(3):
+        spp.gather_features(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, m.node_ids, n=m.n[-1])
+    ms, cnt, shortest, median = ctx.time_stats()
+    ctx.timing(False)
+    for idx in (10, 11, 12):                     # hit copy, miss copy, classification
+        longest = ms[idx] - shortest[idx] - median[idx]          # three pieces: the sum is shortest + median + longest
+        assert cnt[idx] == 3 and 0 < shortest[idx] <= median[idx] <= longest + 1e-6
+    assert cnt[9] == 0 and ms[9] == 0 and median[9] == 0
+    assert ctx.times() == ([0.0] * 16, [0] * 16)
     cache.close()
 
 
