@@ -223,6 +223,101 @@ def test_vip_long_rows_in_the_frontier(spp, ctx):
         G.close()
 
 
+def _zipf_graph(rng, N, mean, hubs):
+    """CSR with Zipf out-degrees scaled to `mean`, some empty rows and `hubs` rows of 4000+ entries; rows sorted, unique."""
+    deg = rng.zipf(1.8, N).astype(np.int64)
+    deg = np.minimum((deg * mean / deg.mean()).astype(np.int64), N // 3)
+    deg[rng.integers(0, N, N // 20)] = 0
+    for _ in range(hubs):
+        deg[rng.integers(0, N)] = int(rng.integers(4000, min(N // 3, 20000)))
+    rp = np.zeros(N + 1, np.int64)
+    rp[1:] = np.cumsum(deg)
+    col = np.empty(rp[-1], np.int32)
+    for v in np.flatnonzero(deg):
+        d = int(deg[v])
+        if d > N // 8:
+            row = rng.choice(N, d, replace=False)
+        else:
+            row = np.unique(rng.integers(0, N, 3 * d + 8))
+            while row.size < d:
+                row = np.unique(np.concatenate([row, rng.integers(0, N, 3 * d + 8)]))
+            row = rng.permutation(row)[:d]
+        col[rp[v]:rp[v + 1]] = np.sort(row)
+    return rp, col
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_random_shapes(spp, ctx, case):
+    """Graph size, degree mix, number of hops, fanouts, batch and training-set sizes, row width, element
+    type, cache size, number of id lists and fetch order drawn at random: all four calls (and the
+    general propagation) against the oracle."""
+    rng = np.random.default_rng(9000 + case)
+    N = int(rng.choice([700, 5000, 17000, 40000, 70000]))
+    rp, col = _zipf_graph(rng, N, float(rng.choice([3, 12, 40])), int(rng.integers(1, 4)) if N >= 40000 else 0)
+    L = int(rng.integers(1, 4))
+    fanouts = tuple(int(x) for x in rng.choice([1, 2, 5, 10, 15, 33, 64], L))
+    B = int(rng.choice([1, 17, 256, 1024]))
+    nT = int(min(N, rng.integers(B, 8 * B + 1)))
+    T = np.sort(rng.choice(N, nT, replace=False)).astype(np.int32)
+    K = int(rng.choice([2, 4, 8]))
+    part = int(rng.integers(0, K))
+    lo, hi = N * part // K, N * (part + 1) // K
+    alpha = float(rng.choice([0.0, 0.05, 0.3, 1.0]))
+    np_dt, D = [(np.float32, 100), (np.float32, 8), (np.float16, 128), (np.int16, 768)][int(rng.integers(0, 4))]   # int16: any 2-byte type
+    _say("random shapes", case, "N", N, "M", col.size, "fanouts", fanouts, "B", B, "|T|", nT, "K", K, "part", part,
+         "alpha", alpha, "D", D, np_dt.__name__)
+    dev = torch.device("cuda:0")
+    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), in_lists=True)
+    # (1) vertex-inclusion probabilities, both entry points
+    p, ph = spp.vip_propagate(ctx, G, torch.from_numpy(T).to(dev), B, fanouts, per_hop=True)
+    rt, rh = oracle.vip(rp, col, T, B, fanouts)
+    _check_vip(p, rt)
+    for h in range(L):
+        _check_vip(ph[h], rh[h])
+    deg = np.diff(rp)
+    t_np = [(rng.random(col.size) * np.repeat(np.minimum(1.0, f / np.maximum(deg, 1)), deg)).astype(np.float32) for f in fanouts]
+    p0 = np.zeros(N, np.float32)
+    p0[T] = rng.random(nT).astype(np.float32) * min(1.0, B / nT)
+    pg, pgh = spp.vip_propagate_general(ctx, G, torch.from_numpy(p0).to(dev), [torch.from_numpy(a).to(dev) for a in t_np], L,
+                                        per_hop=True)
+    gt, gh = oracle.vip_general(rp, col, p0, t_np, L)
+    _check_vip(pg, gt)
+    for h in range(L):
+        _check_vip(pgh[h], gh[h])
+    # (2) cache by the propagated probabilities
+    F = rng.integers(-30000, 30000, (N, D)).astype(np_dt)
+    local = torch.from_numpy(F[lo:hi].copy()).to(dev)
+    remote = torch.from_numpy(np.concatenate([F[:lo], F[hi:]])).pin_memory()
+    cache = spp.build_vip_cache(ctx, p, lo, hi, K, alpha, remote, D, F.itemsize) if alpha > 0 else None
+    ids_ref = oracle.cache_select(p.cpu().numpy(), lo, hi, K, alpha) if alpha > 0 else np.zeros(0, np.int32)
+    if cache is not None:
+        assert np.array_equal(cache.ids.cpu().numpy(), ids_ref)
+    # (3) several minibatches with one set of launches
+    nb = int(rng.integers(1, 6))
+    items, refs = [], []
+    for bi in range(nb):
+        seeds = rng.permutation(T)[:int(rng.integers(1, min(B, nT) + 1))].astype(np.int32)
+        items.append((torch.from_numpy(seeds).to(dev), 50 + bi, spp.MFGBuffers("cuda", B, fanouts, N)))
+        refs.append(oracle.sample_mfg(rp, col, seeds, fanouts, 4242 + case, 50 + bi))
+    spp.sample_mfg_multi(ctx, G, items, fanouts, 4242 + case)
+    for (_, _, m), ref in zip(items, refs):
+        _check_mfg(m, ref, L)
+    # (4) their feature rows with one set of launches
+    outs = [torch.full((max(ref.n[-1], 1) + 2, D), 7, dtype=local.dtype, device=dev) for ref in refs]
+    lists = [(m.node_ids, ref.n[-1], None, o) for (_, _, m), ref, o in zip(items, refs, outs)]
+    st = spp.gather_features_multi(ctx, cache, local, N, lo, hi, remote, lists, store_order=bool(rng.random() < 0.5))
+    tot = [0, 0, 0]
+    for ref, o in zip(refs, outs):
+        want, _, counts = oracle.gather(N, lo, hi, F[lo:hi], F[ids_ref], ids_ref, remote.numpy(), ref.node_ids)
+        assert np.array_equal(o[:ref.n[-1]].cpu().numpy(), want)
+        assert bool((o[ref.n[-1]:] == 7).all())
+        tot = [x + y for x, y in zip(tot, counts)]
+    assert (st["n_local"], st["n_cache_hit"], st["n_miss"]) == tuple(tot)
+    if cache is not None:
+        cache.close()
+    G.close()
+
+
 # ----------------------------------------------------------------------------------------------
 # Tiny config, all four calls
 # ----------------------------------------------------------------------------------------------
