@@ -101,7 +101,8 @@ int  spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t* d_T, int
 /* How the last spp_vip_propagate on this context walked each hop: pushed[h-1] = 1 if hop h was done
  * in push form over a sparse frontier (its out-edges were at most M/16), 0 if it was pulled over
  * the transposed structure; frontier_edges[h-1] = out-edges of the vertices with a non-zero weight at hop h
- * (the edges a hop has to touch at all).  Either array may be NULL. */
+ * (the edges a hop has to touch at all), or -1 where the library did not ask: the hop after a pulled
+ * hop is pulled too.  Either array may be NULL. */
 int  spp_vip_last_hops(spp_ctx* ctx, int32_t* pushed, int64_t* frontier_edges, int32_t L);
 
 /* (2) Replica cache (Sec. 3.2): among the vertices outside [lo,hi) with d_score > 0, the first

@@ -816,6 +816,7 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
         fill_f32_kernel<<<1, 64, 0, st>>>(reinterpret_cast<float*>(d_bad), 1, 0.f);
         vip_init_kernel<<<fill_grid, kBlock, 0, st>>>(d_T, nT, N, p0, (double)fanouts[0], g->rowptr, ycur, tot, include0,
                                                       d_bad, fstat);
+        bool prev_pulled = false;
         for (int h = 1; h <= L; ++h) {
             ScopedTimer th(ctx, SPP_T_VIP_HOP_FIRST + h - 1, st);
             VipHop a;
@@ -829,15 +830,18 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
             a.stat = fstat;
             // frontier of this hop and its out-edges, as counted by the kernel that wrote this hop's y;
             // a small frontier is pushed, a large one pulled
+            // (after a pulled hop the next one is pulled without asking: frontiers that have grown large
+            // rarely shrink, either form is correct for any frontier, and the question costs a host
+            // round trip of about 25 us)
             unsigned long long fc[2] = {0, 0};
-            {
+            if (!prev_pulled) {
                 const unsigned long long* hs = reinterpret_cast<const unsigned long long*>(ctx->h_pinned + kStatMirror);
                 SPP_HIP(hipMemcpyAsync(ctx->h_pinned + kStatMirror, fstat, 2 * (size_t)fill_grid * sizeof(unsigned long long),
                                        hipMemcpyDeviceToHost, st));
                 SPP_HIP(hipStreamSynchronize(st));
                 for (int b = 0; b < fill_grid; ++b) { fc[0] += hs[2 * b]; fc[1] += hs[2 * b + 1]; }
             }
-            const bool push = (int64_t)fc[1] * kPushShare <= g->M;
+            const bool push = !prev_pulled && (int64_t)fc[1] * kPushShare <= g->M;
             if (push) {
                 double* acc = ctx->acc.as<double>();
                 fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
@@ -857,7 +861,8 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
                 vip_tile_finish_kernel<<<fill_grid, kBlock, 0, st>>>(a, ctx->acc.as<double>(), parts, part_stride, N);
             }
             ctx->vip_pushed[h - 1] = push ? 1 : 0;
-            ctx->vip_frontier_edges[h - 1] = (int64_t)fc[1];
+            ctx->vip_frontier_edges[h - 1] = prev_pulled ? -1 : (int64_t)fc[1];     // -1: not asked
+            prev_pulled = !push;
             float* t = ycur; ycur = ynext; ynext = t;
         }
     }
