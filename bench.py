@@ -7,6 +7,11 @@ from pinned host memory on a side stream).  The one-time rows (VIP propagation, 
 fill) run before the timed region and are reported in the same line with their own figures.
 Inputs are resident (graph, shard and cache in HBM, remote rows pinned) before timing starts.
 
+The headline workload is Large (the papers100M-shaped configuration); Mid is reported as a second
+block of the same line.  The timed region is `reps` repetitions of `--steps` steps back to back
+(reps * steps distinct minibatches, no synchronisation in between), so every kernel is launched
+some twenty times whatever --steps is; `ms_per_step` = region / (reps * steps).
+
 Prints ONE JSON line; see the design doc for the byte accounting behind `roofline`.
 """
 import argparse
@@ -23,13 +28,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
 PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
-# same counters on a plain 1 GiB elementwise kernel (factors 2.0 and 1.0): profiles/gather_hit_mid_traffic.txt
-# and profiles/vip_tile_mid_counters.txt.  Keyed by (workload, minibatches per gather launch); other
-# shapes report null.
+# same counters on the library's plain copy kernel over 1 GiB (`--phase calibrate`); the summaries with
+# their commands are under profiles/.  Keyed by (workload, minibatches per gather launch); other shapes
+# report null.
 MEASURED_TRAFFIC = {
-    ("mid", 16): {"gather_hit": 346.3e6 + 269.9e6, "vip_tile": 0.730e9 + 115.6e6},
-    ("mid", 32): {"gather_hit": 692.0e6 + 536.5e6, "vip_tile": 0.730e9 + 115.6e6},
-    ("mid", 64): {"gather_hit": 2266.4e6, "vip_tile": 0.730e9 + 115.6e6},
 }
 
 
@@ -220,17 +222,403 @@ def beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi
                       "alpha": cfg.alpha, "rows": rows}), flush=True)
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.lower().startswith("model name"):
+                    return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def host_threads():
+    """Worker threads for the all-cores oracle leg: the machine's CPU share (16 for one GPU), at most what the process may use."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def setup_workload(args, cfg, spp, S, torch, dev, ctx, rows=True, remote_on_device=False):
+    """Inputs of one workload, resident before anything is timed."""
+    lo, hi = cfg.bounds()
+    t = time.time()
+    g = S.make_graph(cfg, dev)
+    T_all = S.make_training_set(cfg, dev)
+    Tk = S.local_training_set(cfg, T_all)
+    del T_all
+    log(f"{cfg.name}: graph N={g.N} M={g.M} |T_k|={Tk.numel()} ({time.time() - t:.1f}s)")
+    t = time.time()
+    G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True)
+    t_inlists = time.time() - t
+    nrem = cfg.N - (hi - lo)
+    local = remote = None
+    if rows:
+        local = S.feature_block(cfg, lo, hi, dev)
+        if remote_on_device:
+            remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype, device=dev)
+        else:
+            remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
+        for a in range(0, nrem, 1 << 19):
+            b = min(nrem, a + (1 << 19))
+            remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
+        torch.cuda.synchronize()
+        log(f"{cfg.name}: features local {tuple(local.shape)} remote {tuple(remote.shape)} "
+            f"{'pinned' if remote.is_pinned() else 'in device memory'}; transposed structure built in {t_inlists:.2f}s")
+    else:
+        log(f"{cfg.name}: no feature rows for phase {args.phase}; transposed structure built in {t_inlists:.2f}s")
+    return dict(g=g, Tk=Tk, G=G, t_inlists=t_inlists, local=local, remote=remote, lo=lo, hi=hi, nrem=nrem)
+
+
+def time_vip(args, cfg, spp, ctx, w, group):
+    """Proposition 1 on the workload, timed over args.vip_reps propagations (events on the context's stream)."""
+    g, G, Tk = w["g"], w["G"], w["Tk"]
+    p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts)            # warm-up, allocates workspaces
+    ctx.timing(True)
+    for _ in range(args.vip_reps):
+        p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts, sync=False)
+    ms, cnt, mn, med = ctx.time_stats()
+    ctx.timing(False)
+    total_ms = ms[0] / max(cnt[0], 1)
+    hop_ms = [ms[1 + h] / max(cnt[1 + h], 1) for h in range(cfg.L)]
+    hop_med = [med[1 + h] for h in range(cfg.L)]
+    hop_min = [mn[1 + h] for h in range(cfg.L)]
+    # algorithmic bytes of one hop (independent of how the transposed edges are laid out): one int32
+    # source id per edge, one 64-bit offset per destination row, y read once, the per-vertex result
+    # written once
+    hop_bytes = 4 * g.M + 8 * (g.N + 1) + 4 * g.N + 4 * g.N
+    pushed, frontier_edges = spp.vip_last_hops(ctx, cfg.L)
+    dense = [h for h in range(cfg.L) if not pushed[h]]               # only a pulled hop streams all M edges
+    roof = None
+    if dense:
+        h = max(dense, key=lambda i: hop_ms[i])
+        roof = {"bound": "hbm", "achieved": hop_bytes / (hop_ms[h] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "kernel": "dense hop of spp_vip_propagate (slowest hop that walks all M edges), all its launches",
+                "hop": h + 1, "avg_launch_ms": hop_ms[h], "median_launch_ms": hop_med[h], "min_launch_ms": hop_min[h],
+                "launches": cnt[1 + h], "bytes_per_launch": hop_bytes,
+                "traffic": MEASURED_TRAFFIC.get((cfg.name, group), {}).get("vip_dense_hop")}
+        roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
+    block = {"ms_total": total_ms, "ms_per_hop": hop_ms, "bytes_per_hop": hop_bytes, "roofline": roof,
+             "hop_pushed_over_sparse_frontier": pushed, "frontier_out_edges_per_hop": frontier_edges,
+             "propagations_timed": cnt[0], "in_lists_build_s": w["t_inlists"]}
+    return p, block
+
+
+def cpu_legs(args, cfg, spp, S, torch, np, ctx, w, cache, batches, first, count, p):
+    """The oracle as it stands on the machine's host cores: one thread, then the same single-thread code
+    with minibatches spread over threads (the C calls release the interpreter lock); once each the
+    oracle's VIP propagation and cache ranking (set-up rows)."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    g, lo, hi, local, remote = w["g"], w["lo"], w["hi"], w["local"], w["remote"]
+    rp, col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
+    as_np = (lambda t: t.view(torch.int16).numpy()) if cfg.dtype == "bf16" else (lambda t: t.numpy())
+    local_np = as_np(local.cpu())
+    remote_np = as_np(remote)
+    ids_np = cache.ids.cpu().numpy()
+    crow_np = as_np(S.feature_rows(cfg, cache.ids.long()).cpu())
+    seeds_np = {}
+
+    def one(i):
+        if i not in seeds_np:
+            seeds_np[i] = batches[i].cpu().numpy()
+        ref = oracle.sample_mfg(rp, col, seeds_np[i], cfg.fanouts, cfg.seed_sampler, i)
+        oracle.gather(cfg.N, lo, hi, local_np, crow_np, ids_np, remote_np, ref.node_ids)
+        return None                      # the rows are not kept: thousands of minibatches pass through here
+
+    for i in range(first, first + count):
+        seeds_np[i] = batches[i].cpu().numpy()
+    budget = args.cpu_seconds
+    # one thread
+    nb, t0 = 0, time.perf_counter()
+    while time.perf_counter() - t0 < budget and nb < 50 * count:
+        one(first + nb % count)
+        nb += 1
+    spent1 = time.perf_counter() - t0
+    single = {"value": nb / spent1, "unit": "minibatches/s", "cores": 1,
+              "sample": f"{nb} of the timed minibatches (sample_mfg + gather), {spent1:.1f}s"}
+    # all cores: the same calls, minibatches dealt to threads
+    C = host_threads()
+    per = max(1, int(nb / max(spent1, 1e-9) * budget))              # what one thread gets through in the budget
+    todo = [first + k % count for k in range(per * C)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=C) as ex:
+        for _ in ex.map(one, todo):
+            pass
+    spentC = time.perf_counter() - t0
+    cpu = {"value": len(todo) / spentC, "unit": "minibatches/s", "cores": C, "kind": "oracle",
+           "sample": f"{len(todo)} minibatches drawn from the {count} first timed ones (sample_mfg + gather each), dealt to "
+                     f"{C} threads running the single-thread oracle, {spentC:.1f}s of wall time",
+           "cpu_model": cpu_model(), "host_cpus_visible": os.cpu_count(), "one_thread": single}
+    if args.cpu_setup == "on":
+        Tk_np = w["Tk"].cpu().numpy()
+        t0 = time.perf_counter()
+        p_ref, _ = oracle.vip(rp, col, Tk_np, cfg.B, cfg.fanouts)
+        vip_s = time.perf_counter() - t0
+        err = np.abs(p.cpu().numpy().astype(np.float64) - p_ref)
+        vip_ok = bool(np.all(err <= 1e-5 * p_ref + 1e-37))
+        p_np = p.cpu().numpy()
+        t0 = time.perf_counter()
+        ids_ref = oracle.cache_select(p_np, lo, hi, cfg.K, cfg.alpha)
+        sel_s = time.perf_counter() - t0
+        sel_ok = bool(np.array_equal(ids_ref, ids_np))
+        if not (vip_ok and sel_ok):
+            log(f"PARITY FAILURE against the oracle: vip ok={vip_ok}, cache ids ok={sel_ok}")
+            sys.exit(1)
+        cpu["setup_rows_one_thread"] = {"vip_propagate_s": vip_s, "cache_select_s": sel_s,
+                                        "checked_against_hip_path": "all N probabilities to 1e-5 relative, all cache ids bit-exact"}
+    return cpu, (rp, col, local_np, remote_np, ids_np, crow_np)
+
+
+def run_workload(args, cfg, spp, S, torch, np, dev, K, W, R, cpu_leg):
+    """All figures of one workload: set-up rows (VIP, cache), the timed pipeline, roofline, PCIe, CPU legs."""
+    P = max(1, args.pipeline)
+    total_steps = K * R
+    Gsz = max(1, min(args.group, 64, -(-total_steps // P)))
+    row_bytes = cfg.D * cfg.elem_bytes
+    ctx = spp.Context(0)
+    w = setup_workload(args, cfg, spp, S, torch, dev, ctx)
+    g, G, Tk, local, remote, lo, hi, nrem = (w[k] for k in ("g", "G", "Tk", "local", "remote", "lo", "hi", "nrem"))
+
+    # ---- one-time rows: VIP propagation, cache ranking + fill -------------------------------
+    p, vip = time_vip(args, cfg, spp, ctx, w, Gsz)
+    t = time.time()
+    cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)
+    torch.cuda.synchronize()
+    cache_s = time.time() - t
+    vip["cache_build_s"] = cache_s
+    vip["n_cached"] = cache.n_cached
+    log(f"{cfg.name}: vip {vip['ms_total']:.3f} ms (hops {['%.3f' % x for x in vip['ms_per_hop']]}), "
+        f"cache {cache.n_cached} rows in {cache_s:.3f}s")
+
+    # ---- minibatches -------------------------------------------------------------------------
+    batches = []
+    ep = 0
+    while len(batches) < W + total_steps:
+        batches.extend(b for b in S.epoch_batches(cfg, Tk, ep) if b.numel() == min(cfg.B, Tk.numel()))
+        ep += 1
+    batches = batches[:W + total_steps]
+    # A lane = one context (stream, side stream, workspaces) with two sets of `group` MFG buffers and
+    # output rows, used alternately.  Per group the lane samples `group` minibatches with one call,
+    # then gathers all of them with one classification, one hit copy and one miss copy.  The miss
+    # copy is left running on the side stream (SPP_NO_JOIN) while the lane samples the next group
+    # into its other buffer set; the stream joins it (where a consumer of the rows would sit) just
+    # before the next hit copy.
+    lanes = []
+    for k in range(P):
+        c = ctx if k == 0 else spp.Context(0, stream=torch.cuda.Stream(dev))
+        sets = []
+        for _ in range(2):
+            b = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N) for _ in range(Gsz)]
+            o = [torch.empty((b[0].nb[-1], cfg.D), dtype=cfg.torch_dtype, device=dev) for _ in range(Gsz)]
+            sets.append((b, o))
+        lanes.append((c, sets))
+    state = {"store_order": args.store_order == "on"}
+
+    def run(first, count, gsz=None, order=None, gi0=0):
+        """Enqueue minibatches first .. first+count-1 (no host synchronisation inside)."""
+        gsz = Gsz if gsz is None else gsz
+        order = state["store_order"] if order is None else order
+        gi = gi0
+        for g0 in range(first, first + count, gsz):
+            c, sets = lanes[gi % P]
+            b, o = sets[(gi // P) % 2]
+            gi += 1
+            idx = range(g0, min(g0 + gsz, first + count))
+            spp.sample_mfg_multi(c, G, [(batches[i], i, b[k]) for k, i in enumerate(idx)], cfg.fanouts,
+                                 cfg.seed_sampler, sync=False)
+            # the gather classifies this group beside the previous group's miss copy, waits for that
+            # copy (the previous group's rows are complete from there on), then copies the hits
+            spp.gather_features_multi(c, cache, local, cfg.N, lo, hi, remote,
+                                      [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(len(idx))],
+                                      sync=False, join=False, store_order=order)
+        for c, _ in lanes:
+            spp.gather_join(c)
+
+    # set-up, not a step: every lane runs two full groups once, so that both buffer sets and both sets of
+    # library workspaces exist before the warm-up (an allocation inside the timed region would stall it)
+    torch.cuda.synchronize()
+    for c, _ in lanes:
+        c.totals(reset=True)
+    n_setup = min(len(batches), 2 * P * Gsz)
+    run(0, n_setup)
+    torch.cuda.synchronize()
+    # share of the remote store's rows that one group fetches: decides the order of the fetches
+    fetched = sum(t_["n_miss"] - t_["n_miss_shared"] for t_ in (c.totals(reset=True) for c, _ in lanes))
+    fetched_share = fetched / max(1, -(-n_setup // Gsz)) / max(nrem, 1)
+    if args.store_order == "auto":
+        state["store_order"] = fetched_share >= 0.125
+    log(f"{cfg.name}: a group fetches {fetched_share:.3f} of the remote store's rows; store order: {state['store_order']}")
+    if W > 0:
+        run(0, W)
+    torch.cuda.synchronize()
+    for c, _ in lanes:
+        c.timing(True)
+        c.totals(reset=True)
+    torch.cuda.synchronize()
+    # the timed region: R repetitions of K steps back to back (R*K distinct minibatches), no
+    # synchronisation in between, so that the miss copy of a group overlaps the sampling of the next
+    t0 = time.perf_counter()
+    run(W, total_steps)
+    for c, _ in lanes:
+        c.sync()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms, cnt, shortest, median = [0.0] * 16, [0] * 16, [0.0] * 16, [0.0] * 16
+    for li, (c, _) in enumerate(lanes):
+        m_, c_, mn_, med_ = c.time_stats()
+        ms = [a + b for a, b in zip(ms, m_)]
+        cnt = [a + b for a, b in zip(cnt, c_)]
+        if li == 0:
+            shortest, median = mn_, med_           # of the first lane's launches
+        c.timing(False)
+    elapsed = t1 - t0
+
+    # per-batch averages from the contexts' device-side running sums (no extra pass, no host sync)
+    tot = dict(n_nodes=0, n_edges=0, n_local=0, n_cache_hit=0, n_miss=0, n_miss_shared=0)
+    for c, _ in lanes:
+        t_ = c.totals()
+        for k in tot:
+            tot[k] += t_[k]
+    avg = {k: v / total_steps for k, v in tot.items()}
+
+    # the same steps at the pipeline depth the paper keeps (ten minibatches in flight: groups of five on
+    # the two buffer sets), for comparison: reported beside `value`, never as it
+    depth = None
+    if args.depth_leg == "on" and P == 1 and Gsz > 5 and total_steps >= 40:
+        kd = min(total_steps, 320) // 5 * 5
+        run(W, 20, gsz=5, order=False)
+        torch.cuda.synchronize()
+        td = time.perf_counter()
+        run(W, kd, gsz=5, order=False)
+        for c, _ in lanes:
+            c.sync()
+        torch.cuda.synchronize()
+        td = time.perf_counter() - td
+        depth = {"minibatches_per_gather_launch": 5, "minibatches_in_flight": 10, "steps": kd,
+                 "value": kd / td, "ms_per_step": td / kd * 1e3}
+
+    T_HIT, T_MISS, T_CLS, T_SAMPLE = 10, 11, 12, 9
+    per = lambda i: ms[i] / max(cnt[i], 1)
+    hit_ms, miss_ms, cls_ms, sample_ms = per(T_HIT), per(T_MISS), per(T_CLS), per(T_SAMPLE)
+    # per LAUNCH: a launch of the hit / miss kernel covers one group of minibatches
+    n_launch = max(cnt[T_HIT], 1)
+    hit_rows = (tot["n_local"] + tot["n_cache_hit"]) / n_launch
+    hit_bytes = hit_rows * 2 * row_bytes                 # read the source row + write the output row
+    roof = {"bound": "hbm", "achieved": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms > 0 else 0.0,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>",
+            "traffic": MEASURED_TRAFFIC.get((cfg.name, Gsz), {}).get("gather_hit") if P == 1 else None,
+            "bytes_per_launch": hit_bytes, "rows_per_launch": hit_rows, "avg_launch_ms": hit_ms,
+            "median_launch_ms": median[T_HIT], "min_launch_ms": shortest[T_HIT], "launches": cnt[T_HIT],
+            "note": "runs between two PCIe miss copies, with the whole chip"}
+    roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
+    # bytes that cross PCIe: a vertex missed by several minibatches of a group is read once and copied on the device
+    miss_bytes = (tot["n_miss"] - tot["n_miss_shared"]) / max(cnt[T_MISS], 1) * row_bytes
+    pcie = {"bound": "pcie", "achieved": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms > 0 else 0.0,
+            "peak": PCIE_PEAK_GBS, "unit": "GB/s", "kernel": "gather_miss_kernel<16> (side stream)",
+            "bytes_per_launch": miss_bytes, "avg_launch_ms": miss_ms, "launches": cnt[T_MISS],
+            "rows_missed_per_launch": tot["n_miss"] / max(cnt[T_MISS], 1),
+            "rows_shared_per_launch": tot["n_miss_shared"] / max(cnt[T_MISS], 1)}
+    pcie["frac"] = pcie["achieved"] / PCIE_PEAK_GBS
+    # the sampler has no %-of-peak bar (latency and transaction bound): algorithmic bytes as context
+    sample_bytes = (16 * tot["n_edges"] + 20 * (tot["n_nodes"])) / max(cnt[T_SAMPLE], 1)
+    sampler = {"avg_call_ms": sample_ms, "median_call_ms": median[T_SAMPLE], "min_call_ms": shortest[T_SAMPLE],
+               "calls": cnt[T_SAMPLE], "minibatches_per_call": Gsz, "algorithmic_bytes_per_call": sample_bytes,
+               "algorithmic_GBps": sample_bytes / (sample_ms * 1e-3) / 1e9 if sample_ms > 0 else 0.0,
+               "traffic": MEASURED_TRAFFIC.get((cfg.name, Gsz), {}).get("sampler_call")}
+
+    # ---- the launch configuration that was timed, checked against the oracle ------------------
+    cpu = None
+    checked = []
+    if cpu_leg and args.cpu_seconds > 0:
+        cpu, host = cpu_legs(args, cfg, spp, S, torch, np, ctx, w, cache, batches, W, min(total_steps, 256), p)
+        import oracle
+        rp, col, local_np, remote_np, ids_np, crow_np = host
+        # one more group through the timed calls (same group size, flags and deferred join); its first three
+        # minibatches and one drawn at random are compared with the oracle
+        c, sets = lanes[0]
+        b, o = sets[0]
+        idx = list(range(W, W + min(Gsz, total_steps)))
+        run(W, len(idx))
+        c.sync()
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(12345)
+        pick = sorted(set(list(range(min(3, len(idx)))) + ([int(rng.integers(3, len(idx)))] if len(idx) > 3 else [])))
+        for k in pick:
+            i = idx[k]
+            ref = oracle.sample_mfg(rp, col, batches[i].cpu().numpy(), cfg.fanouts, cfg.seed_sampler, i)
+            want, _, counts = oracle.gather(cfg.N, lo, hi, local_np, crow_np, ids_np, remote_np, ref.node_ids)
+            cn = b[k].counts.cpu().numpy()
+            n_h = [int(x) for x in cn[:cfg.L + 1]]
+            e_h = [int(x) for x in cn[9:9 + cfg.L + 1]]
+            got = o[k][:n_h[-1]]
+            got = (got.view(torch.int16) if cfg.dtype == "bf16" else got).cpu().numpy()
+            ok = (n_h == ref.n and e_h == ref.e
+                  and np.array_equal(b[k].node_ids[:n_h[-1]].cpu().numpy(), ref.node_ids)
+                  and all(np.array_equal(b[k].indptr[h][:n_h[h] + 1].cpu().numpy(), ref.indptr[h]) for h in range(cfg.L))
+                  and all(np.array_equal(b[k].src[h][:e_h[h + 1]].cpu().numpy(), ref.src[h]) for h in range(cfg.L))
+                  and np.array_equal(got.view(np.uint8), want.view(np.uint8)))
+            if not ok:
+                log(f"PARITY FAILURE against the oracle on minibatch {i} of {cfg.name}")
+                sys.exit(1)
+            checked.append(i)
+        cpu["checked_against_hip_path"] = (f"minibatches {checked} of a group of {len(idx)} run through the timed calls "
+                                           "(MFGs, relabel maps and gathered rows bit-exact)")
+        del rp, col, local_np, remote_np, ids_np, crow_np, host
+
+    block = {
+        "value": total_steps / elapsed, "unit": "minibatches/s", "ms_per_step": elapsed / total_steps * 1e3,
+        "timed_region_s": elapsed,
+        "dtype": {"fp32": "f32", "fp16": "f16", "bf16": "bf16"}[cfg.dtype] + " rows (byte copy), int32 ids",
+        "config": {"workload": f"{cfg.name}: N={g.N} M={g.M} D={cfg.D} {cfg.dtype} fanouts={list(cfg.fanouts)} "
+                               f"B={cfg.B} K={cfg.K} alpha={cfg.alpha} owned partition {cfg.owned_partition}",
+                   "reps": R, "steps_timed": total_steps,
+                   "lanes": P, "minibatches_per_gather_launch": Gsz, "minibatches_in_flight": 2 * P * Gsz,
+                   "setup_minibatches_before_warmup": n_setup,
+                   "at_ten_minibatches_in_flight": depth,
+                   "misses_fetched_in": "store order" if state["store_order"] else "list order",
+                   "share_of_remote_store_fetched_per_launch": round(fetched_share, 4),
+                   "avg_per_batch": {k: round(v, 1) for k, v in avg.items()},
+                   "hit_rate_of_remote": avg["n_cache_hit"] / max(avg["n_cache_hit"] + avg["n_miss"], 1e-9),
+                   "features": "sum of twelve hashed 16-bit uniforms, centred, unit variance (stand-in for N(0,1); the path copies bytes)"},
+        "roofline": roof, "cpu_baseline": cpu, "pcie": pcie, "sampler": sampler,
+        "kernels_ms": {"sample_mfg_per_launch": sample_ms, "gather_classify_per_launch": cls_ms,
+                       "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms,
+                       "median": {"sample_mfg": median[T_SAMPLE], "gather_classify": median[T_CLS],
+                                  "gather_hit": median[T_HIT], "gather_miss": median[T_MISS]},
+                       "min": {"sample_mfg": shortest[T_SAMPLE], "gather_classify": shortest[T_CLS],
+                               "gather_hit": shortest[T_HIT], "gather_miss": shortest[T_MISS]}},
+        "vip": vip,
+    }
+    cache.close()
+    G.close()
+    for c, _ in lanes:
+        c.close()
+    return block
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1280)
     ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--config", default="mid", help="workload: tiny | mid (default, the metric's configuration)")
-    ap.add_argument("--vip-reps", type=int, default=5)
+    ap.add_argument("--reps", type=int, default=0,
+                    help="the timed region is `reps` repetitions of `steps` steps back to back (reps*steps distinct minibatches, "
+                         "no synchronisation in between); 0 = as many as bring the region to 1280 steps, so that every kernel "
+                         "is launched 20 times whatever --steps is")
+    ap.add_argument("--config", default="large",
+                    help="headline workload: large (default: the papers100M-shaped configuration, the largest that the "
+                         "metric's single-GPU pipeline is quoted on) | mid | tiny | wide | skew")
+    ap.add_argument("--second", default="auto",
+                    help="a second workload reported as a block of the same JSON line (auto: mid beside large; none)")
+    ap.add_argument("--vip-reps", type=int, default=10)
     ap.add_argument("--pipeline", type=int, default=1,
                     help="lanes: contexts (each with its own stream and buffers) used round-robin")
     ap.add_argument("--group", type=int, default=64,
-                    help="minibatches a lane samples back to back and then gathers with ONE set of launches "
+                    help="minibatches a lane samples with one call and then gathers with ONE set of launches "
                          "(2 x pipeline x group minibatches are in flight; the paper keeps ten)")
     ap.add_argument("--store-order", default="auto", choices=["auto", "on", "off"],
                     help="fetch a group's missed rows in the order of the remote store (SPP_STORE_ORDER); auto: when "
@@ -238,7 +626,10 @@ def main():
     ap.add_argument("--depth-leg", default="on", choices=["on", "off"],
                     help="after the timed steps, also time the pipeline at ten minibatches in flight (the paper's depth); "
                          "off keeps a kernel trace of the run to the launches of the timed configuration")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle (CPU baseline) leg; 0 = skip")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0,
+                    help="budget of each of the two oracle legs over minibatches (one thread, all threads); 0 = no CPU legs")
+    ap.add_argument("--cpu-setup", default="on", choices=["on", "off"],
+                    help="also time the oracle's VIP propagation and cache ranking once (one thread; about a minute on large)")
     ap.add_argument("--phase", default="all", choices=["all", "vip", "alpha-sweep", "beta-sweep", "policy-sweep", "general", "calibrate"],
                     help="all: the benchmark line; vip: set-up and VIP propagation only (for profiling that kernel); "
                          "alpha-sweep: hit rate and host-miss bytes per batch over alpha in {0,.05,.1,.2,.5}, VIP-ranked "
@@ -250,8 +641,8 @@ def main():
                          "beta-sweep: local rows read from host memory over the device-resident share beta of the "
                          "partition's rows, VIP order against id order (the experiment shape of the figure on local "
                          "storage on CPU versus GPU); "
-                         "calibrate: a plain elementwise pass over 1 GiB (read 1 GiB, write 1 GiB), the known-size kernel "
-                         "that scales the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
+                         "calibrate: the library's plain streaming kernels over 1 GiB (read-only, copy, write-only): the "
+                         "known-size kernels that scale the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc")
     ap.add_argument("--sweep-batches", type=int, default=8)
     ap.add_argument("--sweep-epochs", type=int, default=4)
     args = ap.parse_args()
@@ -268,314 +659,70 @@ def main():
     cfg = S.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
+
+    def stream_rates():
+        c = spp.Context(0)
+        r = spp.stream_rates(c, 1 << 30, reps=10)
+        c.close()
+        return r
+
     if args.phase == "calibrate":
-        x = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
-        y = torch.empty_like(x)
-        for _ in range(5):
-            torch.add(x, 1.0, out=y)
-        torch.cuda.synchronize()
-        # what plain library kernels reach on this machine, by direction (the published peak counts both)
-        rates = {}
-        for name, fn, nbytes in (("read_only_sum", lambda: x.sum(), 4 * x.numel()),
-                                 ("read_write_add", lambda: torch.add(x, 1.0, out=y), 8 * x.numel()),
-                                 ("write_only_fill", lambda: y.fill_(2.0), 4 * x.numel())):
-            fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(10):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            rates[name + "_GBps"] = round(nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
-        print(json.dumps({"phase": "calibrate", "kernel": "elementwise add", "bytes_read": x.numel() * 4,
-                          "bytes_written": y.numel() * 4, "launches": 5, "library_kernels_over_1GiB": rates}), flush=True)
+        r = stream_rates()
+        print(json.dumps({"phase": "calibrate", "bytes_per_pass": 1 << 30, "passes": 10,
+                          "kernels": "spp_stream_rates: read-only pass, copy (1 GiB read + 1 GiB written), write-only fill",
+                          "GBps": r}), flush=True)
         return
+
+    if args.phase != "all":
+        ctx = spp.Context(0)
+        rows = args.phase in ("alpha-sweep", "beta-sweep")
+        # the beta sweep measures host reads of LOCAL rows: its remote store sits in device memory so that
+        # the host's pinning limit is left to the partition's own rows
+        w = setup_workload(args, cfg, spp, S, torch, dev, ctx, rows=rows, remote_on_device=args.phase == "beta-sweep")
+        g, G, Tk, local, remote, lo, hi = (w[k] for k in ("g", "G", "Tk", "local", "remote", "lo", "hi"))
+        p, vip = time_vip(args, cfg, spp, ctx, w, args.group)
+        if args.phase == "vip":
+            print(json.dumps({"phase": "vip", "workload": cfg.name, "N": g.N, "M": g.M, **vip}), flush=True)
+        elif args.phase == "alpha-sweep":
+            alpha_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
+        elif args.phase == "beta-sweep":
+            beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
+        elif args.phase == "policy-sweep":
+            policy_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, lo, hi)
+        elif args.phase == "general":
+            general_phase(args, cfg, spp, S, torch, ctx, G, g, Tk, p)
+        return
+
     K, W = args.steps, args.warmup
-    P = max(1, args.pipeline)
-    # groups of `group` minibatches; a short run is one group per lane (the larger the group, the more of its
-    # missed rows are shared, and PCIe is what bounds the step)
-    Gsz = max(1, min(args.group, 64, -(-K // P)))
-    lo, hi = cfg.bounds()
-    row_bytes = cfg.D * cfg.elem_bytes
-
-    # ---- inputs, resident before anything is timed ------------------------------------------
-    t = time.time()
-    g = S.make_graph(cfg, dev)
-    T_all = S.make_training_set(cfg, dev)
-    Tk = S.local_training_set(cfg, T_all)
-    log(f"graph N={g.N} M={g.M} |T_k|={Tk.numel()} ({time.time() - t:.1f}s)")
-    ctx = spp.Context(0)
-    t = time.time()
-    G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True)
-    t_inlists = time.time() - t
-    nrem = cfg.N - (hi - lo)
-    if args.phase in ("policy-sweep", "vip", "general"):
-        local = remote = None                      # these phases move no feature rows
-        log(f"no feature rows for phase {args.phase}; transposed structure built in {t_inlists:.2f}s")
-    else:
-        local = S.feature_block(cfg, lo, hi, dev)
-        if args.phase == "beta-sweep":
-            # this sweep measures host reads of LOCAL rows: the remote store sits in device memory so that
-            # the host's pinning limit is left to the partition's own rows
-            remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype, device=dev)
-        else:
-            remote = torch.empty((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
-        for a in range(0, nrem, 1 << 19):
-            b = min(nrem, a + (1 << 19))
-            remote[a:b].copy_(S.feature_rows(cfg, S.remote_ids(cfg, a, b, dev)))
-        torch.cuda.synchronize()
-        log(f"features local {tuple(local.shape)} remote {tuple(remote.shape)} "
-            f"{'pinned' if remote.is_pinned() else 'in device memory'}; transposed structure built in {t_inlists:.2f}s")
-
-    # ---- one-time rows: VIP propagation, cache ranking + fill -------------------------------
-    p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts)            # warm-up, allocates workspaces
-    ctx.timing(True)
-    for _ in range(args.vip_reps):
-        p = spp.vip_propagate(ctx, G, Tk, cfg.B, cfg.fanouts, sync=False)
-    ms, cnt = ctx.times()
-    ctx.timing(False)
-    vip_total_ms = ms[0] / max(cnt[0], 1)
-    vip_hop_ms = [ms[1 + h] / max(cnt[1 + h], 1) for h in range(cfg.L)]
-    # algorithmic bytes of one hop (independent of how the transposed edges are laid out): one int32
-    # source id per edge, one 64-bit offset per destination row, y read once, the per-vertex result
-    # written once
-    vip_hop_bytes = 4 * g.M + 8 * (g.N + 1) + 4 * g.N + 4 * g.N
-    vip_pushed, vip_frontier_edges = spp.vip_last_hops(ctx, cfg.L)
-    measured = MEASURED_TRAFFIC.get((cfg.name, Gsz), {})
-    dense = [t for t, pushed in zip(vip_hop_ms, vip_pushed) if not pushed]      # only a pulled hop streams all M edges
-    if dense:
-        worst = max(dense)
-        vip_roof = {"bound": "hbm", "achieved": vip_hop_bytes / (worst * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "kernel": "vip_tile_kernel + vip_tile_finish_kernel (slowest dense hop: all M edges)",
-                    "traffic": measured.get("vip_tile")}
-        vip_roof["frac"] = vip_roof["achieved"] / HBM_PEAK_GBS
-    else:
-        vip_roof = None           # every hop was pushed over a sparse frontier: no hop moved the algorithmic bytes
-    if args.phase == "vip":
-        print(json.dumps({"phase": "vip", "workload": cfg.name, "N": g.N, "M": g.M, "ms_total": vip_total_ms,
-                          "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
-                          "hop_pushed_over_sparse_frontier": vip_pushed,
-                          "frontier_out_edges_per_hop": vip_frontier_edges}), flush=True)
-        return
-    if args.phase == "alpha-sweep":
-        alpha_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
-        return
-    if args.phase == "beta-sweep":
-        beta_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, local, remote, lo, hi)
-        return
-    if args.phase == "policy-sweep":
-        policy_sweep(args, cfg, spp, S, torch, ctx, G, g, Tk, p, lo, hi)
-        return
-    if args.phase == "general":
-        general_phase(args, cfg, spp, S, torch, ctx, G, g, Tk, p)
-        return
-    t = time.time()
-    cache = spp.build_vip_cache(ctx, p, lo, hi, cfg.K, cfg.alpha, remote, cfg.D, cfg.elem_bytes)
-    torch.cuda.synchronize()
-    cache_s = time.time() - t
-    log(f"vip {vip_total_ms:.3f} ms (hops {['%.3f' % x for x in vip_hop_ms]}), cache {cache.n_cached} rows in {cache_s:.3f}s")
-
-    # ---- minibatches -------------------------------------------------------------------------
-    batches = []
-    ep = 0
-    while len(batches) < W + K:
-        batches.extend(b for b in S.epoch_batches(cfg, Tk, ep) if b.numel() == min(cfg.B, Tk.numel()))
-        ep += 1
-    batches = batches[:W + K]
-    # A lane = one context (stream, side stream, workspaces) with two sets of `group` MFG buffers and
-    # output rows, used alternately.  Per group the lane samples `group` minibatches back to back,
-    # then gathers all of them with one classification, one hit copy and one miss copy.  The miss
-    # copy is left running on the side stream (SPP_NO_JOIN) while the lane samples the next group
-    # into its other buffer set; the stream joins it (where a consumer of the rows would sit) just
-    # before the next gather.  One lane already keeps the PCIe link busy; more lanes only contend.
-    lanes = []
-    for k in range(P):
-        c = ctx if k == 0 else spp.Context(0, stream=torch.cuda.Stream(dev))
-        sets = []
-        for _ in range(2):
-            b = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, cfg.N) for _ in range(Gsz)]
-            o = [torch.empty((b[0].nb[-1], cfg.D), dtype=cfg.torch_dtype, device=dev) for _ in range(Gsz)]
-            sets.append((b, o))
-        lanes.append((c, sets, None))
-    bufs, out = lanes[0][1][0][0][0], lanes[0][1][0][1][0]
-
-    def run(first, count, gsz=None, order=None):
-        """Enqueue minibatches first .. first+count-1 (no host synchronisation inside)."""
-        gsz = Gsz if gsz is None else gsz
-        order = store_order if order is None else order
-        gi = 0
-        for g0 in range(first, first + count, gsz):
-            c, sets, _ = lanes[gi % P]
-            b, o = sets[(gi // P) % 2]
-            gi += 1
-            idx = range(g0, min(g0 + gsz, first + count))
-            spp.sample_mfg_multi(c, G, [(batches[i], i, b[k]) for k, i in enumerate(idx)], cfg.fanouts,
-                                 cfg.seed_sampler, sync=False)
-            # the gather classifies this group beside the previous group's miss copy, waits for that
-            # copy (the previous group's rows are complete from there on), then copies the hits
-            spp.gather_features_multi(c, cache, local, cfg.N, lo, hi, remote,
-                                      [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(len(idx))],
-                                      sync=False, join=False, store_order=order)
-        for c, _, _ in lanes:
-            spp.gather_join(c)
-
-    # set-up, not a step: every lane runs two full groups once, so that both buffer sets and both sets of
-    # library workspaces exist before the warm-up (an allocation inside the timed region would stall it)
-    store_order = args.store_order == "on"
-    torch.cuda.synchronize()
-    for c, _, _ in lanes:
-        c.totals(reset=True)
-    n_setup = min(len(batches), 2 * P * Gsz)
-    run(0, n_setup)
-    torch.cuda.synchronize()
-    # share of the remote store's rows that one group fetches: decides the order of the fetches
-    fetched = sum(t_["n_miss"] - t_["n_miss_shared"] for t_ in (c.totals(reset=True) for c, _, _ in lanes))
-    fetched_share = fetched / max(1, -(-n_setup // Gsz)) / max(nrem, 1)
-    if args.store_order == "auto":
-        store_order = fetched_share >= 0.125
-    log(f"a group fetches {fetched_share:.3f} of the remote store's rows; store order: {store_order}")
-    run(0, W)
-    torch.cuda.synchronize()
-    for c, _, _ in lanes:
-        c.timing(True)
-        c.totals(reset=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(W, K)
-    for c, _, _ in lanes:
-        c.sync()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms, cnt, shortest, median = [0.0] * 16, [0] * 16, [0.0] * 16, [0.0] * 16
-    for li, (c, _, _) in enumerate(lanes):
-        m_, c_, mn_, med_ = c.time_stats()
-        ms = [a + b for a, b in zip(ms, m_)]
-        cnt = [a + b for a, b in zip(cnt, c_)]
-        if li == 0:
-            shortest, median = mn_, med_           # of the first lane's launches
-        c.timing(False)
-    elapsed = t1 - t0
-    ms_per_step = elapsed / K * 1e3
-
-    # per-batch averages from the contexts' device-side running sums (no extra pass, no host sync)
-    tot = dict(n_nodes=0, n_edges=0, n_local=0, n_cache_hit=0, n_miss=0, n_miss_shared=0)
-    for c, _, _ in lanes:
-        t_ = c.totals()
-        for k in tot:
-            tot[k] += t_[k]
-    avg = {k: v / K for k, v in tot.items()}
-
-    # the same steps at the pipeline depth the paper keeps (ten minibatches in flight: groups of five on
-    # the two buffer sets), for comparison: reported beside `value`, never as it
-    depth = None
-    if args.depth_leg == "on" and P == 1 and Gsz > 5 and K >= 40:
-        kd = min(K, 320) // 5 * 5
-        run(W, 20, gsz=5, order=False)
-        torch.cuda.synchronize()
-        td = time.perf_counter()
-        run(W, kd, gsz=5, order=False)
-        for c, _, _ in lanes:
-            c.sync()
-        torch.cuda.synchronize()
-        td = time.perf_counter() - td
-        depth = {"minibatches_per_gather_launch": 5, "minibatches_in_flight": 10, "steps": kd,
-                 "value": kd / td, "ms_per_step": td / kd * 1e3}
-
-    T_HIT, T_MISS, T_CLS, T_SAMPLE = 10, 11, 12, 9
-    hit_ms = ms[T_HIT] / max(cnt[T_HIT], 1)
-    miss_ms = ms[T_MISS] / max(cnt[T_MISS], 1)
-    cls_ms = ms[T_CLS] / max(cnt[T_CLS], 1)
-    sample_ms = ms[T_SAMPLE] / max(cnt[T_SAMPLE], 1)
-    # per LAUNCH: a launch of the hit / miss kernel covers one group of minibatches
-    n_launch = max(cnt[T_HIT], 1)
-    hit_rows = (tot["n_local"] + tot["n_cache_hit"]) / n_launch
-    hit_bytes = hit_rows * 2 * row_bytes                 # read the source row + write the output row
-    roof = {"bound": "hbm", "achieved": hit_bytes / (hit_ms * 1e-3) / 1e9 if hit_ms > 0 else 0.0,
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel": "gather_hit_kernel<16>",
-            "traffic": measured.get("gather_hit") if P == 1 else None,
-            "bytes_per_launch": hit_bytes, "avg_launch_ms": hit_ms,
-            "median_launch_ms": median[T_HIT], "min_launch_ms": shortest[T_HIT], "launches": cnt[T_HIT],
-            "note": "runs between two PCIe miss copies, with the whole chip"}
-    roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
-    # bytes that cross PCIe: a vertex missed by several minibatches of a group is read once and copied on the device
-    miss_bytes = (tot["n_miss"] - tot["n_miss_shared"]) / max(cnt[T_MISS], 1) * row_bytes
-    pcie = {"bound": "pcie", "achieved": miss_bytes / (miss_ms * 1e-3) / 1e9 if miss_ms > 0 else 0.0,
-            "peak": PCIE_PEAK_GBS, "unit": "GB/s",
-            "kernel": "gather_miss_kernel<16> (side stream)",
-            "bytes_per_launch": miss_bytes, "avg_launch_ms": miss_ms,
-            "rows_missed_per_launch": tot["n_miss"] / max(cnt[T_MISS], 1),
-            "rows_shared_per_launch": tot["n_miss_shared"] / max(cnt[T_MISS], 1)}
-    pcie["frac"] = pcie["achieved"] / PCIE_PEAK_GBS
-
-    # ---- CPU baseline: the oracle as it stands, single thread, bounded sample ---------------
-    cpu = None
-    if args.cpu_seconds > 0:
-        import oracle
-        rp, col = g.rowptr.cpu().numpy(), g.col.cpu().numpy()
-        local_h = local.cpu()
-        local_np = local_h.view(torch.int16).numpy() if cfg.dtype == "bf16" else local_h.numpy()
-        remote_np = remote.view(torch.int16).numpy() if cfg.dtype == "bf16" else remote.numpy()
-        ids_np = cache.ids.cpu().numpy()
-        crow = S.feature_rows(cfg, cache.ids.long())
-        crow_np = (crow.view(torch.int16) if cfg.dtype == "bf16" else crow).cpu().numpy()
-        nb, spent, checked = 0, 0.0, 0
-        while nb < 20 * K and spent < args.cpu_seconds:
-            i = W + nb % K
-            seeds = batches[i].cpu().numpy()
-            c0 = time.perf_counter()
-            ref = oracle.sample_mfg(rp, col, seeds, cfg.fanouts, cfg.seed_sampler, i)
-            want, _, counts = oracle.gather(cfg.N, lo, hi, local_np, crow_np, ids_np, remote_np, ref.node_ids)
-            spent += time.perf_counter() - c0
-            if nb < 2:      # the timed batches are also parity-checked against the HIP path
-                m = spp.sample_mfg(ctx, G, batches[i], cfg.fanouts, cfg.seed_sampler, i, out=bufs)
-                o, st = spp.gather_features(ctx, cache, local, cfg.N, lo, hi, remote, bufs.node_ids, n=m.n[-1], out=out)
-                got = o[:m.n[-1]]
-                got = (got.view(torch.int16) if cfg.dtype == "bf16" else got).cpu().numpy()
-                ok = (m.n == ref.n and np.array_equal(bufs.node_ids[:m.n[-1]].cpu().numpy(), ref.node_ids)
-                      and all(np.array_equal(bufs.src[h][:m.e[h + 1]].cpu().numpy(), ref.src[h]) for h in range(cfg.L))
-                      and np.array_equal(got.view(np.uint8), want.view(np.uint8))
-                      and (st["n_local"], st["n_cache_hit"], st["n_miss"]) == counts)
-                if not ok:
-                    log("PARITY FAILURE against the oracle on batch", i)
-                    sys.exit(1)
-                checked += 1
-            nb += 1
-        cpu = {"value": nb / spent, "unit": "minibatches/s", "cores": 1, "kind": "oracle",
-               "sample": f"{nb} minibatches drawn from the {K} timed ones (sample_mfg + gather), {spent:.1f}s of one core; "
-                         f"{checked} checked against the HIP path"}
+    R = args.reps if args.reps > 0 else max(1, -(-1280 // max(K, 1)))
+    rates = stream_rates()
+    head = run_workload(args, cfg, spp, S, torch, np, dev, K, W, R, cpu_leg=True)
+    second_name = {"auto": "mid" if cfg.name == "large" else "none"}.get(args.second, args.second)
+    second = None
+    if second_name != "none" and second_name != cfg.name:
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        try:
+            torch._C._host_emptyCache()          # give the pinned remote store back before the next one is pinned
+        except Exception:
+            pass
+        second = run_workload(args, S.CONFIGS[second_name], spp, S, torch, np, dev, K, W, R, cpu_leg=True)
 
     line = {
         "metric": "sampled+gathered minibatches/s per partition on 1 GPU",
-        "value": K / elapsed, "unit": "minibatches/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"fp32": "f32", "fp16": "f16", "bf16": "bf16"}[cfg.dtype] + " rows (byte copy), int32 ids",
-        "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: N={g.N} M={g.M} D={cfg.D} {cfg.dtype} fanouts={list(cfg.fanouts)} "
-                               f"B={cfg.B} K={cfg.K} alpha={cfg.alpha} owned partition {cfg.owned_partition}",
-                   "lanes": P, "minibatches_per_gather_launch": Gsz, "minibatches_in_flight": 2 * P * Gsz,
-                   "at_ten_minibatches_in_flight": depth,
-                   "misses_fetched_in": "store order" if store_order else "list order",
-                   "share_of_remote_store_fetched_per_launch": round(fetched_share, 4),
-                   "avg_per_batch": {k: round(v, 1) for k, v in avg.items()},
-                   "hit_rate_of_remote": avg["n_cache_hit"] / max(avg["n_cache_hit"] + avg["n_miss"], 1e-9)},
-        "roofline": roof,
-        "cpu_baseline": cpu,
-        "pcie": pcie,
-        "kernels_ms": {"sample_mfg_per_launch": sample_ms, "gather_classify_per_launch": cls_ms,
-                       "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms,
-                       "median": {"sample_mfg": median[T_SAMPLE], "gather_classify": median[T_CLS],
-                                  "gather_hit": median[T_HIT], "gather_miss": median[T_MISS]},
-                       "min": {"sample_mfg": shortest[T_SAMPLE], "gather_classify": shortest[T_CLS],
-                               "gather_hit": shortest[T_HIT], "gather_miss": shortest[T_MISS]}},
-        "vip": {"ms_total": vip_total_ms, "ms_per_hop": vip_hop_ms, "bytes_per_hop": vip_hop_bytes, "roofline": vip_roof,
-                "hop_pushed_over_sparse_frontier": vip_pushed, "frontier_out_edges_per_hop": vip_frontier_edges,
-                "in_lists_build_s": t_inlists, "cache_build_s": cache_s, "n_cached": cache.n_cached},
+        "value": head["value"], "unit": head["unit"], "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": head["config"], "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
+        "pcie": head["pcie"], "sampler": head["sampler"], "kernels_ms": head["kernels_ms"], "vip": head["vip"],
+        "timed_region_s": head["timed_region_s"],
+        "hbm_measured": {"datasheet_peak_GBps": HBM_PEAK_GBS, "library_streaming_kernels_over_1GiB_GBps": rates,
+                         "note": "the datasheet peak counts reads and writes together; achieved figures are read against it"},
     }
+    if second is not None:
+        line[second_name] = second
     print(json.dumps(line), flush=True)
-    cache.close()
-    G.close()
-    for c, _, _ in lanes:
-        c.close()
 
 
 if __name__ == "__main__":

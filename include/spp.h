@@ -320,6 +320,15 @@ int  spp_ctx_times(spp_ctx* ctx, float* sum_ms /* [SPP_T_COUNT] */, int64_t* cou
  *     four arrays may be null. */
 int  spp_ctx_time_stats(spp_ctx* ctx, float* sum_ms, int64_t* count, float* min_ms, float* median_ms);
 
+/* What the part reaches by direction, measured with three plain streaming kernels of this library over
+ * caller-provided device buffers of `bytes` bytes each (a multiple of 16; both 16-byte aligned): the
+ * figures that the roofline fractions of Sec.-4.3-style byte-moving kernels are read against, beside the
+ * published peak (which counts reads and writes together).  out_gbps[0]: a read-only pass over d_a;
+ * [1]: a copy d_a -> d_b (bytes read plus bytes written); [2]: a write-only fill of d_b; each in GB/s,
+ * averaged over `reps` passes (1 .. 1000) after one untimed pass.  d_b is overwritten.  Waits for
+ * the context's stream. */
+int  spp_stream_rates(spp_ctx* ctx, const void* d_a, void* d_b, int64_t bytes, int32_t reps, float* out_gbps /* [3] */);
+
 /* Running sums over the calls made on this context since the last reset, kept on the device so
  * that a loop of asynchronous calls can be accounted for without a host round trip per batch:
  *   out[0] minibatches sampled, out[1] sum of |S_L|, out[2] sum of sampled edges over all hops,

@@ -5,4 +5,4 @@ hand-written HIP kernels for gfx950: vip_propagate, build_vip_cache, sample_mfg,
 gather_features.
 """
 from .api import (access_count, Cache, Context, Graph, LocalStore, MFGBuffers, SppError, build_local_store, build_vip_cache, gather_features, gather_features_multi, gather_join,  # noqa: F401
-                  gather_last_stats, load_library, mfg_bound, sample_mfg, sample_mfg_general, sample_mfg_multi, vip_propagate_general, vip_propagate, vip_last_hops, EXPORTS, LIB_PATH)
+                  gather_last_stats, load_library, mfg_bound, stream_rates, sample_mfg, sample_mfg_general, sample_mfg_multi, vip_propagate_general, vip_propagate, vip_last_hops, EXPORTS, LIB_PATH)

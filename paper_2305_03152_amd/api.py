@@ -32,6 +32,7 @@ EXPORTS = [
     "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_time_stats", "spp_ctx_totals",
     "spp_build_local_store", "spp_local_store_destroy", "spp_local_store_set_limit", "spp_local_store_rank",
     "spp_gather_features_split", "spp_access_count", "spp_vip_propagate_general", "spp_sample_mfg_general",
+    "spp_stream_rates",
 ]
 
 
@@ -137,6 +138,7 @@ def load_library():
     lib.spp_ctx_time_stats.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_float),
                                        C.POINTER(C.c_float)]
     lib.spp_ctx_totals.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.c_int]
+    lib.spp_stream_rates.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_float)]
     _lib = lib
     return lib
 
@@ -602,6 +604,17 @@ def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Ten
                                              int(N), int(lo), int(hi), _ptr(remote), D, eb, arr, len(lists),
                                              C.byref(st), flags))
     return _stats_dict(st) if sync else None
+
+
+def stream_rates(ctx: Context, nbytes: int = 1 << 30, reps: int = 10):
+    """GB/s of the library's plain streaming kernels over two fresh buffers of `nbytes` bytes: read-only,
+    copy (bytes read + bytes written), write-only."""
+    dev = torch.device("cuda", ctx.device)
+    a = torch.zeros(nbytes // 4, dtype=torch.int32, device=dev)
+    b = torch.empty_like(a)
+    out = (C.c_float * 3)()
+    _check(load_library().spp_stream_rates(ctx._h, _ptr(a), _ptr(b), a.numel() * 4, int(reps), out))
+    return {"read_only": round(out[0], 1), "copy_read_plus_write": round(out[1], 1), "write_only": round(out[2], 1)}
 
 
 def gather_join(ctx: Context):

@@ -127,6 +127,70 @@ extern "C" int spp_ctx_totals(spp_ctx* c, int64_t* out, int reset) {
     return SPP_OK;
 }
 
+// ---- plain streaming kernels: what the part reaches by direction, for reading rooflines -------
+namespace spp {
+typedef uint32_t probe_vec __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(512) stream_read_kernel(const probe_vec* __restrict__ p, int64_t nvec, uint32_t* sink) {
+    const int64_t stride = (int64_t)gridDim.x * 512;
+    int64_t i = (int64_t)blockIdx.x * 512 + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        probe_vec v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(p + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < nvec; i += stride) { const probe_vec v = __builtin_nontemporal_load(p + i); acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+    if (acc == 0x9E3779B9u) *sink = acc;            // keeps the loads alive; practically never taken
+}
+// one vector per lane, one tile per workgroup: the shape that copies fastest on this part
+__global__ void __launch_bounds__(256) stream_copy_kernel(const probe_vec* __restrict__ s, probe_vec* __restrict__ d, int64_t nvec) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < nvec) __builtin_nontemporal_store(s[i], d + i);
+}
+__global__ void __launch_bounds__(256) stream_write_kernel(probe_vec* __restrict__ d, int64_t nvec) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const probe_vec v = {(uint32_t)i, 1u, 2u, 3u};
+    if (i < nvec) __builtin_nontemporal_store(v, d + i);
+}
+}  // namespace spp
+
+extern "C" int spp_stream_rates(spp_ctx* c, const void* d_a, void* d_b, int64_t bytes, int32_t reps, float* out_gbps) {
+    using namespace spp;
+    SPP_CHECK(c && d_a && d_b && out_gbps, SPP_E_ARG, "spp_stream_rates: null argument");
+    SPP_CHECK(bytes >= 16 && bytes % 16 == 0 && bytes / 16 / 256 < 0x7FFFFFFFll && reps >= 1 && reps <= 1000, SPP_E_ARG,
+              "spp_stream_rates: bytes = %lld (a multiple of 16), reps = %d (1 .. 1000)", (long long)bytes, reps);
+    SPP_CHECK((((uintptr_t)d_a | (uintptr_t)d_b) & 15) == 0, SPP_E_ARG, "spp_stream_rates: buffers must be 16-byte aligned");
+    SPP_HIP(hipSetDevice(c->device));
+    hipStream_t st = c->stream;
+    const int64_t nvec = bytes / 16;
+    const unsigned tiles = (unsigned)((nvec + 255) / 256);
+    const probe_vec* a = static_cast<const probe_vec*>(d_a);
+    probe_vec* b = static_cast<probe_vec*>(d_b);
+    uint32_t* sink = reinterpret_cast<uint32_t*>(c->totals + 15);       // an unused slot of the running sums
+    hipEvent_t e0 = c->take_event(), e1 = c->take_event();
+    SPP_CHECK(e0 && e1, SPP_E_HIP, "spp_stream_rates: no events");
+    for (int k = 0; k < 3; ++k) {
+        const double moved = (k == 1 ? 2.0 : 1.0) * (double)bytes * reps;
+        for (int r = -1; r < reps; ++r) {                                // one untimed pass first
+            if (r == 0) SPP_HIP(hipEventRecord(e0, st));
+            if (k == 0) stream_read_kernel<<<c->num_cu * 64, 512, 0, st>>>(a, nvec, sink);
+            else if (k == 1) stream_copy_kernel<<<tiles, 256, 0, st>>>(a, b, nvec);
+            else stream_write_kernel<<<tiles, 256, 0, st>>>(b, nvec);
+        }
+        SPP_HIP(hipEventRecord(e1, st));
+        SPP_HIP(hipEventSynchronize(e1));
+        float ms = 0.f;
+        SPP_HIP(hipEventElapsedTime(&ms, e0, e1));
+        out_gbps[k] = ms > 0.f ? (float)(moved / (ms * 1e-3) / 1e9) : 0.f;
+    }
+    c->ev_free.push_back(e0); c->ev_free.push_back(e1);
+    SPP_HIP(hipGetLastError());
+    return SPP_OK;
+}
+
 extern "C" int spp_vip_last_hops(spp_ctx* c, int32_t* pushed, int64_t* frontier_edges, int32_t L) {
     SPP_CHECK(c != nullptr && L >= 0 && L <= SPP_MAX_L, SPP_E_ARG, "spp_vip_last_hops: bad argument");
     for (int h = 0; h < L; ++h) {
