@@ -89,8 +89,9 @@ void spp_graph_destroy(spp_graph* g);
  *       p^[h](u) = 1 - prod over {v : u in adj(v)} of (1 - min(1, f_h/d(v)) * p^[h-1](v))    eq. (2)
  *       p(u)     = 1 - prod_{h=1..L} (1 - p^[h](u))                                         eq. (1)
  *     Products are carried as sums of log1p in fp64; results are stored as fp32.  The call waits
- *     for the device once per hop (it reads the size of the hop's frontier to choose between the
- *     push and the pull form).
+ *     for the device at most once per hop (it reads the size of the hop's frontier to choose
+ *     between the push and the pull form), and not at all after the first pulled hop: the hops
+ *     that follow are pulled without asking.
  *     d_p_total: fp32[N], required.  d_p_hop: fp32[L*N] (hop h at offset (h-1)*N) or NULL.
  *     flags: SPP_VIP_INCLUDE_HOP0, SPP_SYNC.  The graph must have been created with
  *     SPP_GRAPH_IN_LISTS (else SPP_E_ARG).  Vertices with d(v) = 0 contribute nothing. */

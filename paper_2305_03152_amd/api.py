@@ -6,8 +6,12 @@ library is missing or a call fails, an exception is raised.
 """
 from __future__ import annotations
 
+import atexit
 import ctypes as C
 import os
+import sys
+import threading
+import weakref
 from typing import List, Optional, Sequence
 
 import torch
@@ -163,8 +167,59 @@ def _fan(fanouts: Sequence[int]):
     return (C.c_int32 * L)(*[int(f) for f in fanouts]), L
 
 
-class Context:
+# Lifetime rules of the handles (Context, Graph, Cache, LocalStore):
+#  * every destroy call of the library is safe on its own: a graph, cache or local store keeps the
+#    device it lives on, not the context it was built with, so it may be closed before or after the
+#    context; closing twice, or closing a handle that was never created, does nothing;
+#  * Context.close() closes the handles built with it first (they would otherwise outlive their
+#    workspaces' owner and keep device memory until the collector finds them), then the context;
+#  * at interpreter exit every handle still alive is closed by one atexit hook, children before
+#    contexts, while the HIP runtime is still up; a __del__ that runs later, while the interpreter
+#    is finalizing, makes no library call at all (the runtime's own teardown may already have run);
+#  * a Context keeps a reference to the torch stream it was given, so the stream outlives it.
+_live_lock = threading.Lock()
+_live = weakref.WeakSet()           # every open handle object
+
+
+class _Handle:
+    """Shared close / __del__ behaviour of the four handle classes; `_destroy` names the C call."""
+    _destroy = ""
+    _h = None
+
+    def _opened(self):
+        with _live_lock:
+            _live.add(self)
+
+    def close(self):
+        h, self._h = self._h, C.c_void_p()
+        if h:
+            with _live_lock:
+                _live.discard(self)
+            getattr(load_library(), self._destroy)(h)
+
+    def __del__(self):
+        if sys.is_finalizing():         # the atexit hook has closed what was open; make no call into a runtime
+            return                      # that may be tearing down
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+@atexit.register
+def _close_all_handles():
+    with _live_lock:
+        objs = list(_live)
+    for o in sorted(objs, key=lambda o: isinstance(o, Context)):     # children first, contexts last
+        try:
+            o.close()
+        except Exception:
+            pass
+
+
+class Context(_Handle):
     """Owns the library context bound to a torch stream (default: the current stream)."""
+    _destroy = "spp_ctx_destroy"
 
     def __init__(self, device: int = 0, stream: Optional[torch.cuda.Stream] = None):
         lib = load_library()
@@ -173,8 +228,14 @@ class Context:
         torch.cuda.set_device(device)
         self.device = device
         self.stream = stream if stream is not None else torch.cuda.current_stream(device)
+        self._children = weakref.WeakSet()
         self._h = C.c_void_p()
         _check(lib.spp_ctx_create(C.byref(self._h), device, C.c_void_p(self.stream.cuda_stream)))
+        self._opened()
+
+    def _adopt(self, child):
+        self._children.add(child)
+        child._opened()
 
     def sync(self):
         _check(load_library().spp_ctx_sync(self._h))
@@ -206,19 +267,14 @@ class Context:
         return dict(zip(keys, list(buf)))
 
     def close(self):
-        if self._h:
-            load_library().spp_ctx_destroy(self._h)
-            self._h = C.c_void_p()
-
-    def __del__(self):
-        try:
-            self.close()
-        except Exception:
-            pass
+        for child in list(getattr(self, "_children", ())):
+            child.close()
+        super().close()
 
 
-class Graph:
+class Graph(_Handle):
     """G in CSR on the device: rowptr int64[N+1], col int32[M]; keeps the tensors alive."""
+    _destroy = "spp_graph_destroy"
 
     def __init__(self, ctx: Context, rowptr: torch.Tensor, col: torch.Tensor, in_lists: bool = False):
         self.ctx = ctx
@@ -230,17 +286,7 @@ class Graph:
         flags = SPP_GRAPH_IN_LISTS if in_lists else 0
         _check(load_library().spp_graph_create(ctx._h, self.N, self.M, _ptr(rowptr), _ptr(col), flags,
                                                C.byref(self._h)))
-
-    def close(self):
-        if self._h:
-            load_library().spp_graph_destroy(self._h)
-            self._h = C.c_void_p()
-
-    def __del__(self):
-        try:
-            self.close()
-        except Exception:
-            pass
+        ctx._adopt(self)
 
 
 def vip_propagate(ctx: Context, graph: Graph, T: torch.Tensor, B: int, fanouts: Sequence[int],
@@ -292,12 +338,14 @@ def vip_last_hops(ctx: Context, L: int):
     return [bool(x) for x in pushed], [int(x) for x in edges]
 
 
-class Cache:
+class Cache(_Handle):
     """Replica cache handle: ids in rank order (slot = rank) plus the library-owned table and rows."""
+    _destroy = "spp_cache_destroy"
 
     def __init__(self, ctx, handle, ids, N, lo, hi, remote_keepalive):
         self.ctx, self._h, self.ids, self.N, self.lo, self.hi = ctx, handle, ids, N, lo, hi
         self._keep = remote_keepalive
+        ctx._adopt(self)
 
     @property
     def n_cached(self) -> int:
@@ -311,17 +359,6 @@ class Cache:
         out = torch.empty_like(ids)
         _check(load_library().spp_cache_lookup(self.ctx._h, self._h, _ptr(ids), ids.numel(), _ptr(out)))
         return out
-
-    def close(self):
-        if self._h:
-            load_library().spp_cache_destroy(self._h)
-            self._h = C.c_void_p()
-
-    def __del__(self):
-        try:
-            self.close()
-        except Exception:
-            pass
 
 
 def _row_store(t: Optional[torch.Tensor], name: str):
@@ -350,12 +387,14 @@ def build_vip_cache(ctx: Context, score: torch.Tensor, lo: int, hi: int, K: int,
     return Cache(ctx, h, ids[:n_cached.value], N, lo, hi, remote)
 
 
-class LocalStore:
+class LocalStore(_Handle):
     """The partition's own rows split by a score order: a device-resident prefix plus the caller's host array."""
+    _destroy = "spp_local_store_destroy"
 
     def __init__(self, ctx, handle, n_device_rows, N, lo, hi, local_rows):
         self.ctx, self._h, self.n_device_rows, self.N, self.lo, self.hi = ctx, handle, n_device_rows, N, lo, hi
         self.local_rows = local_rows            # kept alive: the library reads it on the miss path
+        ctx._adopt(self)
 
     def set_limit(self, n_rows: int):
         _check(load_library().spp_local_store_set_limit(self._h, int(n_rows)))
@@ -365,17 +404,6 @@ class LocalStore:
         out = torch.empty_like(ids)
         _check(load_library().spp_local_store_rank(self.ctx._h, self._h, _ptr(ids), ids.numel(), _ptr(out)))
         return out
-
-    def close(self):
-        if self._h:
-            load_library().spp_local_store_destroy(self._h)
-            self._h = C.c_void_p()
-
-    def __del__(self):
-        try:
-            self.close()
-        except Exception:
-            pass
 
 
 def build_local_store(ctx: Context, score: torch.Tensor, lo: int, hi: int, beta: float,

@@ -54,7 +54,9 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
 
 extern "C" void spp_ctx_destroy(spp_ctx* c) {
     if (!c) return;
-    (void)hipSetDevice(c->device);
+    // Once the HIP runtime has shut down (a destroy that reaches here during process exit) nothing is
+    // left to release on the device, and its handles must not be touched.
+    if (hipSetDevice(c->device) != hipSuccess) { (void)hipGetLastError(); delete c; return; }
     (void)hipStreamSynchronize(c->stream);
     if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);

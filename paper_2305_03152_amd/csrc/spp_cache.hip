@@ -205,7 +205,7 @@ extern "C" int spp_build_vip_cache(spp_ctx* ctx, const float* d_score, int64_t N
 
 extern "C" void spp_cache_destroy(spp_cache* c) {
     if (!c) return;
-    (void)hipSetDevice(c->device);
+    if (hipSetDevice(c->device) != hipSuccess) { (void)hipGetLastError(); delete c; return; }   // runtime already shut down
     (void)hipDeviceSynchronize();      // a gather that still reads the cache may be in flight
     if (c->table) (void)hipFree(c->table);
     if (c->rows) (void)hipFree(c->rows);

@@ -338,12 +338,48 @@ int launch_dup(spp_ctx* ctx, const PendingGather& pg) {
 
 }  // namespace spp
 
-// The gather behind both entry points: the local shard is either d_local (all rows in device
-// memory) or a split store.
+// Device workspace of one gather call over `rows` virtual rows (padded): the counters and the
+// layout of the lists, one source descriptor per row, and the four row lists.
+namespace spp {
+struct GatherWs {
+    unsigned long long* counters;   // [8]
+    int64_t* off;                   // [kMaxLists + 1]
+    int64_t* cnt;                   // [kMaxLists + 1]
+    int64_t* minfo;                 // [4]
+    int64_t* desc;                  // [rows]
+    int64_t* hitlist;               // [rows]
+    int32_t* misslist;              // [rows]
+    int32_t* duplist;               // [rows]
+    int32_t* ordered;               // [rows]
+    int32_t* hcount;                // [rows / kListAlign]
+};
+constexpr size_t kWsHeadBytes = 2048;       // counters, off, cnt, minfo: (8 + 2 * (kMaxLists + 1) + 4) * 8 = 1136 bytes
+static_assert((8 + 2 * (kMaxLists + 1) + 4) * sizeof(int64_t) <= kWsHeadBytes, "the head of the workspace holds the counters and the layout");
+static GatherWs carve_ws(void* head, void* desc, void* lists, int64_t rows) {
+    GatherWs w;
+    w.counters = static_cast<unsigned long long*>(head);
+    w.off = static_cast<int64_t*>(head) + 8;
+    w.cnt = w.off + kMaxLists + 1;
+    w.minfo = w.cnt + kMaxLists + 1;
+    w.desc = static_cast<int64_t*>(desc);
+    w.hitlist = static_cast<int64_t*>(lists);
+    w.misslist = static_cast<int32_t*>(lists) + 2 * rows;
+    w.duplist = w.misslist + rows;
+    w.ordered = w.duplist + rows;
+    w.hcount = w.ordered + rows;
+    return w;
+}
+
+}  // namespace spp
+
+// The gather behind the entry points: the local shard is either d_local (all rows in device
+// memory) or a split store.  With `fixed` the workspace is the caller's (holding fixed_rows virtual
+// rows) and nothing is allocated; otherwise it comes from the context's grow-only buffers.
 static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_local, const spp_local_store* store,
                         int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
                         int32_t elem_bytes, const spp_gather_list* lists, int32_t n_lists,
-                        spp_gather_stats* stats, uint32_t flags) {
+                        spp_gather_stats* stats, uint32_t flags, const spp::GatherWs* fixed = nullptr,
+                        int64_t fixed_rows = 0) {
     using namespace spp;
     SPP_CHECK(ctx, SPP_E_ARG, "spp_gather_features: ctx is null");
     SPP_CHECK(n_lists >= 0 && n_lists <= SPP_MAX_GATHER_LISTS && (lists || n_lists == 0), SPP_E_ARG,
@@ -403,13 +439,15 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     // runs beside that miss copy.  The set used two calls ago is free: the call before joined that
     // gather before its own hit copy (if it had no rows and joined nothing, it is joined here).
     const int slot = ctx->gslot ^= 1;
-    if (ctx->pending.active && ctx->pending.slot == slot) SPP_TRY(spp_gather_join(ctx));
-    SPP_TRY(ctx->gcount[slot].reserve((8 + 2 * (kMaxLists + 1) + 4) * sizeof(int64_t)));
-    unsigned long long* counters = ctx->gcount[slot].as<unsigned long long>();
-    int64_t* off = ctx->gcount[slot].as<int64_t>() + 8;
-    int64_t* cnt = off + kMaxLists + 1;
-    int64_t* minfo = cnt + kMaxLists + 1;
-    a.t.off = off; a.t.cnt = cnt;
+    if (ctx->pending.active && (ctx->pending.slot == slot || fixed)) SPP_TRY(spp_gather_join(ctx));
+    if (fixed) {
+        SPP_CHECK(vbound <= fixed_rows, SPP_E_ARG, "gather: %lld rows (padded) exceed the fixed workspace of %lld",
+                  (long long)vbound, (long long)fixed_rows);
+        SPP_CHECK(n_lists <= 1 && !(flags & (SPP_STORE_ORDER | SPP_NO_JOIN)), SPP_E_ARG,
+                  "gather: a fixed workspace serves one list, without SPP_STORE_ORDER or SPP_NO_JOIN");
+    } else {
+        SPP_TRY(ctx->gcount[slot].reserve(kWsHeadBytes));
+    }
     // several lists make it worth claiming missed vertices: one list of a sampler's distinct ids
     // has nothing to share
     const int64_t n_remote = N - (hi - lo);
@@ -417,6 +455,7 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     const bool share_misses = dremote != nullptr && vbound > 0 && (n_lists > 1 || store_order);
     const int order_grid = 256;         // workgroups of the scan over the store's rows
     uint32_t mcap = 0;
+    SPP_CHECK(!fixed || (!store_order && !share_misses), SPP_E_ARG, "gather: a call that shares misses needs tables a fixed workspace does not hold");
     if (store_order) {
         SPP_TRY(ctx->gfirst.reserve((size_t)n_remote * sizeof(uint32_t)));
         SPP_TRY(ctx->partials.reserve((size_t)order_grid * sizeof(int) + 64));
@@ -424,11 +463,18 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         mcap = next_pow2((uint64_t)(2 * vbound > 1024 ? 2 * vbound : 1024));
         SPP_TRY(ctx->gtable.reserve((size_t)mcap * sizeof(uint64_t)));
     }
-    if (vbound > 0) {
+    if (vbound > 0 && !fixed) {
         SPP_TRY(ctx->srcdesc[slot].reserve((size_t)vbound * sizeof(int64_t)));
         // hit list (64-bit entries), miss list, copy list, misses in store order, hits per chunk
         SPP_TRY(ctx->misslist[slot].reserve((size_t)vbound * sizeof(int32_t) * 5 + (size_t)(vbound / kListAlign) * sizeof(int32_t)));
     }
+    const GatherWs ws = fixed ? *fixed
+                              : carve_ws(ctx->gcount[slot].ptr, ctx->srcdesc[slot].ptr, ctx->misslist[slot].ptr, vbound);
+    unsigned long long* counters = ws.counters;
+    int64_t* off = ws.off;
+    int64_t* cnt = ws.cnt;
+    int64_t* minfo = ws.minfo;
+    a.t.off = off; a.t.cnt = cnt;
     pro.n_remote = n_remote;
     gather_prologue_kernel<<<1, 64, 0, st>>>(pro, counters, off, cnt, minfo);
     if (vbound > 0) {
@@ -438,12 +484,12 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         a.limit = cache ? cache->limit : 0;
         a.local_rank = store ? store->rank : nullptr;
         a.local_limit = store ? store->limit : 0;
-        a.desc = ctx->srcdesc[slot].as<int64_t>(); a.counters = counters;
-        a.hitlist = ctx->misslist[slot].as<int64_t>();
-        a.misslist = ctx->misslist[slot].as<int32_t>() + 2 * vbound;
-        int32_t* duplist = a.misslist + vbound;
-        int32_t* ordered = duplist + vbound;
-        a.hcount = ordered + vbound;
+        a.desc = ws.desc; a.counters = counters;
+        a.hitlist = ws.hitlist;
+        a.misslist = ws.misslist;
+        int32_t* duplist = ws.duplist;
+        int32_t* ordered = ws.ordered;
+        a.hcount = ws.hcount;
         a.totals = reinterpret_cast<unsigned long long*>(ctx->totals);
         const int64_t cneed = vbound / kListAlign;
         const int cgrid = (int)(cneed < (int64_t)ctx->num_cu * 8 ? cneed : (int64_t)ctx->num_cu * 8);
@@ -626,3 +672,4 @@ extern "C" int spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats) {
               (long long)(hp[2] - hp[5]));
     return SPP_OK;
 }
+

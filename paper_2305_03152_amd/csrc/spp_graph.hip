@@ -201,7 +201,7 @@ extern "C" int spp_graph_create(spp_ctx* ctx, int64_t N, int64_t M, const int64_
 
 extern "C" void spp_graph_destroy(spp_graph* g) {
     if (!g) return;
-    (void)hipSetDevice(g->device);
+    if (hipSetDevice(g->device) != hipSuccess) { (void)hipGetLastError(); delete g; return; }   // runtime already shut down
     (void)hipDeviceSynchronize();      // work that still reads the row blocks may be in flight
     if (g->t_edge) (void)hipFree(g->t_edge);
     if (g->tile_first) (void)hipFree(g->tile_first);

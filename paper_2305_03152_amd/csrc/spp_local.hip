@@ -119,7 +119,7 @@ extern "C" int spp_build_local_store(spp_ctx* ctx, const float* d_score, int64_t
 
 extern "C" void spp_local_store_destroy(spp_local_store* s) {
     if (!s) return;
-    (void)hipSetDevice(s->device);
+    if (hipSetDevice(s->device) != hipSuccess) { (void)hipGetLastError(); delete s; return; }   // runtime already shut down
     (void)hipDeviceSynchronize();      // a gather that still reads the store may be in flight
     if (s->rank) (void)hipFree(s->rank);
     if (s->rows) (void)hipFree(s->rows);

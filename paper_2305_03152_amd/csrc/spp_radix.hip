@@ -1,6 +1,8 @@
 // Stable least-significant-digit radix sort of 64-bit keys, 8 bits per pass, used at set-up time:
-// to transpose the CSR into in-lists (sort packed (u << 32 | v) edge keys by u, which keeps v
-// ascending inside every in-list) and to rank cache candidates (Sec. 3.2).
+// to build the transposed edge structure (edge keys packed as (row block of u, source v, row of u
+// inside its block), sorted on the block and source bits, which groups the edges by destination
+// row block and orders them by source inside a block) and to rank cache candidates and local
+// vertices (Sec. 3.2).
 //
 // A tile is 4096 keys handled by one 256-thread workgroup; wavefront w owns the w-th quarter of
 // the tile and walks it in order, 64 keys at a time, so a key's stable rank among equal digits is

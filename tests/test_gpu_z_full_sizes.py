@@ -4,7 +4,9 @@ Each case generates the graph on the GPU (seeded), hands the same arrays to the 
 compares: fp32 VIP of every vertex (1e-5 relative), cache ids bit-exactly, three sampled
 minibatches bit-exactly (node ids, indptr, src per hop), and the gathered rows bit-exactly (against
 the oracle's gather where the pinned remote store fits the host, and in every case against the
-features regenerated from feat(seed, vertex, column)).
+features regenerated from feat(seed, vertex, column)) -- through the single-minibatch calls and
+through the batched calls (spp_sample_mfg_multi, spp_gather_features_multi with a deferred join,
+misses in list order and in store order), which is what the benchmark launches.
 
 Measured on the MI355X machine: Large 46 s, Wide 11 s (without the gather), Skew 63 s, most of it the
 single-threaded oracle and filling the pinned remote store.  SPP_FULL_SIZE=none skips them,
@@ -193,6 +195,7 @@ def _full_size(name):
     ids_ref_t = torch.from_numpy(ids_ref).to(dev)
     cache_rows = np.concatenate([_as_np(S.feature_rows(cfg, ids_ref_t[a:a + (1 << 16)]))
                                  for a in range(0, ids_ref.size, 1 << 16)])
+    wants = []
     for bi, ref in enumerate(mfgs):
         ids = torch.from_numpy(ref.node_ids).to(dev)
         out, st = spp.gather_features(ctx, cache, local, N, lo, hi, remote, ids)
@@ -203,6 +206,85 @@ def _full_size(name):
         regen = _as_np(S.feature_rows(cfg, ids))
         assert np.array_equal(got.view(np.uint8), regen.view(np.uint8))
         _say("gather batch", bi, "ok", st)
+        wants.append((want, counts))
+        del out, got, regen
+
+    # The same three minibatches through the batched calls, i.e. the launch configuration the benchmark
+    # times (one sampling call, one classification / hit copy / miss copy for all lists, the miss copy left
+    # running and joined afterwards), with the misses fetched in list order and in store order.
+    _say("batched calls: sample_mfg_multi + gather_features_multi (deferred join; list order, then store order)")
+    mb = [spp.MFGBuffers(dev, cfg.B, cfg.fanouts, N) for _ in batches]
+    spp.sample_mfg_multi(ctx, G, [(seeds, bi, mb[bi]) for bi, seeds in enumerate(batches)], cfg.fanouts, cfg.seed_sampler)
+    for bi, ref in enumerate(mfgs):
+        m = mb[bi]
+        assert m.n == ref.n and m.e == ref.e, (bi, m.n, ref.n)
+        assert np.array_equal(m.node_ids[:m.n[-1]].cpu().numpy(), ref.node_ids)
+        for h in range(cfg.L):
+            assert np.array_equal(m.indptr[h][:m.n[h] + 1].cpu().numpy(), ref.indptr[h])
+            assert np.array_equal(m.src[h][:m.e[h + 1]].cpu().numpy(), ref.src[h])
+    outs = [torch.empty((max(r.n[-1], 1), cfg.D), dtype=cfg.torch_dtype, device=dev) for r in mfgs]
+    for order in (False, True):
+        for o in outs:
+            o.zero_()
+        lists = [(mb[bi].node_ids, mfgs[bi].n[-1], mb[bi].n_final_device, outs[bi]) for bi in range(len(mfgs))]
+        spp.gather_features_multi(ctx, cache, local, N, lo, hi, remote, lists, sync=False, join=False, store_order=order)
+        spp.gather_join(ctx)
+        ctx.sync()
+        st = spp.gather_last_stats(ctx)
+        for bi, (want, counts) in enumerate(wants):
+            got = _as_np(outs[bi][:mfgs[bi].n[-1]])
+            assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (order, bi)
+        assert st["n_local"] == sum(c[0] for _, c in wants) and st["n_cache_hit"] == sum(c[1] for _, c in wants)
+        assert st["n_miss"] == sum(c[2] for _, c in wants)
+        _say("batched gather ok; store order", order, st)
+    del mb, outs, wants
     cache.close()
     G.close()
     ctx.close()
+
+
+def test_wide_rows_from_pinned_memory_beyond_4gib():
+    """Wide's row shape (768 fp16 = 1536 bytes) read from PINNED host memory at row offsets beyond 2^32
+    bytes: what the full-size Wide case cannot show within the default pinning limit (its 163 GB store
+    is then held in device memory).  A store of 3.0M rows (4.6 GB) is pinned; the ids asked for lie on
+    both sides of the 4 GiB offset, in the local range, and next to the ends of the store."""
+    import dataclasses
+    import paper_2305_03152_amd as spp
+    _release_memory()
+    cfg = dataclasses.replace(S.WIDE, N=3_400_000)
+    dev = torch.device("cuda:0")
+    lo, hi = cfg.bounds()
+    N = cfg.N
+    nrem = N - (hi - lo)
+    row_bytes = cfg.D * cfg.elem_bytes
+    first_beyond = (1 << 32) // row_bytes + 1                 # first remote row that starts beyond 4 GiB
+    assert nrem > first_beyond + 100_000
+    gen = torch.Generator().manual_seed(11)
+    rows = torch.cat([torch.randint(0, first_beyond, (6000,), generator=gen),
+                      torch.randint(first_beyond, nrem, (9000,), generator=gen),
+                      torch.tensor([0, first_beyond - 1, first_beyond, nrem - 1])]).unique()
+    ids_remote = torch.where(rows < lo, rows, rows + (hi - lo))             # remote row -> vertex id
+    ids_local = torch.randint(lo, hi, (3000,), generator=gen)
+    ids = torch.cat([ids_remote, ids_local])
+    ids = ids[torch.randperm(ids.numel(), generator=gen)].to(torch.int32)
+    _say(f"pinning {nrem * row_bytes / 1e9:.1f} GB; {ids.numel()} ids, {int((rows >= first_beyond).sum())} beyond 4 GiB")
+    remote = torch.zeros((nrem, cfg.D), dtype=cfg.torch_dtype).pin_memory()
+    ids_d = ids.to(dev)
+    need = ids_remote.to(dev)
+    remote[rows] = S.feature_rows(cfg, need).cpu()
+    local = S.feature_block(cfg, lo, hi, dev, chunk=1 << 16)
+    ctx = spp.Context(0)
+    for order in (False, True):
+        out = torch.zeros((ids.numel(), cfg.D), dtype=cfg.torch_dtype, device=dev)
+        st = spp.gather_features_multi(ctx, None, local, N, lo, hi, remote, [(ids_d, ids.numel(), None, out)],
+                                       store_order=order)
+        want, _, counts = oracle.gather(N, lo, hi, _as_np(local), None, None, _as_np(remote), ids.numpy())
+        got = _as_np(out)
+        assert np.array_equal(got.view(np.uint8), want.view(np.uint8))
+        assert (st["n_local"], st["n_cache_hit"], st["n_miss"]) == counts == (3000, 0, ids_remote.numel())
+        regen = _as_np(S.feature_rows(cfg, ids_d))
+        assert np.array_equal(got.view(np.uint8), regen.view(np.uint8))
+        _say("1536-byte rows over PCIe ok; store order", order, st)
+    ctx.close()
+    del remote, local
+    _release_memory()
