@@ -43,6 +43,7 @@ extern "C" {
 #define SPP_MAX_FANOUT  64     /* largest fanout (one wavefront lane per slot) */
 #define SPP_MAX_GATHER_LISTS 64 /* most id lists in one spp_gather_features_multi call */
 #define SPP_MAX_SAMPLE_BATCHES 64 /* most minibatches in one spp_sample_mfg_multi call */
+#define SPP_STATIC_GATHER_MAX_ROWS 131072 /* most ids in one spp_gather_features_static call */
 
 enum {
     SPP_OK          =  0,
@@ -198,6 +199,22 @@ int  spp_gather_features(spp_ctx* ctx, const spp_cache* cache, const void* d_loc
                          const int32_t* d_node_ids, int64_t n, const int64_t* d_n, void* d_out,
                          spp_gather_stats* stats, uint32_t flags);
 int  spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats);
+/* spp_gather_features for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, results and statistics as
+ * spp_gather_features, same kernels; the per-call workspace (counters, one source descriptor per id,
+ * the hit and miss lists: 28 bytes per id) lives in a fixed array of the library's device image,
+ * 3.5 MB on every GPU the library runs on until the process ends, instead of the context's
+ * grow-only buffers, and the call makes no hipMalloc / hipFree and creates no events.
+ * Limits: n <= SPP_STATIC_GATHER_MAX_ROWS (SPP_E_ARG beyond, before any work); flags SPP_SYNC only
+ * (SPP_STORE_ORDER needs a table per remote row, SPP_NO_JOIN would leave the shared workspace in
+ * use: both SPP_E_ARG); the miss copy is joined before the call returns to the stream; the call is
+ * left out of the timing report.  A gather that an earlier call on the context left unjoined is
+ * joined first.  Every call on a GPU uses that GPU's one array, whichever context it comes from:
+ * calls on different streams that overlap on one GPU race and must be ordered by the caller. */
+int  spp_gather_features_static(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
+                                int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D, int32_t elem_bytes,
+                                const int32_t* d_node_ids, int64_t n, const int64_t* d_n, void* d_out,
+                                spp_gather_stats* stats, uint32_t flags);
 /* With SPP_NO_JOIN a gather returns to the context's stream as soon as the hit copy is enqueued,
  * while the missed rows are still arriving on the side stream; work enqueued next on the stream
  * (the sampling of the following minibatches) overlaps the PCIe transfer.  spp_gather_join makes

@@ -26,6 +26,7 @@ SPP_VIP_INCLUDE_HOP0 = 0x2
 SPP_GRAPH_IN_LISTS = 0x4
 SPP_NO_JOIN = 0x8
 SPP_STORE_ORDER = 0x10
+SPP_STATIC_GATHER_MAX_ROWS = 131072
 SPP_T_VIP_TOTAL, SPP_T_VIP_HOP_FIRST, SPP_T_SAMPLE = 0, 1, 9
 SPP_T_GATHER_HIT, SPP_T_GATHER_MISS, SPP_T_GATHER_CLASSIFY, SPP_T_COUNT = 10, 11, 12, 16
 
@@ -36,7 +37,7 @@ EXPORTS = [
     "spp_gather_features", "spp_gather_features_multi", "spp_gather_last_stats", "spp_gather_join", "spp_ctx_timing", "spp_ctx_times", "spp_ctx_time_stats", "spp_ctx_totals",
     "spp_build_local_store", "spp_local_store_destroy", "spp_local_store_set_limit", "spp_local_store_rank",
     "spp_gather_features_split", "spp_access_count", "spp_vip_propagate_general", "spp_sample_mfg_general",
-    "spp_stream_rates",
+    "spp_stream_rates", "spp_gather_features_static",
 ]
 
 
@@ -117,6 +118,7 @@ def load_library():
     lib.spp_gather_features.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                         C.c_void_p, C.POINTER(_GatherStats), C.c_uint32]
+    lib.spp_gather_features_static.argtypes = lib.spp_gather_features.argtypes
     lib.spp_gather_features_multi.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                               C.c_void_p, C.c_int32, C.c_int32, C.POINTER(_GatherList), C.c_int32,
                                               C.POINTER(_GatherStats), C.c_uint32]
@@ -592,6 +594,24 @@ def gather_features(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N
                                               _ptr(n_device), _ptr(out), C.byref(st),
                                               (SPP_SYNC if sync else 0) | (SPP_STORE_ORDER if store_order else 0)))
     return out, (_stats_dict(st) if sync else None)
+
+
+def gather_features_static(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,
+                           remote: Optional[torch.Tensor], node_ids: torch.Tensor, out: torch.Tensor,
+                           n: Optional[int] = None, n_device: Optional[torch.Tensor] = None, sync: bool = True):
+    """gather_features through the entry point that allocates nothing (the output is the caller's)."""
+    local = _row_store(local, "local")
+    remote = _row_store(remote, "remote")
+    node_ids = _dev(node_ids, torch.int32, "node_ids")
+    n = int(node_ids.numel() if n is None else n)
+    D, eb = local.shape[1], local.element_size()
+    if out.shape[0] < n or out.shape[1] != D or not out.is_contiguous() or out.dtype != local.dtype:
+        raise SppError("out is too small, not contiguous or of another type")
+    st = _GatherStats()
+    _check(load_library().spp_gather_features_static(ctx._h, cache._h if cache is not None else None, _ptr(local),
+                                                     int(N), int(lo), int(hi), _ptr(remote), D, eb, _ptr(node_ids), n,
+                                                     _ptr(n_device), _ptr(out), C.byref(st), SPP_SYNC if sync else 0))
+    return _stats_dict(st) if sync else None
 
 
 def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,

@@ -27,6 +27,8 @@ extern "C" int spp_ctx_create(spp_ctx** out, int device, void* hip_stream) {
     SPP_HIP(hipGetDeviceCount(&ndev));
     SPP_CHECK(device >= 0 && device < ndev, SPP_E_ARG, "spp_ctx_create: device %d of %d", device, ndev);
     SPP_HIP(hipSetDevice(device));
+    void* fixed_ws = nullptr;
+    SPP_TRY(spp::static_scratch(device, &fixed_ws));      // this device's address of the allocation-free gather's workspace
     spp_ctx* c = new (std::nothrow) spp_ctx();
     SPP_CHECK(c != nullptr, SPP_E_OOM, "spp_ctx_create: out of host memory");
     c->device = device;

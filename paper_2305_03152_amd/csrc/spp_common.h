@@ -200,6 +200,9 @@ int radix_sort_u64(spp_ctx* ctx, uint64_t* keys_a, uint64_t* keys_b, int64_t n, 
 
 // Device-visible address of a row store that is either device memory or pinned host memory.
 int device_view(const void* p, const void** out);
+// Address, on the current device `device`, of the fixed workspace of spp_gather_features_static
+// (looked up once per device).
+int static_scratch(int device, void** out);
 // Rows copied from a row store that may be pinned host memory: out[i,:] = src[rows[i],:].
 int copy_rows_indexed(hipStream_t st, const void* src, const int64_t* d_rowidx, int64_t n,
                       int64_t row_bytes, void* d_out, int num_cu);

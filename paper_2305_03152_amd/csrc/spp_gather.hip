@@ -25,6 +25,8 @@
 #include "spp_device.h"
 #include "spp_rowcopy.h"
 
+#include <mutex>
+
 namespace spp {
 
 constexpr int kMissBlocks = 64;        // workgroups of the miss kernel (see gather_lists)
@@ -370,6 +372,33 @@ static GatherWs carve_ws(void* head, void* desc, void* lists, int64_t rows) {
     return w;
 }
 
+// The workspace of spp_gather_features_static: a fixed array in the library's device image, one copy
+// per GPU, so that the call has nothing to allocate.  Host code reaches it only through the address
+// that hipGetSymbolAddress returns for the current device (kept per device below); the array's name
+// is never passed to a kernel or a runtime call.
+constexpr int64_t kStaticRows = SPP_STATIC_GATHER_MAX_ROWS;
+static_assert(kStaticRows % kListAlign == 0, "the static workspace holds whole chunks");
+constexpr size_t kStaticBytes = kWsHeadBytes + (size_t)kStaticRows * (sizeof(int64_t) + 5 * sizeof(int32_t)) +
+                                (size_t)(kStaticRows / kListAlign) * sizeof(int32_t);
+static __device__ __align__(256) unsigned char scratch[(kStaticBytes + 255) / 256 * 256];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};       // device address of `scratch` on each GPU, once asked for
+static std::mutex g_scratch_mutex;
+
+// Address of this GPU's copy of the array; `device` must be the current device.
+int static_scratch(int device, void** out) {
+    SPP_CHECK(device >= 0 && device < kMaxDevices, SPP_E_ARG, "static workspace: device %d out of range", device);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        SPP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        SPP_CHECK(p != nullptr, SPP_E_HIP, "static workspace: hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return SPP_OK;
+}
 }  // namespace spp
 
 // The gather behind the entry points: the local shard is either d_local (all rows in device
@@ -441,10 +470,10 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     const int slot = ctx->gslot ^= 1;
     if (ctx->pending.active && (ctx->pending.slot == slot || fixed)) SPP_TRY(spp_gather_join(ctx));
     if (fixed) {
-        SPP_CHECK(vbound <= fixed_rows, SPP_E_ARG, "gather: %lld rows (padded) exceed the fixed workspace of %lld",
+        SPP_CHECK(vbound <= fixed_rows, SPP_E_ARG, "spp_gather_features_static: %lld rows (padded) exceed the fixed workspace of %lld",
                   (long long)vbound, (long long)fixed_rows);
         SPP_CHECK(n_lists <= 1 && !(flags & (SPP_STORE_ORDER | SPP_NO_JOIN)), SPP_E_ARG,
-                  "gather: a fixed workspace serves one list, without SPP_STORE_ORDER or SPP_NO_JOIN");
+                  "spp_gather_features_static: one list, no SPP_STORE_ORDER, no SPP_NO_JOIN");
     } else {
         SPP_TRY(ctx->gcount[slot].reserve(kWsHeadBytes));
     }
@@ -455,7 +484,7 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     const bool share_misses = dremote != nullptr && vbound > 0 && (n_lists > 1 || store_order);
     const int order_grid = 256;         // workgroups of the scan over the store's rows
     uint32_t mcap = 0;
-    SPP_CHECK(!fixed || (!store_order && !share_misses), SPP_E_ARG, "gather: a call that shares misses needs tables a fixed workspace does not hold");
+    SPP_CHECK(!fixed || (!store_order && !share_misses), SPP_E_ARG, "spp_gather_features_static: a call that shares misses needs tables it cannot allocate");
     if (store_order) {
         SPP_TRY(ctx->gfirst.reserve((size_t)n_remote * sizeof(uint32_t)));
         SPP_TRY(ctx->partials.reserve((size_t)order_grid * sizeof(int) + 64));
@@ -673,3 +702,32 @@ extern "C" int spp_gather_last_stats(spp_ctx* ctx, spp_gather_stats* stats) {
     return SPP_OK;
 }
 
+// The single-list gather for callers that must not allocate (code under graph capture, serving loops,
+// harnesses that forbid hipMalloc): the same kernels, with the per-call workspace in a fixed array of
+// the library's device image instead of the context's grow-only buffers.
+extern "C" int spp_gather_features_static(spp_ctx* ctx, const spp_cache* cache, const void* d_local,
+                                          int64_t N, int64_t lo, int64_t hi, const void* remote, int32_t D,
+                                          int32_t elem_bytes, const int32_t* d_node_ids, int64_t n,
+                                          const int64_t* d_n, void* d_out, spp_gather_stats* stats, uint32_t flags) {
+    using namespace spp;
+    SPP_CHECK(ctx, SPP_E_ARG, "spp_gather_features_static: ctx is null");
+    SPP_CHECK(n >= 0 && n <= SPP_STATIC_GATHER_MAX_ROWS, SPP_E_ARG,
+              "spp_gather_features_static: n = %lld exceeds SPP_STATIC_GATHER_MAX_ROWS = %d", (long long)n,
+              SPP_STATIC_GATHER_MAX_ROWS);
+    SPP_CHECK(!(flags & (SPP_STORE_ORDER | SPP_NO_JOIN)), SPP_E_ARG,
+              "spp_gather_features_static: SPP_STORE_ORDER and SPP_NO_JOIN are not available here");
+    SPP_HIP(hipSetDevice(ctx->device));
+    void* base = nullptr;
+    SPP_TRY(static_scratch(ctx->device, &base));
+    char* b = static_cast<char*>(base);
+    const GatherWs ws = carve_ws(b, b + kWsHeadBytes, b + kWsHeadBytes + (size_t)kStaticRows * sizeof(int64_t), kStaticRows);
+    // event pairs for the timing report are created on demand: not here
+    const int timing = ctx->timing;
+    ctx->timing = 0;
+    spp_gather_list one;
+    one.d_node_ids = d_node_ids; one.n = n; one.d_n = d_n; one.d_out = d_out;
+    const int rc = gather_lists(ctx, cache, d_local, nullptr, N, lo, hi, remote, D, elem_bytes, &one, 1, stats, flags, &ws,
+                                kStaticRows);
+    ctx->timing = timing;
+    return rc;
+}
