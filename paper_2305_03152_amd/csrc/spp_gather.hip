@@ -541,10 +541,11 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         const int V = pick_vec(row_bytes, addr_bits);
         const uint32_t vpr = (uint32_t)(row_bytes / V);
         const int64_t vecs = vbound * vpr;
-        // hit copy: many small workgroups (512 vectors each, at most 64 per CU in the grid) let the
-        // dispatcher balance the copy around CUs that are busy with slow host-memory loads
-        const int64_t hneed = vbound / kListAlign * kHitSlices;
-        const int grid = (int)(hneed < (int64_t)ctx->num_cu * 64 ? hneed : (int64_t)ctx->num_cu * 64);
+        // hit copy: many small work items (one tile of 1024 vectors each; at most 256 workgroups per CU in
+        // the grid, which then take several tiles each) let the dispatcher balance the copy
+        const uint32_t tiles_per_chunk = (uint32_t)((kListAlign * vpr + kBlock * kHitUnroll - 1) / (kBlock * kHitUnroll));
+        const int64_t hneed = vbound / kListAlign * tiles_per_chunk;
+        const int grid = (int)(hneed < (int64_t)ctx->num_cu * 256 ? hneed : (int64_t)ctx->num_cu * 256);
         // The miss kernel is kept to 64 workgroups of 256 threads: they saturate the PCIe link (32
         // workgroups of 512 threads or 16 of 1024 reach 95 % of their rate, 64 of 512 less).  A CU
         // that hosts host-memory loads serves every other wavefront on it slowly, so each of these
@@ -599,10 +600,10 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
             const char* loc = static_cast<const char*>(d_local);
             const char* cr = static_cast<const char*>(crow);
             switch (V) {
-                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr); break;
-                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr); break;
-                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr); break;
-                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr); break;
+                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
+                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
+                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
+                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
             }
         };
         // Order of the copies.  The stream waits for the miss copy of the call before (its fetched

@@ -39,7 +39,7 @@ __device__ __forceinline__ void store_stream(void* p, typename VecOf<V>::type v)
 }
 
 constexpr int kCopyUnroll = 4;          // vectors in flight per lane, indexed (PCIe) copy
-constexpr int kHitUnroll = 2;           // vectors in flight per lane, hit copy
+constexpr int kHitUnroll = 4;           // vectors in flight per lane, hit copy
 constexpr int64_t kListAlign = 2048;    // every list starts at a multiple of this in the virtual row space
 
 // The offsets and counts are read many times by every workgroup: a copy in LDS keeps the search for
@@ -71,58 +71,62 @@ __device__ __forceinline__ int list_of(const ListLds& s, int n_lists, int64_t r)
 // order in which workgroups finished, the same copy was 5 to 9 % slower).
 // A hit-list entry names the output row and its source in one 64-bit word (bit 63: cache instead
 // of local shard, bits 32-62: row in that store, bits 26-31: list, bits 0-25: row in the list's
-// output), so a lane reaches the source row with one dependent load.  A chunk's vectors are cut
-// into kHitSlices equal parts, one workgroup pass each, so every lane copies (no lane idles on a
-// row that missed) and the work items stay small enough for the dispatcher to balance.
+// output), so a lane reaches the source row with one dependent load.  Only hits are walked, so
+// every lane copies (no lane idles on a row that missed).
 // Source rows are read with ordinary loads (hot rows of the shard and the cache stay in L2 and
 // the Infinity Cache across batches), the output is written with streaming stores (it is not read
 // again by this path).
 constexpr int kHitRowBits = 26;         // rows of one list that a hit-list entry can name
-constexpr int kHitSlices = 16;          // parts a chunk's copy is cut into
 static_assert(SPP_MAX_GATHER_LISTS <= (1 << (32 - kHitRowBits)), "the list index has 32 - kHitRowBits bits");
 __device__ __forceinline__ int64_t make_hit(bool from_cache, int64_t src_row, int list, int64_t row_in_list) {
     return (int64_t)(((uint64_t)(from_cache ? 1 : 0) << 63) | ((uint64_t)src_row << 32) |
                      ((uint64_t)list << kHitRowBits) | (uint64_t)row_in_list);
 }
+// A work item is one tile of kBlock * U consecutive vectors of one chunk's hits (every lane U
+// vectors, all loads issued before the first store), so items are equal whatever the chunk holds,
+// except the last tile of a chunk; a chunk has tiles_per_chunk of them (enough for 2048 hits), and
+// tiles beyond the chunk's hits are skipped.  (Cutting every chunk into 16 slices of hits/16 rows
+// instead left the last round of most slices two thirds full: 5.2 TB/s on 256-byte rows of a
+// 3.5 GB shard where tiles reach 5.5 on the same box.  One, two, four or eight vectors per lane:
+// four is best by 1 to 4 %; non-temporal loads of the source rows cost 4 % when the shard is in
+// HBM and 25 % when it fits the Infinity Cache.)
 template <int V, int U = kHitUnroll>
 __global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __restrict__ hitlist,
                                                             const int32_t* __restrict__ hcount, ListTable t,
                                                             const char* __restrict__ local,
-                                                            const char* __restrict__ cache, uint32_t vpr) {
+                                                            const char* __restrict__ cache, uint32_t vpr,
+                                                            uint32_t tiles_per_chunk) {
     typedef typename VecOf<V>::type vec_t;
-    const int64_t items = t.off[t.n_lists] / kListAlign * kHitSlices;     // chunks in use x slices
+    const int64_t items = t.off[t.n_lists] / kListAlign * tiles_per_chunk;     // chunks in use x tiles
     for (int64_t w = blockIdx.x; w < items; w += gridDim.x) {
-        const int64_t chunk = w / kHitSlices;
-        const uint32_t slice = (uint32_t)(w % kHitSlices);
+        const int64_t chunk = w / tiles_per_chunk;
+        const uint32_t base = (uint32_t)(w - chunk * tiles_per_chunk) * (uint32_t)(kBlock * U);
         const uint32_t nv = (uint32_t)hcount[chunk] * vpr;                 // at most 2048 rows: fits 32 bits
-        const uint32_t vbeg = (uint32_t)((uint64_t)nv * slice / kHitSlices);
-        const uint32_t vend = (uint32_t)((uint64_t)nv * (slice + 1) / kHitSlices);
+        if (base >= nv) continue;
         const int64_t* __restrict__ hl = hitlist + chunk * kListAlign;
-        for (uint32_t base = vbeg; base < vend; base += kBlock * U) {
-            vec_t v[U];
-            char* dst[U];
-            bool ok[U];
+        vec_t v[U];
+        char* dst[U];
+        bool ok[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t c = base + (uint32_t)u * kBlock + threadIdx.x;
-                ok[u] = c < vend;
-                if (ok[u]) {
-                    const uint32_t m = c / vpr;
-                    const uint32_t k = c - m * vpr;
-                    const uint64_t h = (uint64_t)hl[m];
-                    const uint64_t srow = (h >> 32) & 0x7FFFFFFFull;
-                    const char* src = ((h >> 63) ? cache : local) + (srow * vpr + k) * (uint64_t)V;
-                    v[u] = *reinterpret_cast<const vec_t*>(src);
-                    const uint32_t lo = (uint32_t)h;
-                    // a chunk belongs to one list: its output pointer is the same for all lanes
-                    char* out = t.out[__builtin_amdgcn_readfirstlane((int)(lo >> kHitRowBits))];
-                    dst[u] = out + ((uint64_t)(lo & ((1u << kHitRowBits) - 1u)) * vpr + k) * (uint64_t)V;
-                }
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = base + (uint32_t)u * kBlock + threadIdx.x;
+            ok[u] = c < nv;
+            if (ok[u]) {
+                const uint32_t m = c / vpr;
+                const uint32_t k = c - m * vpr;
+                const uint64_t h = (uint64_t)hl[m];
+                const uint64_t srow = (h >> 32) & 0x7FFFFFFFull;
+                const char* src = ((h >> 63) ? cache : local) + (srow * vpr + k) * (uint64_t)V;
+                v[u] = *reinterpret_cast<const vec_t*>(src);
+                const uint32_t lo = (uint32_t)h;
+                // a chunk belongs to one list: its output pointer is the same for all lanes
+                char* out = t.out[__builtin_amdgcn_readfirstlane((int)(lo >> kHitRowBits))];
+                dst[u] = out + ((uint64_t)(lo & ((1u << kHitRowBits) - 1u)) * vpr + k) * (uint64_t)V;
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (ok[u]) store_stream<V>(dst[u], v[u]);
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) store_stream<V>(dst[u], v[u]);
     }
 }
 
