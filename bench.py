@@ -252,7 +252,7 @@ def setup_workload(args, cfg, spp, S, torch, dev, ctx, rows=True, remote_on_devi
     del T_all
     log(f"{cfg.name}: graph N={g.N} M={g.M} |T_k|={Tk.numel()} ({time.time() - t:.1f}s)")
     t = time.time()
-    G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True)
+    G = spp.Graph(ctx, g.rowptr, g.col, in_lists=True, chunked=args.vip_layout == "chunked")
     t_inlists = time.time() - t
     nrem = cfg.N - (hi - lo)
     local = remote = None
@@ -615,6 +615,9 @@ def main():
     ap.add_argument("--second", default="auto",
                     help="a second workload reported as a block of the same JSON line (auto: mid beside large; none)")
     ap.add_argument("--vip-reps", type=int, default=10)
+    ap.add_argument("--vip-layout", default="auto", choices=["auto", "chunked"],
+                    help="transposed edges: auto = row blocks up to 2^23 vertices, the chunked two-pass layout above; "
+                         "chunked = the chunked layout whatever the size")
     ap.add_argument("--pipeline", type=int, default=1,
                     help="lanes: contexts (each with its own stream and buffers) used round-robin")
     ap.add_argument("--group", type=int, default=64,

@@ -58,6 +58,9 @@ enum {
 #define SPP_VIP_INCLUDE_HOP0  0x2u   /* also multiply (1 - p^[0]) into eq. (1); default: as printed, h = 1..L */
 #define SPP_GRAPH_IN_LISTS    0x4u   /* spp_graph_create: also build the transposed edge structure (who can sample u)
                                         that vip_propagate needs: 4 bytes per edge of device memory */
+#define SPP_GRAPH_CHUNKED     0x20u  /* spp_graph_create, with SPP_GRAPH_IN_LISTS: build the layout for graphs whose
+                                        per-vertex vectors exceed the caches (two passes per dense hop) whatever N is;
+                                        by default graphs above 2^23 vertices get it */
 #define SPP_NO_JOIN           0x8u   /* gather: leave the miss copy running on the side stream; see spp_gather_join */
 #define SPP_STORE_ORDER       0x10u  /* gather: fetch the call's missed remote rows in the order of the remote store;
                                         see spp_gather_features_multi */

@@ -26,6 +26,7 @@ SPP_VIP_INCLUDE_HOP0 = 0x2
 SPP_GRAPH_IN_LISTS = 0x4
 SPP_NO_JOIN = 0x8
 SPP_STORE_ORDER = 0x10
+SPP_GRAPH_CHUNKED = 0x20
 SPP_STATIC_GATHER_MAX_ROWS = 131072
 SPP_T_VIP_TOTAL, SPP_T_VIP_HOP_FIRST, SPP_T_SAMPLE = 0, 1, 9
 SPP_T_GATHER_HIT, SPP_T_GATHER_MISS, SPP_T_GATHER_CLASSIFY, SPP_T_COUNT = 10, 11, 12, 16
@@ -278,14 +279,17 @@ class Graph(_Handle):
     """G in CSR on the device: rowptr int64[N+1], col int32[M]; keeps the tensors alive."""
     _destroy = "spp_graph_destroy"
 
-    def __init__(self, ctx: Context, rowptr: torch.Tensor, col: torch.Tensor, in_lists: bool = False):
+    def __init__(self, ctx: Context, rowptr: torch.Tensor, col: torch.Tensor, in_lists: bool = False,
+                 chunked: bool = False):
+        """in_lists: also build the transposed structure that vip_propagate needs; chunked: in the layout for
+        graphs whose per-vertex vectors exceed the caches, whatever N is (default: above 2^23 vertices)."""
         self.ctx = ctx
         self.rowptr = _dev(rowptr, torch.int64, "rowptr")
         self.col = _dev(col, torch.int32, "col")
         self.N = rowptr.numel() - 1
         self.M = col.numel()
         self._h = C.c_void_p()
-        flags = SPP_GRAPH_IN_LISTS if in_lists else 0
+        flags = (SPP_GRAPH_IN_LISTS if in_lists else 0) | (SPP_GRAPH_CHUNKED if in_lists and chunked else 0)
         _check(load_library().spp_graph_create(ctx._h, self.N, self.M, _ptr(rowptr), _ptr(col), flags,
                                                C.byref(self._h)))
         ctx._adopt(self)

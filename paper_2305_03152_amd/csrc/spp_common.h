@@ -117,9 +117,11 @@ struct spp_ctx {
     int64_t*    totals = nullptr;       // device int64[16], running sums since the last reset (see spp_ctx_totals)
     // vip workspaces
     spp::DevBuf y0, y1, tot, acc, frontier;
+    spp::DevBuf xvals;                  // dense hops over the chunked layout: y[source] of every entry
     spp::DevBuf bins;                   // general propagation: per row block the (row, weight) entries of a hop, and the fill counts
     int         bin_lds_set = 0, sum_lds_set = 0;   // dynamic LDS bytes its two kernels have been allowed
     int         tile_lds_set = 0;       // dynamic LDS bytes the dense-hop kernel has been allowed on this device
+    int         x_lds_set = 0;          // the two kernels of the chunked layout have been allowed theirs
     int         vip_pushed[SPP_MAX_L] = {};          // last vip_propagate: hop done in push form?
     int64_t     vip_frontier_edges[SPP_MAX_L] = {};  // last vip_propagate: out-edges of each hop's frontier
     // timing: while enabled every timed piece of device work gets its own pair of events
@@ -151,6 +153,20 @@ struct spp_graph {
     int       tile_rbits = 0;
     int64_t   nrb = 0;                  // row blocks
     int       nch = 0;                  // source chunks (of 2^kTileSrcLoBits vertices)
+    int64_t*  block_first = nullptr;    // int64[nrb + 1]: edges that end in row blocks before b (either layout)
+    // The second layout of the same edges, built instead of the first for graphs whose per-vertex
+    // vector is too large to be gathered from (see spp_vip.hip): the edges sorted by (chunk of 2^15
+    // sources, row block, source), every (chunk, row block) piece padded to a multiple of four
+    // entries, 2 + 2 bytes per entry.  A dense hop first writes y[source] for every entry in this
+    // order (a chunk of y sits in LDS), then every row block adds up its pieces.
+    bool      has_x = false;
+    uint16_t* x_src = nullptr;          // uint16[x_entries]: source inside its chunk; bit 15: padding
+    uint16_t* x_row = nullptr;          // uint16[x_entries]: row inside its block
+    int64_t*  x_chunk_first = nullptr;  // int64[x_nch + 1]: first entry of chunk c
+    uint32_t* x_start = nullptr;        // uint32[nrb * x_nch]: piece (b, c): its first vector (four entries) in the arrays
+    uint32_t* x_prefix = nullptr;       // uint32[nrb * (x_nch + 1)]: vectors of row block b in chunks before c
+    int64_t   x_entries = 0;
+    int       x_nch = 0;
 };
 
 struct spp_cache {

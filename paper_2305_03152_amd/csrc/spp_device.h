@@ -367,6 +367,14 @@ __device__ __forceinline__ uint32_t tile_source(uint32_t word, int chunk) {
     return ((uint32_t)chunk << kTileSrcLoBits) | (word >> kTileRowBits);
 }
 
+// The chunked layout of the same edges: chunks of 2^kXSrcBits sources, row blocks of 2^kTileRowBits
+// rows; an entry is a 16-bit source inside its chunk (kXPad marks padding) and a 16-bit row inside
+// its block.
+constexpr int kXSrcBits = 15;
+constexpr uint32_t kXPad = 0x8000u;
+constexpr int kXGroup = 2048;            // pieces of a row block whose table entries sit in LDS at a time
+constexpr int64_t kChunkedAboveVertices = (int64_t)1 << 23;   // graphs with more vertices get the chunked layout
+
 // ---------------------------------------------------------------------------------------------
 // Philox-4x32 with 10 rounds (Salmon et al., SC'11), from the published round function:
 // two 32x32->64 multiplies per round, key bumped by the Weyl constants between rounds.

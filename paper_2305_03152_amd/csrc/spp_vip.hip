@@ -273,6 +273,186 @@ __global__ void __launch_bounds__(kBlock) vip_tile_finish_kernel(VipHop a, const
     if (!a.last) write_frontier_stat(a.stat, verts, edges);
 }
 
+// ---- dense hops over the chunked layout -------------------------------------------------------
+// When y does not stay in the caches (10^8 vertices: 444 MB), the gathers of the kernel above fetch
+// a 128-byte line per edge and the hop runs at a tenth of the edge stream's rate.  The chunked
+// layout trades bytes for order.  First pass: one workgroup per chunk of 2^15 sources keeps the
+// chunk's y in LDS (128 KB) and writes y[source] for every entry of the chunk, in entry order:
+// 2 bytes read and 4 written per entry, all of it streamed.  Second pass: one workgroup per row
+// block keeps the block's fp64 sums in LDS and adds up the block's pieces, one from every chunk
+// (4 + 2 bytes read per entry in runs of about a hundred entries, found through two tables that are
+// staged in LDS 2048 pieces at a time), then finishes the block's vertices itself.  12 bytes per
+// entry instead of 4, but no line is fetched for four of its bytes.
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kXBlock = 1024;
+constexpr int kXUnroll = 4;              // vectors (four entries) per lane and round of the first pass (2, 4, 8: the same time)
+
+__global__ void __launch_bounds__(kXBlock) vip_expand_kernel(const uint16_t* __restrict__ x_src,
+                                                             const int64_t* __restrict__ chunk_first, int nch, int64_t N,
+                                                             const float* __restrict__ y, float* __restrict__ vals) {
+    extern __shared__ float ych[];
+    constexpr int C = 1 << kXSrcBits;
+    for (int c = blockIdx.x; c < nch; c += gridDim.x) {
+        const int64_t v0 = (int64_t)c << kXSrcBits;
+        int any = 0;
+        if (v0 + C <= N) {               // y is 16-byte aligned and v0 a multiple of C
+            const f32x4* __restrict__ y4 = reinterpret_cast<const f32x4*>(y + v0);
+            f32x4 t[C / 4 / kXBlock];
+#pragma unroll
+            for (int k = 0; k < C / 4 / kXBlock; ++k) t[k] = y4[threadIdx.x + k * kXBlock];
+#pragma unroll
+            for (int k = 0; k < C / 4 / kXBlock; ++k) {
+                reinterpret_cast<f32x4*>(ych)[threadIdx.x + k * kXBlock] = t[k];
+                any |= (t[k].x != 0.0f) | (t[k].y != 0.0f) | (t[k].z != 0.0f) | (t[k].w != 0.0f);
+            }
+        } else {
+            for (int i = threadIdx.x; i < C; i += kXBlock) {
+                const float t = v0 + i < N ? y[v0 + i] : 0.0f;
+                ych[i] = t;
+                any |= t != 0.0f;
+            }
+        }
+        if (threadIdx.x == 0) ych[C] = 0.0f;     // what a padding entry (source kXPad = C) looks up
+        any = __syncthreads_or(any);
+        const int64_t q0 = chunk_first[c] >> 2, q1 = chunk_first[c + 1] >> 2;
+        const u16x4* __restrict__ sv = reinterpret_cast<const u16x4*>(x_src);
+        f32x4* __restrict__ out = reinterpret_cast<f32x4*>(vals);
+        if (!any) {                      // nothing of this chunk is in the frontier: zeros, without reading the entries
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            for (int64_t q = q0 + threadIdx.x; q < q1; q += kXBlock) __builtin_nontemporal_store(z, out + q);
+        } else {
+            // the next round's entries are in flight while this round's values are looked up and stored
+            constexpr int64_t kRound = (int64_t)kXBlock * kXUnroll;
+            u16x4 s[kXUnroll];
+            int64_t q = q0 + threadIdx.x;
+#pragma unroll
+            for (int u = 0; u < kXUnroll; ++u)
+                if (q + u * kXBlock < q1) s[u] = __builtin_nontemporal_load(sv + q + u * kXBlock);
+            for (; q < q1; q += kRound) {
+                u16x4 n[kXUnroll];
+#pragma unroll
+                for (int u = 0; u < kXUnroll; ++u)
+                    if (q + kRound + u * kXBlock < q1) n[u] = __builtin_nontemporal_load(sv + q + kRound + u * kXBlock);
+#pragma unroll
+                for (int u = 0; u < kXUnroll; ++u)
+                    if (q + u * kXBlock < q1) {
+                        f32x4 w;
+                        w.x = ych[s[u].x];
+                        w.y = ych[s[u].y];
+                        w.z = ych[s[u].z];
+                        w.w = ych[s[u].w];
+                        __builtin_nontemporal_store(w, out + q + u * kXBlock);
+                    }
+#pragma unroll
+                for (int u = 0; u < kXUnroll; ++u) s[u] = n[u];
+            }
+        }
+        __syncthreads();                 // the next chunk overwrites ych
+    }
+}
+
+// Second pass.  The block's vectors form one sequence (vector q of the block: the pieces of chunks
+// 0, 1, ... end to end); the j-th of `parts` equal shares of it is walked by this workgroup, a
+// group of kXGroup pieces at a time: prefix[k] = first vector of piece k in that sequence, start[k]
+// = where the piece lies in the arrays.  With one share per block the workgroup finishes the
+// block's vertices itself (p^[h], running total, next hop's y); otherwise it leaves its sums in
+// part[j] for vip_tile_finish_kernel.
+__global__ void __launch_bounds__(kXBlock) vip_reduce_kernel(const float* __restrict__ vals,
+                                                             const uint16_t* __restrict__ x_row,
+                                                             const uint32_t* __restrict__ x_start,
+                                                             const uint32_t* __restrict__ x_prefix, int nch, int parts,
+                                                             int64_t N, double* __restrict__ part, int64_t part_stride,
+                                                             VipHop a) {
+    extern __shared__ double acc[];
+    constexpr int R = 1 << kTileRowBits;
+    uint32_t* prefix = reinterpret_cast<uint32_t*>(acc + R);     // [kXGroup + 1]
+    uint32_t* start = prefix + kXGroup + 1;                      // [kXGroup]
+    const int64_t nrb = gridDim.x / parts;
+    const int64_t rb = blockIdx.x % nrb;
+    const int j = (int)(blockIdx.x / nrb);
+    for (int i = threadIdx.x; i < R; i += kXBlock) acc[i] = 0.0;
+    const uint32_t* __restrict__ pre_b = x_prefix + rb * (nch + 1);
+    const uint32_t* __restrict__ sta_b = x_start + rb * nch;
+    const uint32_t nvec = pre_b[nch];
+    const uint32_t beg = (uint32_t)((uint64_t)nvec * j / parts), end = (uint32_t)((uint64_t)nvec * (j + 1) / parts);
+    const f32x4* __restrict__ vv = reinterpret_cast<const f32x4*>(vals);
+    const u16x4* __restrict__ rv = reinterpret_cast<const u16x4*>(x_row);
+    for (int g0 = 0; g0 < nch; g0 += kXGroup) {
+        const int gn = nch - g0 < kXGroup ? nch - g0 : kXGroup;
+        __syncthreads();                 // the tables of the group before are no longer read; acc is cleared
+        for (int k = threadIdx.x; k <= gn; k += kXBlock) prefix[k] = pre_b[g0 + k];
+        for (int k = threadIdx.x; k < gn; k += kXBlock) start[k] = sta_b[g0 + k];
+        __syncthreads();
+        const uint32_t lo = prefix[0] > beg ? prefix[0] : beg, hi = prefix[gn] < end ? prefix[gn] : end;
+        if (lo >= hi) continue;          // uniform over the workgroup
+        // Every wavefront takes a contiguous run of the group's vectors and walks it 64 vectors at a
+        // time, so a lane's piece is found by bisection once and then moves on by a piece or two per
+        // round (pieces hold some tens of vectors).  (With the workgroup striding over the group
+        // together, a lane skipped some sixty pieces between two of its vectors and spent its time
+        // stepping through the table: 6.6 ms per hop of the 10^8-vertex graph instead of 3.)
+        const uint32_t per_wave = ((hi - lo + (kXBlock / kWave) - 1) / (kXBlock / kWave) + kWave - 1) / kWave * kWave;
+        const uint32_t wlo = lo + (threadIdx.x >> 6) * per_wave;
+        const uint32_t whi = wlo + per_wave < hi ? wlo + per_wave : hi;     // wlo may lie beyond hi: then nothing to do
+        uint32_t q = wlo + (threadIdx.x & (kWave - 1));
+        int k = 0;
+        {
+            int l = 0, h = gn - 1;       // last piece with prefix[k] <= q (used only where q < whi <= prefix[gn])
+            while (l < h) {
+                const int mid = (l + h + 1) >> 1;
+                if (prefix[mid] <= q) l = mid; else h = mid - 1;
+            }
+            k = l;
+        }
+        uint32_t kend = prefix[k + 1];
+        constexpr int U = 4;             // vectors in flight per lane
+        f32x4 v[U];
+        u16x4 r[U];
+        bool ok[U];
+        auto fetch = [&](int u, uint32_t qq) {
+            ok[u] = qq < whi && wlo < hi;
+            if (ok[u]) {
+                while (qq >= kend) { ++k; kend = prefix[k + 1]; }
+                const uint32_t at = start[k] + (qq - prefix[k]);
+                v[u] = __builtin_nontemporal_load(vv + at);
+                r[u] = __builtin_nontemporal_load(rv + at);
+            }
+        };
+        auto add = [&](const f32x4& w, const u16x4& rr) {
+            if (w.x != 0.0f) unsafeAtomicAdd(&acc[rr.x], (double)w.x);
+            if (w.y != 0.0f) unsafeAtomicAdd(&acc[rr.y], (double)w.y);
+            if (w.z != 0.0f) unsafeAtomicAdd(&acc[rr.z], (double)w.z);
+            if (w.w != 0.0f) unsafeAtomicAdd(&acc[rr.w], (double)w.w);
+        };
+#pragma unroll
+        for (int u = 0; u < U; ++u) fetch(u, q + u * kWave);
+        while (ok[0]) {
+            f32x4 cv[U];
+            u16x4 cr[U];
+            bool cok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) { cv[u] = v[u]; cr[u] = r[u]; cok[u] = ok[u]; }
+            q += U * kWave;
+            // the next round's loads are in flight while this round's sums are formed
+#pragma unroll
+            for (int u = 0; u < U; ++u) fetch(u, q + u * kWave);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (cok[u]) add(cv[u], cr[u]);
+        }
+    }
+    __syncthreads();
+    const int64_t u0 = rb << kTileRowBits;
+    if (parts == 1) {
+        unsigned long long verts = 0, edges = 0;
+        for (int i = threadIdx.x; i < R; i += kXBlock)
+            if (u0 + i < N) vip_finish_vertex(a, u0 + i, acc[i], verts, edges);
+    } else {
+        double* __restrict__ out = part + (int64_t)j * part_stride + u0;
+        for (int i = threadIdx.x; i < R; i += kXBlock) out[i] = acc[i];
+    }
+}
+
 // y_1(v) for the training vertices (p^[0] = min(1, B/|T|), Sec. 3.1); optionally hop 0 into the
 // total; counts hop 1's frontier on the way.
 __global__ void __launch_bounds__(kBlock) vip_init_kernel(const int32_t* __restrict__ T, int64_t nT, int64_t N, double p0,
@@ -729,11 +909,12 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
             if (binned) {
                 fill_f32_kernel<<<(unsigned)((g->nrb + kBlock) / kBlock), kBlock, 0, st>>>(
                     reinterpret_cast<float*>(cursor), g->nrb + 1, 0.f);         // all-zero bits either way
+                // a bin is the range of the edges that end in its row block: block_first, with a stride of one
                 vipg_bin_fill_kernel<<<ctx->num_cu * 8, kBinBlock, fill_lds, st>>>(
                     flist, fcount + 2, pcur, g->rowptr, g->col, d_t[h - 1], g->tile_rbits, (int)g->nrb,
-                    g->tile_first, g->nch, cursor, bins, d_bad);
+                    g->block_first, 1, cursor, bins, d_bad);
                 vip_bin_sum_kernel<<<(unsigned)(g->nrb * parts), kTileBlock, sum_lds, st>>>(
-                    bins, cursor, g->tile_first, g->nch, parts, g->tile_rbits, acc, part_stride);
+                    bins, cursor, g->block_first, 1, parts, g->tile_rbits, acc, part_stride);
             } else {
                 fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
                 vipg_push_kernel<<<ctx->num_cu * 32, kBlock, 0, st>>>(flist, fcount + 2, pcur, g->rowptr, g->col,
@@ -781,6 +962,9 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
         const int64_t want = (int64_t)ctx->num_cu * 4 / g->nrb;
         parts = (int)(want < 1 ? 1 : (want > 16 ? 16 : want));
     }
+    // the chunked layout: with a row block per CU or more, one workgroup takes a whole block and
+    // finishes its vertices itself (no partial sums leave the chip)
+    if (g->has_x && g->nrb >= ctx->num_cu) parts = 1;
     const int64_t part_stride = g->nrb << g->tile_rbits;
     {
         const size_t tile_bytes = (size_t)parts * (size_t)part_stride * sizeof(double);
@@ -788,10 +972,23 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
         SPP_TRY(ctx->acc.reserve(tile_bytes > push_bytes ? tile_bytes : push_bytes));
     }
     const size_t lds_bytes = (sizeof(double) << g->tile_rbits) + (size_t)(g->nch + 1) * sizeof(uint32_t);
-    if (ctx->tile_lds_set < (int)lds_bytes) {        // more than the 64 KB a launch may ask for by default
+    const size_t x_lds_expand = (sizeof(float) << kXSrcBits) + sizeof(float);
+    static_assert(kXPad == (1u << kXSrcBits), "a padding entry indexes the slot after the chunk's values");
+    const size_t x_lds_reduce = (sizeof(double) << kTileRowBits) + (2 * kXGroup + 1) * sizeof(uint32_t);
+    if (!g->has_x && ctx->tile_lds_set < (int)lds_bytes) {        // more than the 64 KB a launch may ask for by default
         SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vip_tile_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         ctx->tile_lds_set = (int)lds_bytes;
+    }
+    if (g->has_x) {
+        if (!ctx->x_lds_set) {
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vip_expand_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)x_lds_expand));
+            SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vip_reduce_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)x_lds_reduce));
+            ctx->x_lds_set = 1;
+        }
+        SPP_TRY(ctx->xvals.reserve((size_t)(g->x_entries > 0 ? g->x_entries : 4) * sizeof(float)));
     }
     // the kernels that write a hop's y run this many workgroups; each leaves the size of the part of
     // the next frontier it saw (at most kStatBlocks pairs fit the pinned mirror)
@@ -855,6 +1052,14 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
                         flist, fcount + 2, ycur, g->rowptr, g->col, acc);
                 }
                 vip_push_finish_kernel<<<fill_grid, kBlock, 0, st>>>(a, acc, N);
+            } else if (g->has_x) {
+                const int egrid = g->x_nch < ctx->num_cu * 4 ? g->x_nch : ctx->num_cu * 4;
+                vip_expand_kernel<<<egrid, kXBlock, x_lds_expand, st>>>(g->x_src, g->x_chunk_first, g->x_nch, N, ycur,
+                                                                        ctx->xvals.as<float>());
+                vip_reduce_kernel<<<(unsigned)(g->nrb * parts), kXBlock, x_lds_reduce, st>>>(
+                    ctx->xvals.as<float>(), g->x_row, g->x_start, g->x_prefix, g->x_nch, parts, N, ctx->acc.as<double>(),
+                    part_stride, a);
+                if (parts > 1) vip_tile_finish_kernel<<<fill_grid, kBlock, 0, st>>>(a, ctx->acc.as<double>(), parts, part_stride, N);
             } else {
                 vip_tile_kernel<<<(unsigned)(g->nrb * parts), kTileBlock, lds_bytes, st>>>(
                     g->t_edge, g->tile_first, g->nch, parts, g->tile_rbits, ycur, ctx->acc.as<double>(), part_stride);

@@ -24,8 +24,21 @@ def spp():
     return m
 
 
+# Every case runs twice: with the transposed edges in row blocks (graphs whose per-vertex vectors stay in
+# the caches) and in the chunked layout that graphs above 2^23 vertices get (forced here at small sizes).
+_CHUNKED = False
+
+
+@pytest.fixture(scope="module", params=["row-blocks", "chunked"], autouse=True)
+def layout(request):
+    global _CHUNKED
+    _CHUNKED = request.param == "chunked"
+    yield request.param
+    _CHUNKED = False
+
+
 @pytest.fixture(scope="module")
-def ctx(spp):
+def ctx(spp, layout):
     c = spp.Context(0)
     yield c
     c.close()
@@ -46,7 +59,7 @@ class Case:
         self.Tk = self.Tk_d.cpu().numpy()
         self.T_all = T.cpu().numpy()
         self.lo, self.hi = cfg.bounds()
-        self.G = spp.Graph(ctx, self.rowptr_d, self.col_d, in_lists=in_lists)
+        self.G = spp.Graph(ctx, self.rowptr_d, self.col_d, in_lists=in_lists, chunked=_CHUNKED)
 
     def features(self):
         cfg = self.cfg
@@ -101,7 +114,7 @@ def _mini_graph(spp, ctx, adj, N):
     col = np.asarray(col, dtype=np.int32)
     dev = torch.device("cuda:0")
     G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev) if col.size else torch.zeros(0, dtype=torch.int32, device=dev),
-                  in_lists=True)
+                  in_lists=True, chunked=_CHUNKED)
     return G, rp, col
 
 
@@ -162,7 +175,7 @@ def test_sampler_and_vip_shape_sweep(spp, ctx, fanouts):
     degrees[:8] = [0, 1, 600, 65, 64, 63, 2, 0]
     rp, col = _random_graph(rng, N, degrees)
     dev = torch.device("cuda:0")
-    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), in_lists=True)
+    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), in_lists=True, chunked=_CHUNKED)
     L = len(fanouts)
     seeds = np.concatenate([np.arange(8), 8 + rng.permutation(N - 8)[:43]]).astype(np.int32)    # distinct, as a minibatch is
     _say("shape sweep: fanouts", fanouts, "M", col.size)
@@ -210,7 +223,7 @@ def test_vip_long_rows_in_the_frontier(spp, ctx):
     gen_t, gen_h = oracle.vip_general(rp, col, p0, t_np, 2)
     for in_lists in (True, False):
         _say("long rows in the frontier, row blocks", in_lists)
-        G = spp.Graph(ctx, rp_d, col_d, in_lists=in_lists)
+        G = spp.Graph(ctx, rp_d, col_d, in_lists=in_lists, chunked=_CHUNKED)
         if in_lists:
             p, ph = spp.vip_propagate(ctx, G, torch.from_numpy(T).to(dev), 8, fanouts, per_hop=True)
             assert spp.vip_last_hops(ctx, 2)[0][0], "hop 1 was meant to be pushed"
@@ -221,6 +234,52 @@ def test_vip_long_rows_in_the_frontier(spp, ctx):
         _check_vip(pg, gen_t)
         _check_vip(pgh[0], gen_h[0])
         G.close()
+
+
+def test_vip_chunked_layout_whole_blocks(spp, ctx, layout):
+    """The chunked layout with more row blocks than CUs (257 blocks of 2^14 rows, 129 chunks of 2^15 sources):
+    one workgroup then sums a whole row block and finishes its vertices itself.  Sparse (two or three
+    out-edges per vertex) plus hub rows and hub columns, so that pieces are empty, tiny and large."""
+    if layout != "chunked":
+        pytest.skip("one layout only")
+    rng = np.random.default_rng(2024)
+    N = (1 << 22) + 1000
+    deg = rng.integers(1, 4, N).astype(np.int64)
+    deg[rng.integers(0, N, 2000)] = 0
+    hubs = rng.integers(0, N, 12)
+    deg[hubs] = rng.integers(3000, 9000, hubs.size)
+    rp = np.zeros(N + 1, np.int64)
+    rp[1:] = np.cumsum(deg)
+    M = int(rp[-1])
+    tgt = rng.integers(0, N, M).astype(np.int64)
+    popular = rng.integers(0, N, 8)                        # columns that a tenth of the edges point at
+    pick = rng.random(M) < 0.1
+    tgt[pick] = popular[rng.integers(0, popular.size, int(pick.sum()))]
+    # rows sorted and unique: sort by (row, target), drop repeats and self loops, rebuild the offsets
+    row = np.repeat(np.arange(N, dtype=np.int64), deg)
+    key = np.unique(row * N + tgt)
+    row, tgt = key // N, key % N
+    keep = row != tgt
+    row, tgt = row[keep], tgt[keep]
+    rp = np.zeros(N + 1, np.int64)
+    np.add.at(rp, row + 1, 1)
+    rp = np.cumsum(rp)
+    col = tgt.astype(np.int32)
+    dev = torch.device("cuda:0")
+    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), in_lists=True, chunked=True)
+    T = np.sort(np.concatenate([hubs, rng.choice(N, 200_000, replace=False)])).astype(np.int32)
+    T = np.unique(T)
+    fanouts = (4, 3, 2)
+    _say("chunked layout, whole blocks: N", N, "M", col.size, "|T|", T.size)
+    for include0 in (False, True):
+        p, ph = spp.vip_propagate(ctx, G, torch.from_numpy(T).to(dev), 1024, fanouts, per_hop=True, include_hop0=include0)
+        pushed, _ = spp.vip_last_hops(ctx, 3)
+        assert not pushed[2], "the last hop was meant to be a dense one"
+        ref_t, ref_h = oracle.vip(rp, col, T, 1024, fanouts, include_hop0=include0)
+        _check_vip(p, ref_t)
+        for h in range(3):
+            _check_vip(ph[h], ref_h[h])
+    G.close()
 
 
 def _zipf_graph(rng, N, mean, hubs):
@@ -267,7 +326,7 @@ def test_random_shapes(spp, ctx, case):
     _say("random shapes", case, "N", N, "M", col.size, "fanouts", fanouts, "B", B, "|T|", nT, "K", K, "part", part,
          "alpha", alpha, "D", D, np_dt.__name__)
     dev = torch.device("cuda:0")
-    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), in_lists=True)
+    G = spp.Graph(ctx, torch.from_numpy(rp).to(dev), torch.from_numpy(col).to(dev), in_lists=True, chunked=_CHUNKED)
     # (1) vertex-inclusion probabilities, both entry points
     p, ph = spp.vip_propagate(ctx, G, torch.from_numpy(T).to(dev), B, fanouts, per_hop=True)
     rt, rh = oracle.vip(rp, col, T, B, fanouts)
@@ -323,7 +382,7 @@ def test_random_shapes(spp, ctx, case):
 # ----------------------------------------------------------------------------------------------
 
 @pytest.fixture(scope="module")
-def tiny_case(spp, ctx):
+def tiny_case(spp, ctx, layout):
     _say("building Tiny")
     c = Case(spp, ctx, S.TINY)
     c.features()
