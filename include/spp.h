@@ -61,6 +61,8 @@ enum {
 #define SPP_GRAPH_CHUNKED     0x20u  /* spp_graph_create, with SPP_GRAPH_IN_LISTS: build the layout for graphs whose
                                         per-vertex vectors exceed the caches (two passes per dense hop) whatever N is;
                                         by default graphs above 2^23 vertices get it */
+#define SPP_SAMPLE_GLOBAL_TABLE 0x40u /* spp_sample_mfg(_multi): deduplicate every hop through the id table in global memory,
+                                        also the hops small enough for the LDS form (same results; for comparison and tests) */
 #define SPP_NO_JOIN           0x8u   /* gather: leave the miss copy running on the side stream; see spp_gather_join */
 #define SPP_STORE_ORDER       0x10u  /* gather: fetch the call's missed remote rows in the order of the remote store;
                                         see spp_gather_features_multi */

@@ -27,6 +27,7 @@ SPP_GRAPH_IN_LISTS = 0x4
 SPP_NO_JOIN = 0x8
 SPP_STORE_ORDER = 0x10
 SPP_GRAPH_CHUNKED = 0x20
+SPP_SAMPLE_GLOBAL_TABLE = 0x40
 SPP_STATIC_GATHER_MAX_ROWS = 131072
 SPP_T_VIP_TOTAL, SPP_T_VIP_HOP_FIRST, SPP_T_SAMPLE = 0, 1, 9
 SPP_T_GATHER_HIT, SPP_T_GATHER_MISS, SPP_T_GATHER_CLASSIFY, SPP_T_COUNT = 10, 11, 12, 16
@@ -500,7 +501,8 @@ class MFGBuffers:
 
 
 def sample_mfg(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: Sequence[int], seed: int,
-               batch_index: int, out: Optional[MFGBuffers] = None, sync: bool = True) -> MFGBuffers:
+               batch_index: int, out: Optional[MFGBuffers] = None, sync: bool = True,
+               global_table: bool = False) -> MFGBuffers:
     """Multi-hop fanout sampling into per-layer MFGs.  With sync the host counts out.n / out.e are filled."""
     seeds = _dev(seeds, torch.int32, "seeds")
     if out is None:
@@ -508,14 +510,16 @@ def sample_mfg(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: Sequenc
     f, L = _fan(fanouts)
     _check(load_library().spp_sample_mfg(ctx._h, graph._h, _ptr(seeds), seeds.numel(), f, L,
                                          C.c_uint64(int(seed) & (2**64 - 1)), C.c_uint64(int(batch_index) & (2**64 - 1)),
-                                         C.byref(out._s), SPP_SYNC if sync else 0))
+                                         C.byref(out._s),
+                                         (SPP_SYNC if sync else 0) | (SPP_SAMPLE_GLOBAL_TABLE if global_table else 0)))
     if sync:
         out.n = [int(out._s.n[h]) for h in range(L + 1)]
         out.e = [int(out._s.e[h]) for h in range(L + 1)]
     return out
 
 
-def sample_mfg_multi(ctx: Context, graph: Graph, items, fanouts: Sequence[int], seed: int, sync: bool = True):
+def sample_mfg_multi(ctx: Context, graph: Graph, items, fanouts: Sequence[int], seed: int, sync: bool = True,
+                     global_table: bool = False):
     """Several minibatches sampled by one set of launches.
 
     `items` is a sequence of (seeds, batch_index, MFGBuffers); each MFGBuffers receives the result of
@@ -530,7 +534,8 @@ def sample_mfg_multi(ctx: Context, graph: Graph, items, fanouts: Sequence[int], 
         arr[j].batch_index = int(batch_index) & (2**64 - 1)
         arr[j].io = C.pointer(out._s)
     _check(load_library().spp_sample_mfg_multi(ctx._h, graph._h, arr, len(items), f, L,
-                                               C.c_uint64(int(seed) & (2**64 - 1)), SPP_SYNC if sync else 0))
+                                               C.c_uint64(int(seed) & (2**64 - 1)),
+                                               (SPP_SYNC if sync else 0) | (SPP_SAMPLE_GLOBAL_TABLE if global_table else 0)))
     if sync:
         for _, _, out in items:
             out.n = [int(out._s.n[h]) for h in range(L + 1)]

@@ -121,6 +121,7 @@ struct spp_ctx {
     spp::DevBuf bins;                   // general propagation: per row block the (row, weight) entries of a hop, and the fill counts
     int         bin_lds_set = 0, sum_lds_set = 0;   // dynamic LDS bytes its two kernels have been allowed
     int         tile_lds_set = 0;       // dynamic LDS bytes the dense-hop kernel has been allowed on this device
+    int         dedup_lds_set = 0;      // the LDS dedup kernel of the sampler has been allowed its 128 KB
     int         x_lds_set = 0;          // the two kernels of the chunked layout have been allowed theirs
     int         vip_pushed[SPP_MAX_L] = {};          // last vip_propagate: hop done in push form?
     int64_t     vip_frontier_edges[SPP_MAX_L] = {};  // last vip_propagate: out-edges of each hop's frontier

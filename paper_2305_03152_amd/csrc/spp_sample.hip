@@ -7,18 +7,28 @@
 //   1. grid scan of c_i = min(f_h, d(S_{h-1}[i]))            -> indptr of MFG h, e_h
 //   2. sample: a group of G lanes (G = 8/16/32/64 >= f_h) per target draws its slots in parallel
 //      (one Philox block per lane), resolves Floyd's "already taken" rule with ballots, reads the
-//      neighbour ids, offers (id, n_{h-1} + flat position) to the id table with atomic min and
-//      keeps the table slot of every sampled id, so that the later steps read the entry directly
-//   3. grid scan of "this flat entry is the first appearance of a new id"
-//                                                            -> S_h appended in order, n_h, table value := local id
-//   4. relabel: src[e] = table value of the e-th sampled id
-// The id table (open addressing, global memory) is right-sized per hop on the device: once e_h is
-// known, the hop uses the first 2^k >= 2 (n_{h-1} + e_h) slots of the minibatch's region, clears
-// exactly those, and the sample kernel re-offers S_{h-1} (value = index, which is below any
-// position offered at this hop, so earlier vertices keep their ids) next to the new ids.  The
-// worst-case bound on |S_L| only sizes the allocation: a Mid minibatch reaches 66k of 1.08M
-// possible vertices, and a table laid out for the bound (32 MB per minibatch, touched at random)
-// pushed the feature rows out of the caches (the hit copy ran 20 % slower) besides missing L2 itself.
+//      neighbour ids and stores them in flat (edge) order
+//   3. dedup: for every sampled id the position of its first appearance among S_{h-1} followed by
+//      the hop's flat list (an index below n_{h-1} means the vertex is an earlier one)
+//   4. grid scan of "this flat entry is the first appearance of a new id"
+//                                                            -> S_h appended in order, n_h, src of those entries
+//   5. relabel: src[e] of a repeated id = its index in S_{h-1}, or the src of its first appearance
+// Step 3 is where the ids meet.  A hop of up to 16 x 8192 ids (with S_{h-1}) is deduplicated in LDS:
+// the ids are dealt by hash to up to 16 partitions, one workgroup per partition keeps an id table of
+// 16384 slots in LDS (128 KB), reads the minibatch's whole list (a few hundred KB, from L2), inserts
+// the ids of its partition with LDS atomics (smallest position wins) and, after a barrier, writes
+// out what each of them resolved to.  Global memory sees only sequential reads and writes.  (The
+// earlier form, a table in global memory fed by the sample kernel, was bound by the rate of global
+// atomics, about 16 G/s: 0.31 ms for the 5 M inserts of the last hop of 64 minibatches.)  Larger hops
+// keep that form: the id table (open addressing, global memory) is right-sized per hop on the device:
+// once e_h is known, the hop uses the first 2^k >= 2 (n_{h-1} + e_h) slots of the minibatch's region,
+// clears exactly those, and the sample kernel offers S_{h-1} (value = index, which is below any
+// position offered at this hop, so earlier vertices keep their ids) next to the new ids with atomic
+// minima; the scan's first pass then reads what each entry resolved to.  The worst-case bound on
+// |S_L| only sizes the allocation: a Mid minibatch reaches 66k of 1.08M possible vertices, and a
+// table laid out for the bound (32 MB per minibatch, touched at random) pushed the feature rows out
+// of the caches (the hit copy ran 20 % slower) besides missing L2 itself.  Which form a hop takes is
+// decided per minibatch on the device, from the hop's size.
 //
 // The same machinery serves the sampler with given transition probabilities (Sec. 3.1, paragraph
 // after Prop. 1): a target takes every entry of its row independently with the entry's probability,
@@ -39,7 +49,8 @@ struct BatchDesc {
     int32_t*       indptr[SPP_MAX_L];
     int32_t*       src[SPP_MAX_L];
     int64_t*       counts;              // n[0..MAX_L], e[0..MAX_L]
-    uint32_t*      tinfo;               // [0] mask, [1] shift of the table for the current hop, [2] abandoned (workspace)
+    uint32_t*      tinfo;               // [0] mask, [1] shift of the table for the current hop, [2] abandoned (workspace),
+                                        // [3] log2 of the LDS partitions of the current hop, or kGlobalTable
     unsigned long long* taken;          // 64-bit count of taken entries of the current hop (given probabilities only)
     int64_t        ncap;                // capacities of the caller's buffers (checked on the device
     int64_t        ecap[SPP_MAX_L];     //   only when sizes are not bounded by fanouts)
@@ -57,8 +68,11 @@ struct SampleArgs {
     int64_t        N;
     unsigned long long* tab;            // one region of `cap` entries per minibatch
     int64_t        cap;                 // slots per region (a power of two, sized for the bound on |S_L|)
-    int32_t*       flat;                // one region of `flat_stride` entries per minibatch: the id-table slot of
-                                        // every sampled id of the current hop, in flat (edge) order
+    int32_t*       flat;                // one region of `flat_stride` entries per minibatch, in flat (edge) order: what
+                                        // every sampled id of the current hop resolved to (an index into S_{h-1}, or
+                                        // n_{h-1} + the flat position of the id's first appearance); with the table in
+                                        // global memory, until the scan's first pass, the table slot of the id
+    int32_t*       gids;                // the same shape: the sampled ids themselves
     int64_t        flat_stride;
     unsigned long long* totals;         // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
     int*           bad;
@@ -70,10 +84,12 @@ struct SampleArgs {
     int32_t*       cnt;                 // one region of `cnt_stride` per-target counts per minibatch (given probabilities)
     int64_t        cnt_stride;
     int*           ovf;                 // set when a minibatch was abandoned for lack of capacity
+    int            force_global;        // SPP_SAMPLE_GLOBAL_TABLE: every hop deduplicates in the global-memory table
 };
 
 __device__ __forceinline__ unsigned long long* tab_of(const SampleArgs& a, int j) { return a.tab + (int64_t)j * a.cap; }
 __device__ __forceinline__ int32_t* flat_of(const SampleArgs& a, int j) { return a.flat + (int64_t)j * a.flat_stride; }
+__device__ __forceinline__ int32_t* gids_of(const SampleArgs& a, int j) { return a.gids + (int64_t)j * a.flat_stride; }
 __device__ __forceinline__ int32_t* cnt_of(const SampleArgs& a, int j) { return a.cnt + (int64_t)j * a.cnt_stride; }
 constexpr int kE = SPP_MAX_L + 1;      // offset of e[] inside counts
 
@@ -126,6 +142,20 @@ __device__ __forceinline__ void hop_table(const SampleArgs& a, int64_t n_prev, i
     shift = 22;
     while (capj < want && (int64_t)capj < a.cap) { capj <<= 1; --shift; }
 }
+// Where a hop's ids are deduplicated: in LDS, dealt to 2^k partitions of at most kLdsPartKeys ids on
+// average (k returned), or in the table in global memory (kGlobalTable).  A function of the hop's size
+// alone, so every workgroup of a launch that has the scan's total takes the same decision.
+constexpr int kLdsSlots = 16384;                 // slots of a partition's table (64-bit entries: 128 KB of LDS)
+constexpr int kLdsPartKeys = kLdsSlots / 2;
+constexpr int kLdsMaxPartsLog2 = 4;
+constexpr uint32_t kGlobalTable = 0xFFFFFFFFu;
+__device__ __forceinline__ uint32_t hop_mode(const SampleArgs& a, int64_t n_prev, int e_h) {
+    const int64_t keys = n_prev + (int64_t)(uint32_t)e_h;
+    if (a.t != nullptr || a.force_global || keys > ((int64_t)kLdsPartKeys << kLdsMaxPartsLog2)) return kGlobalTable;
+    uint32_t k = 0;
+    while (((int64_t)kLdsPartKeys << k) < keys) ++k;
+    return k;
+}
 struct CountFin {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int total) const {
@@ -144,6 +174,7 @@ struct CountFin {
         hop_table(a, c[a.h - 1], total, capj, shift);
         t->b[j].tinfo[0] = capj - 1;
         t->b[j].tinfo[1] = (uint32_t)shift;
+        t->b[j].tinfo[3] = hop_mode(a, c[a.h - 1], total);
     }
 };
 
@@ -155,6 +186,7 @@ struct TableClear {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, unsigned x, unsigned gx, int total) const {
         if (t->b[j].tinfo[2] || hop_overflows(a, t->b[j])) return;
+        if (hop_mode(a, t->b[j].counts[a.h - 1], total) != kGlobalTable) return;     // deduplicated in LDS: no table to empty
         unsigned long long* tab = tab_of(a, j);
         uint32_t capj;
         int shift;
@@ -181,9 +213,11 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
     const int32_t* __restrict__ S = t->b[jb].S;
     const int32_t* __restrict__ indptr = t->b[jb].indptr[a.h - 1];
     int32_t* __restrict__ flat = flat_of(a, jb);
+    int32_t* __restrict__ gids = gids_of(a, jb);
     unsigned long long* tab = tab_of(a, jb);
     const uint32_t mask = t->b[jb].tinfo[0];
     const int shift = (int)t->b[jb].tinfo[1];
+    const bool global_table = t->b[jb].tinfo[3] == kGlobalTable;
 
     for (int64_t first = wave * kGroupsPerWave; first < n_prev; first += nwaves * kGroupsPerWave) {
         const int64_t i = first + (lane / G);
@@ -216,16 +250,22 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
                 if (j == jj && b != 0ull) pos = (int64_t)m;
             }
         }
+        const bool mine = valid && j < c;
+        int32_t gid = 0;
+        int64_t e = -1;                            // flat position of this lane's sampled id, if it has one
+        if (mine) {
+            gid = a.col[r0 + pos];
+            e = (int64_t)off + j;
+            gids[e] = gid;
+        }
+        if (!global_table) continue;               // the ids meet in LDS, in the launch that follows
         // the table was emptied for this hop, so the target is offered again with its index; the
         // group's last lane does it when it has no neighbour of its own (c < G), else lane 0 after
         // its neighbour
         const bool spare = c < G;
         uint32_t key = 0, val = 0;
-        int64_t e = -1;                            // flat position of this lane's sampled id, if it has one
         bool ins = false;
-        if (valid && j < c) {
-            const int32_t gid = a.col[r0 + pos];
-            e = (int64_t)off + j;
+        if (mine) {
             key = (uint32_t)gid; val = (uint32_t)(n_prev + e); ins = true;
         } else if (valid && spare && j == G - 1) {
             key = (uint32_t)v; val = (uint32_t)i; ins = true;
@@ -235,6 +275,146 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
             if (e >= 0) flat[e] = (int32_t)slot;
         }
         if (valid && !spare && j == 0) table_insert_min(tab, mask, shift, (uint32_t)v, (uint32_t)i);
+    }
+}
+
+// ---- step 3 in LDS ----
+// One workgroup per (partition, minibatch).  An id belongs to the partition named by the top bits of
+// its hash; its slot comes from the bits below.  Entries are (id << 32 | position), empty = all ones;
+// an insertion keeps the smallest position offered for an id.  A partition holds 8192 ids on average
+// and 16384 at most; more than that in one partition (ids that share their hash's top bits by the
+// thousand) cannot be held: the call then reports an error and the minibatch's output is not valid.
+constexpr int kDedupBlock = 1024;
+__device__ __forceinline__ bool lds_insert_min(unsigned long long* tab, uint32_t slot, uint32_t key, uint32_t value) {
+    const unsigned long long want = ((unsigned long long)key << 32) | value;
+    for (int probes = 0; probes < kLdsSlots; ++probes) {
+        unsigned long long cur = tab[slot];
+        if (cur == kEmpty) {
+            const unsigned long long old = atomicCAS(&tab[slot], (unsigned long long)kEmpty, want);
+            if (old == kEmpty) return true;
+            cur = old;
+        }
+        if ((uint32_t)(cur >> 32) == key) {
+            if (want < cur) atomicMin(&tab[slot], want);
+            return true;
+        }
+        slot = (slot + 1) & (kLdsSlots - 1);
+    }
+    return false;
+}
+__device__ __forceinline__ uint32_t lds_find(const unsigned long long* tab, uint32_t slot, uint32_t key) {
+    for (int probes = 0; probes < kLdsSlots; ++probes) {
+        const unsigned long long cur = tab[slot];
+        if ((uint32_t)(cur >> 32) == key) return (uint32_t)cur;
+        if (cur == kEmpty) break;
+        slot = (slot + 1) & (kLdsSlots - 1);
+    }
+    return 0xFFFFFFFFu;                            // not reached for an id that was inserted
+}
+// Only one id in 2^k belongs to the workgroup's partition, so the ids that do are first gathered, per
+// wavefront, in a small queue in LDS (ballot, rank among the lanes that have one) and handed out 64
+// at a time: the atomics of an insertion then run with every lane busy.  (With each lane inserting
+// the ids it had read itself, an atomic instruction served 8 lanes of 64 and the LDS pipeline, which
+// takes one instruction at a time, set the pace: 0.37 ms for the last hop of 64 minibatches.)
+constexpr int kQueue = 2 * kWave;                 // entries a wavefront's queue holds
+struct WaveQueue {
+    unsigned long long* q;                        // this wavefront's kQueue entries: (id << 32 | payload)
+    int n;                                        // entries queued (the same in every lane)
+    // Queues `item` of the lanes where `has` is set.  Returns true when 64 entries are ready: `out` is
+    // this lane's (the queue keeps the rest).
+    __device__ __forceinline__ bool push(bool has, unsigned long long item, unsigned long long& out) {
+        const uint64_t m = __ballot(has);
+        if (has) q[n + __popcll(m & ((1ull << lane_id()) - 1ull))] = item;
+        n += __popcll(m);
+        if (n < kWave) return false;
+        out = q[lane_id()];
+        const unsigned long long rest = q[kWave + lane_id()];     // n < 2 * 64: at most 64 entries stay
+        n -= kWave;
+        if (lane_id() < n) q[lane_id()] = rest;
+        return true;
+    }
+    // What is left at the end: true in the lanes that get an entry.
+    __device__ __forceinline__ bool drain(unsigned long long& out) {
+        const bool mine = lane_id() < n;
+        if (mine) out = q[lane_id()];
+        n = 0;
+        return mine;
+    }
+};
+
+__global__ void __launch_bounds__(kDedupBlock) dedup_lds_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
+    extern __shared__ unsigned long long ltab[];
+    const int jb = blockIdx.x;                     // partitions are the slow index: the workgroups of partitions
+    const uint32_t part = blockIdx.y;              // that a minibatch does not use come last and leave at once
+    const uint32_t k = t->b[jb].tinfo[3];
+    if (t->b[jb].tinfo[2] || k == kGlobalTable || part >= (1u << k)) return;
+    const int64_t n_prev = t->b[jb].counts[a.h - 1];
+    const int64_t e_h = t->b[jb].counts[kE + a.h];
+    const int32_t* __restrict__ S = t->b[jb].S;
+    const int32_t* __restrict__ gids = gids_of(a, jb);
+    int32_t* __restrict__ flat = flat_of(a, jb);
+    WaveQueue wq;
+    wq.q = ltab + kLdsSlots + (threadIdx.x >> 6) * kQueue;
+    wq.n = 0;
+    for (int i = threadIdx.x; i < kLdsSlots; i += kDedupBlock) ltab[i] = kEmpty;
+    __syncthreads();
+    // hash bits: the top k name the partition, the 14 below them the slot
+    auto mine = [&](uint32_t key) { return k == 0 || ((key * 0x9E3779B1u) >> (32 - k)) == part; };
+    auto slot_of = [&](uint32_t key) { return ((key * 0x9E3779B1u) << k) >> (32 - 14); };
+    // The lists are short (tens of thousands of ids) and every workgroup of the minibatch reads all of
+    // them, so a pass is a chain of L2 round trips: eight loads per thread are in flight at a time.
+    // Whole wavefronts walk the rounds together (the queue's ballots need every lane).
+    constexpr int kU = 8;
+    bool ok = true;
+    auto insert = [&](unsigned long long item) {
+        const uint32_t key = (uint32_t)(item >> 32);
+        ok = lds_insert_min(ltab, slot_of(key), key, (uint32_t)item) && ok;
+    };
+    auto insert_all = [&](const int32_t* __restrict__ ids, int64_t count, int64_t first_value) {
+        const int64_t rounds = (count + (int64_t)kDedupBlock * kU - 1) / ((int64_t)kDedupBlock * kU);
+        for (int64_t r = 0; r < rounds; ++r) {
+            const int64_t i0 = r * kDedupBlock * kU + threadIdx.x;
+            uint32_t key[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u)
+                if (i0 + u * kDedupBlock < count) key[u] = (uint32_t)ids[i0 + u * kDedupBlock];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const bool has = i0 + u * kDedupBlock < count && mine(key[u]);
+                unsigned long long item;
+                if (wq.push(has, ((unsigned long long)key[u] << 32) | (uint32_t)(first_value + i0 + u * kDedupBlock), item)) insert(item);
+            }
+        }
+    };
+    insert_all(S, n_prev, 0);
+    insert_all(gids, e_h, n_prev);
+    {
+        unsigned long long item;
+        if (wq.drain(item)) insert(item);
+    }
+    if (!ok) atomicOr(a.bad, 4);
+    __syncthreads();
+    auto resolve = [&](unsigned long long item) {
+        const uint32_t key = (uint32_t)(item >> 32);
+        flat[(uint32_t)item] = (int32_t)lds_find(ltab, slot_of(key), key);
+    };
+    const int64_t rounds = (e_h + (int64_t)kDedupBlock * kU - 1) / ((int64_t)kDedupBlock * kU);
+    for (int64_t r = 0; r < rounds; ++r) {
+        const int64_t e0 = r * kDedupBlock * kU + threadIdx.x;
+        uint32_t key[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u)
+            if (e0 + u * kDedupBlock < e_h) key[u] = (uint32_t)gids[e0 + u * kDedupBlock];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const bool has = e0 + u * kDedupBlock < e_h && mine(key[u]);
+            unsigned long long item;
+            if (wq.push(has, ((unsigned long long)key[u] << 32) | (uint32_t)(e0 + u * kDedupBlock), item)) resolve(item);
+        }
+    }
+    {
+        unsigned long long item;
+        if (wq.drain(item)) resolve(item);
     }
 }
 
@@ -348,7 +528,8 @@ __global__ void __launch_bounds__(kBlock) general_count_kernel(SampleArgs a, con
 
 template <int G>
 __device__ __forceinline__ void general_sample_rows(const SampleArgs& a, const BatchDesc& b, const BatchBlock& bb,
-                                                    int32_t* __restrict__ flat, unsigned long long* tab) {
+                                                    int32_t* __restrict__ flat, int32_t* __restrict__ gids,
+                                                    unsigned long long* tab) {
     const GroupWalk w = group_walk<G>(bb);
     const int lane = lane_id();
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
@@ -381,6 +562,7 @@ __device__ __forceinline__ void general_sample_rows(const SampleArgs& a, const B
             for (int q = 0; q < 4; ++q) {
                 if ((m >> q) & 1u) {
                     const int32_t gid = a.col[r0 + k4 + q];
+                    gids[pos] = gid;
                     flat[pos] = (int32_t)table_insert_min(tab, mask, shift, (uint32_t)gid, (uint32_t)(n_prev + pos));
                     ++pos;
                 }
@@ -394,18 +576,24 @@ __global__ void __launch_bounds__(kBlock) general_sample_kernel(SampleArgs a, co
     const BatchBlock bb = batch_block();
     const int jb = bb.j;
     if (t->b[jb].tinfo[2]) return;
-    general_sample_rows<kShortGroup>(a, t->b[jb], bb, flat_of(a, jb), tab_of(a, jb));
-    general_sample_rows<kWave>(a, t->b[jb], bb, flat_of(a, jb), tab_of(a, jb));
+    general_sample_rows<kShortGroup>(a, t->b[jb], bb, flat_of(a, jb), gids_of(a, jb), tab_of(a, jb));
+    general_sample_rows<kWave>(a, t->b[jb], bb, flat_of(a, jb), gids_of(a, jb), tab_of(a, jb));
 }
 
-// ---- step 3 ----
+// ---- step 4 ----
 struct NewIn {
     SampleArgs a; const BatchTable* t;
     __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[kE + a.h]; }
-    // The look-up is a random 8-byte read that moves a whole line, so the outcome is left in the
-    // entry's place in the hop's src array (-2 first appearance, -1 repeat) for the second pass.
+    // With the table in global memory, what the entry resolved to is read from its slot here (a
+    // random 8-byte read that moves a whole line) and kept in the slot's place; the outcome is left
+    // in the entry's place in the hop's src array (-2 first appearance, -1 repeat) for the second pass.
     __device__ int operator()(int j, int64_t e) const {
-        const uint32_t val = (uint32_t)tab_of(a, j)[(uint32_t)flat_of(a, j)[e]];
+        int32_t* __restrict__ flat = flat_of(a, j);
+        uint32_t val = (uint32_t)flat[e];
+        if (t->b[j].tinfo[3] == kGlobalTable) {
+            val = (uint32_t)tab_of(a, j)[val];
+            flat[e] = (int32_t)val;
+        }
         const int first = (int64_t)val == t->b[j].counts[a.h - 1] + e ? 1 : 0;
         t->b[j].src[a.h - 1][e] = first ? -2 : -1;
         return first;
@@ -420,20 +608,12 @@ struct NewOut {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int64_t e, int ex, int v, int total) const {
         if (!v || t->b[j].tinfo[2]) return;
-        // A first appearance knows its local id here; the relabel pass looks up only the entries
-        // still marked -1.
-        int32_t* __restrict__ src = t->b[j].src[a.h - 1];
+        // A first appearance gets its local id here; the relabel pass fills in the repeats.
         const int64_t n_prev = t->b[j].counts[a.h - 1];
         if (a.t && n_prev + (int64_t)(uint32_t)total > t->b[j].ncap) return;      // NewFin abandons the minibatch
-        unsigned long long* tab = tab_of(a, j);
-        const uint32_t slot = (uint32_t)flat_of(a, j)[e];
-        const uint32_t gid = (uint32_t)(tab[slot] >> 32);            // a slot's key never changes
         const int64_t id = n_prev + ex;
-        src[e] = (int32_t)id;
-        t->b[j].S[id] = (int32_t)gid;
-        // (no other thread reads the slot in this launch: "first appearance" was decided in the launch before)
-        __hip_atomic_store(&tab[slot], ((unsigned long long)gid << 32) | (uint32_t)id, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+        t->b[j].src[a.h - 1][e] = (int32_t)id;
+        t->b[j].S[id] = gids_of(a, j)[e];
     }
 };
 struct NewFin {
@@ -454,17 +634,22 @@ struct NewFin {
     }
 };
 
-// ---- step 4 ----
+// ---- step 5 ----
+// A repeated id takes the index of the earlier vertex it resolved to, or the local id that the scan
+// gave to its first appearance (an entry before it in the same list, final since the launch before).
 __device__ __forceinline__ void relabel_rows(const SampleArgs& a, const BatchTable* __restrict__ t, int j, unsigned x,
                                              unsigned gx) {
     if (t->b[j].tinfo[2]) return;
     const int64_t e_h = t->b[j].counts[kE + a.h];
-    const unsigned long long* tab = tab_of(a, j);
+    const int64_t n_prev = t->b[j].counts[a.h - 1];
     const int32_t* __restrict__ flat = flat_of(a, j);
-    int32_t* __restrict__ src = t->b[j].src[a.h - 1];
+    int32_t* src = t->b[j].src[a.h - 1];
     const int64_t stride = (int64_t)gx * kBlock;
     for (int64_t e = (int64_t)x * kBlock + threadIdx.x; e < e_h; e += stride)
-        if (src[e] < 0) src[e] = (int32_t)(uint32_t)tab[(uint32_t)flat[e]];      // first appearances were numbered by the scan
+        if (src[e] < 0) {
+            const int64_t fp = (uint32_t)flat[e];
+            src[e] = fp < n_prev ? (int32_t)fp : src[fp - n_prev];
+        }
 }
 __global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
     const BatchBlock bb = batch_block();
@@ -580,7 +765,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
     const int per_batch = (ctx->num_cu * 4 + n_items - 1) / n_items;
     const int scan_grid = ((per_batch < 32 ? 32 : per_batch) + 7) & ~7;     // multiples of 8: see batch_block()
     SPP_TRY(ctx->table.reserve((size_t)cap * sizeof(uint64_t) * n_items));
-    SPP_TRY(ctx->flat.reserve((size_t)emax * sizeof(int32_t) * n_items));
+    SPP_TRY(ctx->flat.reserve((size_t)emax * sizeof(int32_t) * n_items * 2));        // what the ids resolve to, and the ids
     SPP_TRY(ctx->slots.reserve((size_t)(4 * sizeof(uint32_t) + sizeof(unsigned long long)) * kMaxBatches + 64 +
                                (general ? (size_t)nb[L] * sizeof(int32_t) * n_items : 0)));
     unsigned long long* taken = ctx->slots.as<unsigned long long>();
@@ -601,9 +786,17 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
     a.rowptr = g->rowptr; a.col = g->col; a.N = g->N;
     a.tab = ctx->table.as<unsigned long long>(); a.cap = cap;
     a.flat = ctx->flat.as<int32_t>(); a.flat_stride = emax;
+    a.gids = a.flat + (size_t)emax * n_items;
+    const size_t dedup_lds = ((size_t)kLdsSlots + (size_t)(kDedupBlock / kWave) * kQueue) * sizeof(unsigned long long);
+    if (!general && !ctx->dedup_lds_set) {
+        SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&dedup_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)dedup_lds));
+        ctx->dedup_lds_set = 1;
+    }
     a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.bad = d_bad; a.ovf = d_bad + 1;
     a.L = L; a.h = 0; a.f = 0; a.seed = seed;
     a.t = nullptr;
+    a.force_global = (flags & SPP_SAMPLE_GLOBAL_TABLE) ? 1 : 0;
     a.cnt = reinterpret_cast<int32_t*>(tinfo + 4 * kMaxBatches + 16); a.cnt_stride = nb[L];
 
     auto capped = [&](int64_t need, int64_t lim) {
@@ -644,6 +837,11 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
                     case 32: sample_kernel<32><<<sgrid, kBlock, 0, st>>>(a, dt); break;
                     default: sample_kernel<64><<<sgrid, kBlock, 0, st>>>(a, dt); break;
                 }
+                // hops small enough meet in LDS (the workgroups of the others leave at once); a hop whose bound
+                // already exceeds what the partitions hold has no workgroup to launch
+                int64_t parts = 1;
+                while (parts < (1 << kLdsMaxPartsLog2) && parts * kLdsPartKeys < nb[h - 1] + eb[h]) parts <<= 1;
+                dedup_lds_kernel<<<dim3(n_items, (unsigned)parts), kDedupBlock, dedup_lds, st>>>(a, dt);
             }
             grid_scan_batched_two(st, scan_grid, n_items, NewIn{a, dt}, NewInKept{a, dt}, NewOut{a, dt}, NewFin{a, dt}, partial);
             if (h == L || general)
@@ -665,6 +863,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
         const int* fl = reinterpret_cast<const int*>(hp + kMaxBatches * 2 * kE);
         SPP_CHECK((fl[0] & 1) == 0, SPP_E_ARG, "spp_sample_mfg: a seed lies outside [0, N)");
         SPP_CHECK((fl[0] & 2) == 0, SPP_E_ARG, "spp_sample_mfg_general: a transition probability lies outside [0, 1]; it was taken as 0");
+        SPP_CHECK((fl[0] & 4) == 0, SPP_E_HIP, "spp_sample_mfg: more than %d ids of one hop share a hash partition; the minibatch's output is not valid", kLdsSlots);
         SPP_CHECK(fl[1] == 0, SPP_E_CAPACITY, "spp_sample_mfg_general: a minibatch exceeded the capacity of its buffers and was abandoned");
     }
     return SPP_OK;

@@ -25,15 +25,24 @@ def spp():
 
 
 # Every case runs twice: with the transposed edges in row blocks (graphs whose per-vertex vectors stay in
-# the caches) and in the chunked layout that graphs above 2^23 vertices get (forced here at small sizes).
+# the caches) and the sampler's hops deduplicated in LDS (what these sizes get by default), and with the
+# forms that large inputs get, forced here at small sizes: the chunked layout of graphs above 2^23 vertices
+# and the sampler's id table in global memory (hops of more than 131072 ids).
 _CHUNKED = False
 
 
 @pytest.fixture(scope="module", params=["row-blocks", "chunked"], autouse=True)
 def layout(request):
     global _CHUNKED
+    import functools
+    import paper_2305_03152_amd as m
     _CHUNKED = request.param == "chunked"
+    saved = (m.sample_mfg, m.sample_mfg_multi)
+    if _CHUNKED:
+        m.sample_mfg = functools.partial(saved[0], global_table=True)
+        m.sample_mfg_multi = functools.partial(saved[1], global_table=True)
     yield request.param
+    m.sample_mfg, m.sample_mfg_multi = saved
     _CHUNKED = False
 
 
