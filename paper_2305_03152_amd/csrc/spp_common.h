@@ -100,6 +100,7 @@ struct spp_ctx {
     // sampling workspaces
     spp::DevBuf table;                  // uint64 hash table: global id -> local id / first position
     spp::DevBuf flat;                   // int32 sampled global ids of the current hop
+    spp::DevBuf nodeinfo;               // per minibatch: row start and length of the vertices of S_{L-1}
     spp::DevBuf slots;                  // per minibatch: mask and shift of the id table of the current hop
     spp::DevBuf partials;               // scan partial sums
     // gather workspaces

@@ -74,6 +74,9 @@ struct SampleArgs {
                                         // global memory, until the scan's first pass, the table slot of the id
     int32_t*       gids;                // the same shape: the sampled ids themselves
     int64_t        flat_stride;
+    int64_t*       row0;                // one region of `node_stride` entries per minibatch: where the row of the i-th
+    int32_t*       deg;                 // vertex of S starts in col[], and its length (fanout sampling: read from rowptr
+    int64_t        node_stride;         // once, when the vertex joins S; every later pass reads these in order)
     unsigned long long* totals;         // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
     int*           bad;
     int            L;
@@ -90,6 +93,8 @@ struct SampleArgs {
 __device__ __forceinline__ unsigned long long* tab_of(const SampleArgs& a, int j) { return a.tab + (int64_t)j * a.cap; }
 __device__ __forceinline__ int32_t* flat_of(const SampleArgs& a, int j) { return a.flat + (int64_t)j * a.flat_stride; }
 __device__ __forceinline__ int32_t* gids_of(const SampleArgs& a, int j) { return a.gids + (int64_t)j * a.flat_stride; }
+__device__ __forceinline__ int64_t* row0_of(const SampleArgs& a, int j) { return a.row0 + (int64_t)j * a.node_stride; }
+__device__ __forceinline__ int32_t* deg_of(const SampleArgs& a, int j) { return a.deg + (int64_t)j * a.node_stride; }
 __device__ __forceinline__ int32_t* cnt_of(const SampleArgs& a, int j) { return a.cnt + (int64_t)j * a.cnt_stride; }
 constexpr int kE = SPP_MAX_L + 1;      // offset of e[] inside counts
 
@@ -110,6 +115,11 @@ __global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const Batch
     int32_t v = t->b[j].seeds[i];
     if (v < 0 || v >= a.N) { v = 0; atomicOr(a.bad, 1); }       // reported; keeps later row reads in range
     t->b[j].S[i] = v;
+    if (!a.t && i < a.node_stride) {
+        const int64_t r0 = a.rowptr[v];
+        row0_of(a, j)[i] = r0;
+        deg_of(a, j)[i] = (int32_t)(a.rowptr[v + 1] - r0);
+    }
 }
 
 // ---- step 1 ----
@@ -118,9 +128,8 @@ struct CountIn {
     __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[a.h - 1]; }
     __device__ int operator()(int j, int64_t i) const {
         if (a.t) return cnt_of(a, j)[i];
-        const int64_t v = t->b[j].S[i];
-        const int64_t d = a.rowptr[v + 1] - a.rowptr[v];
-        return (int)(d < a.f ? d : a.f);
+        const int d = deg_of(a, j)[i];
+        return d < a.f ? d : a.f;
     }
 };
 struct CountOut {
@@ -214,6 +223,8 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
     const int32_t* __restrict__ indptr = t->b[jb].indptr[a.h - 1];
     int32_t* __restrict__ flat = flat_of(a, jb);
     int32_t* __restrict__ gids = gids_of(a, jb);
+    const int64_t* __restrict__ row0 = row0_of(a, jb);
+    const int32_t* __restrict__ deg = deg_of(a, jb);
     unsigned long long* tab = tab_of(a, jb);
     const uint32_t mask = t->b[jb].tinfo[0];
     const int shift = (int)t->b[jb].tinfo[1];
@@ -226,8 +237,8 @@ __global__ void __launch_bounds__(kBlock) sample_kernel(SampleArgs a, const Batc
         int32_t off = 0, v = 0;
         if (valid) {
             v = S[i];
-            r0 = a.rowptr[v];
-            d = a.rowptr[v + 1] - r0;
+            r0 = row0[i];
+            d = deg[i];
             off = indptr[i];
         }
         const bool floyd = d > f;
@@ -612,8 +623,15 @@ struct NewOut {
         const int64_t n_prev = t->b[j].counts[a.h - 1];
         if (a.t && n_prev + (int64_t)(uint32_t)total > t->b[j].ncap) return;      // NewFin abandons the minibatch
         const int64_t id = n_prev + ex;
+        const int32_t gid = gids_of(a, j)[e];
         t->b[j].src[a.h - 1][e] = (int32_t)id;
-        t->b[j].S[id] = gids_of(a, j)[e];
+        t->b[j].S[id] = gid;
+        // a vertex that will be a target of the next hop: its row is looked up here, once
+        if (!a.t && a.h < a.L && id < a.node_stride) {
+            const int64_t r0 = a.rowptr[gid];
+            row0_of(a, j)[id] = r0;
+            deg_of(a, j)[id] = (int32_t)(a.rowptr[gid + 1] - r0);
+        }
     }
 };
 struct NewFin {
@@ -787,6 +805,11 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
     a.tab = ctx->table.as<unsigned long long>(); a.cap = cap;
     a.flat = ctx->flat.as<int32_t>(); a.flat_stride = emax;
     a.gids = a.flat + (size_t)emax * n_items;
+    // row start and length of every vertex that can be a target: the members of S_{L-1}
+    a.node_stride = general ? 0 : nb[L - 1];
+    SPP_TRY(ctx->nodeinfo.reserve((size_t)a.node_stride * n_items * (sizeof(int64_t) + sizeof(int32_t)) + 64));
+    a.row0 = ctx->nodeinfo.as<int64_t>();
+    a.deg = reinterpret_cast<int32_t*>(a.row0 + (size_t)a.node_stride * n_items);
     const size_t dedup_lds = ((size_t)kLdsSlots + (size_t)(kDedupBlock / kWave) * kQueue) * sizeof(unsigned long long);
     if (!general && !ctx->dedup_lds_set) {
         SPP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&dedup_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
