@@ -66,6 +66,10 @@ enum {
 #define SPP_NO_JOIN           0x8u   /* gather: leave the miss copy running on the side stream; see spp_gather_join */
 #define SPP_STORE_ORDER       0x10u  /* gather: fetch the call's missed remote rows in the order of the remote store;
                                         see spp_gather_features_multi */
+#define SPP_HIT_BESIDE_MISS   0x80u  /* gather, with SPP_NO_JOIN in a loop of calls: queue this call's miss copy before
+                                        its hit copy, so that it starts the moment the miss copy of the call before
+                                        ends and the host link never idles; the hit copy then runs beside it on the
+                                        CUs it leaves free (same results; higher pipeline rate, slower hit copy) */
 
 typedef struct spp_ctx   spp_ctx;    /* workspaces, side stream, events */
 typedef struct spp_graph spp_graph;  /* refers to the caller's CSR; owns the library-built transposed structure */
@@ -242,7 +246,13 @@ int  spp_gather_join(spp_ctx* ctx);
  * and fetched in the store's order, so that rows that are neighbours in the store share the
  * memory lines they straddle.  It pays when a call misses a sizeable share of the store (an
  * eighth or more: then the fetch is 3 to 15 % faster) and costs a pass over that array
- * otherwise. */
+ * otherwise.
+ * SPP_HIT_BESIDE_MISS changes the order of the call's two copies, never the result: by default the
+ * stream waits for the miss copy of the call before, copies the hits with the whole chip and then
+ * starts this call's miss copy; with the flag the miss copy is queued first (it starts when the
+ * earlier one ends) and the hit copy runs beside it.  It pays in a loop of SPP_NO_JOIN calls whose
+ * hit copy takes a sizeable part of the time between two miss copies.
+ * flags: SPP_SYNC, SPP_NO_JOIN, SPP_STORE_ORDER, SPP_HIT_BESIDE_MISS. */
 typedef struct {
     const int32_t* d_node_ids;
     int64_t        n;

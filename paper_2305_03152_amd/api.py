@@ -25,6 +25,7 @@ SPP_SYNC = 0x1
 SPP_VIP_INCLUDE_HOP0 = 0x2
 SPP_GRAPH_IN_LISTS = 0x4
 SPP_NO_JOIN = 0x8
+SPP_HIT_BESIDE_MISS = 0x80
 SPP_STORE_ORDER = 0x10
 SPP_GRAPH_CHUNKED = 0x20
 SPP_SAMPLE_GLOBAL_TABLE = 0x40
@@ -625,11 +626,13 @@ def gather_features_static(ctx: Context, cache: Optional[Cache], local: torch.Te
 
 def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Tensor, N: int, lo: int, hi: int,
                           remote: Optional[torch.Tensor], lists, sync: bool = True, join: bool = True,
-                          store_order: bool = False):
+                          store_order: bool = False, hit_beside_miss: bool = False):
     """One classification / hit copy / miss copy over several id lists.
 
     store_order: fetch the missed remote rows in the order of the remote store (same result; faster when the
     call misses an eighth or more of the store's rows).
+    hit_beside_miss: in a loop of unjoined calls, start this call's miss copy before its hit copy (same result;
+    the host link never idles, the hit copy shares the chip with the miss copy).
 
     `lists` is a sequence of (node_ids, n, n_device or None, out); returns the summed stats when sync.
     `local` is the partition's rows on the GPU, or a LocalStore (rows split between GPU and host).
@@ -650,7 +653,8 @@ def gather_features_multi(ctx: Context, cache: Optional[Cache], local: torch.Ten
         arr[j].d_n = n_dev.data_ptr() if n_dev is not None else None
         arr[j].d_out = out.data_ptr()
     st = _GatherStats()
-    flags = (SPP_SYNC if sync else 0) | (0 if join else SPP_NO_JOIN) | (SPP_STORE_ORDER if store_order else 0)
+    flags = ((SPP_SYNC if sync else 0) | (0 if join else SPP_NO_JOIN) | (SPP_STORE_ORDER if store_order else 0) |
+             (SPP_HIT_BESIDE_MISS if hit_beside_miss else 0))
     lib = load_library()
     if store is not None:
         _check(lib.spp_gather_features_split(ctx._h, cache._h if cache is not None else None, store._h,

@@ -147,14 +147,17 @@ inline void grid_scan(hipStream_t st, int grid, const int64_t* n_ptr, In in, Out
 
 // The same scan for several independent sequences at once, in two launches; batch_block() names the
 // sequence ("batch") j.
-//   In:  int64_t n(int j) const (length, read on the device); int operator()(int j, int64_t i) const
+//   In:  int64_t n(int j) const (length, read on the device; the second launch calls n(j, total) with the
+//        sequence's total); int operator()(int j, int64_t i) const
 //   Out: void operator()(int j, int64_t i, int ex, int v, int total) const
 //   Fin: void operator()(int j, int total) const      called once per sequence, by one thread
 // `partial` holds gridDim.x ints per sequence.  Every workgroup of the second launch adds up the
 // partial sums of its sequence itself (there are a few dozen), so no launch stands between the two
 // passes; Fin runs at the start of the second launch, in workgroup 0 of the sequence, which means
-// that the other workgroups of that launch must not read what Fin writes: Out and Tail get the
-// sequence's total and derive what they need from it.
+// that the other workgroups of that launch must not depend on what Fin writes: n(j, total), Out
+// and Tail get the sequence's total and derive what they need from it.  (Where Fin sets a flag
+// that those workgroups also read, they combine it with the launch-invariant condition under
+// which Fin sets it, so that either value of the flag gives the same outcome.)
 // Two hooks let independent work ride in the same launches (a launch costs more than most of
 // these steps): Head: void operator()(int j, unsigned x, unsigned gx) const runs before the
 // reduction, Tail: void operator()(int j, unsigned x, unsigned gx, int total) const after the write
@@ -194,7 +197,7 @@ __global__ void __launch_bounds__(kBlock) bscan_write_kernel(In in, Out out, Fin
     }
     if (bb.x == 0 && threadIdx.x == 0) fin(j, seq_total);
     int64_t b, e;
-    scan_range(in.n(j), bb.x, b, e);
+    scan_range(in.n(j, seq_total), bb.x, b, e);
     for (int64_t base = b; base < e; base += kBlock) {
         int64_t i = base + threadIdx.x;
         int v = i < e ? in(j, i) : 0;

@@ -31,7 +31,6 @@ namespace spp {
 
 constexpr int kMissBlocks = 64;        // workgroups of the miss kernel (see gather_lists)
 constexpr int kMissThreads = 256;      // threads of each
-constexpr bool kHitBesideMiss = false; // see the order of the copies in gather_lists
 constexpr int kClsPer = 8;             // ids per thread: a workgroup classifies 2048 consecutive ids per round
 static_assert(kBlock * kClsPer == kListAlign, "a classification chunk must not straddle two lists");
 
@@ -472,7 +471,7 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
     if (fixed) {
         SPP_CHECK(vbound <= fixed_rows, SPP_E_ARG, "spp_gather_features_static: %lld rows (padded) exceed the fixed workspace of %lld",
                   (long long)vbound, (long long)fixed_rows);
-        SPP_CHECK(n_lists <= 1 && !(flags & (SPP_STORE_ORDER | SPP_NO_JOIN)), SPP_E_ARG,
+        SPP_CHECK(n_lists <= 1 && !(flags & (SPP_STORE_ORDER | SPP_NO_JOIN | SPP_HIT_BESIDE_MISS)), SPP_E_ARG,
                   "spp_gather_features_static: one list, no SPP_STORE_ORDER, no SPP_NO_JOIN");
     } else {
         SPP_TRY(ctx->gcount[slot].reserve(kWsHeadBytes));
@@ -610,12 +609,13 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         // rows have landed), runs the hit copy with the whole chip, queues this call's miss copy on
         // the side stream and then copies the rows that shared a vertex of the earlier miss copy
         // (device to device, beside the new miss copy; the call before is complete from there on).
-        // kHitBesideMiss queues the new miss copy first instead, so that it starts the moment the
-        // earlier one ends and the PCIe link never idles; the hit copy then runs beside it on the
-        // CUs it leaves free.  Measured on 64 minibatches of 66k rows: link busy 99 % instead of
-        // 95 %, pipeline 4.5 % faster, but the hit copy at three quarters of its rate (0.45 ms
-        // instead of 0.35).  The default keeps the HBM-bound copy at its full rate.
-        if (kHitBesideMiss) {
+        // SPP_HIT_BESIDE_MISS queues the new miss copy first instead, so that it starts the moment
+        // the earlier one ends and the PCIe link never idles; the hit copy then runs beside it on
+        // the CUs it leaves free.  Measured on groups of 64 minibatches: 256-byte rows, a quarter
+        // of the group's time spent in the hit copy: pipeline 19 % faster, hit copy at 0.61 of
+        // the HBM peak instead of 0.69; 400-byte rows, link busy 95 % of the time anyway: 4.5 %
+        // faster, 0.66 instead of 0.73.  The default keeps the HBM-bound copy at its full rate.
+        if (flags & SPP_HIT_BESIDE_MISS) {
             if (miss_path) SPP_TRY(launch_miss());
             SPP_TRY(spp_gather_join(ctx));
             launch_hit();
@@ -715,7 +715,7 @@ extern "C" int spp_gather_features_static(spp_ctx* ctx, const spp_cache* cache, 
     SPP_CHECK(n >= 0 && n <= SPP_STATIC_GATHER_MAX_ROWS, SPP_E_ARG,
               "spp_gather_features_static: n = %lld exceeds SPP_STATIC_GATHER_MAX_ROWS = %d", (long long)n,
               SPP_STATIC_GATHER_MAX_ROWS);
-    SPP_CHECK(!(flags & (SPP_STORE_ORDER | SPP_NO_JOIN)), SPP_E_ARG,
+    SPP_CHECK(!(flags & (SPP_STORE_ORDER | SPP_NO_JOIN | SPP_HIT_BESIDE_MISS)), SPP_E_ARG,
               "spp_gather_features_static: SPP_STORE_ORDER and SPP_NO_JOIN are not available here");
     SPP_HIP(hipSetDevice(ctx->device));
     void* base = nullptr;

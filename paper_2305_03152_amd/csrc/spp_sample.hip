@@ -123,9 +123,23 @@ __global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const Batch
 }
 
 // ---- step 1 ----
+// With given probabilities sizes are not bounded by fanouts: the 64-bit count of the counting pass
+// decides whether the caller's buffers (and the table region laid out for them) hold this hop.
+// The count stays as it is until the hop's last scan resets it, so every workgroup of a launch
+// reads the same decision.
+__device__ __forceinline__ bool hop_overflows(const SampleArgs& a, const BatchDesc& b) {
+    return a.t != nullptr && *b.taken > (unsigned long long)b.ecap[a.h - 1];
+}
+// The flag tinfo[2] ("this minibatch was abandoned") is set by the Fin step of a scan, i.e. by one
+// thread of a launch whose other workgroups read it.  Every reader in such a launch therefore ORs
+// the flag with the condition under which that launch's Fin sets it, a condition that does not
+// change during the launch (the hop's count of taken entries against the edge capacity in the
+// offsets' scan; the scan's total against the vertex capacity in the scan that numbers the new
+// vertices): whichever value of the flag a workgroup happens to see, the outcome is the same.
 struct CountIn {
     SampleArgs a; const BatchTable* t;
-    __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[a.h - 1]; }
+    __device__ int64_t n(int j) const { return t->b[j].tinfo[2] || hop_overflows(a, t->b[j]) ? 0 : t->b[j].counts[a.h - 1]; }
+    __device__ int64_t n(int j, int) const { return n(j); }
     __device__ int operator()(int j, int64_t i) const {
         if (a.t) return cnt_of(a, j)[i];
         const int d = deg_of(a, j)[i];
@@ -136,13 +150,6 @@ struct CountOut {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int64_t i, int ex, int, int) const { t->b[j].indptr[a.h - 1][i] = ex; }
 };
-// With given probabilities sizes are not bounded by fanouts: the 64-bit count of the counting pass
-// decides whether the caller's buffers (and the table region laid out for them) hold this hop.
-// The count stays as it is until the hop's last scan resets it, so every workgroup of a launch
-// reads the same decision.
-__device__ __forceinline__ bool hop_overflows(const SampleArgs& a, const BatchDesc& b) {
-    return a.t != nullptr && *b.taken > (unsigned long long)b.ecap[a.h - 1];
-}
 // This hop's table: the smallest power of two >= 2 (n_{h-1} + e_h), at least 1024 slots, never more
 // than the region (the host sized it for the bound, which dominates).
 __device__ __forceinline__ void hop_table(const SampleArgs& a, int64_t n_prev, int e_h, uint32_t& capj, int& shift) {
@@ -610,18 +617,24 @@ struct NewIn {
         return first;
     }
 };
+// Whether the scan's total of new vertices exceeds the caller's vertex capacity (given probabilities only).
+__device__ __forceinline__ bool ids_overflow(const SampleArgs& a, const BatchDesc& b, int total) {
+    return a.t != nullptr && b.counts[a.h - 1] + (int64_t)(uint32_t)total > b.ncap;
+}
 struct NewInKept {
     SampleArgs a; const BatchTable* t;
-    __device__ int64_t n(int j) const { return t->b[j].tinfo[2] ? 0 : t->b[j].counts[kE + a.h]; }
+    // second launch of the scan: NewFin of this launch abandons the minibatch exactly when ids_overflow()
+    __device__ int64_t n(int j, int total) const {
+        return t->b[j].tinfo[2] || ids_overflow(a, t->b[j], total) ? 0 : t->b[j].counts[kE + a.h];
+    }
     __device__ int operator()(int j, int64_t e) const { return t->b[j].src[a.h - 1][e] == -2 ? 1 : 0; }
 };
 struct NewOut {
     SampleArgs a; const BatchTable* t;
     __device__ void operator()(int j, int64_t e, int ex, int v, int total) const {
-        if (!v || t->b[j].tinfo[2]) return;
+        if (!v || t->b[j].tinfo[2] || ids_overflow(a, t->b[j], total)) return;    // NewFin abandons the minibatch
         // A first appearance gets its local id here; the relabel pass fills in the repeats.
         const int64_t n_prev = t->b[j].counts[a.h - 1];
-        if (a.t && n_prev + (int64_t)(uint32_t)total > t->b[j].ncap) return;      // NewFin abandons the minibatch
         const int64_t id = n_prev + ex;
         const int32_t gid = gids_of(a, j)[e];
         t->b[j].src[a.h - 1][e] = (int32_t)id;
@@ -641,7 +654,7 @@ struct NewFin {
         if (a.t) *t->b[j].taken = 0ull;                    // the next hop counts from zero
         if (t->b[j].tinfo[2]) return;
         const int64_t n = c[a.h - 1] + (int64_t)(uint32_t)total;
-        if (a.t && n > t->b[j].ncap) {                     // the new ids do not fit the caller's buffer
+        if (ids_overflow(a, t->b[j], total)) {             // the new ids do not fit the caller's buffer
             t->b[j].tinfo[2] = 1;
             atomicOr(a.ovf, 1);
             c[kE + a.h] = 0;

@@ -68,7 +68,8 @@ def test_binding_constants_match_the_header():
     text = open(os.path.join(ROOT, "include", "spp.h")).read()
     defines = {k: int(v.rstrip("u"), 0) for k, v in re.findall(r"#define\s+(SPP_[A-Z0-9_]+)\s+(0x[0-9a-fA-F]+u?|\d+)\b", text)}
     for name in ("SPP_MAX_L", "SPP_MAX_FANOUT", "SPP_SYNC", "SPP_VIP_INCLUDE_HOP0", "SPP_GRAPH_IN_LISTS", "SPP_NO_JOIN",
-                 "SPP_STORE_ORDER", "SPP_GRAPH_CHUNKED", "SPP_SAMPLE_GLOBAL_TABLE", "SPP_STATIC_GATHER_MAX_ROWS"):
+                 "SPP_STORE_ORDER", "SPP_GRAPH_CHUNKED", "SPP_SAMPLE_GLOBAL_TABLE", "SPP_STATIC_GATHER_MAX_ROWS",
+                 "SPP_HIT_BESIDE_MISS"):
         assert defines[name] == getattr(api, name), name
     assert defines["SPP_MAX_GATHER_LISTS"] == 64 and defines["SPP_MAX_SAMPLE_BATCHES"] == 64
     enums = {k: int(v) for k, v in re.findall(r"\b(SPP_T_[A-Z_]+)\s*=\s*(\d+)", text)}

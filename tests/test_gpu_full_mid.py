@@ -78,7 +78,8 @@ def test_mid_full_size():
         spp.gather_join(ctx)
         spp.gather_features_multi(ctx, cache, local, cfg.N, lo, hi, remote,
                                   [(b[k].node_ids, b[k].nb[-1], b[k].n_final_device, o[k]) for k in range(G8)],
-                                  sync=False, join=False, store_order=(gi == 1))     # both miss orders
+                                  sync=False, join=False, store_order=(gi == 1),     # both miss orders
+                                  hit_beside_miss=(gi == 1))                         # and both orders of the copies
     spp.gather_join(ctx)
     ctx.sync()
     count_ref = np.zeros(cfg.N, dtype=np.float32)

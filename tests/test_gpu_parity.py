@@ -634,6 +634,22 @@ def test_gather_multi_lists(spp, ctx, tiny_case):
         assert torch.equal(out[:sizes[5]].cpu(), want5)
     for (ids, n, n_dev, out), n0 in zip(lists, sizes):
         assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
+    # each call's miss copy queued before its hit copy: unjoined calls in a row, then a joined one
+    _say("gather multi: hit copy beside the miss copy")
+    for (_, _, _, out) in lists:
+        out.zero_()
+    twins = [(ids, n, n_dev, torch.zeros_like(out)) for (ids, n, n_dev, out) in lists]
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, lists, sync=False, join=False,
+                              hit_beside_miss=True)
+    spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, twins, sync=False, join=False,
+                              hit_beside_miss=True, store_order=True)
+    st3 = spp.gather_features_multi(ctx, cache, c.local_d, cfg.N, c.lo, c.hi, c.remote, same, hit_beside_miss=True)
+    assert st3["n_local"] + st3["n_cache_hit"] + st3["n_miss"] == 3 * sizes[5]
+    for group in (lists, twins):
+        for (ids, n, n_dev, out), n0 in zip(group, sizes):
+            assert torch.equal(out[:n0].cpu(), S.feature_rows(cfg, ids[:n0].cpu()))
+    for (_, _, _, out) in same:
+        assert torch.equal(out[:sizes[5]].cpu(), want5)
     cache.close()
 
 

@@ -227,7 +227,9 @@ def _full_size(name):
         for o in outs:
             o.zero_()
         lists = [(mb[bi].node_ids, mfgs[bi].n[-1], mb[bi].n_final_device, outs[bi]) for bi in range(len(mfgs))]
-        spp.gather_features_multi(ctx, cache, local, N, lo, hi, remote, lists, sync=False, join=False, store_order=order)
+        # the second pass also queues the miss copy before the hit copy
+        spp.gather_features_multi(ctx, cache, local, N, lo, hi, remote, lists, sync=False, join=False, store_order=order,
+                                  hit_beside_miss=order)
         spp.gather_join(ctx)
         ctx.sync()
         st = spp.gather_last_stats(ctx)
