@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <stdarg.h>
 #include <string.h>
+#include <stdlib.h>
 
 #include <vector>
 
@@ -103,6 +104,16 @@ struct spp_ctx {
     spp::DevBuf nodeinfo;               // per minibatch: row start and length of the vertices of S_{L-1}
     spp::DevBuf slots;                  // per minibatch: mask and shift of the id table of the current hop
     spp::DevBuf partials;               // scan partial sums
+    // sampler: the per-call table of per-minibatch pointers is kept on the device in a few slots and stored again
+    // only when a call brings other buffers (a pipeline alternates between a few buffer sets); two sets of error
+    // flags, used alternately, the next call's cleared by the last kernel of this one
+    static constexpr int kBatchSlots = 4;
+    spp::DevBuf btab;                   // kBatchSlots tables, then the flags
+    void*       btab_mirror = nullptr;  // host copies of what the slots hold (malloc)
+    int         btab_n[kBatchSlots] = {};        // minibatches in each slot's table (0: empty)
+    uint64_t    btab_stamp[kBatchSlots] = {};    // last use
+    uint64_t    sample_calls = 0;
+    int         sample_flags_clean = 0; // the flags of the next call have been cleared on the stream
     // gather workspaces
     // two sets, used alternately: the classification of a call may run while the miss copy of the
     // call before still reads its own set

@@ -60,6 +60,17 @@ struct BatchDesc {
 struct BatchTable {
     BatchDesc b[kMaxBatches];
 };
+// What changes from call to call even when the caller reuses its buffers: the seeds and the number
+// of the minibatch.  It rides in the argument block of the call's first launch, which stores it
+// into the table; the rest of the table stays on the device between calls.
+struct BatchDyn {
+    const int32_t* seeds;
+    int32_t        nseeds;
+    uint32_t       batch_lo;
+};
+struct BatchDynAll {
+    BatchDyn d[kMaxBatches];
+};
 
 // What the minibatches of one call share.
 struct SampleArgs {
@@ -79,6 +90,7 @@ struct SampleArgs {
     int64_t        node_stride;         // once, when the vertex joins S; every later pass reads these in order)
     unsigned long long* totals;         // context-wide running sums: [0] batches, [1] |S_L|, [2] edges
     int*           bad;
+    int*           bad_next;            // the next call's flags: cleared by this call's last kernel
     int            L;
     int            h;                   // hop, 1-based
     int            f;                   // fanout of this hop
@@ -98,29 +110,51 @@ __device__ __forceinline__ int32_t* deg_of(const SampleArgs& a, int j) { return 
 __device__ __forceinline__ int32_t* cnt_of(const SampleArgs& a, int j) { return a.cnt + (int64_t)j * a.cnt_stride; }
 constexpr int kE = SPP_MAX_L + 1;      // offset of e[] inside counts
 
-// Zeroes the counts of the new minibatches and copies the seeds into S_0.
-__global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
-    const BatchBlock bb = batch_block();
-    const int j = bb.j;
-    const int i = bb.x * kBlock + threadIdx.x;
-    if (i == 0) {
-        int64_t* c = t->b[j].counts;
+// Zeroes the counts of the new minibatches, stores what this call brings (seeds, minibatch number)
+// into the table and copies the seeds into S_0.  x-th of gx workgroups of minibatch j.
+__device__ __forceinline__ void seeds_rows(const SampleArgs& a, BatchTable* t, const BatchDyn& dyn, int j, unsigned x,
+                                           unsigned gx) {
+    BatchDesc& b = t->b[j];
+    if (x == 0 && threadIdx.x == 0) {
+        int64_t* c = b.counts;
         for (int k = 1; k <= SPP_MAX_L; ++k) c[k] = 0;
         for (int k = 0; k <= SPP_MAX_L; ++k) c[kE + k] = 0;
-        c[0] = t->b[j].nseeds;
-        t->b[j].tinfo[2] = 0;
-        if (t->b[j].taken) *t->b[j].taken = 0ull;
+        c[0] = dyn.nseeds;
+        b.seeds = dyn.seeds; b.nseeds = dyn.nseeds; b.batch_lo = dyn.batch_lo;
+        b.tinfo[2] = 0;
+        if (b.taken) *b.taken = 0ull;
     }
-    if (i >= t->b[j].nseeds) return;
-    int32_t v = t->b[j].seeds[i];
-    if (v < 0 || v >= a.N) { v = 0; atomicOr(a.bad, 1); }       // reported; keeps later row reads in range
-    t->b[j].S[i] = v;
-    if (!a.t && i < a.node_stride) {
-        const int64_t r0 = a.rowptr[v];
-        row0_of(a, j)[i] = r0;
-        deg_of(a, j)[i] = (int32_t)(a.rowptr[v + 1] - r0);
+    for (int64_t i = (int64_t)x * kBlock + threadIdx.x; i < dyn.nseeds; i += (int64_t)gx * kBlock) {
+        int32_t v = dyn.seeds[i];
+        if (v < 0 || v >= a.N) { v = 0; atomicOr(a.bad, 1); }       // reported; keeps later row reads in range
+        b.S[i] = v;
+        if (!a.t && i < a.node_stride) {
+            const int64_t r0 = a.rowptr[v];
+            row0_of(a, j)[i] = r0;
+            deg_of(a, j)[i] = (int32_t)(a.rowptr[v + 1] - r0);
+        }
     }
 }
+__global__ void __launch_bounds__(kBlock) seeds_kernel(SampleArgs a, BatchTable* t, BatchDynAll dyn) {
+    const BatchBlock bb = batch_block();
+    seeds_rows(a, t, dyn.d[bb.j], bb.j, bb.x, gridDim.x);
+}
+// The same riding at the head of the first launch of hop 1's scan (fanout sampling), whose values
+// then come from the seeds themselves: the table's copy is written by that very launch.
+struct SeedsHead {
+    SampleArgs a; BatchTable* t; BatchDynAll dyn;
+    __device__ void operator()(int j, unsigned x, unsigned gx) const { seeds_rows(a, t, dyn.d[j], j, x, gx); }
+};
+struct CountInSeeds {
+    SampleArgs a; BatchDynAll dyn;
+    __device__ int64_t n(int j) const { return dyn.d[j].nseeds; }
+    __device__ int operator()(int j, int64_t i) const {
+        int32_t v = dyn.d[j].seeds[i];
+        if (v < 0 || v >= a.N) v = 0;
+        const int64_t d = a.rowptr[v + 1] - a.rowptr[v];
+        return d < a.f ? (int)d : a.f;
+    }
+};
 
 // ---- step 1 ----
 // With given probabilities sizes are not bounded by fanouts: the 64-bit count of the counting pass
@@ -685,6 +719,8 @@ __device__ __forceinline__ void relabel_rows(const SampleArgs& a, const BatchTab
 __global__ void __launch_bounds__(kBlock) relabel_kernel(SampleArgs a, const BatchTable* __restrict__ t) {
     const BatchBlock bb = batch_block();
     relabel_rows(a, t, bb.j, bb.x, gridDim.x);
+    // the call's last launch: nothing of this call touches the other set of flags
+    if (a.h == a.L && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) a.bad_next[threadIdx.x] = 0;
 }
 // The relabel of hop h-1 riding at the head of hop h's first scan launch (it reads the table, the
 // flat ids and the counts of hop h-1, which that launch only reads too).
@@ -693,16 +729,18 @@ struct RelabelPrev {
     __device__ void operator()(int j, unsigned x, unsigned gx) const { relabel_rows(a, t, j, x, gx); }
 };
 
-// Stores the call's table of per-minibatch pointers in device memory, sixteen entries per launch
-// (a launch's argument block holds 4 KB), and clears the flags.
+// Stores a table of per-minibatch pointers in device memory, sixteen entries per launch (a launch's
+// argument block holds 4 KB).  Only needed when a call brings buffers that no slot holds.
 constexpr int kStoreChunk = 16;
 struct BatchTableChunk { BatchDesc b[kStoreChunk]; };
-__global__ void __launch_bounds__(kBlock) batch_table_store_kernel(BatchTableChunk src, BatchTable* dst, int first, int* bad) {
+__global__ void __launch_bounds__(kBlock) batch_table_store_kernel(BatchTableChunk src, BatchTable* dst, int first) {
     const uint64_t* s = reinterpret_cast<const uint64_t*>(&src);
     uint64_t* d = reinterpret_cast<uint64_t*>(&dst->b[first]);
     for (unsigned i = threadIdx.x; i < sizeof(BatchTableChunk) / sizeof(uint64_t); i += kBlock) d[i] = s[i];
-    // [0] error flag, [1] capacity flag
-    if (first == 0 && threadIdx.x < 2) bad[threadIdx.x] = 0;
+}
+// [0] error flag, [1] capacity flag of a call
+__global__ void sample_flags_clear_kernel(int* bad) {
+    if (threadIdx.x < 2) bad[threadIdx.x] = 0;
 }
 static_assert(sizeof(BatchTableChunk) % sizeof(uint64_t) == 0, "copied as 64-bit words");
 static_assert(sizeof(BatchTableChunk) <= 4000, "must fit a launch's argument block");
@@ -741,7 +779,8 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
         for (int h = 0; h < L; ++h)
             SPP_CHECK(d_t[h] || g->M == 0, SPP_E_ARG, "spp_sample_mfg_general: no transition probabilities for hop %d", h + 1);
     if (n_items == 0) return SPP_OK;
-    BatchTable ht = {};
+    BatchTable ht = {};             // what stays the same while the caller reuses its buffers
+    BatchDynAll dyn = {};           // what every call brings
     int64_t nb[SPP_MAX_L + 1] = {0}, eb[SPP_MAX_L + 1] = {0};       // bounds (capacities) of the largest minibatch
     int max_seeds = 0;
     for (int j = 0; j < n_items; ++j) {
@@ -780,7 +819,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
             ht.b[j].ecap[h - 1] = io->n_edges_cap[h - 1];
         }
         for (int h = 0; h <= L; ++h) { if (nbj[h] > nb[h]) nb[h] = nbj[h]; if (ebj[h] > eb[h]) eb[h] = ebj[h]; }
-        ht.b[j].seeds = it.d_seeds; ht.b[j].nseeds = it.nseeds; ht.b[j].batch_lo = (uint32_t)it.batch_index;
+        dyn.d[j].seeds = it.d_seeds; dyn.d[j].nseeds = it.nseeds; dyn.d[j].batch_lo = (uint32_t)it.batch_index;
         ht.b[j].S = io->d_node_ids; ht.b[j].counts = io->d_counts;
         if (it.nseeds > max_seeds) max_seeds = it.nseeds;
     }
@@ -805,13 +844,40 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
         ht.b[j].tinfo = tinfo + 4 * j;
         ht.b[j].taken = general ? taken + j : nullptr;
     }
-    SPP_TRY(ctx->partials.reserve((size_t)scan_grid * n_items * sizeof(int) + 64 + sizeof(BatchTable) + 256));
+    SPP_TRY(ctx->partials.reserve((size_t)scan_grid * n_items * sizeof(int) + 64));
     int* partial = ctx->partials.as<int>();
-    int* d_bad = partial + (size_t)scan_grid * n_items;
-    // the per-minibatch pointers live in device memory: the table is too large to ride in the
-    // argument block of every kernel, so one small kernel stores it once per call
-    BatchTable* dt = reinterpret_cast<BatchTable*>(
-        (reinterpret_cast<uintptr_t>(d_bad) + 64 + 255) & ~static_cast<uintptr_t>(255));
+    // The table of per-minibatch pointers is too large to ride in the argument block of every kernel, so it
+    // lives in device memory: in one of a few slots, found again by content when a later call brings the same
+    // buffers (then nothing is stored), else stored over the slot used longest ago.
+    constexpr int kSlots = spp_ctx::kBatchSlots;
+    if (!ctx->btab.ptr) {
+        SPP_TRY(ctx->btab.reserve(kSlots * sizeof(BatchTable) + 256));
+        for (int k = 0; k < kSlots; ++k) ctx->btab_n[k] = 0;
+        ctx->sample_flags_clean = 0;
+    }
+    if (!ctx->btab_mirror) {
+        ctx->btab_mirror = calloc(kSlots, sizeof(BatchTable));
+        SPP_CHECK(ctx->btab_mirror, SPP_E_OOM, "spp_sample_mfg: out of host memory");
+    }
+    BatchTable* mirror = static_cast<BatchTable*>(ctx->btab_mirror);
+    int slot = -1;
+    for (int k = 0; k < kSlots && slot < 0; ++k)
+        if (ctx->btab_n[k] == n_items && memcmp(&mirror[k], &ht, (size_t)n_items * sizeof(BatchDesc)) == 0) slot = k;
+    const bool stored = slot >= 0;
+    if (!stored) {
+        slot = 0;
+        for (int k = 1; k < kSlots; ++k)
+            if (ctx->btab_stamp[k] < ctx->btab_stamp[slot]) slot = k;
+        ctx->btab_n[slot] = 0;          // until its launches are enqueued
+    }
+    ctx->btab_stamp[slot] = ++ctx->sample_calls;
+    BatchTable* dt = ctx->btab.as<BatchTable>() + slot;
+    // two sets of flags, used alternately: this call's were cleared by the last kernel of the call before
+    int* flags2 = reinterpret_cast<int*>(ctx->btab.as<BatchTable>() + kSlots);
+    int* d_bad = flags2 + 2 * (ctx->sample_calls & 1);
+    int* d_bad_next = flags2 + 2 * ((ctx->sample_calls + 1) & 1);
+    const bool flags_clean = ctx->sample_flags_clean != 0;
+    ctx->sample_flags_clean = 0;        // set again once this call's last kernel is enqueued
 
     SampleArgs a;
     a.rowptr = g->rowptr; a.col = g->col; a.N = g->N;
@@ -829,7 +895,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
                                     (int)dedup_lds));
         ctx->dedup_lds_set = 1;
     }
-    a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.bad = d_bad; a.ovf = d_bad + 1;
+    a.totals = reinterpret_cast<unsigned long long*>(ctx->totals); a.bad = d_bad; a.ovf = d_bad + 1; a.bad_next = d_bad_next;
     a.L = L; a.h = 0; a.f = 0; a.seed = seed;
     a.t = nullptr;
     a.force_global = (flags & SPP_SAMPLE_GLOBAL_TABLE) ? 1 : 0;
@@ -842,12 +908,18 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
     const int64_t share = (int64_t)ctx->num_cu * 64 / n_items + 1;    // workgroups per minibatch in the wide kernels
     {
         ScopedTimer tt(ctx, SPP_T_SAMPLE, st);
-        for (int first = 0; first < n_items; first += kStoreChunk) {
-            BatchTableChunk chunk;
-            memcpy(&chunk, &ht.b[first], sizeof(chunk));
-            batch_table_store_kernel<<<1, kBlock, 0, st>>>(chunk, dt, first, d_bad);
+        if (!flags_clean) sample_flags_clear_kernel<<<1, 64, 0, st>>>(d_bad);
+        if (!stored) {
+            for (int first = 0; first < n_items; first += kStoreChunk) {
+                BatchTableChunk chunk;
+                memcpy(&chunk, &ht.b[first], sizeof(chunk));
+                batch_table_store_kernel<<<1, kBlock, 0, st>>>(chunk, dt, first);
+            }
+            memcpy(&mirror[slot], &ht, sizeof(BatchTable));
+            ctx->btab_n[slot] = n_items;
         }
-        seeds_kernel<<<dim3(capped((max_seeds + kBlock - 1) / kBlock, 1 << 20), n_items), kBlock, 0, st>>>(a, dt);
+        // with given probabilities the counting kernel needs the seeds in place before the first scan
+        if (general) seeds_kernel<<<dim3(capped((max_seeds + kBlock - 1) / kBlock, 1 << 20), n_items), kBlock, 0, st>>>(a, dt, dyn);
         for (int h = 1; h <= L; ++h) {
             a.h = h; a.f = general ? 0 : fanouts[h - 1]; a.t = general ? d_t[h - 1] : nullptr;
             const dim3 wgrid(capped((nb[h - 1] * kWave + kBlock - 1) / kBlock, share), n_items);   // a wavefront per target
@@ -858,6 +930,10 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
                 ap.h = h - 1;
                 grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial,
                                   RelabelPrev{ap, dt}, TableClear{a, dt});
+            } else if (!general) {
+                // hop 1: the seeds are put in place by the scan's first launch, which counts from the seeds themselves
+                grid_scan_batched_two(st, scan_grid, n_items, CountInSeeds{a, dyn}, CountIn{a, dt}, CountOut{a, dt},
+                                      CountFin{a, dt}, partial, SeedsHead{a, dt, dyn}, TableClear{a, dt});
             } else {
                 grid_scan_batched(st, scan_grid, n_items, CountIn{a, dt}, CountOut{a, dt}, CountFin{a, dt}, partial,
                                   NoHook(), TableClear{a, dt});
@@ -883,6 +959,7 @@ static int sample_batches(spp_ctx* ctx, const spp_graph* g, const spp_sample_ite
             if (h == L || general)
                 relabel_kernel<<<dim3(capped((eb[h] + kBlock - 1) / kBlock, share), n_items), kBlock, 0, st>>>(a, dt);
         }
+        ctx->sample_flags_clean = 1;
     }
     SPP_HIP(hipGetLastError());
     if (flags & SPP_SYNC) {
