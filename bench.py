@@ -610,6 +610,10 @@ def run_workload(args, cfg, spp, S, torch, np, dev, K, W, R, cpu_leg):
                    "hit_rate_of_remote": avg["n_cache_hit"] / max(avg["n_cache_hit"] + avg["n_miss"], 1e-9),
                    "features": "sum of twelve hashed 16-bit uniforms, centred, unit variance (stand-in for N(0,1); the path copies bytes)"},
         "roofline": roof, "cpu_baseline": cpu, "pcie": pcie, "sampler": sampler,
+        # the overlapped pipeline against its pieces run one after the other (Sec. 4.3: what the overlap buys)
+        "overlap": {"serial_sum_ms_per_step": (sample_ms + cls_ms + hit_ms + miss_ms) / max(Gsz, 1),
+                    "pipelined_ms_per_step": elapsed / total_steps * 1e3,
+                    "gain": (sample_ms + cls_ms + hit_ms + miss_ms) / max(Gsz, 1) / (elapsed / total_steps * 1e3)},
         "kernels_ms": {"sample_mfg_per_launch": sample_ms, "gather_classify_per_launch": cls_ms,
                        "gather_hit_per_launch": hit_ms, "gather_miss_per_launch": miss_ms,
                        "median": {"sample_mfg": median[T_SAMPLE], "gather_classify": median[T_CLS],

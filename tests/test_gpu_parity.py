@@ -559,6 +559,39 @@ def test_sample_multi_batches(spp, ctx, tiny_case):
             _check_mfg(m, oracle.sample_mfg(c.rp, c.col, s_, cfg.fanouts, cfg.seed_sampler, bi), cfg.L)
 
 
+def test_sample_calls_that_reuse_and_change_their_buffers(spp, ctx, tiny_case):
+    """The library keeps the per-minibatch pointers of a call on the device and stores them again only when
+    a call brings other buffers: six buffer sets used in turn (more than it keeps), sets used with other seeds
+    and minibatch numbers, with fewer minibatches, and a bad seed whose flag must not leak into later calls."""
+    c = tiny_case
+    cfg = c.cfg
+    rng = np.random.default_rng(77)
+    sets = [[spp.MFGBuffers("cuda", 64, cfg.fanouts, cfg.N) for _ in range(3)] for _ in range(6)]
+    call = 0
+    for rnd in range(3):
+        for si in ([0, 1, 2, 3, 4, 5], [0, 1, 0, 1, 5, 0], [5, 4, 3, 2, 1, 0])[rnd]:
+            count = 3 if (call % 4) else 2          # the same buffers, fewer minibatches
+            seeds = [rng.permutation(c.Tk)[:rng.integers(0, 60)] for _ in range(count)]
+            items = [(torch.from_numpy(np.ascontiguousarray(s_)).cuda(), 5000 + 7 * call + k, sets[si][k])
+                     for k, s_ in enumerate(seeds)]
+            _say("sample: call", call, "buffer set", si, "minibatches", count)
+            spp.sample_mfg_multi(ctx, c.G, items, cfg.fanouts, cfg.seed_sampler, sync=bool(call % 2))
+            ctx.sync()
+            for (sd, bi, m), s_ in zip(items, seeds):
+                cn = m.counts.cpu().numpy()
+                m.n = [int(x) for x in cn[:cfg.L + 1]]
+                m.e = [int(x) for x in cn[9:9 + cfg.L + 1]]
+                _check_mfg(m, oracle.sample_mfg(c.rp, c.col, s_, cfg.fanouts, cfg.seed_sampler, bi), cfg.L)
+            call += 1
+    bad = torch.tensor([int(c.Tk[0]), cfg.N + 5], dtype=torch.int32, device="cuda")
+    with pytest.raises(spp.SppError):
+        spp.sample_mfg_multi(ctx, c.G, [(bad, 1, sets[0][0])], cfg.fanouts, cfg.seed_sampler)
+    for k in range(3):                             # both sets of flags come round again: clean
+        s_ = c.Tk[:10 + k]
+        spp.sample_mfg_multi(ctx, c.G, [(torch.from_numpy(np.ascontiguousarray(s_)).cuda(), 9, sets[0][0])], cfg.fanouts, cfg.seed_sampler)
+        _check_mfg(sets[0][0], oracle.sample_mfg(c.rp, c.col, s_, cfg.fanouts, cfg.seed_sampler, 9), cfg.L)
+
+
 def test_gather_multi_lists(spp, ctx, tiny_case):
     """Several id lists in one call: same rows as one call per list, summed statistics."""
     c = tiny_case
