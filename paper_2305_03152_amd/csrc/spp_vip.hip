@@ -25,6 +25,8 @@
 
 namespace spp {
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int64_t kPushShare = 16;       // push when the frontier's out-edges are at most M/16
 constexpr int kStatBlocks = 2048;        // most workgroups that report a part of the next frontier's size
 constexpr int kStatMirror = 2048;        // where those reports land in the context's pinned mirror (int64 index)
@@ -42,14 +44,15 @@ struct VipHop {
     unsigned long long* stat;  // per workgroup: vertices and out-edges of the next hop's frontier (unused at the last hop)
 };
 
-__device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, double S, unsigned long long& verts,
-                                                  unsigned long long& edges) {
+// `told` = the running total read beforehand (ignored at a first hop).
+__device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, double S, double told,
+                                                  unsigned long long& verts, unsigned long long& edges) {
     // A vertex that no frontier vertex points at has S = 0 exactly (most vertices, at the early hops):
     // its p^[h] is 0 and it needs no exponential; nor does p^[h] at the last hop when it is not asked for.
     const bool need_ph = a.p_hop != nullptr || !a.last;
     const double ph = (need_ph && S != 0.0) ? -expm1(S) : 0.0;
     if (a.p_hop) a.p_hop[u] = (float)ph;
-    const double T = a.first ? S : a.tot[u] + S;
+    const double T = a.first ? S : told + S;
     if (a.last) {
         a.p_total[u] = T != 0.0 ? (float)(-expm1(T)) : 0.0f;
     } else {
@@ -66,6 +69,31 @@ __device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, do
         }
         a.y_next[u] = yn;
     }
+}
+
+__device__ __forceinline__ void vip_finish_vertex(const VipHop& a, int64_t u, double S, unsigned long long& verts,
+                                                  unsigned long long& edges) {
+    vip_finish_vertex(a, u, S, a.first ? 0.0 : a.tot[u], verts, edges);
+}
+// All vertices, grid-stride, four per thread and round: the four sums and running totals are in
+// flight together (one vertex per round leaves a pass over 10^8 vertices waiting on its own loads:
+// 0.87 ms where the bytes take 0.55).  sum_of(u) = S_h(u).
+template <class SumOf>
+__device__ __forceinline__ void vip_finish_all(const VipHop& a, int64_t N, SumOf sum_of, unsigned long long& verts,
+                                               unsigned long long& edges) {
+    constexpr int U = 4;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; u + (U - 1) * stride < N; u += U * stride) {
+        double S[U], T0[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) S[k] = sum_of(u + k * stride);
+#pragma unroll
+        for (int k = 0; k < U; ++k) T0[k] = a.first ? 0.0 : a.tot[u + k * stride];
+#pragma unroll
+        for (int k = 0; k < U; ++k) vip_finish_vertex(a, u + k * stride, S[k], T0[k], verts, edges);
+    }
+    for (; u < N; u += stride) vip_finish_vertex(a, u, sum_of(u), verts, edges);
 }
 
 // The next hop is pushed or pulled depending on the size of its frontier (vertices with y != 0 and
@@ -93,19 +121,31 @@ __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
 }
 __global__ void fill_f64_kernel(double* p, int64_t n, double v) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {        // 128-bit stores for the bulk
+        typedef double f64x2 __attribute__((ext_vector_type(2)));
+        const f64x2 vv = {v, v};
+        f64x2* p2 = reinterpret_cast<f64x2*>(p);
+        for (int64_t i = tid; i < (n >> 1); i += stride) p2[i] = vv;
+        if (tid == 0 && (n & 1)) p[n - 1] = v;
+        return;
+    }
+    for (int64_t i = tid; i < n; i += stride) p[i] = v;
 }
 
 // The frontier itself (any order): list[0 .. *cursor) = vertices whose y is not zero and whose row
 // is not empty; a row of more than kPieceEdges entries is listed once per piece of that many
 // entries (adjacent in the list), so that the kernels that walk the frontier's rows can hand the
-// pieces of a long row to different workgroups.  A thread looks at kListPer consecutive vertices
-// and a workgroup reserves its part of the list with one atomic per round (same-address atomics
-// cost about 15 ns each: one per wavefront of 64 vertices took 0.45 ms on a frontier of 2.4M).
-constexpr int kListPer = 8;
+// pieces of a long row to different workgroups.  A thread looks at kListPer vertices (as 128-bit vectors),
+// first to count its entries and, once the workgroup has reserved its part of the list with one
+// atomic, again to write them (the second look finds its lines in the caches).  Same-address
+// atomics cost about 15 ns each, so what a round covers sets the pace on a large graph: with 8
+// vertices per thread a dense frontier of 10^8 vertices took 0.72 ms (54k atomics), with 64 the
+// pass is bound by reading y.  Small graphs keep 8 per thread (enough workgroups to fill the chip).
 constexpr int64_t kPieceEdges = 4096;
 __host__ __device__ inline int64_t frontier_list_capacity(int64_t N, int64_t M) { return N + M / kPieceEdges; }
 
+template <int kListPer>
 __global__ void __launch_bounds__(kBlock) vip_frontier_list_kernel(const float* __restrict__ y,
                                                                    const int64_t* __restrict__ rowptr, int64_t N,
                                                                    int32_t* __restrict__ list,
@@ -113,26 +153,45 @@ __global__ void __launch_bounds__(kBlock) vip_frontier_list_kernel(const float* 
     __shared__ int scan_lds[4];
     __shared__ unsigned long long start;
     const int64_t round = (int64_t)kBlock * kListPer;
+    auto pieces = [&](int64_t v) { return (int)((rowptr[v + 1] - rowptr[v] + kPieceEdges - 1) / kPieceEdges); };
     for (int64_t r0 = (int64_t)blockIdx.x * round; r0 < N; r0 += (int64_t)gridDim.x * round) {
-        const int64_t v0 = r0 + (int64_t)threadIdx.x * kListPer;
-        int cnt[kListPer], mine = 0;
+        // A wavefront covers kWave * kListPer consecutive vertices; lane l takes the 128-bit vectors
+        // l, 64 + l, 128 + l, ... of them (whole lines per load).  Bit 4 k + c of nz: component c of the
+        // lane's k-th vector is in the frontier.  (y is 16-byte aligned and w0 a multiple of four.)
+        const int64_t w0 = r0 + (int64_t)(threadIdx.x >> 6) * (kWave * kListPer);
+        auto vertex = [&](int bit) { return w0 + 4 * ((int64_t)(bit >> 2) * kWave + lane_id()) + (bit & 3); };
+        uint64_t nz = 0;
 #pragma unroll
-        for (int k = 0; k < kListPer; ++k) {
-            cnt[k] = 0;
-            if (v0 + k < N && y[v0 + k] != 0.0f)
-                cnt[k] = (int)((rowptr[v0 + k + 1] - rowptr[v0 + k] + kPieceEdges - 1) / kPieceEdges);
-            mine += cnt[k];
+        for (int k = 0; k < kListPer / 4; ++k) {
+            const int64_t v = vertex(4 * k);
+            if (v + 3 < N) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(y + v);
+                nz |= (uint64_t)((t.x != 0.0f) | ((t.y != 0.0f) << 1) | ((t.z != 0.0f) << 2) | ((t.w != 0.0f) << 3)) << (4 * k);
+            } else {
+                for (int c = 0; c < 4; ++c)
+                    if (v + c < N && y[v + c] != 0.0f) nz |= 1ull << (4 * k + c);
+            }
         }
+        int mine = 0;
+        for (uint64_t m = nz; m; m &= m - 1) mine += pieces(vertex(__builtin_ctzll(m)));
         int total;
         int at = block_exclusive_scan(mine, scan_lds, total);
-        if (threadIdx.x == 0 && total) start = atomicAdd(cursor, (unsigned long long)total);
+        if (total == 0) continue;        // uniform over the workgroup: the scan has synchronised it
+        if (threadIdx.x == 0) start = atomicAdd(cursor, (unsigned long long)total);
         __syncthreads();
         const unsigned long long base = start;
-#pragma unroll
-        for (int k = 0; k < kListPer; ++k)
-            for (int c = 0; c < cnt[k]; ++c) list[base + at++] = (int32_t)(v0 + k);
+        for (uint64_t m = nz; m; m &= m - 1) {
+            const int64_t v = vertex(__builtin_ctzll(m));
+            for (int c = pieces(v); c > 0; --c) list[base + at++] = (int32_t)v;
+        }
         __syncthreads();
     }
+}
+
+inline void launch_frontier_list(int grid, hipStream_t st, const float* y, const int64_t* rowptr, int64_t N, int32_t* list,
+                                 unsigned long long* cursor) {
+    if (N >= (int64_t)1 << 25) vip_frontier_list_kernel<64><<<grid, kBlock, 0, st>>>(y, rowptr, N, list, cursor);
+    else vip_frontier_list_kernel<8><<<grid, kBlock, 0, st>>>(y, rowptr, N, list, cursor);
 }
 
 // Entry i of that list: where its piece of the row starts in col[] and how many entries it has.
@@ -155,9 +214,8 @@ __device__ __forceinline__ int32_t frontier_entry(const int32_t* __restrict__ li
 }
 
 __global__ void __launch_bounds__(kBlock) vip_push_finish_kernel(VipHop a, const double* __restrict__ acc, int64_t N) {
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
     unsigned long long verts = 0, edges = 0;
-    for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) vip_finish_vertex(a, u, acc[u], verts, edges);
+    vip_finish_all(a, N, [&](int64_t u) { return acc[u]; }, verts, edges);
     if (!a.last) write_frontier_stat(a.stat, verts, edges);
 }
 
@@ -268,13 +326,12 @@ __global__ void __launch_bounds__(kTileBlock) vip_tile_kernel(const uint32_t* __
 
 __global__ void __launch_bounds__(kBlock) vip_tile_finish_kernel(VipHop a, const double* __restrict__ part, int parts,
                                                                  int64_t part_stride, int64_t N) {
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
     unsigned long long verts = 0, edges = 0;
-    for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < N; u += stride) {
+    vip_finish_all(a, N, [&](int64_t u) {
         double S = part[u];
         for (int j = 1; j < parts; ++j) S += part[(int64_t)j * part_stride + u];
-        vip_finish_vertex(a, u, S, verts, edges);
-    }
+        return S;
+    }, verts, edges);
     if (!a.last) write_frontier_stat(a.stat, verts, edges);
 }
 
@@ -289,7 +346,6 @@ __global__ void __launch_bounds__(kBlock) vip_tile_finish_kernel(VipHop a, const
 // staged in LDS 2048 pieces at a time), then finishes the block's vertices itself.  12 bytes per
 // entry instead of 4, but no line is fetched for four of its bytes.
 typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kXBlock = 1024;
 constexpr int kXUnroll = 4;              // vectors (four entries) per lane and round of the first pass (2, 4, 8: the same time)
 
@@ -921,7 +977,7 @@ extern "C" int spp_vip_propagate_general(spp_ctx* ctx, const spp_graph* g, const
         for (int h = 1; h <= L; ++h) {
             ScopedTimer th(ctx, SPP_T_VIP_HOP_FIRST + h - 1, st);
             fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount), 3, 0.0);
-            vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(pcur, g->rowptr, N, flist, fcount + 2);
+            launch_frontier_list(fill_grid, st, pcur, g->rowptr, N, flist, fcount + 2);
             if (binned) {
                 fill_f32_kernel<<<(unsigned)((g->nrb + kBlock) / kBlock), kBlock, 0, st>>>(
                     reinterpret_cast<float*>(cursor), g->nrb + 1, 0.f);         // all-zero bits either way
@@ -1060,7 +1116,7 @@ extern "C" int spp_vip_propagate(spp_ctx* ctx, const spp_graph* g, const int32_t
                 fill_f64_kernel<<<fill_grid, kBlock, 0, st>>>(acc, N, 0.0);
                 if (fc[0] > 0) {
                     fill_f64_kernel<<<1, 64, 0, st>>>(reinterpret_cast<double*>(fcount + 2), 1, 0.0);
-                    vip_frontier_list_kernel<<<fill_grid, kBlock, 0, st>>>(ycur, g->rowptr, N, flist, fcount + 2);
+                    launch_frontier_list(fill_grid, st, ycur, g->rowptr, N, flist, fcount + 2);
                     // at most this many list entries (vertices and pieces of long rows); the kernel reads the count itself
                     const int64_t entries = (int64_t)fc[0] + (int64_t)fc[1] / kPieceEdges;
                     const int64_t pgrid = (int64_t)ctx->num_cu * 8, need = (entries + kWave - 1) / kWave;
