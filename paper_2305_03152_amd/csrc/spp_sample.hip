@@ -30,6 +30,12 @@
 // of the caches (the hit copy ran 20 % slower) besides missing L2 itself.  Which form a hop takes is
 // decided per minibatch on the device, from the hop's size.
 //
+// Launches per call with fanouts: six per hop (two for each scan, the sample kernel, the
+// deduplication) and the last hop's relabel; the seeds are put in place at the head of hop 1's first
+// scan launch and the relabel of hop h-1 rides at the head of hop h's.  The per-minibatch pointers
+// (a table too large for an argument block) stay on the device between calls and are stored again
+// only when a call brings other buffers.
+//
 // The same machinery serves the sampler with given transition probabilities (Sec. 3.1, paragraph
 // after Prop. 1): a target takes every entry of its row independently with the entry's probability,
 // so step 1 is a counting pass with the random draws (one wavefront per target, ballots) and step 2
