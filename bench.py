@@ -523,6 +523,31 @@ def run_workload(args, cfg, spp, S, torch, np, dev, K, W, R, cpu_leg):
                   "value": total_steps / tb, "ms_per_step": tb / total_steps * 1e3, "steps": total_steps,
                   "gather_hit_avg_launch_ms": hb, "gather_hit_median_launch_ms": medb_[10], "launches": cb_[10]}
 
+    # the hit copy by itself, for comparison: as many rows as a timed launch copies, drawn at random from the local
+    # shard, one list, nothing else on the chip.  Reported beside the pipeline's figure, never as it.
+    alone = None
+    if args.depth_leg == "on" and P == 1:
+        n_alone = int((tot["n_local"] + tot["n_cache_hit"]) / max(cnt[10], 1))
+        if n_alone > 0:
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(77)
+            # other rows at every launch: the caches must not hold what the launch before read
+            ids_alone = [(torch.randint(0, hi - lo, (n_alone,), device=dev, generator=gen, dtype=torch.int64) + lo).to(torch.int32)
+                         for _ in range(11)]
+            out_alone = torch.empty((n_alone, cfg.D), dtype=cfg.torch_dtype, device=dev)
+            spp.gather_features(ctx, None, local, cfg.N, lo, hi, None, ids_alone[10], out=out_alone)
+            ctx.timing(True)
+            for k in range(10):
+                spp.gather_features(ctx, None, local, cfg.N, lo, hi, None, ids_alone[k], out=out_alone, sync=False)
+            ctx.sync()
+            ma_, ca_, _, meda_ = ctx.time_stats()
+            ctx.timing(False)
+            ha = ma_[10] / max(ca_[10], 1)
+            alone = {"rows": n_alone, "avg_launch_ms": ha, "median_launch_ms": meda_[10], "launches": ca_[10],
+                     "frac": n_alone * 2 * row_bytes / (ha * 1e-3) / 1e9 / HBM_PEAK_GBS if ha > 0 else None,
+                     "what": "the same kernel on one list of as many random rows of the local shard (other rows at every launch), alone on the chip"}
+            del ids_alone, out_alone
+
     T_HIT, T_MISS, T_CLS, T_SAMPLE = 10, 11, 12, 9
     per = lambda i: ms[i] / max(cnt[i], 1)
     hit_ms, miss_ms, cls_ms, sample_ms = per(T_HIT), per(T_MISS), per(T_CLS), per(T_SAMPLE)
@@ -535,7 +560,7 @@ def run_workload(args, cfg, spp, S, torch, np, dev, K, W, R, cpu_leg):
             "traffic": MEASURED_TRAFFIC.get((cfg.name, Gsz), {}).get("gather_hit") if P == 1 else None,
             "bytes_per_launch": hit_bytes, "rows_per_launch": hit_rows, "avg_launch_ms": hit_ms,
             "median_launch_ms": median[T_HIT], "min_launch_ms": shortest[T_HIT], "launches": cnt[T_HIT],
-            "note": "runs between two PCIe miss copies, with the whole chip"}
+            "note": "runs between two PCIe miss copies, with the whole chip", "same_kernel_alone": alone}
     roof["frac"] = roof["achieved"] / HBM_PEAK_GBS
     if beside is not None and beside["gather_hit_avg_launch_ms"] > 0:
         beside["gather_hit_frac_of_hbm_peak"] = hit_bytes / (beside["gather_hit_avg_launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS
