@@ -204,6 +204,19 @@ def test_sampler_and_vip_shape_sweep(spp, ctx, fanouts):
     G.close()
 
 
+def test_stream_rates_of_the_plain_kernels(spp, ctx, layout):
+    """The streaming kernels behind the bench line's measured HBM rates: three positive rates, far above what a
+    host link could move, and arguments that make no sense are refused."""
+    if layout != "row-blocks":
+        pytest.skip("once is enough")
+    r = spp.stream_rates(ctx, 256 << 20, 3)
+    _say("stream rates over 256 MiB:", r)
+    assert set(r) == {"read_only", "copy_read_plus_write", "write_only"}
+    assert all(v > 500.0 for v in r.values()), r
+    with pytest.raises(spp.SppError):
+        spp.stream_rates(ctx, 256 << 20, 0)
+
+
 def test_sampler_hops_on_both_sides_of_the_lds_capacity(spp, ctx):
     """One call whose minibatches take different forms of the deduplication at their last hop: a few
     hundred ids (one LDS partition), just under 16 x 8192 ids (sixteen partitions, nearly full) and twice
