@@ -772,7 +772,8 @@ def main():
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head["dtype"], "data": "synthetic",
         "config": head["config"], "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
-        "pcie": head["pcie"], "sampler": head["sampler"], "kernels_ms": head["kernels_ms"], "vip": head["vip"],
+        "pcie": head["pcie"], "sampler": head["sampler"], "overlap": head["overlap"], "kernels_ms": head["kernels_ms"],
+        "vip": head["vip"],
         "timed_region_s": head["timed_region_s"],
         "hbm_measured": {"datasheet_peak_GBps": HBM_PEAK_GBS, "library_streaming_kernels_over_1GiB_GBps": rates,
                          "note": "the datasheet peak counts reads and writes together; achieved figures are read against it"},
