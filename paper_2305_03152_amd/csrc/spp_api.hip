@@ -71,7 +71,7 @@ extern "C" void spp_ctx_destroy(spp_ctx* c) {
     c->table.release(); c->flat.release(); c->nodeinfo.release(); c->slots.release(); c->partials.release();
     c->btab.release(); free(c->btab_mirror);
     c->gtable.release(); c->gfirst.release();
-    for (int k = 0; k < 2; ++k) { c->srcdesc[k].release(); c->misslist[k].release(); c->gcount[k].release(); }
+    for (int k = 0; k < 2; ++k) { c->srcdesc[k].release(); c->misslist[k].release(); c->gcount[k].release(); c->hititems[k].release(); }
     c->y0.release(); c->y1.release(); c->tot.release(); c->acc.release(); c->frontier.release(); c->bins.release(); c->xvals.release();
     delete c;
 }

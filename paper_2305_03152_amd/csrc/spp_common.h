@@ -120,6 +120,7 @@ struct spp_ctx {
     spp::DevBuf srcdesc[2];             // int64 per row: where the row comes from
     spp::DevBuf misslist[2];            // the lists of a call: rows that hit (64-bit entries), miss, share a fetch, miss in store order
     spp::DevBuf gcount[2];              // device counters of the gather (int64[8]) and the list layout
+    spp::DevBuf hititems[2];            // the hit copy's work items (chunk, tile) that hold hits, and their number
     int         gslot = 0;              // set used by the last gather
     int         miss_lds = 0;           // dynamic LDS bytes of the miss kernel
     spp::DevBuf gtable;                 // vertices missed by the current gather call (id -> first row)

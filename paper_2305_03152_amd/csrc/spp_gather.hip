@@ -342,6 +342,55 @@ int launch_dup(spp_ctx* ctx, const PendingGather& pg) {
 // Device workspace of one gather call over `rows` virtual rows (padded): the counters and the
 // layout of the lists, one source descriptor per row, and the four row lists.
 namespace spp {
+// Lists the tiles that hold hits for the hit copy (see gather_hit_kernel): one workgroup per id list adds up
+// the tiles of the lists before it (a few thousand chunk counts at most) and then numbers its own.
+constexpr int kItemBlock = 1024;
+__global__ void __launch_bounds__(kItemBlock) hit_items_kernel(const int32_t* __restrict__ hcount, ListTable t, uint32_t vpr,
+                                                               uint32_t tile_vecs, uint64_t* __restrict__ item_list,
+                                                               uint32_t* __restrict__ n_items) {
+    __shared__ uint32_t wsum[kItemBlock / kWave];
+    __shared__ uint32_t carry;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int64_t c0 = t.off[blockIdx.x] / kListAlign, c1 = t.off[blockIdx.x + 1] / kListAlign;
+    auto tiles_of = [&](int64_t c) { return ((uint32_t)hcount[c] * vpr + tile_vecs - 1) / tile_vecs; };
+    // all threads: the tiles of the chunks before this list's; leaves the sum in `carry`
+    uint32_t mine = 0;
+    for (int64_t c = threadIdx.x; c < c0; c += kItemBlock) mine += tiles_of(c);
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) mine += __shfl_down(mine, off, kWave);
+    if (lane == 0) wsum[wave] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t s = 0;
+        for (int w = 0; w < kItemBlock / kWave; ++w) s += wsum[w];
+        carry = s;
+    }
+    __syncthreads();
+    for (int64_t cb = c0; cb < c1; cb += kItemBlock) {
+        const int64_t c = cb + threadIdx.x;
+        const uint32_t n = c < c1 ? tiles_of(c) : 0u;
+        const uint32_t inc = (uint32_t)wave_inclusive_scan((int)n);
+        const uint32_t before = carry;           // read before this round's update (a barrier follows)
+        if (lane == kWave - 1) wsum[wave] = inc;
+        __syncthreads();
+        uint32_t base = before, total = 0;
+        for (int w = 0; w < kItemBlock / kWave; ++w) { const uint32_t v = wsum[w]; total += v; if (w < wave) base += v; }
+        const uint32_t at = base + inc - n;
+        if (n) {
+            const uint32_t nv = (uint32_t)hcount[c] * vpr;
+            for (uint32_t k = 0; k < n; ++k) {
+                const uint32_t in_tile = nv - k * tile_vecs < tile_vecs ? nv - k * tile_vecs : tile_vecs;
+                item_list[at + k] = ((uint64_t)c << 32) | ((uint64_t)k << kHitTileBits) | in_tile;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) carry = before + total;
+        __syncthreads();
+    }
+    if (blockIdx.x == (unsigned)t.n_lists - 1 && threadIdx.x == 0) *n_items = carry;
+}
+
+
 struct GatherWs {
     unsigned long long* counters;   // [8]
     int64_t* off;                   // [kMaxLists + 1]
@@ -545,6 +594,17 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
         const uint32_t tiles_per_chunk = (uint32_t)((kListAlign * vpr + kBlock * kHitUnroll - 1) / (kBlock * kHitUnroll));
         const int64_t hneed = vbound / kListAlign * tiles_per_chunk;
         const int grid = (int)(hneed < (int64_t)ctx->num_cu * 256 ? hneed : (int64_t)ctx->num_cu * 256);
+        // the tiles that hold hits, listed once the classification has counted them (not for the caller that
+        // must not allocate, nor where a chunk or a tile number does not fit the list's entries)
+        uint64_t* item_list = nullptr;
+        uint32_t* n_items = nullptr;
+        static_assert(kBlock * kHitUnroll < (1 << kHitTileBits), "an entry holds the vectors of a tile");
+        if (!fixed && n_lists > 0 && tiles_per_chunk <= (1u << kHitTileBits)) {
+            SPP_TRY(ctx->hititems[slot].reserve((size_t)(hneed + 2) * sizeof(uint64_t)));
+            n_items = ctx->hititems[slot].as<uint32_t>();
+            item_list = ctx->hititems[slot].as<uint64_t>() + 2;
+            hit_items_kernel<<<n_lists, kItemBlock, 0, st>>>(a.hcount, a.t, vpr, (uint32_t)(kBlock * kHitUnroll), item_list, n_items);
+        }
         // The miss kernel is kept to 64 workgroups of 256 threads: they saturate the PCIe link (32
         // workgroups of 512 threads or 16 of 1024 reach 95 % of their rate, 64 of 512 less).  A CU
         // that hosts host-memory loads serves every other wavefront on it slowly, so each of these
@@ -599,10 +659,10 @@ static int gather_lists(spp_ctx* ctx, const spp_cache* cache, const void* d_loca
             const char* loc = static_cast<const char*>(d_local);
             const char* cr = static_cast<const char*>(crow);
             switch (V) {
-                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
-                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
-                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
-                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk); break;
+                case 16: gather_hit_kernel<16><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk, item_list, n_items, hneed); break;
+                case 8:  gather_hit_kernel<8><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk, item_list, n_items, hneed); break;
+                case 4:  gather_hit_kernel<4><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk, item_list, n_items, hneed); break;
+                default: gather_hit_kernel<2><<<grid, kBlock, 0, st>>>(a.hitlist, a.hcount, a.t, loc, cr, vpr, tiles_per_chunk, item_list, n_items, hneed); break;
             }
         };
         // Order of the copies.  The stream waits for the miss copy of the call before (its fetched

@@ -90,19 +90,24 @@ __device__ __forceinline__ int64_t make_hit(bool from_cache, int64_t src_row, in
 // 3.5 GB shard where tiles reach 5.5 on the same box.  One, two, four or eight vectors per lane:
 // four is best by 1 to 4 %; non-temporal loads of the source rows cost 4 % when the shard is in
 // HBM and 25 % when it fits the Infinity Cache.)
+// The tiles that hold hits, listed: item_list[i] = chunk << 32 | tile << 16 | the tile's vectors,
+// i < *n_items, in the order of the chunks (an entry says all a workgroup needs to start loading).  Without the list a copy's workgroups take every tile a chunk could
+// have and leave at once where the chunk's hits end; a list that misses a tenth of its ids then
+// strews a tenth of empty workgroups among the busy ones, each of which waits out a load behind
+// the copy's own traffic before it can leave (5 % of the copy's time on 256-byte rows).  With the
+// list the surplus workgroups are the last of the grid.  One workgroup per id list: it adds up the
+// tiles of the lists before it (a few thousand chunk counts at most) and then numbers its own.
+constexpr int kHitTileBits = 16;         // tiles of a chunk that an entry of the list can name
 template <int V, int U = kHitUnroll>
 __global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __restrict__ hitlist,
                                                             const int32_t* __restrict__ hcount, ListTable t,
                                                             const char* __restrict__ local,
                                                             const char* __restrict__ cache, uint32_t vpr,
-                                                            uint32_t tiles_per_chunk) {
+                                                            uint32_t tiles_per_chunk, const uint64_t* __restrict__ item_list,
+                                                            const uint32_t* __restrict__ n_items, int64_t item_cap) {
     typedef typename VecOf<V>::type vec_t;
-    const int64_t items = t.off[t.n_lists] / kListAlign * tiles_per_chunk;     // chunks in use x tiles
-    for (int64_t w = blockIdx.x; w < items; w += gridDim.x) {
-        const int64_t chunk = w / tiles_per_chunk;
-        const uint32_t base = (uint32_t)(w - chunk * tiles_per_chunk) * (uint32_t)(kBlock * U);
-        const uint32_t nv = (uint32_t)hcount[chunk] * vpr;                 // at most 2048 rows: fits 32 bits
-        if (base >= nv) continue;
+    // one tile: vectors [base, nv) of the chunk's hits, kBlock * U of them at most
+    auto copy_tile = [&](int64_t chunk, uint32_t base, uint32_t nv) {
         const int64_t* __restrict__ hl = hitlist + chunk * kListAlign;
         vec_t v[U];
         char* dst[U];
@@ -127,6 +132,29 @@ __global__ void __launch_bounds__(kBlock) gather_hit_kernel(const int64_t* __res
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (ok[u]) store_stream<V>(dst[u], v[u]);
+    };
+    if (item_list) {
+        // the list of the tiles that hold hits: the workgroup's first entry is asked for together with the
+        // list's length (entries beyond the length are stale and never used), so a workgroup's rows are two
+        // round trips away from its start
+        int64_t w = blockIdx.x;
+        uint64_t e = w < item_cap ? item_list[w] : 0ull;
+        const int64_t items = (int64_t)*n_items;
+        while (w < items) {
+            const uint32_t base = ((uint32_t)e >> kHitTileBits) * (uint32_t)(kBlock * U);
+            copy_tile((int64_t)(e >> 32), base, base + ((uint32_t)e & ((1u << kHitTileBits) - 1u)));
+            w += gridDim.x;
+            if (w < items) e = item_list[w];
+        }
+        return;
+    }
+    // without the list: every tile of every chunk in use
+    const int64_t items = t.off[t.n_lists] / kListAlign * tiles_per_chunk;
+    for (int64_t w = blockIdx.x; w < items; w += gridDim.x) {
+        const int64_t chunk = w / tiles_per_chunk;
+        const uint32_t base = (uint32_t)(w - chunk * tiles_per_chunk) * (uint32_t)(kBlock * U);
+        const uint32_t nv = (uint32_t)hcount[chunk] * vpr;                 // at most 2048 rows: fits 32 bits
+        if (base < nv) copy_tile(chunk, base, nv);
     }
 }
 
