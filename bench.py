@@ -32,8 +32,8 @@ PCIE_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction
 # their commands are under profiles/.  Keyed by (workload, minibatches per gather launch); other shapes
 # report null.
 MEASURED_TRAFFIC = {
-    ("large", 64): {"gather_hit": 1.377e+09, "sampler_call": 5.567e+08, "vip_dense_hop": 4.831e+10},
-    ("mid", 64): {"gather_hit": 2.274e+09, "sampler_call": 7.067e+08, "vip_dense_hop": 8.44e+08},
+    ("large", 64): {"gather_hit": 1.385e+09, "sampler_call": 5.571e+08, "vip_dense_hop": 4.831e+10},
+    ("mid", 64): {"gather_hit": 2.28e+09, "sampler_call": 7.06e+08, "vip_dense_hop": 8.44e+08},
 }
 
 
